@@ -1,0 +1,323 @@
+"""ctypes access to the C oracle and the layer-by-layer policy that strings its
+functions together.  TEST INFRASTRUCTURE ONLY (never imported by the HIP path).
+
+The order of operations is the one the method states (Sec. 3.1-3.2 of the
+paper: quantize the learner's fp32 policy, then actors run the 8-bit policy):
+quantize weights -> per-layer integer constants -> quantize the observation ->
+for every layer: integer accumulator, then requantize / LayerNorm+tanh, or for
+the last layer dequantize and apply the action head.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.build(force=False)
+        _LIB = C.CDLL(path)
+        _LIB.orc_num_threads.restype = C.c_int
+    return _LIB
+
+
+def _p(a, t):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+_f32, _f64, _i32, _i16, _i8, _u8, _i64 = (C.c_float, C.c_double, C.c_int32, C.c_int16, C.c_int8, C.c_uint8,
+                                           C.c_int64)
+
+
+def _chk(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with status {rc}")
+
+
+def c_qparams_asym(w, qdenom=255.0):
+    w = np.ascontiguousarray(w, np.float32).ravel()
+    s, z = _f32(), _i32()
+    _chk(lib().orc_qparams_asym(_p(w, _f32), _i64(w.size), _f32(qdenom), C.byref(s), C.byref(z)), "qparams_asym")
+    return np.float32(s.value), int(z.value)
+
+
+def c_quantize_asym(w, scale, zp):
+    w = np.ascontiguousarray(w, np.float32)
+    q = np.empty(w.shape, np.uint8)
+    lib().orc_quantize_asym(_p(w, _f32), _i64(w.size), _f32(scale), _i32(zp), _p(q, _u8))
+    return q
+
+
+def c_dequantize_asym(q, scale, zp):
+    q = np.ascontiguousarray(q, np.uint8)
+    w = np.empty(q.shape, np.float32)
+    lib().orc_dequantize_asym(_p(q, _u8), _i64(q.size), _f32(scale), _i32(zp), _p(w, _f32))
+    return w
+
+
+def c_quantize_sym_rows(w2d):
+    w2d = np.ascontiguousarray(w2d, np.float32)
+    rows, cols = w2d.shape
+    s = np.empty(rows, np.float32)
+    q = np.empty((rows, cols), np.int8)
+    _chk(lib().orc_quantize_sym_rows(_p(w2d, _f32), _i64(rows), _i64(cols), _p(s, _f32), _p(q, _i8)),
+         "quantize_sym_rows")
+    return q, s
+
+
+def c_dequantize_sym_rows(q, s):
+    q = np.ascontiguousarray(q, np.int8)
+    w = np.empty(q.shape, np.float32)
+    lib().orc_dequantize_sym_rows(_p(q, _i8), _i64(q.shape[0]), _i64(q.shape[1]), _p(np.ascontiguousarray(s, np.float32), _f32),
+                                  _p(w, _f32))
+    return w
+
+
+def c_layer_consts(s_in, s_w, s_out, bias):
+    s_w = np.ascontiguousarray(s_w, np.float32)
+    bias = np.ascontiguousarray(bias, np.float32)
+    n = s_w.size
+    m = np.empty(n, np.float32)
+    bq, M0, r = np.empty(n, np.int32), np.empty(n, np.int32), np.empty(n, np.int32)
+    _chk(lib().orc_layer_consts(_f32(s_in), _p(s_w, _f32), _f32(s_out), _p(bias, _f32), _i64(n), _p(m, _f32),
+                                _p(bq, _i32), _p(M0, _i32), _p(r, _i32)), "layer_consts")
+    return m, bq, M0, r
+
+
+def c_fc_acc(a, z_a, w_codes, z_w, bias_q):
+    a = np.ascontiguousarray(a, np.uint8)
+    B, K = a.shape
+    w16 = np.ascontiguousarray(w_codes, np.int16)
+    N = w16.shape[0]
+    acc = np.empty((B, N), np.int32)
+    _chk(lib().orc_fc_acc(_p(a, _u8), _i64(B), _i64(K), _i32(z_a), _p(w16, _i16), _i64(N),
+                          _p(np.ascontiguousarray(z_w, np.int32), _i32), _p(np.ascontiguousarray(bias_q, np.int32), _i32),
+                          _p(acc, _i32)), "fc_acc")
+    return acc
+
+
+def c_conv_acc(a, z_a, w_codes, stride, z_w, bias_q):
+    a = np.ascontiguousarray(a, np.uint8)
+    B, H, W, Cc = a.shape
+    w16 = np.ascontiguousarray(w_codes, np.int16)
+    Co, kh, kw, _ = w16.shape
+    OH, OW = (H - kh) // stride + 1, (W - kw) // stride + 1
+    acc = np.empty((B, OH, OW, Co), np.int32)
+    _chk(lib().orc_conv_acc(_p(a, _u8), _i64(B), _i64(H), _i64(W), _i64(Cc), _i32(z_a), _p(w16, _i16), _i64(Co),
+                            _i64(kh), _i64(kw), _i64(stride), _p(np.ascontiguousarray(z_w, np.int32), _i32),
+                            _p(np.ascontiguousarray(bias_q, np.int32), _i32), _p(acc, _i32)), "conv_acc")
+    return acc
+
+
+def c_requant(acc, M0, r, z_out, relu):
+    acc = np.ascontiguousarray(acc, np.int32)
+    N = acc.shape[-1]
+    rows = acc.size // N
+    out = np.empty(acc.shape, np.uint8)
+    lib().orc_requant(_p(acc, _i32), _i64(rows), _i64(N), _p(np.ascontiguousarray(M0, np.int32), _i32),
+                      _p(np.ascontiguousarray(r, np.int32), _i32), _i32(z_out), _i32(1 if relu else 0), _p(out, _u8))
+    return out
+
+
+def c_dequant_acc(acc, m):
+    acc = np.ascontiguousarray(acc, np.int32)
+    N = acc.shape[-1]
+    y = np.empty(acc.shape, np.float32)
+    lib().orc_dequant_acc(_p(acc, _i32), _i64(acc.size // N), _i64(N), _p(np.ascontiguousarray(m, np.float32), _f32),
+                          _p(y, _f32))
+    return y
+
+
+def c_ln_tanh(acc, m, gamma, beta, eps, s_out, z_out):
+    acc = np.ascontiguousarray(acc, np.int32)
+    N = acc.shape[-1]
+    t = np.empty(acc.shape, np.float32)
+    codes = np.empty(acc.shape, np.uint8)
+    lib().orc_ln_tanh(_p(acc, _i32), _i64(acc.size // N), _i64(N), _p(np.ascontiguousarray(m, np.float32), _f32),
+                      _p(np.ascontiguousarray(gamma, np.float32), _f32), _p(np.ascontiguousarray(beta, np.float32), _f32),
+                      _f64(eps), _f32(s_out), _i32(z_out), _p(t, _f32), _p(codes, _u8))
+    return t, codes
+
+
+def c_tanh_f32(y):
+    y = np.ascontiguousarray(y, np.float32)
+    t = np.empty(y.shape, np.float32)
+    lib().orc_tanh_f32(_p(y, _f32), _i64(y.size), _p(t, _f32))
+    return t
+
+
+def c_argmax_rows(y):
+    y = np.ascontiguousarray(y, np.float32)
+    N = y.shape[-1]
+    idx = np.empty(y.size // N, np.int32)
+    lib().orc_argmax_rows(_p(y, _f32), _i64(y.size // N), _i64(N), _p(idx, _i32))
+    return idx
+
+
+def c_fc_f64(x, w, b):
+    x = np.ascontiguousarray(x, np.float64)
+    B, K = x.shape
+    w = np.ascontiguousarray(w, np.float32)
+    N = w.shape[0]
+    y = np.empty((B, N), np.float64)
+    lib().orc_fc_f64(_p(x, _f64), _i64(B), _i64(K), _p(w, _f32), _p(np.ascontiguousarray(b, np.float32), _f32), _i64(N),
+                     _p(y, _f64))
+    return y
+
+
+def c_conv_f64(x, w, b, stride):
+    x = np.ascontiguousarray(x, np.float64)
+    B, H, W, Cc = x.shape
+    w = np.ascontiguousarray(w, np.float32)
+    Co, kh, kw, _ = w.shape
+    OH, OW = (H - kh) // stride + 1, (W - kw) // stride + 1
+    y = np.empty((B, OH, OW, Co), np.float64)
+    lib().orc_conv_f64(_p(x, _f64), _i64(B), _i64(H), _i64(W), _i64(Cc), _p(w, _f32),
+                       _p(np.ascontiguousarray(b, np.float32), _f32), _i64(Co), _i64(kh), _i64(kw), _i64(stride), _p(y, _f64))
+    return y
+
+
+def c_relu_f64(x):
+    x = np.ascontiguousarray(x, np.float64).copy()
+    lib().orc_relu_f64(_p(x, _f64), _i64(x.size))
+    return x
+
+
+def c_tanh_f64(x):
+    x = np.ascontiguousarray(x, np.float64).copy()
+    lib().orc_tanh_f64(_p(x, _f64), _i64(x.size))
+    return x
+
+
+def c_layernorm_f64(x, gamma, beta, eps):
+    x = np.ascontiguousarray(x, np.float64).copy()
+    N = x.shape[-1]
+    lib().orc_layernorm_f64(_p(x, _f64), _i64(x.size // N), _i64(N), _p(np.ascontiguousarray(gamma, np.float32), _f32),
+                            _p(np.ascontiguousarray(beta, np.float32), _f32), _f64(eps))
+    return x
+
+
+class OraclePolicy:
+    """The whole path, one layer at a time, every intermediate kept.
+
+    `net` is a plain description (dict) of the policy: layer kinds and shapes,
+    activation after each layer ("relu", "none", "ln_tanh"), head ("tanh",
+    "argmax", "linear"), weight scheme ("tensor_asym_u8" | "channel_sym_s8"),
+    input type ("f32" | "u8") and the quantizer's denominator.
+    """
+
+    def __init__(self, net):
+        self.net = net
+        self.layers = net["layers"]
+        self.q = None
+
+    # -- full-precision policy (Sec. 3.1: the learner's network) ------------------------------
+    def forward_fp32(self, params, obs):
+        """Returns (actions, ranges): ranges[i] = (min, max) of the network input (i = 0) and
+        of each hidden layer's output (after its activation), as fp32."""
+        x = np.asarray(obs, np.float64)
+        ranges = [(np.float32(x.min()), np.float32(x.max()))]
+        nl = len(self.layers)
+        for i, (l, p) in enumerate(zip(self.layers, params)):
+            if l["kind"] == "fc":
+                x = c_fc_f64(x.reshape(x.shape[0], -1), p["w"], p["b"])
+            else:
+                x = c_conv_f64(x, p["w"], p["b"], l["stride"])
+            if i == nl - 1:
+                break
+            if l["act"] == "relu":
+                x = c_relu_f64(x)
+            elif l["act"] == "ln_tanh":
+                x = c_tanh_f64(c_layernorm_f64(x, p["gamma"], p["beta"], self.net["ln_eps"]))
+            ranges.append((np.float32(x.min()), np.float32(x.max())))
+        y = x.reshape(x.shape[0], -1)
+        if self.net["head"] == "tanh":
+            out = c_tanh_f64(y).astype(np.float32)
+        elif self.net["head"] == "argmax":
+            out = c_argmax_rows(y.astype(np.float32))
+        else:
+            out = y.astype(np.float32)
+        return out, ranges
+
+    # -- quantizer block (Sec. 3.2) ---------------------------------------------------------
+    def quantize_params(self, params, act_ranges):
+        """act_ranges[i] = (lo, hi) for the input (i = 0) and each hidden output."""
+        qd = float(self.net["qdenom"])
+        nl = len(self.layers)
+        assert len(act_ranges) == nl
+        act_q = []
+        for i, (lo, hi) in enumerate(act_ranges):
+            if i == 0 and self.net["in_type"] == "u8":
+                act_q.append((np.float32(1.0), 0))  # raw frame codes are consumed as they are
+            else:
+                act_q.append(c_qparams_asym(np.array([lo, hi], np.float32), qd))
+        q = []
+        for i, (l, p) in enumerate(zip(self.layers, params)):
+            w = p["w"]
+            n_out = w.shape[0]
+            if self.net["wscheme"] == "tensor_asym_u8":
+                s, z = c_qparams_asym(w, qd)
+                codes = c_quantize_asym(w, s, z)
+                s_w = np.full(n_out, s, np.float32)
+                z_w = np.full(n_out, z, np.int32)
+            else:
+                c2, s_w = c_quantize_sym_rows(w.reshape(n_out, -1))
+                codes = c2.reshape(w.shape)
+                z_w = np.zeros(n_out, np.int32)
+            s_in, z_in = act_q[i]
+            requant = (i < nl - 1) and l["act"] != "ln_tanh"
+            s_out = act_q[i + 1][0] if requant else np.float32(0.0)
+            m, bias_q, M0, r = c_layer_consts(s_in, s_w, s_out, p["b"])
+            q.append({"codes": codes, "s_w": s_w, "z_w": z_w, "s_in": s_in, "z_in": z_in, "m": m, "bias_q": bias_q,
+                      "M0": M0, "rshift": r, "gamma": p.get("gamma"), "beta": p.get("beta"),
+                      "s_out": act_q[i + 1][0] if i < nl - 1 else None,
+                      "z_out": act_q[i + 1][1] if i < nl - 1 else None})
+        self.q = q
+        self.act_q = act_q
+        return q
+
+    # -- actor inference on the 8-bit policy (Sec. 3.1) ----------------------------------------
+    def quantize_obs(self, obs):
+        if self.net["in_type"] == "u8":
+            return np.ascontiguousarray(obs, np.uint8)
+        s0, z0 = self.act_q[0]
+        return c_quantize_asym(np.ascontiguousarray(obs, np.float32), s0, z0)
+
+    def forward_int8(self, obs=None, start_layer=0, start_codes=None):
+        """Runs layers start_layer.. on `obs` (start_layer = 0) or on the given
+        unsigned activation codes.  Returns dict(acc=[...], act=[...], ln_t=[...], y, actions);
+        lists are indexed by layer, entries before start_layer are None."""
+        nl = len(self.layers)
+        a = self.quantize_obs(obs) if start_codes is None else np.ascontiguousarray(start_codes, np.uint8)
+        taps = {"a0": a if start_layer == 0 else None, "acc": [None] * nl, "act": [None] * nl, "ln_t": [None] * nl}
+        for i in range(start_layer, nl):
+            l, q = self.layers[i], self.q[i]
+            if l["kind"] == "fc":
+                acc = c_fc_acc(a.reshape(a.shape[0], -1), q["z_in"], q["codes"], q["z_w"], q["bias_q"])
+            else:
+                acc = c_conv_acc(a.reshape(a.shape[0], l["in_h"], l["in_w"], l["in_c"]), q["z_in"], q["codes"],
+                                 l["stride"], q["z_w"], q["bias_q"])
+            taps["acc"][i] = acc
+            if i == nl - 1:
+                y = c_dequant_acc(acc.reshape(acc.shape[0], -1), q["m"])
+                taps["y"] = y
+                if self.net["head"] == "tanh":
+                    taps["actions"] = c_tanh_f32(y)
+                elif self.net["head"] == "argmax":
+                    taps["actions"] = c_argmax_rows(y)
+                else:
+                    taps["actions"] = y
+            elif l["act"] == "ln_tanh":
+                t, codes = c_ln_tanh(acc, q["m"], q["gamma"], q["beta"], self.net["ln_eps"], q["s_out"], q["z_out"])
+                taps["ln_t"][i] = t
+                taps["act"][i] = a = codes
+            else:
+                taps["act"][i] = a = c_requant(acc, q["M0"], q["rshift"], q["z_out"], l["act"] == "relu")
+        return taps
