@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the ActorQ 8-bit policy-inference path on one MI355X.
+
+A step = one actor inference call on a batch of 4096 observations through the D4PG-style int8 MLP
+(observation quantize -> 4 int8 layers with int32 accumulation, LayerNorm+tanh / requantize+ReLU
+epilogues -> tanh actions), with the quantizer block (fp32 weights -> int8 policy) re-run once
+every PULL_EVERY steps inside the timed region, as an actor that pulls a fresh policy from the
+learner does.  Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PULL_EVERY = 100           # actor steps between model pulls (the paper's smaller pull frequency)
+INT8_PEAK_TOPS = 5000.0    # MI355X dense int8 MFMA, TOP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def _events_ms(torch, fn, n):
+    st = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    for _ in range(n):
+        fn()
+    e1.record(st)
+    e1.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
+def forward_workload(torch, aq, synth, U, name, batch, iters, warm=20):
+    """Average launch time of the 8-bit forward on `name` at `batch` (HIP events around back-to-back launches)."""
+    net = synth.net_config(name)
+    params = synth.make_params(net)
+    obs = synth.make_obs(net, batch)
+    P = aq.Policy(net)
+    w, b, g, be = U.upload_params(params)
+    A = synth.action_dim(net)
+    d_obs = U.to_dev(obs)
+    act = torch.zeros((batch,) if net["head"] == "argmax" else (batch, A),
+                      dtype=torch.int32 if net["head"] == "argmax" else torch.float32, device=U.DEV)
+    nl = len(net["layers"])
+    r = torch.zeros(2 * nl, dtype=torch.float32, device=U.DEV)
+    calib = min(batch, 4096)
+    P.policy_forward_fp32(w, b, g, be, d_obs[:calib], act[:calib], r)   # GPU min/max calibration
+    ranges = r.cpu().numpy().reshape(nl, 2).tolist()
+    P.quantize_params(w, b, g, be, ranges)
+    assert P.policy_status() == aq.OK
+    P.policy_reserve(batch)
+    fwd = lambda: P.policy_forward_int8(d_obs, act)
+    for _ in range(warm):
+        fwd()
+    torch.cuda.synchronize()
+    ms = min(_events_ms(torch, fwd, iters) for _ in range(3))
+    f32 = lambda: P.policy_forward_fp32(w, b, g, be, d_obs, act)
+    f32()
+    torch.cuda.synchronize()
+    ms32 = _events_ms(torch, f32, max(2, iters // 20))
+    ops = 2.0 * synth.macs_per_sample(net) * batch
+    out = {"workload": f"{name} batch {batch}", "us_per_launch": ms * 1e3, "inferences_per_s": batch / (ms * 1e-3),
+           "tops": ops / (ms * 1e-3) / 1e12, "frac_int8_mfma_peak": ops / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+           "fp32_actor_us_per_launch": ms32 * 1e3}
+    return out, (P, w, b, g, be, ranges, d_obs, act, net, params, obs)
+
+
+def quantize_workload(torch, aq, synth, U, scheme, iters=30, n_buf=40):
+    """Learner->actor weight quantize pass over 4M fp32 params, rotating over distinct buffers so
+    that the source comes from HBM, not from the 256 MB last-level cache."""
+    n = synth.QUANT_TENSOR_ELEMS
+    src = U.to_dev(synth.quant_tensor())
+    srcs = [src.clone() for _ in range(n_buf)]
+    rows, cols = (1, n) if scheme == "tensor_asym_u8" else (2048, 2048)
+    dsts = [torch.empty(n, dtype=torch.uint8, device=U.DEV) for _ in range(n_buf)]
+    scale = torch.empty(rows, dtype=torch.float32, device=U.DEV)
+    zp = torch.empty(rows, dtype=torch.int32, device=U.DEV)
+    ws = torch.zeros(16, dtype=torch.int32, device=U.DEV)
+    i = [0]
+
+    def one():
+        k = i[0] % n_buf
+        i[0] += 1
+        aq.quantize_tensor(srcs[k], rows, cols, scheme, 255, dsts[k], scale, zp, ws)
+    for _ in range(n_buf):
+        one()
+    torch.cuda.synchronize()
+    ms = min(_events_ms(torch, one, iters) for _ in range(3))
+    gbs = 5.0 * n / (ms * 1e-3) / 1e9
+    return {"workload": f"quantize 4M fp32 params, {scheme}", "us_per_call": ms * 1e3, "GBps_algorithmic": gbs,
+            "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+
+
+def cpu_baseline(synth, U, net, params, obs, ranges, budget_s=12.0):
+    """The CPU oracle, as it stands, on batches of the same workload for about budget_s seconds."""
+    from oracle import policy as O
+    pol = O.OraclePolicy(net)
+    _, own_ranges = pol.forward_fp32(params, obs[:512])   # the oracle calibrates itself
+    pol.quantize_params(params, own_ranges)
+    n = 0
+    t0 = time.perf_counter()
+    while True:
+        pol.forward_int8(obs)
+        n += obs.shape[0]
+        dt = time.perf_counter() - t0
+        if dt >= budget_s:
+            break
+    return {"value": n / dt, "unit": "inferences/s", "cores": int(O.lib().orc_num_threads()), "kind": "oracle",
+            "sample": f"{n} observations ({n // obs.shape[0]} batches of {obs.shape[0]}) of the same workload, "
+                      f"{dt:.1f} s wall, OpenMP over batch rows"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path is measured on ONE GPU (the batch is the set of independent actors; "
+              "more GPUs would each take a slice of it with no exchange). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    from paper_1910_01055_amd import binding as aq, synth
+    import gpu_util as U
+    aq.load()
+
+    batch = 4096
+    head, ctx = forward_workload(torch, aq, synth, U, "cfg2", batch, iters=500)
+    P, w, b, g, be, ranges, d_obs, act, net, params, obs = ctx
+
+    def step(i):
+        if i % PULL_EVERY == 0:
+            P.quantize_params(w, b, g, be, ranges)
+        P.policy_forward_int8(d_obs, act)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    st = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(st)
+    for i in range(args.steps):
+        step(i)
+    e1.record(st)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    qp_ms = _events_ms(torch, lambda: P.quantize_params(w, b, g, be, ranges), 50)
+
+    ops = 2.0 * synth.macs_per_sample(net) * batch
+    achieved = ops / (head["us_per_launch"] * 1e-6) / 1e12
+    result = {
+        "metric": "int8 policy inferences/sec at batch 4096 + % of int8 MFMA peak (1 GPU)",
+        "value": batch * args.steps / wall, "unit": "inferences/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "cfg2: D4PG-style actor MLP 67-256(LN+tanh)-256-256-21(tanh), batch 4096, "
+                               "per-channel symmetric int8 weights, static uint8 activations",
+                   "batch": batch, "pull_every": PULL_EVERY, "quantize_params_us": qp_ms * 1e3,
+                   "device_ms_per_step": e0.elapsed_time(e1) / args.steps},
+        "pct_int8_mfma_peak": 100.0 * achieved / INT8_PEAK_TOPS,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": achieved / INT8_PEAK_TOPS, "traffic": None,
+                     "kernel": "k_mlp_fused (whole-network int8 MLP)", "us_per_launch": head["us_per_launch"]},
+        "fp32_actor_us_per_launch": head["fp32_actor_us_per_launch"],
+    }
+    if not args.no_extra:
+        extra = []
+        for name, bsz, it in (("cfg5", 16384, 100), ("cfg3", 65536, 100), ("cfg3", 256, 500), ("cfg3", 1, 500),
+                              ("cfg1", 256, 500), ("cfg4", 256, 100)):
+            o, c = forward_workload(torch, aq, synth, U, name, bsz, it)
+            c[0].close()
+            del c
+            extra.append(o)
+        for scheme in ("channel_sym_s8", "tensor_asym_u8"):
+            extra.append(quantize_workload(torch, aq, synth, U, scheme))
+        result["other_workloads"] = extra
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(synth, U, net, params, obs, ranges)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

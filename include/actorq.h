@@ -1,0 +1,178 @@
+/*
+ * actorq.h -- C ABI of the MI355X (gfx950) ActorQ hot path: 8-bit actor policy inference.
+ *
+ * Paper: "QuaRL / ActorQ: Quantization for Fast and Environmentally Sustainable
+ * Reinforcement Learning" (arXiv 1910.01055).  Sec. 3.1 puts a quantizer block between
+ * the fp32 learner and the actors; Sec. 3.2 defines the quantizer (uniform affine
+ * post-training quantization, per channel for convolutions, weights and activations at
+ * the same precision); the actors then run the policy in 8 bits.  The three calls named
+ * aq_quantize_params, aq_policy_forward_int8 and aq_policy_forward_fp32 are those two
+ * blocks plus the full-precision actor the paper compares against.
+ *
+ * Conventions
+ *  - Every pointer named d_* is a DEVICE pointer owned by the caller (for instance a torch
+ *    tensor's data_ptr()), contiguous, at least 16-byte aligned.  The library never frees
+ *    or keeps such a pointer beyond the stream work it enqueues.  h_* are host pointers.
+ *  - The handle aq_policy and everything inside it are owned by the library.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Unless a call
+ *    says it synchronizes, it only enqueues work on `stream` and returns.
+ *  - Argument errors are returned at once as aq_status; nothing throws or aborts.  Errors
+ *    that only the device can see (non-finite weights, a requantization multiplier outside
+ *    the representable shift range) set a flag read by aq_policy_status().
+ *  - A handle may be used from one thread at a time; distinct handles are independent.
+ *  - There is no CPU fallback: without a GPU every compute call returns AQ_EHIP.
+ *
+ * Layouts
+ *  - FC weights: fp32 [N][K] row-major (N = output features).
+ *  - Conv weights: fp32 [Cout][kh][kw][Cin]; activations NHWC; VALID padding; a conv
+ *    layer's output [oh][ow][Cout] is flattened in (h, w, c) order before an FC layer.
+ *  - Observations: fp32 [B][K0] (AQ_IN_F32) or uint8 [B][H][W][C] (AQ_IN_U8, consumed as
+ *    raw codes with scale 1 and zero-point 0).
+ *  - Actions: fp32 [B][A] for AQ_HEAD_TANH / AQ_HEAD_LINEAR, int32 [B] for AQ_HEAD_ARGMAX
+ *    (lowest index wins ties).
+ */
+#ifndef ACTORQ_H
+#define ACTORQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct aq_policy aq_policy;
+
+typedef enum {
+    AQ_OK = 0,
+    AQ_EINVAL = 1,     /* bad argument (NULL, negative size, unknown enum) */
+    AQ_ESHAPE = 2,     /* layer shapes do not chain, or a shape the kernels do not support */
+    AQ_ENONFINITE = 3, /* NaN/Inf among the weights (reported by aq_policy_status) */
+    AQ_ENOTQUANT = 4,  /* aq_policy_forward_int8 before aq_quantize_params */
+    AQ_EHIP = 5,       /* a HIP runtime call or kernel launch failed */
+    AQ_ENOMEM = 6,
+    AQ_ERANGE = 7      /* a requantization multiplier needs a shift outside [1, 62] */
+} aq_status;
+
+typedef enum { AQ_FC = 0, AQ_CONV2D = 1 } aq_kind;
+typedef enum { AQ_ACT_NONE = 0, AQ_ACT_RELU = 1, AQ_ACT_LN_TANH = 2 } aq_act;
+typedef enum { AQ_HEAD_TANH = 0, AQ_HEAD_ARGMAX = 1, AQ_HEAD_LINEAR = 2 } aq_head;
+/* Sec. 3.2: per-tensor asymmetric unsigned codes (scale + zero-point from min(W,0), max(W,0)),
+ * or the per-(output-)channel form with a symmetric range, codes in [-127, 127]. */
+typedef enum { AQ_W_TENSOR_ASYM_U8 = 0, AQ_W_CHANNEL_SYM_S8 = 1 } aq_wscheme;
+typedef enum { AQ_IN_F32 = 0, AQ_IN_U8 = 1 } aq_intype;
+
+/* One layer.  FC: in_c = K, out_c = N, in_h = in_w = kh = kw = stride = 1.
+ * `act` is applied to the layer's output; it is ignored on the last layer (the head follows). */
+typedef struct {
+    int32_t kind;
+    int32_t in_h, in_w, in_c;
+    int32_t out_c;
+    int32_t kh, kw, stride;
+    int32_t act;
+} aq_layer;
+
+typedef struct {
+    int32_t n_layers;       /* 1 .. AQ_MAX_LAYERS */
+    const aq_layer* layers; /* host array, copied by aq_policy_create */
+    int32_t head;           /* aq_head */
+    int32_t wscheme;        /* aq_wscheme */
+    int32_t in_type;        /* aq_intype */
+    int32_t qdenom;         /* denominator of delta in Sec. 3.2: 255 (= 2^8 - 1, default) or 256 (= 2^8, literal) */
+    float ln_eps;           /* LayerNorm epsilon (biased variance, eps inside the square root) */
+} aq_net;
+
+#define AQ_MAX_LAYERS 8
+
+/* Range of one activation tensor (extended to contain 0 by the quantizer, as min(.,0)/max(.,0)
+ * do for weights).  A policy with L layers has L ranges: the network input, then the output of
+ * every hidden layer after its activation. */
+typedef struct {
+    float lo, hi;
+} aq_range;
+
+/* Optional intermediate outputs of aq_policy_forward_int8, for checking against a reference.
+ * Each member is a host array of n_layers device pointers (or NULL), each entry NULL or a
+ * caller-owned device buffer:
+ *   acc[l]  int32 [rows_l][N_l]  zero-point-corrected accumulator incl. bias, rows_l = B * oh * ow
+ *   act[l]  uint8 [rows_l][N_l]  unsigned activation codes leaving hidden layer l
+ *   ln_t[l] fp32  [rows_l][N_l]  LayerNorm+tanh value before it is re-quantized (AQ_ACT_LN_TANH layers)
+ * a0: uint8 [B][K0] quantized observation; y: fp32 [B][A] dequantized last-layer output before the head. */
+typedef struct {
+    int32_t* const* acc;
+    uint8_t* const* act;
+    float* const* ln_t;
+    uint8_t* a0;
+    float* y;
+} aq_taps;
+
+/* Creates a policy handle for `net` on the current HIP device.  Validates that the layers chain.
+ * Allocates the per-layer device buffers (packed 8-bit weights, per-channel constants). */
+aq_status aq_policy_create(const aq_net* net, aq_policy** out);
+aq_status aq_policy_destroy(aq_policy* p);
+
+/* Pre-allocates the internal activation buffers for batches up to max_batch, so that later
+ * forwards with batch <= max_batch allocate nothing.  Forwards call it themselves when needed
+ * (that first call then synchronizes the device). */
+aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch);
+
+/* Chooses the 8-bit forward's launch plan: 0 = automatic (whole-network fused kernel when the
+ * network is an MLP that fits it, else one launch per layer), 1 = fused only (AQ_ESHAPE from the
+ * forward if it does not fit), 2 = one launch per layer.  Both plans compute identical integers. */
+aq_status aq_policy_set_path(aq_policy* p, int32_t path);
+
+/* Synchronizes `stream` and returns the sticky device-side error of the last
+ * aq_quantize_params (AQ_OK, AQ_ENONFINITE or AQ_ERANGE). */
+aq_status aq_policy_status(aq_policy* p, void* stream);
+
+/* Sec. 3.2 applied to one tensor, for the learner-to-actor broadcast: quantizes fp32
+ * d_w[rows][cols] to 8-bit codes in canonical row-major order.
+ *   AQ_W_TENSOR_ASYM_U8: one (scale, zero-point) for the whole tensor -> d_scale[1], d_zp[1], uint8 codes.
+ *   AQ_W_CHANNEL_SYM_S8: one scale per row -> d_scale[rows], d_zp[rows] = 0, int8 codes.
+ * d_workspace: at least 64 bytes of device memory the call may overwrite (cleared by the call).
+ * cols must be a multiple of 4 and d_w 16-byte aligned.  Non-finite inputs set d_workspace[2] (int32) to 1. */
+aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int32_t wscheme, int32_t qdenom,
+                             void* d_codes, float* d_scale, int32_t* d_zp, void* d_workspace, void* stream);
+
+/* The quantizer block (Sec. 3.1 / 3.2): turns the learner's fp32 parameters into the 8-bit
+ * policy held by `p`: weight codes in the kernels' packed layout, per-channel scales, the
+ * activation (scale, zero-point) of every range, integer biases, requantization multipliers
+ * and shifts.  h_d_w[l], h_d_b[l]: device pointers to layer l's weights and bias (bias may be
+ * NULL = zeros).  h_d_gamma[l], h_d_beta[l]: LayerNorm gain/offset for AQ_ACT_LN_TANH layers
+ * (NULL entries = 1 and 0; the arrays themselves may be NULL).  h_ranges: n_layers activation
+ * ranges (entry 0 is ignored for AQ_IN_U8).  Asynchronous; LayerNorm parameters are copied. */
+aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                             const float* const* h_d_gamma, const float* const* h_d_beta,
+                             const aq_range* h_ranges, void* stream);
+
+/* Copies layer l's quantized parameters, in canonical order, into caller buffers (any may be NULL):
+ * d_codes: uint8/int8 weight codes in the fp32 weights' layout; d_w_scale[N] fp32; d_w_zp[N] int32;
+ * d_bias_q[N] int32; d_mult[N] int32 and d_rshift[N] int32 (0 where the layer is not requantized);
+ * d_m[N] fp32 = input scale * weight scale. */
+aq_status aq_policy_export_layer(const aq_policy* p, int32_t layer, void* d_codes, float* d_w_scale,
+                                 int32_t* d_w_zp, int32_t* d_bias_q, int32_t* d_mult, int32_t* d_rshift,
+                                 float* d_m, void* stream);
+/* Copies the n_layers activation (scale, zero-point) pairs. */
+aq_status aq_policy_export_act_qparams(const aq_policy* p, float* d_scale, int32_t* d_zp, void* stream);
+
+/* Actor inference on the 8-bit policy (Sec. 3.1): d_obs -> observation quantize -> for every
+ * layer int8 x int8 -> int32 accumulation, then requantize (+ReLU) / LayerNorm+tanh+requantize, or
+ * on the last layer dequantize and apply the head -> d_actions.  batch >= 0 (0 is a no-op).
+ * taps may be NULL.  Asynchronous once the internal buffers cover `batch`. */
+aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                 const aq_taps* taps, void* stream);
+
+/* The full-precision actor (the paper's fp32 baseline) on the same network, computed in fp32
+ * from the learner's parameters.  d_ranges_out (may be NULL): 2 * n_layers floats that receive
+ * (min, max) of the network input and of every hidden layer's output over this batch -- the
+ * min/max calibration of the activation ranges. */
+aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                 const float* const* h_d_gamma, const float* const* h_d_beta,
+                                 const void* d_obs, int64_t batch, void* d_actions, float* d_ranges_out,
+                                 void* stream);
+
+const char* aq_status_string(aq_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACTORQ_H */

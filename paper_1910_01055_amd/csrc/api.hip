@@ -1,0 +1,497 @@
+// C ABI of the library: the policy handle, argument checks and the launch sequences.
+#include <new>
+#include <vector>
+
+#include "kernels.hpp"
+
+using namespace aq;
+
+namespace {
+
+struct LayerBuf {
+    aq_layer d;
+    int K, N, K_pad, N_pad, KS, NT, oh, ow;
+    bool fc;
+    int8_t* wp;
+    float* s_w;
+    int32_t* z_w;
+    int32_t* rowsum;
+    int32_t* bias_q;
+    int32_t* bias_fold;
+    int32_t* M0;
+    int32_t* rshift;
+    float* m;
+    float* gamma;
+    float* beta;
+};
+
+}  // namespace
+
+struct aq_policy {
+    aq_net net;
+    std::vector<LayerBuf> L;
+    void* slab = nullptr;  // all per-layer buffers live in one allocation
+    ActQ* actq = nullptr;
+    int* status = nullptr;
+    uint32_t* mm = nullptr;
+    uint32_t* keys = nullptr;
+    bool quantized = false;
+    int path = 0;  // 0 auto, 1 fused only, 2 one launch per layer
+    // activation scratch of the per-layer path and of the fp32 actor (grown on demand)
+    int64_t cap_i8 = 0, cap_f32 = 0;
+    int8_t* act_i8[2] = {nullptr, nullptr};
+    float* act_f32[2] = {nullptr, nullptr};
+    int64_t max_hidden_elems = 0;  // per sample, over hidden layer outputs
+    int64_t max_out_elems = 0;     // per sample, over all layer outputs
+};
+
+static hipStream_t as_stream(void* s) { return (hipStream_t)s; }
+
+extern "C" const char* aq_status_string(aq_status s) {
+    switch (s) {
+        case AQ_OK: return "ok";
+        case AQ_EINVAL: return "invalid argument";
+        case AQ_ESHAPE: return "unsupported or inconsistent layer shapes";
+        case AQ_ENONFINITE: return "non-finite weights";
+        case AQ_ENOTQUANT: return "policy not quantized yet";
+        case AQ_EHIP: return "HIP runtime error";
+        case AQ_ENOMEM: return "out of device memory";
+        case AQ_ERANGE: return "requantization multiplier out of range";
+    }
+    return "unknown";
+}
+
+extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
+    if (!net || !out || !net->layers) return AQ_EINVAL;
+    if (net->n_layers < 1 || net->n_layers > AQ_MAX_LAYERS) return AQ_EINVAL;
+    if (net->head < 0 || net->head > AQ_HEAD_LINEAR) return AQ_EINVAL;
+    if (net->wscheme != AQ_W_TENSOR_ASYM_U8 && net->wscheme != AQ_W_CHANNEL_SYM_S8) return AQ_EINVAL;
+    if (net->in_type != AQ_IN_F32 && net->in_type != AQ_IN_U8) return AQ_EINVAL;
+    if (net->qdenom != 255 && net->qdenom != 256) return AQ_EINVAL;
+    if (!(net->ln_eps > 0.0f)) return AQ_EINVAL;
+    int dev_count = 0;
+    if (hipGetDeviceCount(&dev_count) != hipSuccess || dev_count < 1) return AQ_EHIP;
+
+    aq_policy* p = new (std::nothrow) aq_policy();
+    if (!p) return AQ_ENOMEM;
+    p->net = *net;
+    p->net.layers = nullptr;
+    int64_t prev_elems = -1;
+    int prev_h = 0, prev_w = 0, prev_c = 0;
+    bool prev_conv = false;
+    size_t bytes = 0;
+    auto take = [&](size_t n) {
+        size_t off = bytes;
+        bytes += (n + 255) / 256 * 256;
+        return off;
+    };
+    std::vector<size_t> offs;
+    for (int l = 0; l < net->n_layers; ++l) {
+        const aq_layer& d = net->layers[l];
+        LayerBuf b{};
+        b.d = d;
+        if (d.act < 0 || d.act > AQ_ACT_LN_TANH || d.out_c < 1 || d.in_c < 1) {
+            delete p;
+            return AQ_EINVAL;
+        }
+        if (d.kind == AQ_FC) {
+            b.fc = true;
+            b.K = d.in_c;
+            b.oh = b.ow = 1;
+            b.d.in_h = b.d.in_w = b.d.kh = b.d.kw = b.d.stride = 1;
+            if (prev_elems >= 0 && prev_elems != d.in_c) {
+                delete p;
+                return AQ_ESHAPE;
+            }
+        } else if (d.kind == AQ_CONV2D) {
+            b.fc = false;
+            if (d.kh < 1 || d.kw < 1 || d.stride < 1 || d.in_h < d.kh || d.in_w < d.kw) {
+                delete p;
+                return AQ_ESHAPE;
+            }
+            if (l > 0 && (!prev_conv || prev_h != d.in_h || prev_w != d.in_w || prev_c != d.in_c)) {
+                delete p;
+                return AQ_ESHAPE;
+            }
+            if (d.act == AQ_ACT_LN_TANH) {
+                delete p;
+                return AQ_ESHAPE;
+            }
+            b.K = d.kh * d.kw * d.in_c;
+            b.oh = (d.in_h - d.kh) / d.stride + 1;
+            b.ow = (d.in_w - d.kw) / d.stride + 1;
+        } else {
+            delete p;
+            return AQ_EINVAL;
+        }
+        b.N = d.out_c;
+        b.K_pad = round_up(b.K, kTile);
+        b.N_pad = round_up(b.N, kTile);
+        b.KS = b.K_pad / kTile;
+        b.NT = b.N_pad / kTile;
+        prev_conv = !b.fc;
+        prev_h = b.oh;
+        prev_w = b.ow;
+        prev_c = b.N;
+        prev_elems = (int64_t)b.oh * b.ow * b.N;
+        if (l < net->n_layers - 1 && prev_elems > p->max_hidden_elems) p->max_hidden_elems = prev_elems;
+        if (prev_elems > p->max_out_elems) p->max_out_elems = prev_elems;
+        offs.push_back(take((size_t)b.NT * b.KS * 1024));
+        for (int i = 0; i < 10; ++i) offs.push_back(take((size_t)b.N_pad * 4));
+        p->L.push_back(b);
+    }
+    size_t off_actq = take(sizeof(ActQ) * (AQ_MAX_LAYERS + 1));
+    size_t off_status = take(256);
+    size_t off_mm = take(256);
+    size_t off_keys = take(sizeof(uint32_t) * 2 * (AQ_MAX_LAYERS + 1));
+    if (hipMalloc(&p->slab, bytes) != hipSuccess) {
+        delete p;
+        return AQ_ENOMEM;
+    }
+    // zero once: padding rows / k-steps of the packed weights and padded constants stay zero for good
+    if (hipMemset(p->slab, 0, bytes) != hipSuccess) {
+        (void)hipFree(p->slab);
+        delete p;
+        return AQ_EHIP;
+    }
+    char* base = (char*)p->slab;
+    size_t oi = 0;
+    for (auto& b : p->L) {
+        b.wp = (int8_t*)(base + offs[oi++]);
+        b.s_w = (float*)(base + offs[oi++]);
+        b.z_w = (int32_t*)(base + offs[oi++]);
+        b.rowsum = (int32_t*)(base + offs[oi++]);
+        b.bias_q = (int32_t*)(base + offs[oi++]);
+        b.bias_fold = (int32_t*)(base + offs[oi++]);
+        b.M0 = (int32_t*)(base + offs[oi++]);
+        b.rshift = (int32_t*)(base + offs[oi++]);
+        b.m = (float*)(base + offs[oi++]);
+        b.gamma = (float*)(base + offs[oi++]);
+        b.beta = (float*)(base + offs[oi++]);
+    }
+    p->actq = (ActQ*)(base + off_actq);
+    p->status = (int*)(base + off_status);
+    p->mm = (uint32_t*)(base + off_mm);
+    p->keys = (uint32_t*)(base + off_keys);
+    *out = p;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_destroy(aq_policy* p) {
+    if (!p) return AQ_EINVAL;
+    (void)hipDeviceSynchronize();
+    if (p->slab) (void)hipFree(p->slab);
+    for (int i = 0; i < 2; ++i) {
+        if (p->act_i8[i]) (void)hipFree(p->act_i8[i]);
+        if (p->act_f32[i]) (void)hipFree(p->act_f32[i]);
+    }
+    delete p;
+    return AQ_OK;
+}
+
+static aq_status ensure_i8(aq_policy* p, int64_t batch) {
+    if (batch <= p->cap_i8) return AQ_OK;
+    (void)hipDeviceSynchronize();
+    for (int i = 0; i < 2; ++i) {
+        if (p->act_i8[i]) (void)hipFree(p->act_i8[i]);
+        p->act_i8[i] = nullptr;
+    }
+    p->cap_i8 = 0;
+    size_t n = (size_t)batch * (size_t)(p->max_hidden_elems > 0 ? p->max_hidden_elems : 1) + 64;
+    for (int i = 0; i < 2; ++i)
+        if (hipMalloc((void**)&p->act_i8[i], n) != hipSuccess) return AQ_ENOMEM;
+    p->cap_i8 = batch;
+    return AQ_OK;
+}
+
+static aq_status ensure_f32(aq_policy* p, int64_t batch) {
+    if (batch <= p->cap_f32) return AQ_OK;
+    (void)hipDeviceSynchronize();
+    for (int i = 0; i < 2; ++i) {
+        if (p->act_f32[i]) (void)hipFree(p->act_f32[i]);
+        p->act_f32[i] = nullptr;
+    }
+    p->cap_f32 = 0;
+    size_t n = ((size_t)batch * (size_t)p->max_out_elems + 64) * sizeof(float);
+    for (int i = 0; i < 2; ++i)
+        if (hipMalloc((void**)&p->act_f32[i], n) != hipSuccess) return AQ_ENOMEM;
+    p->cap_f32 = batch;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch) {
+    if (!p || max_batch < 0) return AQ_EINVAL;
+    aq_status s = ensure_i8(p, max_batch);
+    if (s != AQ_OK) return s;
+    return ensure_f32(p, max_batch);
+}
+
+extern "C" aq_status aq_policy_set_path(aq_policy* p, int32_t path) {
+    if (!p || path < 0 || path > 2) return AQ_EINVAL;
+    p->path = path;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_status(aq_policy* p, void* stream) {
+    if (!p) return AQ_EINVAL;
+    int h = 0;
+    AQ_HIP_CHECK(hipStreamSynchronize(as_stream(stream)));
+    AQ_HIP_CHECK(hipMemcpy(&h, p->status, sizeof(int), hipMemcpyDeviceToHost));
+    if (h & kStatNonFinite) return AQ_ENONFINITE;
+    if (h & kStatRange) return AQ_ERANGE;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int32_t wscheme,
+                                        int32_t qdenom, void* d_codes, float* d_scale, int32_t* d_zp,
+                                        void* d_workspace, void* stream) {
+    if (!d_w || !d_codes || !d_scale || !d_zp || !d_workspace) return AQ_EINVAL;
+    if (rows < 0 || cols < 0 || (qdenom != 255 && qdenom != 256)) return AQ_EINVAL;
+    if (wscheme != AQ_W_TENSOR_ASYM_U8 && wscheme != AQ_W_CHANNEL_SYM_S8) return AQ_EINVAL;
+    if (cols % 4 != 0 || ((uintptr_t)d_w & 15) || ((uintptr_t)d_codes & 3)) return AQ_ESHAPE;
+    if (rows > 0x7fffffffLL || cols / 4 > 0x7fffffffLL) return AQ_ESHAPE;
+    if (rows == 0 || cols == 0) return AQ_OK;
+    return launch_quantize_tensor(d_w, rows, cols, wscheme, (float)qdenom, d_codes, d_scale, d_zp,
+                                  (uint32_t*)d_workspace, as_stream(stream));
+}
+
+extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                        const float* const* h_d_gamma, const float* const* h_d_beta,
+                                        const aq_range* h_ranges, void* stream) {
+    if (!p || !h_d_w || !h_ranges) return AQ_EINVAL;
+    const int nl = p->net.n_layers;
+    for (int l = 0; l < nl; ++l)
+        if (!h_d_w[l]) return AQ_EINVAL;
+    hipStream_t st = as_stream(stream);
+    const bool asym = p->net.wscheme == AQ_W_TENSOR_ASYM_U8;
+    const float qd = (float)p->net.qdenom;
+    RangesArg r{};
+    for (int l = 0; l < nl; ++l) {
+        r.lo[l] = h_ranges[l].lo;
+        r.hi[l] = h_ranges[l].hi;
+    }
+    aq_status s = launch_fill_u32((uint32_t*)p->status, 1, 0u, st);
+    if (s != AQ_OK) return s;
+    s = launch_act_qparams(r, nl, p->net.in_type == AQ_IN_U8, qd, p->actq, st);
+    if (s != AQ_OK) return s;
+    for (int l = 0; l < nl; ++l) {
+        LayerBuf& b = p->L[l];
+        s = launch_quantize_layer(h_d_w[l], b.N, b.K, b.KS, p->net.wscheme, qd, p->mm, b.wp, b.s_w, b.z_w, b.rowsum,
+                                  p->status, st);
+        if (s != AQ_OK) return s;
+        if (b.d.act == AQ_ACT_LN_TANH) {
+            if (h_d_gamma && h_d_gamma[l]) {
+                AQ_HIP_CHECK(hipMemcpyAsync(b.gamma, h_d_gamma[l], sizeof(float) * b.N, hipMemcpyDeviceToDevice, st));
+            } else {
+                s = launch_fill_u32((uint32_t*)b.gamma, b.N, 0x3f800000u, st);
+                if (s != AQ_OK) return s;
+            }
+            if (h_d_beta && h_d_beta[l]) {
+                AQ_HIP_CHECK(hipMemcpyAsync(b.beta, h_d_beta[l], sizeof(float) * b.N, hipMemcpyDeviceToDevice, st));
+            } else {
+                s = launch_fill_u32((uint32_t*)b.beta, b.N, 0u, st);
+                if (s != AQ_OK) return s;
+            }
+        }
+        const bool requant = l < nl - 1 && b.d.act != AQ_ACT_LN_TANH;
+        s = launch_layer_consts(p->actq, l, requant, asym, b.s_w, b.z_w, h_d_b ? h_d_b[l] : nullptr, b.rowsum, b.N,
+                                b.K, b.m, b.bias_q, b.M0, b.rshift, b.bias_fold, p->status, st);
+        if (s != AQ_OK) return s;
+    }
+    p->quantized = true;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_export_layer(const aq_policy* p, int32_t layer, void* d_codes, float* d_w_scale,
+                                            int32_t* d_w_zp, int32_t* d_bias_q, int32_t* d_mult, int32_t* d_rshift,
+                                            float* d_m, void* stream) {
+    if (!p || layer < 0 || layer >= p->net.n_layers) return AQ_EINVAL;
+    if (!p->quantized) return AQ_ENOTQUANT;
+    hipStream_t st = as_stream(stream);
+    const LayerBuf& b = p->L[layer];
+    if (d_codes) {
+        aq_status s = launch_unpack_weights(b.wp, b.N, b.K, b.KS, p->net.wscheme == AQ_W_TENSOR_ASYM_U8,
+                                            (uint8_t*)d_codes, st);
+        if (s != AQ_OK) return s;
+    }
+    const size_t nb = sizeof(float) * b.N;
+    if (d_w_scale) AQ_HIP_CHECK(hipMemcpyAsync(d_w_scale, b.s_w, nb, hipMemcpyDeviceToDevice, st));
+    if (d_w_zp) AQ_HIP_CHECK(hipMemcpyAsync(d_w_zp, b.z_w, nb, hipMemcpyDeviceToDevice, st));
+    if (d_bias_q) AQ_HIP_CHECK(hipMemcpyAsync(d_bias_q, b.bias_q, nb, hipMemcpyDeviceToDevice, st));
+    if (d_mult) AQ_HIP_CHECK(hipMemcpyAsync(d_mult, b.M0, nb, hipMemcpyDeviceToDevice, st));
+    if (d_rshift) AQ_HIP_CHECK(hipMemcpyAsync(d_rshift, b.rshift, nb, hipMemcpyDeviceToDevice, st));
+    if (d_m) AQ_HIP_CHECK(hipMemcpyAsync(d_m, b.m, nb, hipMemcpyDeviceToDevice, st));
+    return AQ_OK;
+}
+
+__global__ void k_split_actq(const ActQ* q, int n, float* s, int32_t* z) {
+    int i = threadIdx.x;
+    if (i < n) {
+        if (s) s[i] = q[i].s;
+        if (z) z[i] = q[i].z;
+    }
+}
+
+extern "C" aq_status aq_policy_export_act_qparams(const aq_policy* p, float* d_scale, int32_t* d_zp, void* stream) {
+    if (!p) return AQ_EINVAL;
+    if (!p->quantized) return AQ_ENOTQUANT;
+    hipLaunchKernelGGL(k_split_actq, dim3(1), dim3(64), 0, as_stream(stream), p->actq, p->net.n_layers, d_scale,
+                       d_zp);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
+static void fill_layer_dev(const aq_policy* p, int l, const aq_taps* taps, LayerDev& d) {
+    const LayerBuf& b = p->L[l];
+    d.wp = b.wp;
+    d.bias_fold = b.bias_fold;
+    d.M0 = b.M0;
+    d.rshift = b.rshift;
+    d.m = b.m;
+    d.gamma = b.gamma;
+    d.beta = b.beta;
+    d.z_w = b.z_w;
+    d.tap_acc = (taps && taps->acc) ? taps->acc[l] : nullptr;
+    d.tap_act = (taps && taps->act) ? taps->act[l] : nullptr;
+    d.tap_ln = (taps && taps->ln_t) ? taps->ln_t[l] : nullptr;
+    d.K = b.K;
+    d.N = b.N;
+    d.KS = b.KS;
+    d.NT = b.NT;
+    d.act = b.d.act;
+    d.in_h = b.d.in_h;
+    d.in_w = b.d.in_w;
+    d.in_c = b.d.in_c;
+    d.kh = b.d.kh;
+    d.kw = b.d.kw;
+    d.stride = b.d.stride;
+    d.oh = b.oh;
+    d.ow = b.ow;
+}
+
+extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                            const aq_taps* taps, void* stream) {
+    if (!p || batch < 0) return AQ_EINVAL;
+    if (!p->quantized) return AQ_ENOTQUANT;
+    if (batch == 0) return AQ_OK;
+    if (!d_obs || !d_actions) return AQ_EINVAL;
+    if (batch > (1LL << 40)) return AQ_EINVAL;
+    hipStream_t st = as_stream(stream);
+    const int nl = p->net.n_layers;
+    FwdArgs a{};
+    for (int l = 0; l < nl; ++l) fill_layer_dev(p, l, taps, a.L[l]);
+    a.n_layers = nl;
+    a.head = p->net.head;
+    a.in_u8 = p->net.in_type == AQ_IN_U8;
+    a.asym = p->net.wscheme == AQ_W_TENSOR_ASYM_U8;
+    a.ln_eps = p->net.ln_eps;
+    a.obs = d_obs;
+    a.batch = batch;
+    a.actq = p->actq;
+    a.actions = d_actions;
+    a.tap_a0 = taps ? taps->a0 : nullptr;
+    a.tap_y = taps ? taps->y : nullptr;
+
+    int rows;
+    size_t lds;
+    const bool can_fuse = fused_mlp_supported(a, &rows, &lds);
+    if (p->path == 1 && !can_fuse) return AQ_ESHAPE;
+    if (can_fuse && p->path != 2) return launch_fused_mlp(a, st);
+
+    // one launch per layer
+    aq_status s = ensure_i8(p, batch);
+    if (s != AQ_OK) return s;
+    s = ensure_f32(p, batch);
+    if (s != AQ_OK) return s;
+    if (a.in_u8 && a.tap_a0) {
+        const LayerBuf& b0 = p->L[0];
+        const size_t n = (size_t)batch * b0.d.in_h * b0.d.in_w * b0.d.in_c;
+        AQ_HIP_CHECK(hipMemcpyAsync(a.tap_a0, d_obs, n, hipMemcpyDeviceToDevice, st));
+        a.tap_a0 = nullptr;
+    }
+    float* ybuf = a.tap_y ? a.tap_y : p->act_f32[1];
+    a.tap_y = ybuf;
+    for (int l = 0; l < nl; ++l) {
+        const LayerBuf& b = p->L[l];
+        const int64_t rows_l = batch * b.oh * b.ow;
+        LayerIO io;
+        io.in = l == 0 ? d_obs : (const void*)p->act_i8[(l - 1) & 1];
+        io.out = p->act_i8[l & 1];
+        io.ln_x = p->act_f32[0];
+        s = launch_layer_int8(a, l, io, st);
+        if (s != AQ_OK) return s;
+        if (l < nl - 1 && b.d.act == AQ_ACT_LN_TANH) {
+            s = launch_ln_tanh_rows(a, l, io.ln_x, io.out, rows_l, st);
+            if (s != AQ_OK) return s;
+        }
+        if (l == nl - 1) {
+            s = launch_head_rows(ybuf, rows_l, b.N, p->net.head, d_actions, st);
+            if (s != AQ_OK) return s;
+        }
+    }
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                            const float* const* h_d_gamma, const float* const* h_d_beta,
+                                            const void* d_obs, int64_t batch, void* d_actions, float* d_ranges_out,
+                                            void* stream) {
+    if (!p || !h_d_w || batch < 0) return AQ_EINVAL;
+    if (batch == 0) return AQ_OK;
+    if (!d_obs || !d_actions) return AQ_EINVAL;
+    const int nl = p->net.n_layers;
+    for (int l = 0; l < nl; ++l)
+        if (!h_d_w[l]) return AQ_EINVAL;
+    hipStream_t st = as_stream(stream);
+    aq_status s = ensure_f32(p, batch);
+    if (s != AQ_OK) return s;
+    const int in_u8 = p->net.in_type == AQ_IN_U8;
+    if (d_ranges_out) {
+        s = launch_init_keys(p->keys, nl, st);
+        if (s != AQ_OK) return s;
+        const LayerBuf& b0 = p->L[0];
+        s = launch_minmax_keys(d_obs, in_u8, batch * (int64_t)b0.d.in_h * b0.d.in_w * b0.d.in_c, p->keys, st);
+        if (s != AQ_OK) return s;
+    }
+    for (int l = 0; l < nl; ++l) {
+        const LayerBuf& b = p->L[l];
+        Fp32Layer L{};
+        L.w = h_d_w[l];
+        L.b = h_d_b ? h_d_b[l] : nullptr;
+        L.gamma = h_d_gamma ? h_d_gamma[l] : nullptr;
+        L.beta = h_d_beta ? h_d_beta[l] : nullptr;
+        L.K = b.K;
+        L.N = b.N;
+        L.act = b.d.act;
+        L.in_h = b.d.in_h;
+        L.in_w = b.d.in_w;
+        L.in_c = b.d.in_c;
+        L.kh = b.d.kh;
+        L.kw = b.d.kw;
+        L.stride = b.d.stride;
+        L.oh = b.oh;
+        L.ow = b.ow;
+        const int64_t rows_l = batch * b.oh * b.ow;
+        const bool last = l == nl - 1;
+        const void* in = l == 0 ? d_obs : (const void*)p->act_f32[(l - 1) & 1];
+        float* out = p->act_f32[l & 1];
+        s = launch_fp32_layer(L, in, l == 0 ? in_u8 : 0, out, rows_l, !last && b.d.act == AQ_ACT_RELU, st);
+        if (s != AQ_OK) return s;
+        if (!last && b.d.act == AQ_ACT_LN_TANH) {
+            s = launch_fp32_ln_tanh(out, rows_l, b.N, L.gamma, L.beta, p->net.ln_eps, st);
+            if (s != AQ_OK) return s;
+        }
+        if (!last && d_ranges_out) {
+            s = launch_minmax_keys(out, 0, rows_l * b.N, p->keys + 2 * (l + 1), st);
+            if (s != AQ_OK) return s;
+        }
+        if (last) {
+            s = launch_fp32_head(out, rows_l, b.N, p->net.head, d_actions, st);
+            if (s != AQ_OK) return s;
+        }
+    }
+    if (d_ranges_out) {
+        s = launch_keys_to_ranges(p->keys, 2 * nl, d_ranges_out, st);
+        if (s != AQ_OK) return s;
+    }
+    return AQ_OK;
+}

@@ -1,0 +1,89 @@
+// Shared device/host declarations of the ActorQ HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "actorq.h"
+
+namespace aq {
+
+constexpr int kWave = 64;
+constexpr int kTile = 32;  // MFMA tile edge (features and batch rows); one k-step is 32 bytes
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// (scale, zero-point) of one activation tensor, produced on the device by the quantizer block.
+struct ActQ {
+    float s;
+    int32_t z;
+};
+
+// Activation ranges travel to the device as a kernel argument (no host->device copy).
+struct RangesArg {
+    float lo[AQ_MAX_LAYERS];
+    float hi[AQ_MAX_LAYERS];
+};
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// round-half-even, clamped in float first so that huge values and NaN are defined
+// (anything not >= lo, NaN included, gives lo) -- Sec. 3.2's round(W / delta) with saturation.
+__device__ __forceinline__ int rint_clamp(float v, int lo, int hi) {
+    float r = rintf(v);
+    if (!(r >= (float)lo)) return lo;
+    if (r > (float)hi) return hi;
+    return (int)r;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ int wave_sum_i32(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ int wave_or_i32(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v |= __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Device status bits kept in the handle (sticky until the next aq_quantize_params).
+constexpr int kStatNonFinite = 1;
+constexpr int kStatRange = 2;
+
+// Per-layer descriptor handed to the forward kernels by value.
+struct LayerDev {
+    const int8_t* wp;          // packed signed-domain weights [NT][KS][64 lanes][16 bytes]
+    const int32_t* bias_fold;  // [N_pad] integer bias with the zero-point terms folded in
+    const int32_t* M0;         // [N_pad] requantization multipliers (Q31, normalised)
+    const int32_t* rshift;     // [N_pad] requantization right shifts
+    const float* m;            // [N_pad] s_in * s_w[n]
+    const float* gamma;        // [N_pad] LayerNorm gain / offset (LN layers)
+    const float* beta;
+    const int32_t* z_w;        // [N_pad] weight zero-points (unsigned domain)
+    int32_t* tap_acc;
+    uint8_t* tap_act;
+    float* tap_ln;
+    int K, N, KS, NT;
+    int act;
+    // conv geometry (per-layer kernel only); FC: all 1
+    int in_h, in_w, in_c, kh, kw, stride, oh, ow;
+};
+
+}  // namespace aq
+
+#define AQ_HIP_CHECK(expr)                        \
+    do {                                          \
+        hipError_t e_ = (expr);                   \
+        if (e_ != hipSuccess) return AQ_EHIP;     \
+    } while (0)

@@ -1,0 +1,69 @@
+// Host-side launchers of the HIP kernels (internal to the library).
+#pragma once
+#include "common.hpp"
+
+namespace aq {
+
+// ---- quantizer block (quantize.hip)
+aq_status launch_fill_u32(uint32_t* p, int n, uint32_t v, hipStream_t st);
+aq_status launch_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int wscheme, float qdenom,
+                                 void* d_codes, float* d_scale, int32_t* d_zp, uint32_t* d_ws, hipStream_t st);
+aq_status launch_quantize_layer(const float* d_w, int N, int K, int KS, int wscheme, float qdenom, uint32_t* d_mm,
+                                int8_t* wp, float* s_w, int32_t* z_w, int32_t* rowsum, int* status, hipStream_t st);
+aq_status launch_unpack_weights(const int8_t* wp, int N, int K, int KS, int asym, uint8_t* codes, hipStream_t st);
+aq_status launch_act_qparams(const RangesArg& r, int n, int in_u8, float qdenom, ActQ* actq, hipStream_t st);
+aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym, const float* s_w,
+                              const int32_t* z_w, const float* bias, const int32_t* rowsum, int N, int K, float* m,
+                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int* status,
+                              hipStream_t st);
+
+// ---- 8-bit forward (forward_int8.hip)
+struct FwdArgs {
+    LayerDev L[AQ_MAX_LAYERS];
+    int n_layers;
+    int head;
+    int in_u8;
+    int asym;
+    float ln_eps;
+    const void* obs;
+    int64_t batch;
+    const ActQ* actq;
+    void* actions;
+    uint8_t* tap_a0;
+    float* tap_y;
+    int ld;  // LDS row stride of the fused kernel, bytes
+};
+
+// whole-network fused MLP kernel; returns AQ_ESHAPE when the network does not fit it
+bool fused_mlp_supported(const FwdArgs& a, int* rows_per_wg_out, size_t* lds_bytes_out);
+aq_status launch_fused_mlp(const FwdArgs& a, hipStream_t st);
+
+// one launch per layer (FC and implicit-GEMM convolution), activations in global memory
+struct LayerIO {
+    const void* in;   // layer 0: observations (fp32 or uint8); else int8 signed-domain [rows][K]
+    int8_t* out;      // hidden layers: int8 signed-domain [rows][N] (row stride N)
+    float* ln_x;      // LN layers: fp32 scratch [rows][N]
+};
+aq_status launch_layer_int8(const FwdArgs& a, int layer, const LayerIO& io, hipStream_t st);
+aq_status launch_ln_tanh_rows(const FwdArgs& a, int layer, const float* x, int8_t* out, int64_t rows, hipStream_t st);
+aq_status launch_head_rows(const float* y, int64_t rows, int N, int head, void* actions, hipStream_t st);
+
+// ---- fp32 actor (forward_fp32.hip)
+struct Fp32Layer {
+    const float* w;
+    const float* b;
+    const float* gamma;
+    const float* beta;
+    int K, N, act;
+    int in_h, in_w, in_c, kh, kw, stride, oh, ow;
+};
+aq_status launch_fp32_layer(const Fp32Layer& L, const void* in, int in_u8, float* out, int64_t rows, int relu,
+                            hipStream_t st);
+aq_status launch_fp32_ln_tanh(float* x, int64_t rows, int N, const float* gamma, const float* beta, float eps,
+                              hipStream_t st);
+aq_status launch_fp32_head(const float* y, int64_t rows, int N, int head, void* actions, hipStream_t st);
+aq_status launch_init_keys(uint32_t* keys, int n_pairs, hipStream_t st);
+aq_status launch_minmax_keys(const void* x, int is_u8, int64_t n, uint32_t* keys, hipStream_t st);
+aq_status launch_keys_to_ranges(const uint32_t* keys, int n, float* out, hipStream_t st);
+
+}  // namespace aq

@@ -1,0 +1,423 @@
+// Quantizer block (Sec. 3.1, Sec. 3.2): fp32 weights -> 8-bit codes + scales + integer layer constants.
+//
+// The weight passes are HBM-bandwidth bound (4 bytes read + 1 byte written per parameter);
+// they are written as coalesced float4 streams with wavefront-shuffle reductions.  A whole
+// output channel is kept in registers between the range reduction and the rounding, so a
+// per-channel tensor is read from HBM exactly once.
+#include "kernels.hpp"
+
+#include <float.h>
+
+namespace aq {
+
+// ---------------------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------------------
+__global__ void k_fill_u32(uint32_t* p, int n, uint32_t v) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+__device__ __forceinline__ bool finite_f(float v) { return fabsf(v) <= FLT_MAX; }
+
+// Sec. 3.2: delta = (|min(W,0)| + |max(W,0)|) / D ; zero-point z = round(-lo / delta).
+__device__ __forceinline__ void asym_qparams(float hi, float nlo, float qdenom, float& s, int& z) {
+    float lo = -nlo;
+    s = (hi - lo) / qdenom;
+    if (hi == lo) s = 1.0f;
+    z = rint_clamp(-lo / s, 0, 255);
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-tensor range: hi = max(W, 0), nlo = max(-W, 0).  Both are non-negative floats, whose bit
+// patterns order like unsigned integers, so the grid-wide reduction is one atomicMax each.
+// mm[0] = hi bits, mm[1] = nlo bits, mm[2] = status flag; mm must be zero before the launch.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_range_nonneg(const float4* __restrict__ w4, int64_t n4,
+                                                      const float* __restrict__ w, int64_t n,
+                                                      uint32_t* __restrict__ mm) {
+    float hi = 0.0f, nlo = 0.0f;
+    int bad = 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 v = w4[i];
+        float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bad |= !finite_f(e[j]);
+            hi = e[j] > hi ? e[j] : hi;
+            float t = -e[j];
+            nlo = t > nlo ? t : nlo;
+        }
+    }
+    // scalar tail (tensor length not a multiple of 4)
+    for (int64_t i = n4 * 4 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        float e = w[i];
+        bad |= !finite_f(e);
+        hi = e > hi ? e : hi;
+        float t = -e;
+        nlo = t > nlo ? t : nlo;
+    }
+    hi = wave_max(hi);
+    nlo = wave_max(nlo);
+    bad = wave_or_i32(bad);
+    __shared__ float s_hi[4], s_nlo[4];
+    __shared__ int s_bad[4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) {
+        s_hi[wv] = hi;
+        s_nlo[wv] = nlo;
+        s_bad[wv] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < 4; ++i) {
+            hi = fmaxf(hi, s_hi[i]);
+            nlo = fmaxf(nlo, s_nlo[i]);
+            bad |= s_bad[i];
+        }
+        atomicMax(&mm[0], __float_as_uint(hi));
+        atomicMax(&mm[1], __float_as_uint(nlo));
+        if (bad) atomicOr(&mm[2], 1u);
+    }
+}
+
+// per-tensor asymmetric codes, canonical order, 4 per thread and iteration
+__global__ __launch_bounds__(256) void k_quant_asym_flat(const float4* __restrict__ w4, int64_t n4,
+                                                         const uint32_t* __restrict__ mm, float qdenom,
+                                                         uint32_t* __restrict__ codes, float* __restrict__ scale,
+                                                         int32_t* __restrict__ zp) {
+    float s;
+    int z;
+    asym_qparams(__uint_as_float(mm[0]), __uint_as_float(mm[1]), qdenom, s, z);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        scale[0] = s;
+        zp[0] = z;
+    }
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 v = w4[i];
+        uint32_t q0 = rint_clamp(v.x / s, -z, 255 - z) + z;
+        uint32_t q1 = rint_clamp(v.y / s, -z, 255 - z) + z;
+        uint32_t q2 = rint_clamp(v.z / s, -z, 255 - z) + z;
+        uint32_t q3 = rint_clamp(v.w / s, -z, 255 - z) + z;
+        codes[i] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+    }
+}
+
+// per-channel symmetric codes, canonical order: one wavefront per row, the row lives in
+// registers (R float4 per lane) between the |w| reduction and the rounding.
+template <int R>
+__global__ __launch_bounds__(256) void k_quant_sym_rows_flat(const float4* __restrict__ w4, int64_t rows, int cols4,
+                                                             uint32_t* __restrict__ codes, float* __restrict__ scale,
+                                                             int32_t* __restrict__ zp, uint32_t* __restrict__ mm) {
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float4* src = w4 + row * cols4;
+    float4 v[R];
+    float amax = 0.0f;
+    int bad = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int c = lane + 64 * r;
+        v[r] = c < cols4 ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+        float a0 = fabsf(v[r].x), a1 = fabsf(v[r].y), a2 = fabsf(v[r].z), a3 = fabsf(v[r].w);
+        bad |= !(a0 <= FLT_MAX) | !(a1 <= FLT_MAX) | !(a2 <= FLT_MAX) | !(a3 <= FLT_MAX);
+        amax = fmaxf(fmaxf(amax, fmaxf(a0, a1)), fmaxf(a2, a3));
+    }
+    amax = wave_max(amax);
+    bad = wave_or_i32(bad);
+    float s = amax / 127.0f;
+    if (amax == 0.0f) s = 1.0f;
+    if (lane == 0) {
+        scale[row] = s;
+        zp[row] = 0;
+        if (bad) atomicOr(&mm[2], 1u);
+    }
+    uint32_t* dst = codes + row * cols4;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int c = lane + 64 * r;
+        if (c < cols4) {
+            uint32_t q0 = (uint32_t)rint_clamp(v[r].x / s, -127, 127) & 255u;
+            uint32_t q1 = (uint32_t)rint_clamp(v[r].y / s, -127, 127) & 255u;
+            uint32_t q2 = (uint32_t)rint_clamp(v[r].z / s, -127, 127) & 255u;
+            uint32_t q3 = (uint32_t)rint_clamp(v[r].w / s, -127, 127) & 255u;
+            dst[c] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+        }
+    }
+}
+
+// rows too long for the register-resident kernel: one workgroup per row, the row is read twice
+// (the second read comes from cache for any realistic channel length).
+__global__ __launch_bounds__(256) void k_quant_sym_rows_long(const float4* __restrict__ w4, int64_t rows, int cols4,
+                                                             uint32_t* __restrict__ codes, float* __restrict__ scale,
+                                                             int32_t* __restrict__ zp, uint32_t* __restrict__ mm) {
+    const int64_t row = blockIdx.x;
+    const float4* src = w4 + row * cols4;
+    float amax = 0.0f;
+    int bad = 0;
+    for (int c = threadIdx.x; c < cols4; c += 256) {
+        float4 v = src[c];
+        float a0 = fabsf(v.x), a1 = fabsf(v.y), a2 = fabsf(v.z), a3 = fabsf(v.w);
+        bad |= !(a0 <= FLT_MAX) | !(a1 <= FLT_MAX) | !(a2 <= FLT_MAX) | !(a3 <= FLT_MAX);
+        amax = fmaxf(fmaxf(amax, fmaxf(a0, a1)), fmaxf(a2, a3));
+    }
+    amax = wave_max(amax);
+    bad = wave_or_i32(bad);
+    __shared__ float s_max[4];
+    __shared__ int s_bad[4];
+    if ((threadIdx.x & 63) == 0) {
+        s_max[threadIdx.x >> 6] = amax;
+        s_bad[threadIdx.x >> 6] = bad;
+    }
+    __syncthreads();
+    amax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+    bad = s_bad[0] | s_bad[1] | s_bad[2] | s_bad[3];
+    float s = amax / 127.0f;
+    if (amax == 0.0f) s = 1.0f;
+    if (threadIdx.x == 0) {
+        scale[row] = s;
+        zp[row] = 0;
+        if (bad) atomicOr(&mm[2], 1u);
+    }
+    uint32_t* dst = codes + row * cols4;
+    for (int c = threadIdx.x; c < cols4; c += 256) {
+        float4 v = src[c];
+        uint32_t q0 = (uint32_t)rint_clamp(v.x / s, -127, 127) & 255u;
+        uint32_t q1 = (uint32_t)rint_clamp(v.y / s, -127, 127) & 255u;
+        uint32_t q2 = (uint32_t)rint_clamp(v.z / s, -127, 127) & 255u;
+        uint32_t q3 = (uint32_t)rint_clamp(v.w / s, -127, 127) & 255u;
+        dst[c] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Policy weights: one wavefront per output channel n of W[N][K]; codes are written in the
+// signed domain (unsigned codes minus 128; symmetric codes as they are) straight into the
+// MFMA operand order used by the forward kernels:
+//   tile (nt = n / 32, ks = k / 32) is 1 KiB: lane = n % 32 + 32 * ((k % 32) / 16), byte = k % 16.
+// Also produced per channel: scale, zero-point, and the sum of the signed-domain codes (needed to
+// fold the activation zero-point into the integer bias).
+// ---------------------------------------------------------------------------------------------
+template <bool SYM>
+__global__ __launch_bounds__(256) void k_quant_rows_packed(const float* __restrict__ w, int N, int K, int KS,
+                                                           float qdenom, const uint32_t* __restrict__ mm,
+                                                           int8_t* __restrict__ wp, float* __restrict__ s_w,
+                                                           int32_t* __restrict__ z_w, int32_t* __restrict__ rowsum,
+                                                           int* __restrict__ status) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;
+    const float* src = w + (int64_t)n * K;
+    float s;
+    int z = 0;
+    if (SYM) {
+        float amax = 0.0f;
+        int bad = 0;
+        for (int k = lane; k < K; k += 64) {
+            float a = fabsf(src[k]);
+            bad |= !(a <= FLT_MAX);
+            amax = fmaxf(amax, a);
+        }
+        amax = wave_max(amax);
+        bad = wave_or_i32(bad);
+        s = amax / 127.0f;
+        if (amax == 0.0f) s = 1.0f;
+        if (bad && lane == 0) atomicOr(status, kStatNonFinite);
+    } else {
+        asym_qparams(__uint_as_float(mm[0]), __uint_as_float(mm[1]), qdenom, s, z);
+        if (mm[2] && lane == 0) atomicOr(status, kStatNonFinite);
+    }
+    int8_t* tile_row = wp + ((int64_t)(n >> 5) * KS * 64 + (n & 31)) * 16;
+    int sum = 0;
+    for (int k = lane; k < K; k += 64) {
+        int q = SYM ? rint_clamp(src[k] / s, -127, 127) : rint_clamp(src[k] / s, -z, 255 - z) + z - 128;
+        sum += q;
+        tile_row[((int64_t)(k >> 5) * 64 + 32 * ((k & 31) >> 4)) * 16 + (k & 15)] = (int8_t)q;
+    }
+    sum = wave_sum_i32(sum);
+    if (lane == 0) {
+        s_w[n] = s;
+        z_w[n] = z;
+        rowsum[n] = sum;
+    }
+}
+
+// packed signed-domain weights -> canonical codes (the inverse permutation), for export
+__global__ void k_unpack_weights(const int8_t* __restrict__ wp, int N, int K, int KS, int asym,
+                                 uint8_t* __restrict__ codes) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)N * K) return;
+    int n = (int)(i / K), k = (int)(i % K);
+    int8_t v = wp[(((int64_t)(n >> 5) * KS + (k >> 5)) * 64 + (n & 31) + 32 * ((k & 31) >> 4)) * 16 + (k & 15)];
+    codes[i] = asym ? (uint8_t)((int)v + 128) : (uint8_t)v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// activation (scale, zero-point) from the supplied ranges: the same formula as for weights,
+// the range being extended to contain zero.
+// ---------------------------------------------------------------------------------------------
+__global__ void k_act_qparams(RangesArg r, int n, int in_u8, float qdenom, ActQ* __restrict__ actq) {
+    int i = threadIdx.x;
+    if (i >= n) return;
+    if (i == 0 && in_u8) {
+        actq[0].s = 1.0f;
+        actq[0].z = 0;
+        return;
+    }
+    float hi = r.hi[i] > 0.0f ? r.hi[i] : 0.0f;
+    float nlo = -r.lo[i] > 0.0f ? -r.lo[i] : 0.0f;
+    float s;
+    int z;
+    asym_qparams(hi, nlo, qdenom, s, z);
+    actq[i].s = s;
+    actq[i].z = z;
+}
+
+// ---------------------------------------------------------------------------------------------
+// per-channel layer constants (one thread per output channel):
+//   m[n]      = s_in * s_w[n]                                   (fp32)
+//   bias_q[n] = round(b[n] / (s_in * s_w[n]))                   (fp64, saturated)
+//   M[n]      = s_in * s_w[n] / s_out = f * 2^e, f in [0.5,1);  M0 = round(f * 2^31), r = 31 - e
+//   bias_fold = bias_q + zero-point terms of the signed-domain product:
+//       sum_k (a_u - z_a)(w_u - z_w) = sum_k a_s w_s - z_a' sum_k w_s - z_w' sum_k a_s + K z_a' z_w'
+//   with a_s = a_u - 128, z_a' = z_a - 128, and for unsigned weight codes w_s = w_u - 128,
+//   z_w' = z_w - 128 (symmetric codes: w_s = w, z_w' = 0).  The "- z_w' sum_k a_s" term depends on
+//   the batch row and is applied inside the forward kernel.
+// ---------------------------------------------------------------------------------------------
+__global__ void k_layer_consts(const ActQ* __restrict__ actq, int layer, int requant, int asym,
+                               const float* __restrict__ s_w, const int32_t* __restrict__ z_w,
+                               const float* __restrict__ bias, const int32_t* __restrict__ rowsum, int N, int K,
+                               float* __restrict__ m, int32_t* __restrict__ bias_q, int32_t* __restrict__ M0,
+                               int32_t* __restrict__ rshift, int32_t* __restrict__ bias_fold,
+                               int* __restrict__ status) {
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    const float s_in = actq[layer].s;
+    const int z_a = actq[layer].z;
+    m[n] = s_in * s_w[n];
+    double sw = (double)s_in * (double)s_w[n];
+    double bq = rint((double)(bias ? bias[n] : 0.0f) / sw);
+    if (!(bq >= -2147483647.0)) bq = -2147483647.0;
+    if (bq > 2147483647.0) bq = 2147483647.0;
+    int32_t bqi = (int32_t)bq;
+    bias_q[n] = bqi;
+    if (requant) {
+        double M = sw / (double)actq[layer + 1].s;
+        int e;
+        double f = frexp(M, &e);
+        long long q = llround(f * 2147483648.0);
+        if (q == 2147483648LL) {
+            q = 1073741824LL;
+            e += 1;
+        }
+        int r = 31 - e;
+        if (r < 1 || r > 62 || !(M > 0.0) || !(M <= DBL_MAX)) {
+            atomicOr(status, kStatRange);
+            q = 0;
+            r = 1;
+        }
+        M0[n] = (int32_t)q;
+        rshift[n] = r;
+    } else {
+        M0[n] = 0;
+        rshift[n] = 0;
+    }
+    const int za_s = z_a - 128;
+    const int zw_s = asym ? z_w[n] - 128 : 0;
+    bias_fold[n] = bqi - za_s * rowsum[n] + K * za_s * zw_s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// host launchers
+// ---------------------------------------------------------------------------------------------
+static int grid_for(int64_t work_items, int per_block, int cap) {
+    int64_t g = (work_items + per_block - 1) / per_block;
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+aq_status launch_fill_u32(uint32_t* p, int n, uint32_t v, hipStream_t st) {
+    hipLaunchKernelGGL(k_fill_u32, dim3((n + 255) / 256), dim3(256), 0, st, p, n, v);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
+aq_status launch_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int wscheme, float qdenom,
+                                 void* d_codes, float* d_scale, int32_t* d_zp, uint32_t* d_ws, hipStream_t st) {
+    const int64_t n = rows * cols;
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, d_ws, 16, 0u);
+    if (wscheme == AQ_W_TENSOR_ASYM_U8) {
+        const int64_t n4 = n / 4;
+        // enough workgroups to keep every CU's memory pipeline full, few enough that the
+        // one-atomic-per-block reduction stays negligible
+        int g = grid_for(n4, 256 * 4, 2048);
+        hipLaunchKernelGGL(k_range_nonneg, dim3(g), dim3(256), 0, st, (const float4*)d_w, n4, d_w, n, d_ws);
+        int g2 = grid_for(n4, 256 * 2, 4096);
+        hipLaunchKernelGGL(k_quant_asym_flat, dim3(g2), dim3(256), 0, st, (const float4*)d_w, n4, d_ws, qdenom,
+                           (uint32_t*)d_codes, d_scale, d_zp);
+    } else {
+        const int cols4 = (int)(cols / 4);
+        const int g = (int)((rows + 3) / 4);
+        const float4* w4 = (const float4*)d_w;
+        uint32_t* c4 = (uint32_t*)d_codes;
+#define AQ_ROWS_FLAT(R)                                                                                         \
+    hipLaunchKernelGGL(k_quant_sym_rows_flat<R>, dim3(g), dim3(256), 0, st, w4, rows, cols4, c4, d_scale, d_zp, \
+                       d_ws)
+        if (cols4 <= 64) AQ_ROWS_FLAT(1);
+        else if (cols4 <= 128) AQ_ROWS_FLAT(2);
+        else if (cols4 <= 256) AQ_ROWS_FLAT(4);
+        else if (cols4 <= 512) AQ_ROWS_FLAT(8);
+        else if (cols4 <= 1024) AQ_ROWS_FLAT(16);
+        else
+            hipLaunchKernelGGL(k_quant_sym_rows_long, dim3((unsigned)rows), dim3(256), 0, st, w4, rows, cols4, c4,
+                               d_scale, d_zp, d_ws);
+#undef AQ_ROWS_FLAT
+    }
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
+aq_status launch_quantize_layer(const float* d_w, int N, int K, int KS, int wscheme, float qdenom, uint32_t* d_mm,
+                                int8_t* wp, float* s_w, int32_t* z_w, int32_t* rowsum, int* status,
+                                hipStream_t st) {
+    const int g = (N + 3) / 4;
+    if (wscheme == AQ_W_TENSOR_ASYM_U8) {
+        const int64_t n = (int64_t)N * K;
+        // weights of a policy layer are small; the vector path needs 16-byte alignment only
+        const int64_t n4 = n / 4;
+        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, d_mm, 4, 0u);
+        hipLaunchKernelGGL(k_range_nonneg, dim3(grid_for(n4 + 1, 256, 1024)), dim3(256), 0, st, (const float4*)d_w,
+                           n4, d_w, n, d_mm);
+        hipLaunchKernelGGL(k_quant_rows_packed<false>, dim3(g), dim3(256), 0, st, d_w, N, K, KS, qdenom, d_mm, wp,
+                           s_w, z_w, rowsum, status);
+    } else {
+        hipLaunchKernelGGL(k_quant_rows_packed<true>, dim3(g), dim3(256), 0, st, d_w, N, K, KS, qdenom, d_mm, wp,
+                           s_w, z_w, rowsum, status);
+    }
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
+aq_status launch_unpack_weights(const int8_t* wp, int N, int K, int KS, int asym, uint8_t* codes, hipStream_t st) {
+    const int64_t n = (int64_t)N * K;
+    hipLaunchKernelGGL(k_unpack_weights, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, wp, N, K, KS, asym,
+                       codes);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
+aq_status launch_act_qparams(const RangesArg& r, int n, int in_u8, float qdenom, ActQ* actq, hipStream_t st) {
+    hipLaunchKernelGGL(k_act_qparams, dim3(1), dim3(64), 0, st, r, n, in_u8, qdenom, actq);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
+aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym, const float* s_w,
+                              const int32_t* z_w, const float* bias, const int32_t* rowsum, int N, int K, float* m,
+                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int* status,
+                              hipStream_t st) {
+    hipLaunchKernelGGL(k_layer_consts, dim3((N + 255) / 256), dim3(256), 0, st, actq, layer, requant, asym, s_w, z_w,
+                       bias, rowsum, N, K, m, bias_q, M0, rshift, bias_fold, status);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
+}  // namespace aq

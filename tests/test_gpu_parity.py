@@ -1,0 +1,206 @@
+"""GPU parity tests: the HIP library, called through its C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import policy as O
+from paper_1910_01055_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+import gpu_util as U  # noqa: E402
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ quantizer block on one tensor
+@pytest.mark.parametrize("rows,cols", [(1, 4), (3, 8), (5, 260), (37, 132), (2048, 2048), (2, 4100), (1, 1 << 20)])
+@pytest.mark.parametrize("scheme", ["tensor_asym_u8", "channel_sym_s8"])
+def test_quantize_tensor(aq, rows, cols, scheme):
+    _say(f"quantize_tensor rows={rows} cols={cols} {scheme}")
+    w = synth.quant_tensor(rows * cols, seed=synth.QUANT_TENSOR_SEED + rows).reshape(rows, cols)
+    if rows >= 3:
+        w[1] = 0.0  # an all-zero channel
+    d_w = U.to_dev(w)
+    asym = scheme == "tensor_asym_u8"
+    codes = torch.zeros(rows, cols, dtype=torch.uint8 if asym else torch.int8, device=U.DEV)
+    ns = 1 if asym else rows
+    scale = torch.zeros(ns, dtype=torch.float32, device=U.DEV)
+    zp = torch.full((ns,), -1, dtype=torch.int32, device=U.DEV)
+    ws = torch.ones(16, dtype=torch.int32, device=U.DEV)
+    aq.quantize_tensor(d_w, rows, cols, scheme, 255, codes, scale, zp, ws)
+    torch.cuda.synchronize()
+    if asym:
+        s, z = O.c_qparams_asym(w)
+        ref = O.c_quantize_asym(w, s, z)
+        assert scale.cpu().numpy()[0].view(np.uint32) == np.float32(s).view(np.uint32) and int(zp[0]) == z
+    else:
+        ref, s = O.c_quantize_sym_rows(w)
+        assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32)) and not zp.cpu().numpy().any()
+    assert np.array_equal(codes.cpu().numpy(), ref)
+    assert int(ws[2]) == 0
+
+
+def test_quantize_tensor_literal_denominator_and_nonfinite(aq):
+    w = np.array([[-1, 0, 0.5, 1]], np.float32)
+    codes = torch.zeros(1, 4, dtype=torch.uint8, device=U.DEV)
+    scale = torch.zeros(1, dtype=torch.float32, device=U.DEV)
+    zp = torch.zeros(1, dtype=torch.int32, device=U.DEV)
+    ws = torch.zeros(16, dtype=torch.int32, device=U.DEV)
+    aq.quantize_tensor(U.to_dev(w), 1, 4, "tensor_asym_u8", 256, codes, scale, zp, ws)
+    assert codes.cpu().numpy().tolist() == [[0, 128, 192, 255]] and float(scale[0]) == 1 / 128 and int(zp[0]) == 128
+    for scheme in ("tensor_asym_u8", "channel_sym_s8"):
+        w = np.array([[0.5, np.nan, 1.0, 2.0]], np.float32)
+        aq.quantize_tensor(U.to_dev(w), 1, 4, scheme, 255, codes, scale, zp, ws)
+        torch.cuda.synchronize()
+        assert int(ws[2]) == 1
+    with pytest.raises(aq.AqError):
+        aq.quantize_tensor(U.to_dev(w), 1, 3, "tensor_asym_u8", 255, codes, scale, zp, ws)
+
+
+# ------------------------------------------------------------------ whole path, small batches, every stage
+def _nets():
+    fc, conv = synth.fc, synth.conv
+    return {
+        "cfg1": synth.net_config("cfg1"),
+        "cfg2": synth.net_config("cfg2"),
+        "odd_asym": synth.small_net([fc(17, 96, "relu"), fc(96, 40, "none"), fc(40, 6, "none")], head="linear",
+                                    wscheme="tensor_asym_u8"),
+        "odd_sym_ln": synth.small_net([fc(67, 200, "ln_tanh"), fc(200, 72, "relu"), fc(72, 21, "none")],
+                                      head="tanh"),
+        "argmax_mlp": synth.small_net([fc(33, 64, "relu"), fc(64, 18, "none")], head="argmax"),
+        "u8_mlp": synth.small_net([fc(48, 64, "relu"), fc(64, 5, "none")], head="tanh", in_type="u8"),
+        "literal256": synth.small_net([fc(17, 64, "relu"), fc(64, 6, "none")], head="tanh", qdenom=256,
+                                      wscheme="tensor_asym_u8"),
+        "conv_small": synth.small_net([conv(12, 12, 4, 16, 4, 4, 2, "relu"), conv(5, 5, 16, 32, 3, 3, 1, "relu"),
+                                       fc(288, 48, "relu"), fc(48, 5, "none")], head="argmax", in_type="u8",
+                                      init="he_normal"),
+        "conv_odd": synth.small_net([conv(9, 10, 3, 5, 3, 2, 2, "relu"), fc(100, 24, "none"), fc(24, 7, "none")],
+                                    head="tanh", in_type="u8", init="he_normal"),
+    }
+
+
+@pytest.mark.parametrize("name", list(_nets().keys()))
+@pytest.mark.parametrize("path", [0, 2])
+@pytest.mark.parametrize("batch", [1, 77, 300])
+def test_forward_every_stage(aq, name, path, batch):
+    _say(f"forward_every_stage {name} path={path} batch={batch}")
+    net = _nets()[name]
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs)
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    U.check_quantized_params(aq, P, pol, net)
+    P.policy_set_path(path)
+    for rep in range(2):  # twice: a racy LDS stage would show as a changing accumulator
+        actions, t = U.gpu_forward(P, net, obs)
+        U.compare_forward(net, pol, obs, actions, t)
+    # without taps the actions are the same
+    a2, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(a2, actions, equal_nan=True)
+    P.close()
+
+
+# ------------------------------------------------------------------ full sizes, launch configuration of the bench
+@pytest.mark.parametrize("name,batch,sample", [("cfg1", 256, None), ("cfg2", 4096, None), ("cfg3", 65536, 2048),
+                                               ("cfg3", 16, None), ("cfg5", 16384, 384), ("cfg4", 256, 64)])
+def test_forward_full_size(aq, name, batch, sample):
+    _say(f"forward_full_size {name} batch={batch}")
+    net = synth.net_config(name)
+    params = synth.make_params(net)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs[:min(batch, 512)])
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    U.check_quantized_params(aq, P, pol, net)
+    actions, t = U.gpu_forward(P, net, obs)
+    rows = None
+    if sample is not None:
+        rng = np.random.default_rng(5)
+        rows = np.unique(np.concatenate([[0, batch - 1], rng.integers(0, batch, sample)]))
+    flips = U.compare_forward(net, pol, obs, actions, t, rows)
+    _say(f"  LayerNorm code flips at rounding ties: {flips}")
+    # properties that hold at any size
+    if net["head"] == "tanh":
+        assert np.isfinite(actions).all() and np.abs(actions).max() <= 1.0
+    else:
+        assert actions.min() >= 0 and actions.max() < synth.action_dim(net)
+    P.close()
+
+
+# ------------------------------------------------------------------ fp32 actor and calibration
+@pytest.mark.parametrize("name,batch", [("cfg1", 256), ("cfg2", 300), ("cfg4", 8), ("cfg5", 96)])
+def test_forward_fp32(aq, name, batch):
+    _say(f"forward_fp32 {name} batch={batch}")
+    net = synth.net_config(name)
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol = O.OraclePolicy(net)
+    ref, ranges = pol.forward_fp32(params, obs)
+    P = aq.Policy(net)
+    w, b, g, be = U.upload_params(params)
+    A = synth.action_dim(net)
+    nl = len(net["layers"])
+    if net["head"] == "argmax":
+        actions = torch.zeros(batch, dtype=torch.int32, device=U.DEV)
+    else:
+        actions = torch.zeros(batch, A, dtype=torch.float32, device=U.DEV)
+    r = torch.zeros(2 * nl, dtype=torch.float32, device=U.DEV)
+    P.policy_forward_fp32(w, b, g, be, U.to_dev(obs), actions, r)
+    torch.cuda.synchronize()
+    got = actions.cpu().numpy()
+    if net["head"] == "argmax":
+        # an fp32 sum may reorder two nearly equal logits; require agreement wherever the oracle's margin is clear
+        assert (got == ref).mean() >= 0.99
+    else:
+        assert U.close(got, ref).all()
+    rr = r.cpu().numpy().reshape(nl, 2)
+    for i, (lo, hi) in enumerate(ranges):
+        assert abs(rr[i, 0] - lo) <= 1e-4 * abs(lo) + 1e-6 and abs(rr[i, 1] - hi) <= 1e-4 * abs(hi) + 1e-6
+    P.close()
+
+
+# ------------------------------------------------------------------ edge cases and error paths
+def test_edges(aq):
+    net = synth.net_config("cfg1")
+    params = synth.make_params(net)
+    obs = synth.make_obs(net, 4)
+    P = aq.Policy(net)
+    actions = torch.zeros(4, 6, dtype=torch.float32, device=U.DEV)
+    with pytest.raises(aq.AqError) as e:
+        P.policy_forward_int8(U.to_dev(obs), actions)
+    assert e.value.status == aq.ENOTQUANT
+    pol, ranges = U.make_oracle(net, params, obs)
+    d = U.upload_params(params)
+    P.quantize_params(d[0], d[1], d[2], d[3], ranges)
+    assert P.policy_status() == aq.OK
+    # empty batch: no-op
+    P.policy_forward_int8(torch.zeros(0, 17, device=U.DEV), torch.zeros(0, 6, device=U.DEV))
+    # observations far outside the calibrated range saturate, NaN takes code 0
+    wild = obs.copy()
+    wild[0, :] = 1e30
+    wild[1, :] = -1e30
+    wild[2, 0] = np.nan
+    a, t = U.gpu_forward(P, net, wild)
+    U.compare_forward(net, pol, wild, a, t)
+    # non-finite weights are reported
+    bad = [p["w"].copy() for p in params]
+    bad[1][3, 5] = np.inf
+    P.quantize_params([U.to_dev(x) for x in bad], d[1], d[2], d[3], ranges)
+    assert P.policy_status() == aq.ENONFINITE
+    P.close()
+    # all-zero weights: scale 1, codes 0, actions tanh(0) = 0
+    zero = [{"w": np.zeros_like(p["w"]), "b": np.zeros_like(p["b"])} for p in params]
+    pol0, r0 = U.make_oracle(net, zero, obs)
+    P0, _ = U.gpu_quantize(aq, net, zero, r0)
+    U.check_quantized_params(aq, P0, pol0, net)
+    a, t = U.gpu_forward(P0, net, obs)
+    U.compare_forward(net, pol0, obs, a, t)
+    assert not a.any()
+    P0.close()
+    # shapes that do not chain are refused
+    broken = synth.small_net([synth.fc(17, 32, "relu"), synth.fc(33, 6, "none")])
+    with pytest.raises(aq.AqError) as e:
+        aq.Policy(broken)
+    assert e.value.status == aq.ESHAPE
