@@ -35,6 +35,8 @@ struct aq_policy {
     int* status = nullptr;
     uint32_t* mm = nullptr;
     uint32_t* keys = nullptr;
+    NetDev h_net{};            // host copy of the device-resident network description
+    NetDev* d_net = nullptr;
     bool quantized = false;
     int path = 0;  // 0 auto, 1 fused only, 2 one launch per layer
     // activation scratch of the per-layer path and of the fp32 actor (grown on demand)
@@ -44,6 +46,31 @@ struct aq_policy {
     int64_t max_hidden_elems = 0;  // per sample, over hidden layer outputs
     int64_t max_out_elems = 0;     // per sample, over all layer outputs
 };
+
+static void fill_layer_dev(const aq_policy* p, int l, LayerDev& d) {
+    const LayerBuf& b = p->L[l];
+    d.wp = b.wp;
+    d.bias_fold = b.bias_fold;
+    d.M0 = b.M0;
+    d.rshift = b.rshift;
+    d.m = b.m;
+    d.gamma = b.gamma;
+    d.beta = b.beta;
+    d.z_w = b.z_w;
+    d.K = b.K;
+    d.N = b.N;
+    d.KS = b.KS;
+    d.NT = b.NT;
+    d.act = b.d.act;
+    d.in_h = b.d.in_h;
+    d.in_w = b.d.in_w;
+    d.in_c = b.d.in_c;
+    d.kh = b.d.kh;
+    d.kw = b.d.kw;
+    d.stride = b.d.stride;
+    d.oh = b.oh;
+    d.ow = b.ow;
+}
 
 static hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
@@ -144,6 +171,7 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     size_t off_status = take(256);
     size_t off_mm = take(256);
     size_t off_keys = take(sizeof(uint32_t) * 2 * (AQ_MAX_LAYERS + 1));
+    size_t off_net = take(sizeof(NetDev));
     if (hipMalloc(&p->slab, bytes) != hipSuccess) {
         delete p;
         return AQ_ENOMEM;
@@ -173,6 +201,19 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     p->status = (int*)(base + off_status);
     p->mm = (uint32_t*)(base + off_mm);
     p->keys = (uint32_t*)(base + off_keys);
+    p->d_net = (NetDev*)(base + off_net);
+    for (int l = 0; l < net->n_layers; ++l) fill_layer_dev(p, l, p->h_net.L[l]);
+    p->h_net.actq = p->actq;
+    p->h_net.n_layers = net->n_layers;
+    p->h_net.head = net->head;
+    p->h_net.in_u8 = net->in_type == AQ_IN_U8;
+    p->h_net.asym = net->wscheme == AQ_W_TENSOR_ASYM_U8;
+    p->h_net.ln_eps = net->ln_eps;
+    if (hipMemcpy(p->d_net, &p->h_net, sizeof(NetDev), hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(p->slab);
+        delete p;
+        return AQ_EHIP;
+    }
     *out = p;
     return AQ_OK;
 }
@@ -340,34 +381,6 @@ extern "C" aq_status aq_policy_export_act_qparams(const aq_policy* p, float* d_s
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
-static void fill_layer_dev(const aq_policy* p, int l, const aq_taps* taps, LayerDev& d) {
-    const LayerBuf& b = p->L[l];
-    d.wp = b.wp;
-    d.bias_fold = b.bias_fold;
-    d.M0 = b.M0;
-    d.rshift = b.rshift;
-    d.m = b.m;
-    d.gamma = b.gamma;
-    d.beta = b.beta;
-    d.z_w = b.z_w;
-    d.tap_acc = (taps && taps->acc) ? taps->acc[l] : nullptr;
-    d.tap_act = (taps && taps->act) ? taps->act[l] : nullptr;
-    d.tap_ln = (taps && taps->ln_t) ? taps->ln_t[l] : nullptr;
-    d.K = b.K;
-    d.N = b.N;
-    d.KS = b.KS;
-    d.NT = b.NT;
-    d.act = b.d.act;
-    d.in_h = b.d.in_h;
-    d.in_w = b.d.in_w;
-    d.in_c = b.d.in_c;
-    d.kh = b.d.kh;
-    d.kw = b.d.kw;
-    d.stride = b.d.stride;
-    d.oh = b.oh;
-    d.ow = b.ow;
-}
-
 extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
                                             const aq_taps* taps, void* stream) {
     if (!p || batch < 0) return AQ_EINVAL;
@@ -378,18 +391,20 @@ extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int
     hipStream_t st = as_stream(stream);
     const int nl = p->net.n_layers;
     FwdArgs a{};
-    for (int l = 0; l < nl; ++l) fill_layer_dev(p, l, taps, a.L[l]);
-    a.n_layers = nl;
-    a.head = p->net.head;
-    a.in_u8 = p->net.in_type == AQ_IN_U8;
-    a.asym = p->net.wscheme == AQ_W_TENSOR_ASYM_U8;
-    a.ln_eps = p->net.ln_eps;
-    a.obs = d_obs;
-    a.batch = batch;
-    a.actq = p->actq;
-    a.actions = d_actions;
-    a.tap_a0 = taps ? taps->a0 : nullptr;
-    a.tap_y = taps ? taps->y : nullptr;
+    a.net = p->h_net;
+    a.d_net = p->d_net;
+    a.c.obs = d_obs;
+    a.c.actions = d_actions;
+    a.c.batch = batch;
+    if (taps) {
+        for (int l = 0; l < nl; ++l) {
+            a.t.acc[l] = taps->acc ? taps->acc[l] : nullptr;
+            a.t.act[l] = taps->act ? taps->act[l] : nullptr;
+            a.t.ln[l] = taps->ln_t ? taps->ln_t[l] : nullptr;
+        }
+        a.t.a0 = taps->a0;
+        a.t.y = taps->y;
+    }
 
     int rows;
     size_t lds;
@@ -402,14 +417,13 @@ extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int
     if (s != AQ_OK) return s;
     s = ensure_f32(p, batch);
     if (s != AQ_OK) return s;
-    if (a.in_u8 && a.tap_a0) {
+    if (a.net.in_u8 && a.t.a0) {
         const LayerBuf& b0 = p->L[0];
         const size_t n = (size_t)batch * b0.d.in_h * b0.d.in_w * b0.d.in_c;
-        AQ_HIP_CHECK(hipMemcpyAsync(a.tap_a0, d_obs, n, hipMemcpyDeviceToDevice, st));
-        a.tap_a0 = nullptr;
+        AQ_HIP_CHECK(hipMemcpyAsync(a.t.a0, d_obs, n, hipMemcpyDeviceToDevice, st));
+        a.t.a0 = nullptr;
     }
-    float* ybuf = a.tap_y ? a.tap_y : p->act_f32[1];
-    a.tap_y = ybuf;
+    float* ybuf = a.t.y ? a.t.y : p->act_f32[1];
     for (int l = 0; l < nl; ++l) {
         const LayerBuf& b = p->L[l];
         const int64_t rows_l = batch * b.oh * b.ow;
@@ -417,6 +431,7 @@ extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int
         io.in = l == 0 ? d_obs : (const void*)p->act_i8[(l - 1) & 1];
         io.out = p->act_i8[l & 1];
         io.ln_x = p->act_f32[0];
+        io.y = ybuf;
         s = launch_layer_int8(a, l, io, st);
         if (s != AQ_OK) return s;
         if (l < nl - 1 && b.d.act == AQ_ACT_LN_TANH) {

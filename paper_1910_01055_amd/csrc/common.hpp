@@ -71,13 +71,46 @@ struct LayerDev {
     const float* gamma;        // [N_pad] LayerNorm gain / offset (LN layers)
     const float* beta;
     const int32_t* z_w;        // [N_pad] weight zero-points (unsigned domain)
-    int32_t* tap_acc;
-    uint8_t* tap_act;
-    float* tap_ln;
     int K, N, KS, NT;
     int act;
     // conv geometry (per-layer kernel only); FC: all 1
     int in_h, in_w, in_c, kh, kw, stride, oh, ow;
+};
+
+// The static description of a quantized policy, kept in DEVICE memory and read by the forward
+// kernels through one pointer: kernel arguments live in host-visible memory, and every cache line
+// of a large by-value argument costs a round trip over the host link on first touch.
+struct NetDev {
+    LayerDev L[AQ_MAX_LAYERS];
+    const ActQ* actq;
+    int n_layers;
+    int head;
+    int in_u8;
+    int asym;
+    float ln_eps;
+};
+
+// Per-call arguments (small, by value).
+struct CallArgs {
+    const void* obs;
+    void* actions;
+    int64_t batch;
+    int ld;     // fused kernel: LDS row stride, bytes
+    int cst_n;  // fused kernel: words per constant array in the LDS staging area
+};
+
+// Optional intermediate outputs (by value, only read by the kernels compiled with TAPS).
+struct TapArgs {
+    int32_t* acc[AQ_MAX_LAYERS];
+    uint8_t* act[AQ_MAX_LAYERS];
+    float* ln[AQ_MAX_LAYERS];
+    uint8_t* a0;
+    float* y;
+};
+struct LayerTaps {
+    int32_t* acc;
+    uint8_t* act;
+    float* ln;
 };
 
 }  // namespace aq

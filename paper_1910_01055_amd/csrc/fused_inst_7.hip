@@ -1,0 +1,8 @@
+// Explicit instantiation of one fused-MLP kernel variant (rows = 32 * 4, 1 feature tile(s) per wave,
+// per-tensor asymmetric weights), with and without intermediate taps.
+#include "fused_mlp.hpp"
+
+namespace aq {
+AQ_FUSED_INST(4, 1, true, false);
+AQ_FUSED_INST(4, 1, true, true);
+}  // namespace aq

@@ -1,0 +1,106 @@
+// Host side of the whole-network fused int8 MLP: decides whether a network fits the kernel, picks
+// rows per workgroup and feature tiles per wave, and dispatches to the compiled variant.
+#include "fused_mlp.hpp"
+
+namespace aq {
+
+AQ_FUSED_DECL(1, 1, false, false);
+AQ_FUSED_DECL(1, 1, false, true);
+AQ_FUSED_DECL(2, 1, false, false);
+AQ_FUSED_DECL(2, 1, false, true);
+AQ_FUSED_DECL(4, 1, false, false);
+AQ_FUSED_DECL(4, 1, false, true);
+AQ_FUSED_DECL(1, 4, false, false);
+AQ_FUSED_DECL(1, 4, false, true);
+AQ_FUSED_DECL(2, 4, false, false);
+AQ_FUSED_DECL(2, 4, false, true);
+AQ_FUSED_DECL(1, 1, true, false);
+AQ_FUSED_DECL(1, 1, true, true);
+AQ_FUSED_DECL(2, 1, true, false);
+AQ_FUSED_DECL(2, 1, true, true);
+AQ_FUSED_DECL(4, 1, true, false);
+AQ_FUSED_DECL(4, 1, true, true);
+
+namespace {
+struct Plan {
+    int mt, nb, ld, cst_n;
+    size_t lds;
+};
+
+bool make_plan(const FwdArgs& a, Plan* p) {
+    int maxw = 0, max_np = 0, max_nt = 0;
+    for (int l = 0; l < a.net.n_layers; ++l) {
+        const LayerDev& L = a.net.L[l];
+        if (L.kh != 1 || L.kw != 1 || L.in_h != 1 || L.in_w != 1) return false;
+        maxw = maxw > L.KS * 32 ? maxw : L.KS * 32;
+        if (l < a.net.n_layers - 1) maxw = maxw > L.NT * 32 ? maxw : L.NT * 32;
+        max_np = max_np > L.NT * 32 ? max_np : L.NT * 32;
+        max_nt = max_nt > L.NT ? max_nt : L.NT;
+    }
+    if (max_np > CST_MAXN) return false;
+    // the last layer's fp32 rows (NT * 32 floats) reuse an activation buffer
+    const int lastw = a.net.L[a.net.n_layers - 1].NT * 32 * 4;
+    maxw = maxw > lastw ? maxw : lastw;
+    p->ld = maxw + 16;
+    p->cst_n = max_np;
+    // feature tiles per wave: wide layers take 4 so that one pass of the 8 waves covers 32 tiles
+    p->nb = (max_nt >= 32 && !a.net.asym) ? 4 : 1;
+    for (int l = 0; l < a.net.n_layers - 1; ++l)  // LayerNorm needs its whole row resident in one pass
+        if (a.net.L[l].act == AQ_ACT_LN_TANH && (a.net.L[l].NT + p->nb - 1) / p->nb > FW) return false;
+    // rows per workgroup: enough workgroups to cover the 256 CUs first, more rows per workgroup
+    // (fewer weight re-reads from L2) once the batch is large enough
+    int mt = 1;
+    if (a.c.batch >= 256 * 64) mt = 2;
+    if (a.c.batch >= 512 * 128 && p->nb == 1) mt = 4;
+    for (; mt >= 1; mt >>= 1) {
+        p->lds = fused_lds_bytes(32 * mt, p->ld, p->cst_n);
+        if (p->lds <= 160 * 1024) {
+            p->mt = mt;
+            return true;
+        }
+    }
+    return false;
+}
+}  // namespace
+
+bool any_taps(const FwdArgs& a) {
+    if (a.t.a0 || a.t.y) return true;
+    for (int l = 0; l < a.net.n_layers; ++l)
+        if (a.t.acc[l] || a.t.act[l] || a.t.ln[l]) return true;
+    return false;
+}
+
+bool fused_mlp_supported(const FwdArgs& a, int* rows_out, size_t* lds_out) {
+    Plan p;
+    if (!make_plan(a, &p)) return false;
+    *rows_out = 32 * p.mt;
+    *lds_out = p.lds;
+    return true;
+}
+
+aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
+    Plan p;
+    if (!make_plan(a_in, &p)) return AQ_ESHAPE;
+    FwdArgs a = a_in;
+    a.c.ld = p.ld;
+    a.c.cst_n = p.cst_n;
+    const bool tp = any_taps(a);
+    const bool as = a.net.asym != 0;
+#define AQ_GO(MT, NB, AS) \
+    return tp ? launch_fused_t<MT, NB, AS, true>(a, p.lds, st) : launch_fused_t<MT, NB, AS, false>(a, p.lds, st)
+    if (p.nb == 4) {
+        if (p.mt == 1) AQ_GO(1, 4, false);
+        AQ_GO(2, 4, false);
+    }
+    if (as) {
+        if (p.mt == 1) AQ_GO(1, 1, true);
+        if (p.mt == 2) AQ_GO(2, 1, true);
+        AQ_GO(4, 1, true);
+    }
+    if (p.mt == 1) AQ_GO(1, 1, false);
+    if (p.mt == 2) AQ_GO(2, 1, false);
+    AQ_GO(4, 1, false);
+#undef AQ_GO
+}
+
+}  // namespace aq

@@ -1,0 +1,207 @@
+// Actor inference on the 8-bit policy (Sec. 3.1; quantized weights and activations, Sec. 3.2).
+//
+// Arithmetic: activations are unsigned 8-bit codes a_u with zero-point z_a, weights 8-bit codes.
+// The int8 MFMA is signed x signed, so both operands live in the signed domain (a_s = a_u - 128,
+// unsigned weight codes likewise); the zero-point terms of
+//   sum_k (a_u - z_a)(w_u - z_w) = sum_k a_s w_s - z_a' sum_k w_s - z_w' sum_k a_s + K z_a' z_w'
+// are folded into a per-channel integer bias at quantize time, except "- z_w' sum_k a_s", which is
+// applied here (per-tensor asymmetric weights only; the row sums come from one extra MFMA against
+// an all-ones operand).  The canonical accumulator that leaves the MFMA + bias is therefore the
+// exact integer sum_k (a_u - z_a)(w_u - z_w) + bias_q.
+//
+// MFMA mapping: v_mfma_i32_32x32x32_i8 computes D[32x32] += A[32x32] * B[32x32].  Weights are
+// the A operand (rows = output features), batch rows are the B operand (columns), so that one
+// lane owns one batch row and four consecutive output features per register quad: the requantized
+// bytes of a quad pack into one 32-bit word of the next layer's row-major activation row.
+//   A lane l: row  n = l % 32, bytes k = 16 * (l / 32) .. +15 of the 32-byte k-step
+//   B lane l: col  m = l % 32, same bytes
+//   D reg 4j+i of lane l: row n = 8 j + 4 (l / 32) + i, col m = l % 32
+#pragma once
+#include <type_traits>
+
+#include "kernels.hpp"
+
+namespace aq {
+
+
+// compile-time loop: accumulator tiles are register arrays and must only ever be indexed by constants
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+__device__ __forceinline__ v16i zero16() {
+    v16i z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0;
+    return z;
+}
+
+// tanh for hidden activations that are re-quantized to 8 bits right away: 1 - 2 / (e^{2|x|} + 1)
+// on the hardware exp2 / rcp units; absolute error about 2e-7.
+__device__ __forceinline__ float tanh_fast(float x) {
+    float ax = fabsf(x);
+    float e = __builtin_amdgcn_exp2f(fminf(ax, 20.0f) * 2.885390081777927f);  // e^{2|x|}
+    float t = 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
+    return copysignf(t, x);
+}
+
+// tanh for the action head: odd polynomial near zero (no cancellation), exponential form elsewhere;
+// relative error below 1e-6.
+__device__ __forceinline__ float tanh_head(float x) {
+    float ax = fabsf(x);
+    if (ax < 0.5f) {
+        float u = x * x;
+        // Taylor series of tanh(x)/x in u = x^2 up to u^6 (remainder < 2e-7 relative at |x| = 0.5)
+        float p = 0.0035921280f;        // 21844/6081075
+        p = fmaf(p, u, -0.0088632355f);  // -1382/155925
+        p = fmaf(p, u, 0.0218694885f);   // 62/2835
+        p = fmaf(p, u, -0.0539682540f);  // -17/315
+        p = fmaf(p, u, 0.1333333333f);   // 2/15
+        p = fmaf(p, u, -0.3333333333f);  // -1/3
+        return fmaf(x * u, p, x);
+    }
+    float e = expf(2.0f * fminf(ax, 20.0f));
+    float t = 1.0f - 2.0f / (e + 1.0f);
+    return copysignf(t, x);
+}
+
+// ---------------------------------------------------------------------------------------------
+// MFMA core: accumulates NB feature tiles x MT row tiles over k-steps [ks_begin, ks_end).
+// Weights stream global -> registers (already in operand order), activations come from LDS
+// (row-major int8, row stride ld, column 0 = k-step ks_lds0).
+// ---------------------------------------------------------------------------------------------
+// PF = weight k-steps in flight per wave (global -> register prefetch depth)
+template <int MT, int NB, bool ASYM, int PF>
+__device__ __forceinline__ void mma_block(const v4i* (&wptr)[NB], const int8_t* xs, int ld, int ks_begin,
+                                          int ks_end, int ks_lds0, v16i (&acc)[NB][MT], v16i (&rs)[MT], int lane) {
+    v4i wreg[PF][NB];
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+        if (ks_begin + p < ks_end) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) wreg[p][nb] = wptr[nb][(int64_t)(ks_begin + p) * 64];
+        }
+    const int8_t* xrow = xs + (lane & 31) * ld + (lane >> 5) * 16;
+    v4i ones;
+    ones[0] = ones[1] = ones[2] = ones[3] = 0x01010101;
+    for (int ks = ks_begin; ks < ks_end; ks += PF) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            const int k = ks + p;
+            if (k < ks_end) {
+                v4i xf[MT];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    xf[mt] = *(const v4i*)(xrow + mt * 32 * ld + (k - ks_lds0) * 32);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        acc[nb][mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[p][nb], xf[mt], acc[nb][mt], 0, 0, 0);
+                if (ASYM) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        rs[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, xf[mt], rs[mt], 0, 0, 0);
+                }
+                if (k + PF < ks_end) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) wreg[p][nb] = wptr[nb][(int64_t)(k + PF) * 64];
+                }
+            }
+        }
+    }
+}
+
+// where an epilogue reads the per-channel constants from (global memory or a copy staged in LDS)
+struct CPtrs {
+    const int32_t* bias_fold;
+    const int32_t* M0;
+    const int32_t* rshift;
+    const float* m;
+};
+__device__ __forceinline__ CPtrs global_consts(const LayerDev& L) { return CPtrs{L.bias_fold, L.M0, L.rshift, L.m}; }
+
+// requantize one accumulator: v = (acc * M0 + 2^(r-1)) >> r, code = clamp(v + z_out, lo, 255)
+__device__ __forceinline__ int requant_code(int acc, int M0, int r, int z_out, int lo) {
+    long long p = (long long)acc * (long long)M0 + ((1LL << r) >> 1);
+    long long v = (p >> r) + z_out;
+    v = v < lo ? lo : v;
+    v = v > 255 ? 255 : v;
+    return (int)v;
+}
+
+// canonical accumulator of one register quad: MFMA sum + folded bias (- z_w' * row sum of a_s)
+template <bool ASYM, bool TAPS>
+__device__ __forceinline__ void quad_acc(const LayerDev& L, const LayerTaps& T, const CPtrs& C, const v16i& c, int j, int n0, int rs0, int zw_s,
+                                         int64_t row, bool row_ok, int (&val)[4]) {
+    const int4 bf = *(const int4*)(C.bias_fold + n0);
+    const int bfv[4] = {bf.x, bf.y, bf.z, bf.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        val[i] = c[4 * j + i] + bfv[i];
+        if (ASYM) val[i] -= zw_s * rs0;
+        if (TAPS) {
+            if (T.acc && row_ok && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val[i];
+        }
+    }
+}
+
+// Hidden layer: requantize (+ReLU through the clamp) one 32x32 tile and store the codes, signed
+// domain, four per 32-bit word (packed) or bytewise, for features below n_store.
+template <bool ASYM, bool TAPS>
+__device__ __forceinline__ void epi_hidden_tile(const LayerDev& L, const LayerTaps& T, const CPtrs& C, const v16i& c, int rs0, int zw_s, int nt, int g,
+                                                int64_t row, bool row_ok, int z_out, int lo, int8_t* out_row,
+                                                bool packed, int n_store) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int n0 = nt * 32 + 8 * j + 4 * g;
+        int val[4];
+        quad_acc<ASYM, TAPS>(L, T, C, c, j, n0, rs0, zw_s, row, row_ok, val);
+        const int4 M = *(const int4*)(C.M0 + n0);
+        const int4 R = *(const int4*)(C.rshift + n0);
+        const int Mv[4] = {M.x, M.y, M.z, M.w}, Rv[4] = {R.x, R.y, R.z, R.w};
+        uint32_t pack = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int code = requant_code(val[i], Mv[i], Rv[i], z_out, lo);
+            if (n0 + i >= L.N) code = 128;  // padding features are zero in the signed domain
+            if (TAPS) {
+                if (T.act && row_ok && n0 + i < L.N) T.act[row * L.N + n0 + i] = (uint8_t)code;
+            }
+            pack |= (uint32_t)((code ^ 0x80) & 255) << (8 * i);
+        }
+        if (out_row) {
+            if (packed) {
+                if (n0 < n_store) *(uint32_t*)(out_row + n0) = pack;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (n0 + i < n_store) out_row[n0 + i] = (int8_t)(pack >> (8 * i));
+            }
+        }
+    }
+}
+
+// Last layer: y = (float)acc * m[n] for one tile, stored to y_row[n] (n < n_store).
+template <bool ASYM, bool TAPS>
+__device__ __forceinline__ void epi_last_tile(const LayerDev& L, const LayerTaps& T, const CPtrs& C, const v16i& c, int rs0, int zw_s, int nt, int g,
+                                              int64_t row, bool row_ok, float* y_row, int n_store) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int n0 = nt * 32 + 8 * j + 4 * g;
+        int val[4];
+        quad_acc<ASYM, TAPS>(L, T, C, c, j, n0, rs0, zw_s, row, row_ok, val);
+        const float4 mm = *(const float4*)(C.m + n0);
+        const float mv[4] = {mm.x, mm.y, mm.z, mm.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (y_row && n0 + i < n_store) y_row[n0 + i] = (float)val[i] * mv[i];
+    }
+}
+
+
+}  // namespace aq

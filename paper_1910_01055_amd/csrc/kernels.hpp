@@ -19,22 +19,14 @@ aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym
 
 // ---- 8-bit forward (forward_int8.hip)
 struct FwdArgs {
-    LayerDev L[AQ_MAX_LAYERS];
-    int n_layers;
-    int head;
-    int in_u8;
-    int asym;
-    float ln_eps;
-    const void* obs;
-    int64_t batch;
-    const ActQ* actq;
-    void* actions;
-    uint8_t* tap_a0;
-    float* tap_y;
-    int ld;  // LDS row stride of the fused kernel, bytes
+    NetDev net;           // host copy, for planning
+    const NetDev* d_net;  // the same, in device memory
+    CallArgs c;
+    TapArgs t;
 };
 
 // whole-network fused MLP kernel; returns AQ_ESHAPE when the network does not fit it
+bool any_taps(const FwdArgs& a);
 bool fused_mlp_supported(const FwdArgs& a, int* rows_per_wg_out, size_t* lds_bytes_out);
 aq_status launch_fused_mlp(const FwdArgs& a, hipStream_t st);
 
@@ -43,6 +35,7 @@ struct LayerIO {
     const void* in;   // layer 0: observations (fp32 or uint8); else int8 signed-domain [rows][K]
     int8_t* out;      // hidden layers: int8 signed-domain [rows][N] (row stride N)
     float* ln_x;      // LN layers: fp32 scratch [rows][N]
+    float* y;         // last layer: dequantized outputs [rows][N]
 };
 aq_status launch_layer_int8(const FwdArgs& a, int layer, const LayerIO& io, hipStream_t st);
 aq_status launch_ln_tanh_rows(const FwdArgs& a, int layer, const float* x, int8_t* out, int64_t rows, hipStream_t st);
