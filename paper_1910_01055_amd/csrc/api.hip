@@ -23,6 +23,9 @@ struct LayerBuf {
     float* m;
     float* gamma;
     float* beta;
+    int32_t* rz;
+    int32_t* sh;
+    int* fast;  // points into the device-resident NetDev
 };
 
 }  // namespace
@@ -57,6 +60,8 @@ static void fill_layer_dev(const aq_policy* p, int l, LayerDev& d) {
     d.gamma = b.gamma;
     d.beta = b.beta;
     d.z_w = b.z_w;
+    d.rz = b.rz;
+    d.sh = b.sh;
     d.K = b.K;
     d.N = b.N;
     d.KS = b.KS;
@@ -164,10 +169,9 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         if (l < net->n_layers - 1 && prev_elems > p->max_hidden_elems) p->max_hidden_elems = prev_elems;
         if (prev_elems > p->max_out_elems) p->max_out_elems = prev_elems;
         offs.push_back(take((size_t)b.NT * b.KS * 1024));
-        for (int i = 0; i < 10; ++i) offs.push_back(take((size_t)b.N_pad * 4));
+        for (int i = 0; i < 12; ++i) offs.push_back(take((size_t)b.N_pad * 4));
         p->L.push_back(b);
     }
-    size_t off_actq = take(sizeof(ActQ) * (AQ_MAX_LAYERS + 1));
     size_t off_status = take(256);
     size_t off_mm = take(256);
     size_t off_keys = take(sizeof(uint32_t) * 2 * (AQ_MAX_LAYERS + 1));
@@ -196,14 +200,18 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         b.m = (float*)(base + offs[oi++]);
         b.gamma = (float*)(base + offs[oi++]);
         b.beta = (float*)(base + offs[oi++]);
+        b.rz = (int32_t*)(base + offs[oi++]);
+        b.sh = (int32_t*)(base + offs[oi++]);
     }
-    p->actq = (ActQ*)(base + off_actq);
     p->status = (int*)(base + off_status);
     p->mm = (uint32_t*)(base + off_mm);
     p->keys = (uint32_t*)(base + off_keys);
     p->d_net = (NetDev*)(base + off_net);
-    for (int l = 0; l < net->n_layers; ++l) fill_layer_dev(p, l, p->h_net.L[l]);
-    p->h_net.actq = p->actq;
+    p->actq = p->d_net->actq;  // device address arithmetic only
+    for (int l = 0; l < net->n_layers; ++l) {
+        fill_layer_dev(p, l, p->h_net.L[l]);
+        p->L[l].fast = &p->d_net->fast[l];
+    }
     p->h_net.n_layers = net->n_layers;
     p->h_net.head = net->head;
     p->h_net.in_u8 = net->in_type == AQ_IN_U8;
@@ -335,8 +343,10 @@ extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w,
             }
         }
         const bool requant = l < nl - 1 && b.d.act != AQ_ACT_LN_TANH;
+        s = launch_fill_u32((uint32_t*)b.fast, 1, requant ? 1u : 0u, st);
+        if (s != AQ_OK) return s;
         s = launch_layer_consts(p->actq, l, requant, asym, b.s_w, b.z_w, h_d_b ? h_d_b[l] : nullptr, b.rowsum, b.N,
-                                b.K, b.m, b.bias_q, b.M0, b.rshift, b.bias_fold, p->status, st);
+                                b.K, b.m, b.bias_q, b.M0, b.rshift, b.bias_fold, b.rz, b.sh, b.fast, p->status, st);
         if (s != AQ_OK) return s;
     }
     p->quantized = true;
@@ -396,6 +406,9 @@ extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int
     a.c.obs = d_obs;
     a.c.actions = d_actions;
     a.c.batch = batch;
+    a.c.K0 = p->L[0].K;
+    a.c.Kp0 = p->L[0].K_pad;
+    a.c.in_u8 = p->h_net.in_u8;
     if (taps) {
         for (int l = 0; l < nl; ++l) {
             a.t.acc[l] = taps->acc ? taps->acc[l] : nullptr;

@@ -12,6 +12,12 @@ constexpr int kTile = 32;  // MFMA tile edge (features and batch rows); one k-st
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+// Pointers that are known to address global memory.  A pointer read back from LDS is a generic
+// ("flat") pointer to the compiler; flat loads are tracked by both memory counters and cannot be
+// kept in flight selectively, so every prefetch through them would serialize.
+#define AQ_GLOBAL __attribute__((address_space(1)))
+typedef const v4i AQ_GLOBAL* gv4i_ptr;
+typedef const int AQ_GLOBAL* gint_ptr;
 
 // (scale, zero-point) of one activation tensor, produced on the device by the quantizer block.
 struct ActQ {
@@ -71,6 +77,8 @@ struct LayerDev {
     const float* gamma;        // [N_pad] LayerNorm gain / offset (LN layers)
     const float* beta;
     const int32_t* z_w;        // [N_pad] weight zero-points (unsigned domain)
+    const int32_t* rz;         // [N_pad] short-form requantization: rounding constant + (z_out << sh)
+    const int32_t* sh;         // [N_pad] short-form shift r - 32
     int K, N, KS, NT;
     int act;
     // conv geometry (per-layer kernel only); FC: all 1
@@ -82,7 +90,8 @@ struct LayerDev {
 // of a large by-value argument costs a round trip over the host link on first touch.
 struct NetDev {
     LayerDev L[AQ_MAX_LAYERS];
-    const ActQ* actq;
+    ActQ actq[AQ_MAX_LAYERS + 1];  // written by the quantizer kernels: (scale, zero-point) per activation tensor
+    int fast[AQ_MAX_LAYERS];       // written by the quantizer kernels: layer qualifies for the short requant form
     int n_layers;
     int head;
     int in_u8;
@@ -97,6 +106,8 @@ struct CallArgs {
     int64_t batch;
     int ld;     // fused kernel: LDS row stride, bytes
     int cst_n;  // fused kernel: words per constant array in the LDS staging area
+    int K0, Kp0, in_u8;  // first layer's input width (real, padded) and input type, so the observation
+                         // loads can be issued before anything else has been read
 };
 
 // Optional intermediate outputs (by value, only read by the kernels compiled with TAPS).

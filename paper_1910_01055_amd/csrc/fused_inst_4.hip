@@ -1,8 +1,8 @@
-// Explicit instantiation of one fused-MLP kernel variant (rows = 32 * 2, 4 feature tile(s) per wave,
+// Explicit instantiation of one fused-MLP kernel variant (rows = 32 * 2, 2 feature tile(s) per wave,
 // symmetric weights), with and without intermediate taps.
 #include "fused_mlp.hpp"
 
 namespace aq {
-AQ_FUSED_INST(2, 4, false, false);
-AQ_FUSED_INST(2, 4, false, true);
+AQ_FUSED_INST(2, 2, false, false);
+AQ_FUSED_INST(2, 2, false, true);
 }  // namespace aq

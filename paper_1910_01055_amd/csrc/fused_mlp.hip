@@ -10,10 +10,10 @@ AQ_FUSED_DECL(2, 1, false, false);
 AQ_FUSED_DECL(2, 1, false, true);
 AQ_FUSED_DECL(4, 1, false, false);
 AQ_FUSED_DECL(4, 1, false, true);
-AQ_FUSED_DECL(1, 4, false, false);
-AQ_FUSED_DECL(1, 4, false, true);
-AQ_FUSED_DECL(2, 4, false, false);
-AQ_FUSED_DECL(2, 4, false, true);
+AQ_FUSED_DECL(1, 2, false, false);
+AQ_FUSED_DECL(1, 2, false, true);
+AQ_FUSED_DECL(2, 2, false, false);
+AQ_FUSED_DECL(2, 2, false, true);
 AQ_FUSED_DECL(1, 1, true, false);
 AQ_FUSED_DECL(1, 1, true, true);
 AQ_FUSED_DECL(2, 1, true, false);
@@ -43,8 +43,9 @@ bool make_plan(const FwdArgs& a, Plan* p) {
     maxw = maxw > lastw ? maxw : lastw;
     p->ld = maxw + 16;
     p->cst_n = max_np;
-    // feature tiles per wave: wide layers take 4 so that one pass of the 8 waves covers 32 tiles
-    p->nb = (max_nt >= 32 && !a.net.asym) ? 4 : 1;
+    // feature tiles per wave: wide layers take 2 (two passes of the 8 waves cover 32 tiles); more would
+    // not leave registers for the operand pipeline at two waves per SIMD
+    p->nb = (max_nt >= 32 && !a.net.asym) ? 2 : 1;
     for (int l = 0; l < a.net.n_layers - 1; ++l)  // LayerNorm needs its whole row resident in one pass
         if (a.net.L[l].act == AQ_ACT_LN_TANH && (a.net.L[l].NT + p->nb - 1) / p->nb > FW) return false;
     // rows per workgroup: enough workgroups to cover the 256 CUs first, more rows per workgroup
@@ -88,9 +89,9 @@ aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     const bool as = a.net.asym != 0;
 #define AQ_GO(MT, NB, AS) \
     return tp ? launch_fused_t<MT, NB, AS, true>(a, p.lds, st) : launch_fused_t<MT, NB, AS, false>(a, p.lds, st)
-    if (p.nb == 4) {
-        if (p.mt == 1) AQ_GO(1, 4, false);
-        AQ_GO(2, 4, false);
+    if (p.nb == 2) {
+        if (p.mt == 1) AQ_GO(1, 2, false);
+        AQ_GO(2, 2, false);
     }
     if (as) {
         if (p.mt == 1) AQ_GO(1, 1, true);

@@ -1,7 +1,10 @@
 // Whole-network fused int8 MLP (Sec. 3.1 actor inference, quantized per Sec. 3.2): one workgroup
 // of 8 wavefronts owns ROWS = 32 * MT batch rows from the observation to the action.
 //   - activations never leave LDS (two ping-pong row-major int8 buffers, signed domain)
-//   - weights stream from L2 straight into MFMA operand registers (pre-packed at quantize time)
+//   - weights stream from L2 straight into MFMA operand registers (pre-packed at quantize time);
+//     the first k-steps of the NEXT pass or layer are requested before the current epilogue starts,
+//     and the next layer's descriptor is fetched one layer ahead, so no layer begins with a chain
+//     of dependent memory round trips
 //   - each wave owns NB feature tiles per pass; per-channel constants of the layer are fetched
 //     while the MFMAs run and handed to the epilogue through LDS
 //   - epilogues: requantize(+ReLU) / LayerNorm+tanh+requantize in registers, last layer dequantize,
@@ -15,238 +18,134 @@ constexpr int FW = 8;            // wavefronts per workgroup
 constexpr int FT = FW * 64;      // threads per workgroup
 constexpr int CST_MAXN = 1024;   // widest layer whose constants fit the LDS staging area
 
-// LDS layout (bytes): [buf_in ROWS*ld][buf_out ROWS*ld][red 2*FW*ROWS floats][cst 6*cst_n words]
+constexpr int NET_WORDS = (sizeof(NetDev) + 15) / 16 * 4;
+
+// LDS layout (bytes): [buf_in ROWS*ld][buf_out ROWS*ld][red 2*FW*ROWS floats][cst 4*cst_n words][net]
 __host__ __device__ inline size_t fused_lds_bytes(int rows, int ld, int cst_n) {
-    return (size_t)2 * rows * ld + (size_t)2 * FW * rows * 4 + (size_t)6 * cst_n * 4;
+    return (size_t)2 * rows * ld + (size_t)2 * FW * rows * 4 + (size_t)4 * cst_n * 4 + (size_t)NET_WORDS * 4;
 }
 
-template <int MT, int NB, bool ASYM, bool TAPS>
-__device__ __forceinline__ void fused_layer(const NetDev& a, const CallArgs& c, const TapArgs& t, int l,
-                                            const int8_t* in, int8_t* out, float* red, int32_t* cst, int cst_n,
-                                            int64_t row0) {
-    constexpr int ROWS = 32 * MT;
-    constexpr int PF = NB == 1 ? 8 : 4;
-    const LayerDev& L = a.L[l];
-    LayerTaps T{nullptr, nullptr, nullptr};
-    if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-    const bool last = l == a.n_layers - 1;
-    const bool ln = !last && L.act == AQ_ACT_LN_TANH;
-    const int ngroups = (L.NT + NB - 1) / NB;
-    const int Np = L.NT * 32;
-    float s_out = 1.0f;
-    int z_out = 0;
-    if (!last) {
-        s_out = a.actq[l + 1].s;
-        z_out = a.actq[l + 1].z;
+// Values read from the LDS copy of the network description arrive in vector registers;
+// readfirstlane moves them to scalar registers so that loop bounds and branches stay scalar.
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float unif(float v) { return __int_as_float(uni(__float_as_int(v))); }
+template <class T>
+__device__ __forceinline__ T* uni_ptr(T* p) {
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (T*)(((uint64_t)hi << 32) | lo);
+}
+
+// One layer as the kernel needs it: plain scalars, built field by field from the LDS copy.
+struct LayerView {
+    const int8_t* wp;
+    gv4i_ptr slot[4];     // sources of the four staged constant arrays (see below), as 16-byte pieces
+    const int32_t* rshift;
+    gint_ptr z_w;
+    int N, NT, KS, act, nslots, fast, z_out;
+    float s_out;
+    bool last, ln;
+};
+// Constant slots by layer type: slot 0 = bias_fold; requantized: M0, rz, sh (the general requantization
+// form reads its shifts from global memory); LayerNorm: m, gamma, beta; last: m.
+__device__ __forceinline__ LayerView layer_view(const NetDev& n, int l, int n_layers) {
+    const LayerDev& s = n.L[l];
+    LayerView v;
+    v.last = l == n_layers - 1;
+    v.act = uni(s.act);
+    v.ln = !v.last && v.act == AQ_ACT_LN_TANH;
+    v.wp = uni_ptr(s.wp);
+    v.slot[0] = (gv4i_ptr)uni_ptr(s.bias_fold);
+    v.slot[1] = (gv4i_ptr)((v.ln || v.last) ? (const void*)uni_ptr(s.m) : (const void*)uni_ptr(s.M0));
+    v.slot[2] = (gv4i_ptr)(v.ln ? (const void*)uni_ptr(s.gamma) : (const void*)uni_ptr(s.rz));
+    v.slot[3] = (gv4i_ptr)(v.ln ? (const void*)uni_ptr(s.beta) : (const void*)uni_ptr(s.sh));
+    v.rshift = uni_ptr(s.rshift);
+    v.z_w = (gint_ptr)uni_ptr(s.z_w);
+    v.N = uni(s.N);
+    v.NT = uni(s.NT);
+    v.KS = uni(s.KS);
+    v.nslots = v.last ? 2 : 4;
+    v.s_out = 1.0f;
+    v.z_out = 0;
+    v.fast = 0;
+    if (!v.last) {
+        v.s_out = unif(n.actq[l + 1].s);
+        v.z_out = uni(n.actq[l + 1].z);
+        v.fast = uni(n.fast[l]);
     }
-    const int lo = (!last && L.act == AQ_ACT_RELU) ? z_out : 0;
-    const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
-    const int ld = c.ld;
-    const int ldy = Np;  // last layer: fp32 row stride of y in LDS
-
-    // Per-channel constants: issue the global loads now, park them in LDS after the MFMA loop.
-    // Six arrays of Np words: bias_fold, M0, rshift, m, gamma, beta (as 16-byte pieces).
-    const int n4 = Np / 4;
-    auto csrc = [&](int w) __attribute__((always_inline)) -> const int4* {
-        return (const int4*)(w == 0 ? (const void*)L.bias_fold : w == 1 ? (const void*)L.M0 : w == 2 ? (const void*)L.rshift
-                             : w == 3 ? (const void*)L.m : w == 4 ? (const void*)L.gamma : (const void*)L.beta);
-    };
-    int4 cv[3];
-    const int pieces = (ln ? 6 : 4) * n4;  // <= 6 * 256 = 3 * FT for Np <= CST_MAXN
-#pragma unroll
-    for (int r = 0; r < 3; ++r) {
-        const int idx = tid + r * FT;
-        if (idx < pieces) cv[r] = csrc(idx / n4)[idx % n4];
+    return v;
+}
+// this thread's share of a layer's constants: up to two 16-byte pieces (Np <= CST_MAXN)
+__device__ __forceinline__ void load_consts(const LayerView& v, int tid, v4i& c0, v4i& c1) {
+    const int n4 = v.NT * 8, pieces = v.nslots * n4;
+    const int i0 = tid, i1 = tid + FW * 64;
+    if (i0 < pieces) {
+        const int w = i0 / n4;
+        c0 = (w == 0 ? v.slot[0] : w == 1 ? v.slot[1] : w == 2 ? v.slot[2] : v.slot[3])[i0 - w * n4];
     }
+    if (i1 < pieces) {
+        const int w = i1 / n4;
+        c1 = (w == 0 ? v.slot[0] : w == 1 ? v.slot[1] : w == 2 ? v.slot[2] : v.slot[3])[i1 - w * n4];
+    }
+}
+__device__ __forceinline__ void park_consts(const LayerView& v, int tid, int32_t* cst, int cst_n, const v4i& c0,
+                                            const v4i& c1) {
+    const int n4 = v.NT * 8, pieces = v.nslots * n4;
+    const int i0 = tid, i1 = tid + FW * 64;
+    if (i0 < pieces) *(v4i*)(cst + (i0 / n4) * cst_n + (i0 % n4) * 4) = c0;
+    if (i1 < pieces) *(v4i*)(cst + (i1 / n4) * cst_n + (i1 % n4) * 4) = c1;
+}
 
-    CPtrs C;
-    C.bias_fold = cst;
-    C.M0 = cst + cst_n;
-    C.rshift = cst + 2 * cst_n;
-    C.m = (const float*)(cst + 3 * cst_n);
-    const float* c_gamma = (const float*)(cst + 4 * cst_n);
-    const float* c_beta = (const float*)(cst + 5 * cst_n);
-
-    for (int g0 = 0; g0 < ngroups; g0 += FW) {
-        const int grp = g0 + wave;
-        const bool active = grp < ngroups;
-        v16i acc[NB][MT];
-        v16i rs[MT];
+template <int NB>
+__device__ __forceinline__ void tile_ptrs(const int8_t* wp, int NT, int KS, int grp, int lane,
+                                          gv4i_ptr (&wptr)[NB]) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            rs[mt] = zero16();
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) acc[nb][mt] = zero16();
-        }
-        if (active) {
-            const v4i* wptr[NB];
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                int nt = grp * NB + nb;
-                nt = nt < L.NT ? nt : L.NT - 1;
-                wptr[nb] = (const v4i*)L.wp + (int64_t)nt * L.KS * 64 + lane;
-            }
-            mma_block<MT, NB, ASYM, PF>(wptr, in, ld, 0, L.KS, 0, acc, rs, lane);
-        }
-        if (g0 == 0) {
-#pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                const int idx = tid + r * FT;
-                if (idx < pieces) *(int4*)(cst + (idx / n4) * cst_n + (idx % n4) * 4) = cv[r];
-            }
-            __syncthreads();
-        }
-        if (!ln) {
-            if (active) {
-                static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
-                    constexpr int nb = decltype(nb_c)::value;
-                    const int nt = grp * NB + nb;
-                    if (nt < L.NT) {
-                        static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
-                            constexpr int mt = decltype(mt_c)::value;
-                            const int m = mt * 32 + (lane & 31);
-                            const int64_t row = row0 + m;
-                            const bool row_ok = row < c.batch;
-                            if (last)
-                                epi_last_tile<ASYM, TAPS>(L, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
-                                                          (float*)out + m * ldy, ldy);
-                            else
-                                epi_hidden_tile<ASYM, TAPS>(L, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
-                                                            z_out, lo, out + m * ld, true, Np);
-                        });
-                    }
-                });
-            }
-        } else {
-            // LayerNorm over the layer's N features (all resident in this one pass: ngroups <= FW),
-            // tanh, re-quantize.  Row statistics: in-lane sums, lane ^ 32, then across waves via LDS.
-            float* red1 = red;
-            float* red2 = red + FW * ROWS;
-            float mean[MT], inv[MT];
-            static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
-                constexpr int mt = decltype(mt_c)::value;
-                float s = 0.0f;
-                const int64_t row = row0 + mt * 32 + (lane & 31);
-                const bool row_ok = row < c.batch;
-                static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
-                    constexpr int nb = decltype(nb_c)::value;
-                    const int nt = grp * NB + nb;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int n0 = nt * 32 + 8 * j + 4 * g;
-                        if (active && n0 < Np) {
-                            int val[4];
-                            quad_acc<ASYM, TAPS>(L, T, C, acc[nb][mt], j, n0, rs[mt][0], zw_s, row, row_ok, val);
-                            const float4 mm = *(const float4*)(C.m + n0);
-                            const float mv[4] = {mm.x, mm.y, mm.z, mm.w};
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                float x = n0 + i < L.N ? (float)val[i] * mv[i] : 0.0f;
-                                acc[nb][mt][4 * j + i] = __float_as_int(x);
-                                s += x;
-                            }
-                        } else {
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) acc[nb][mt][4 * j + i] = 0;
-                        }
-                    }
-                });
-                s += __shfl_xor(s, 32, 64);
-                if (g == 0) red1[wave * ROWS + mt * 32 + lane] = s;
-            });
-            __syncthreads();
-            static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
-                constexpr int mt = decltype(mt_c)::value;
-                const int m = mt * 32 + (lane & 31);
-                float tot = 0.0f;
-#pragma unroll
-                for (int w = 0; w < FW; ++w) tot += red1[w * ROWS + m];
-                mean[mt] = tot / (float)L.N;
-                float ss = 0.0f;
-                static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
-                    constexpr int nb = decltype(nb_c)::value;
-                    const int nt = grp * NB + nb;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int n = nt * 32 + 8 * j + 4 * g + i;
-                            if (active && n < L.N) {
-                                float d = __int_as_float(acc[nb][mt][4 * j + i]) - mean[mt];
-                                ss += d * d;
-                            }
-                        }
-                });
-                ss += __shfl_xor(ss, 32, 64);
-                if (g == 0) red2[wave * ROWS + mt * 32 + lane] = ss;
-            });
-            __syncthreads();
-            static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
-                constexpr int mt = decltype(mt_c)::value;
-                const int m = mt * 32 + (lane & 31);
-                float tot = 0.0f;
-#pragma unroll
-                for (int w = 0; w < FW; ++w) tot += red2[w * ROWS + m];
-                inv[mt] = 1.0f / sqrtf(tot / (float)L.N + a.ln_eps);
-                const int64_t row = row0 + m;
-                const bool row_ok = row < c.batch;
-                static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
-                    constexpr int nb = decltype(nb_c)::value;
-                    const int nt = grp * NB + nb;
-                    if (active && nt < L.NT) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int n0 = nt * 32 + 8 * j + 4 * g;
-                            const float4 ga = *(const float4*)(c_gamma + n0);
-                            const float4 be = *(const float4*)(c_beta + n0);
-                            const float gv[4] = {ga.x, ga.y, ga.z, ga.w}, bv[4] = {be.x, be.y, be.z, be.w};
-                            uint32_t pack = 0;
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const int n = n0 + i;
-                                float x = __int_as_float(acc[nb][mt][4 * j + i]);
-                                float y = (x - mean[mt]) * inv[mt] * gv[i] + bv[i];
-                                float tv = tanh_fast(y);
-                                int code = rint_clamp(tv / s_out, -z_out, 255 - z_out) + z_out;
-                                if (n >= L.N) code = 128;
-                                if (TAPS) {
-                                    if (row_ok && n < L.N) {
-                                        if (T.ln) T.ln[row * L.N + n] = tv;
-                                        if (T.act) T.act[row * L.N + n] = (uint8_t)code;
-                                    }
-                                }
-                                pack |= (uint32_t)((code ^ 0x80) & 255) << (8 * i);
-                            }
-                            *(uint32_t*)(out + m * ld + n0) = pack;
-                        }
-                    }
-                });
-            });
-        }
+    for (int nb = 0; nb < NB; ++nb) {
+        int nt = grp * NB + nb;
+        nt = nt < NT ? nt : NT - 1;
+        wptr[nb] = (gv4i_ptr)wp + (int64_t)nt * KS * 64 + lane;
     }
 }
 
 template <int MT, int NB, bool ASYM, bool TAPS>
 __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ netp, const CallArgs c,
                                                   const TapArgs t) {
-    const NetDev& a = *netp;
     extern __shared__ __align__(16) int8_t smem[];
     constexpr int ROWS = 32 * MT;
-    const int tid = threadIdx.x;
+    constexpr int PF = NB == 1 ? 8 : 4;
+    // requesting the next weights ahead of the epilogue keeps PF*NB operand registers alive through
+    // it; the wide variant (NB = 2) has no registers to spare and fetches at the start of each pass
+    constexpr bool XPF = NB == 1;
+    const NetDev& a = *netp;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
     const int64_t row0 = (int64_t)blockIdx.x * ROWS;
-    const int ld = c.ld;
+    const int ld = c.ld, cst_n = c.cst_n;
     int8_t* buf_in = smem;
     int8_t* buf_out = smem + ROWS * ld;
     float* red = (float*)(smem + 2 * ROWS * ld);
     int32_t* cst = (int32_t*)(red + 2 * FW * ROWS);
+    int32_t* net_lds = cst + 4 * cst_n;
+    const NetDev& an = *(const NetDev*)net_lds;  // valid after the first barrier
+
+    // the network description: one coalesced read into LDS, so that no layer starts by chasing
+    // pointers through global memory (every dependent global access costs about a microsecond)
+    if (tid < NET_WORDS) net_lds[tid] = tid < (int)(sizeof(NetDev) / 4) ? ((const int32_t*)netp)[tid] : 0;
+
+    // first layer's first weights: requested before the observations are touched
+    v4i wreg[PF][NB];
+    if (XPF) {
+        const int NT0 = a.L[0].NT, KS0 = a.L[0].KS;
+        gv4i_ptr wptr[NB];
+        tile_ptrs<NB>(a.L[0].wp, NT0, KS0, wave, lane, wptr);
+        if (wave * NB < NT0) mma_prefetch<NB, PF>(wptr, 0, KS0, wreg);
+    }
 
     // observation quantize: a0 = clamp(round(x / s0) + z0, 0, 255), kept in the signed domain
     {
-        const int K0 = a.L[0].K, Kp = a.L[0].KS * 32;
+        const int K0 = c.K0, Kp = c.Kp0;
         const float s0 = a.actq[0].s;
         const int z0 = a.actq[0].z;
-        if (!a.in_u8 && (K0 & 3) == 0) {
+        if (!c.in_u8 && (K0 & 3) == 0) {
             // four observations per lane: one 16-byte load, one packed 32-bit LDS store
             const int K4 = K0 >> 2;
             const float4* src = (const float4*)c.obs + row0 * K4;
@@ -271,7 +170,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 const int64_t row = row0 + m;
                 int code = 128;
                 if (row < c.batch) {
-                    if (a.in_u8) {
+                    if (c.in_u8) {
                         code = ((const uint8_t*)c.obs)[row * K0 + k];
                     } else {
                         code = rint_clamp(((const float*)c.obs)[row * K0 + k] / s0, -z0, 255 - z0) + z0;
@@ -289,11 +188,208 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
             buf_in[m * ld + k] = 0;
         }
     }
-    __syncthreads();
+    lds_barrier();
 
-    for (int l = 0; l < a.n_layers; ++l) {
-        fused_layer<MT, NB, ASYM, TAPS>(a, c, t, l, buf_in, buf_out, red, cst, c.cst_n, row0);
-        __syncthreads();
+    const int n_layers = uni(an.n_layers);
+    const float ln_eps = unif(an.ln_eps);
+    int N_last = 0, NT_last = 0;
+    v4i cv0 = {0, 0, 0, 0}, cv1 = cv0;
+    {
+        const LayerView v0 = layer_view(an, 0, n_layers);
+        load_consts(v0, tid, cv0, cv1);
+    }
+    for (int l = 0; l < n_layers; ++l) {
+        const LayerView L = layer_view(an, l, n_layers);
+        const bool last = L.last, ln = L.ln;
+        N_last = L.N;
+        NT_last = L.NT;
+        LayerTaps T{nullptr, nullptr, nullptr};
+        if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
+        const int ngroups = (L.NT + NB - 1) / NB;
+        const int Np = L.NT * 32;
+        const float s_out = L.s_out;
+        const int z_out = L.z_out, fast = L.fast;
+        const int lo = (!last && L.act == AQ_ACT_RELU) ? z_out : 0;
+        const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
+        const int ldy = Np;  // last layer: fp32 row stride of y in LDS
+        const int8_t* in = buf_in;
+        int8_t* out = buf_out;
+
+        // This layer's per-channel constants were requested one layer ago (layer 0: just above);
+        // park them in LDS for the epilogue.  The barrier after the first MFMA pass publishes them.
+        park_consts(L, tid, cst, cst_n, cv0, cv1);
+        const CPtrs C{cst, cst + cst_n, L.rshift, cst + 2 * cst_n, cst + 3 * cst_n, (const float*)(cst + cst_n)};
+        const float* c_gamma = (const float*)(cst + 2 * cst_n);
+        const float* c_beta = (const float*)(cst + 3 * cst_n);
+
+        for (int g0 = 0; g0 < ngroups; g0 += FW) {
+            const int grp = g0 + wave;
+            const bool active = grp < ngroups;
+            v16i acc[NB][MT];
+            v16i rs[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                rs[mt] = zero16();
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) acc[nb][mt] = zero16();
+            }
+            if (active) {
+                gv4i_ptr wptr[NB];
+                tile_ptrs<NB>(L.wp, L.NT, L.KS, grp, lane, wptr);
+                if (!XPF) mma_prefetch<NB, PF>(wptr, 0, L.KS, wreg);
+                mma_run<MT, NB, ASYM, PF>(wptr, wreg, in, ld, 0, L.KS, 0, acc, rs, lane);
+            }
+            // request the next pass's (or the next layer's) first weights before the epilogue
+            if (XPF) {
+                const bool more = g0 + FW < ngroups;
+                const int ln_i = (more || last) ? l : l + 1;
+                const int8_t* wp_n = uni_ptr(an.L[ln_i].wp);
+                const int NT_n = uni(an.L[ln_i].NT), KS_n = uni(an.L[ln_i].KS);
+                const int grp_n = more ? grp + FW : wave;
+                if ((more || !last) && grp_n * NB < NT_n) {
+                    gv4i_ptr wptr[NB];
+                    tile_ptrs<NB>(wp_n, NT_n, KS_n, grp_n, lane, wptr);
+                    mma_prefetch<NB, PF>(wptr, 0, KS_n, wreg);
+                }
+            }
+            // ... and, on the last pass, the next layer's constants
+            if (!last && g0 + FW >= ngroups) {
+                const LayerView vn = layer_view(an, l + 1, n_layers);
+                load_consts(vn, tid, cv0, cv1);
+            }
+            if (g0 == 0) lds_barrier();
+            if (!ln) {
+                if (active) {
+                    static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
+                        constexpr int nb = decltype(nb_c)::value;
+                        const int nt = grp * NB + nb;
+                        if (nt < L.NT) {
+                            static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
+                                constexpr int mt = decltype(mt_c)::value;
+                                const int m = mt * 32 + (lane & 31);
+                                const int64_t row = row0 + m;
+                                const bool row_ok = row < c.batch;
+                                if (last)
+                                    epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
+                                                              (float*)out + m * ldy, ldy);
+                                else if (fast)
+                                    epi_hidden_tile<ASYM, TAPS, true>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row,
+                                                                      row_ok, z_out, lo, out + m * ld, true, Np);
+                                else
+                                    epi_hidden_tile<ASYM, TAPS, false>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row,
+                                                                       row_ok, z_out, lo, out + m * ld, true, Np);
+                            });
+                        }
+                    });
+                }
+            } else {
+                // LayerNorm over the layer's N features (all resident in this one pass: ngroups <= FW),
+                // tanh, re-quantize.  Row statistics: in-lane sums, lane ^ 32, then across waves via LDS.
+                float* red1 = red;
+                float* red2 = red + FW * ROWS;
+                float mean[MT], inv[MT];
+                static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
+                    constexpr int mt = decltype(mt_c)::value;
+                    float s = 0.0f;
+                    const int64_t row = row0 + mt * 32 + (lane & 31);
+                    const bool row_ok = row < c.batch;
+                    static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
+                        constexpr int nb = decltype(nb_c)::value;
+                        const int nt = grp * NB + nb;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int n0 = nt * 32 + 8 * j + 4 * g;
+                            if (active && n0 < Np) {
+                                int val[4];
+                                quad_acc<ASYM, TAPS>(L.N, T, C, acc[nb][mt], j, n0, rs[mt][0], zw_s, row, row_ok, val);
+                                const float4 mm = *(const float4*)(C.m + n0);
+                                const float mv[4] = {mm.x, mm.y, mm.z, mm.w};
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    float x = n0 + i < L.N ? (float)val[i] * mv[i] : 0.0f;
+                                    acc[nb][mt][4 * j + i] = __float_as_int(x);
+                                    s += x;
+                                }
+                            } else {
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) acc[nb][mt][4 * j + i] = 0;
+                            }
+                        }
+                    });
+                    s += __shfl_xor(s, 32, 64);
+                    if (g == 0) red1[wave * ROWS + mt * 32 + lane] = s;
+                });
+                lds_barrier();
+                static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
+                    constexpr int mt = decltype(mt_c)::value;
+                    const int m = mt * 32 + (lane & 31);
+                    float tot = 0.0f;
+#pragma unroll
+                    for (int w = 0; w < FW; ++w) tot += red1[w * ROWS + m];
+                    mean[mt] = tot / (float)L.N;
+                    float ss = 0.0f;
+                    static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
+                        constexpr int nb = decltype(nb_c)::value;
+                        const int nt = grp * NB + nb;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const int n = nt * 32 + 8 * j + 4 * g + i;
+                                if (active && n < L.N) {
+                                    float d = __int_as_float(acc[nb][mt][4 * j + i]) - mean[mt];
+                                    ss += d * d;
+                                }
+                            }
+                    });
+                    ss += __shfl_xor(ss, 32, 64);
+                    if (g == 0) red2[wave * ROWS + mt * 32 + lane] = ss;
+                });
+                lds_barrier();
+                static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
+                    constexpr int mt = decltype(mt_c)::value;
+                    const int m = mt * 32 + (lane & 31);
+                    float tot = 0.0f;
+#pragma unroll
+                    for (int w = 0; w < FW; ++w) tot += red2[w * ROWS + m];
+                    inv[mt] = 1.0f / sqrtf(tot / (float)L.N + ln_eps);
+                    const int64_t row = row0 + m;
+                    const bool row_ok = row < c.batch;
+                    static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
+                        constexpr int nb = decltype(nb_c)::value;
+                        const int nt = grp * NB + nb;
+                        if (active && nt < L.NT) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const int n0 = nt * 32 + 8 * j + 4 * g;
+                                const float4 ga = *(const float4*)(c_gamma + n0);
+                                const float4 be = *(const float4*)(c_beta + n0);
+                                const float gv[4] = {ga.x, ga.y, ga.z, ga.w}, bv[4] = {be.x, be.y, be.z, be.w};
+                                uint32_t pack = 0;
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) {
+                                    const int n = n0 + i;
+                                    float x = __int_as_float(acc[nb][mt][4 * j + i]);
+                                    float y = (x - mean[mt]) * inv[mt] * gv[i] + bv[i];
+                                    float tv = tanh_fast(y);
+                                    int code = rint_clamp(tv / s_out, -z_out, 255 - z_out) + z_out;
+                                    if (n >= L.N) code = 128;
+                                    if (TAPS) {
+                                        if (row_ok && n < L.N) {
+                                            if (T.ln) T.ln[row * L.N + n] = tv;
+                                            if (T.act) T.act[row * L.N + n] = (uint8_t)code;
+                                        }
+                                    }
+                                    pack |= (uint32_t)code << (8 * i);
+                                }
+                                *(uint32_t*)(out + m * ld + n0) = pack ^ 0x80808080u;
+                            }
+                        }
+                    });
+                });
+            }
+        }
+        lds_barrier();
         int8_t* sw = buf_in;
         buf_in = buf_out;
         buf_out = sw;
@@ -301,11 +397,11 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 
     // action head on the dequantized last-layer rows y (fp32, in LDS): tanh / identity / argmax
     {
-        const LayerDev& L = a.L[a.n_layers - 1];
+        const int head = uni(an.head);
         const float* ybuf = (const float*)buf_in;
-        const int ldy = L.NT * 32;
-        const int N = L.N;
-        if (a.head == AQ_HEAD_ARGMAX) {
+        const int ldy = NT_last * 32;
+        const int N = N_last;
+        if (head == AQ_HEAD_ARGMAX) {
             for (int m = tid; m < ROWS; m += FT) {
                 const int64_t row = row0 + m;
                 if (row >= c.batch) continue;
@@ -328,7 +424,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 if (TAPS) {
                     if (t.y) t.y[row * N + n] = y;
                 }
-                ((float*)c.actions)[row * N + n] = a.head == AQ_HEAD_TANH ? tanh_head(y) : y;
+                ((float*)c.actions)[row * N + n] = head == AQ_HEAD_TANH ? tanh_head(y) : y;
             }
         }
     }

@@ -33,6 +33,11 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits for every
+// outstanding global access (vmcnt(0)), which would drain the weight / constant prefetches that
+// are deliberately left in flight across the barrier; here only LDS traffic is waited for.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __device__ __forceinline__ v16i zero16() {
     v16i z;
 #pragma unroll
@@ -75,16 +80,23 @@ __device__ __forceinline__ float tanh_head(float x) {
 // (row-major int8, row stride ld, column 0 = k-step ks_lds0).
 // ---------------------------------------------------------------------------------------------
 // PF = weight k-steps in flight per wave (global -> register prefetch depth)
-template <int MT, int NB, bool ASYM, int PF>
-__device__ __forceinline__ void mma_block(const v4i* (&wptr)[NB], const int8_t* xs, int ld, int ks_begin,
-                                          int ks_end, int ks_lds0, v16i (&acc)[NB][MT], v16i (&rs)[MT], int lane) {
-    v4i wreg[PF][NB];
+// mma_prefetch issues the first PF k-steps' weight loads; mma_run consumes them and keeps the
+// pipeline full for the rest of K.  Splitting the two lets a caller issue the next layer's first
+// loads before it starts the current layer's epilogue.
+template <int NB, int PF>
+__device__ __forceinline__ void mma_prefetch(gv4i_ptr (&wptr)[NB], int ks_begin, int ks_end, v4i (&wreg)[PF][NB]) {
 #pragma unroll
     for (int p = 0; p < PF; ++p)
         if (ks_begin + p < ks_end) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) wreg[p][nb] = wptr[nb][(int64_t)(ks_begin + p) * 64];
         }
+}
+
+template <int MT, int NB, bool ASYM, int PF>
+__device__ __forceinline__ void mma_run(gv4i_ptr (&wptr)[NB], v4i (&wreg)[PF][NB], const int8_t* xs, int ld,
+                                        int ks_begin, int ks_end, int ks_lds0, v16i (&acc)[NB][MT], v16i (&rs)[MT],
+                                        int lane) {
     const int8_t* xrow = xs + (lane & 31) * ld + (lane >> 5) * 16;
     v4i ones;
     ones[0] = ones[1] = ones[2] = ones[3] = 0x01010101;
@@ -116,14 +128,26 @@ __device__ __forceinline__ void mma_block(const v4i* (&wptr)[NB], const int8_t* 
     }
 }
 
+template <int MT, int NB, bool ASYM, int PF>
+__device__ __forceinline__ void mma_block(gv4i_ptr (&wptr)[NB], const int8_t* xs, int ld, int ks_begin,
+                                          int ks_end, int ks_lds0, v16i (&acc)[NB][MT], v16i (&rs)[MT], int lane) {
+    v4i wreg[PF][NB];
+    mma_prefetch<NB, PF>(wptr, ks_begin, ks_end, wreg);
+    mma_run<MT, NB, ASYM, PF>(wptr, wreg, xs, ld, ks_begin, ks_end, ks_lds0, acc, rs, lane);
+}
+
 // where an epilogue reads the per-channel constants from (global memory or a copy staged in LDS)
 struct CPtrs {
     const int32_t* bias_fold;
     const int32_t* M0;
-    const int32_t* rshift;
+    const int32_t* rshift;  // general form
+    const int32_t* rz;      // short form
+    const int32_t* sh;
     const float* m;
 };
-__device__ __forceinline__ CPtrs global_consts(const LayerDev& L) { return CPtrs{L.bias_fold, L.M0, L.rshift, L.m}; }
+__device__ __forceinline__ CPtrs global_consts(const LayerDev& L) {
+    return CPtrs{L.bias_fold, L.M0, L.rshift, L.rz, L.sh, L.m};
+}
 
 // requantize one accumulator: v = (acc * M0 + 2^(r-1)) >> r, code = clamp(v + z_out, lo, 255)
 __device__ __forceinline__ int requant_code(int acc, int M0, int r, int z_out, int lo) {
@@ -136,7 +160,7 @@ __device__ __forceinline__ int requant_code(int acc, int M0, int r, int z_out, i
 
 // canonical accumulator of one register quad: MFMA sum + folded bias (- z_w' * row sum of a_s)
 template <bool ASYM, bool TAPS>
-__device__ __forceinline__ void quad_acc(const LayerDev& L, const LayerTaps& T, const CPtrs& C, const v16i& c, int j, int n0, int rs0, int zw_s,
+__device__ __forceinline__ void quad_acc(const int N, const LayerTaps& T, const CPtrs& C, const v16i& c, int j, int n0, int rs0, int zw_s,
                                          int64_t row, bool row_ok, int (&val)[4]) {
     const int4 bf = *(const int4*)(C.bias_fold + n0);
     const int bfv[4] = {bf.x, bf.y, bf.z, bf.w};
@@ -145,35 +169,52 @@ __device__ __forceinline__ void quad_acc(const LayerDev& L, const LayerTaps& T, 
         val[i] = c[4 * j + i] + bfv[i];
         if (ASYM) val[i] -= zw_s * rs0;
         if (TAPS) {
-            if (T.acc && row_ok && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val[i];
+            if (T.acc && row_ok && n0 + i < N) T.acc[(int64_t)row * N + n0 + i] = val[i];
         }
     }
 }
 
 // Hidden layer: requantize (+ReLU through the clamp) one 32x32 tile and store the codes, signed
 // domain, four per 32-bit word (packed) or bytewise, for features below n_store.
-template <bool ASYM, bool TAPS>
-__device__ __forceinline__ void epi_hidden_tile(const LayerDev& L, const LayerTaps& T, const CPtrs& C, const v16i& c, int rs0, int zw_s, int nt, int g,
-                                                int64_t row, bool row_ok, int z_out, int lo, int8_t* out_row,
-                                                bool packed, int n_store) {
+// FAST: every channel has 33 <= r <= 54, so (acc*M0 + 2^(r-1)) >> r + z_out collapses to
+// (mulhi(acc, M0) + rz) >> sh with rz = 2^(r-33) + (z_out << sh), sh = r - 32 (same integers).
+template <bool ASYM, bool TAPS, bool FAST>
+__device__ __forceinline__ void epi_hidden_tile(const int N, const LayerTaps& T, const CPtrs& C, const v16i& c,
+                                                int rs0, int zw_s, int nt, int g, int64_t row, bool row_ok, int z_out,
+                                                int lo, int8_t* out_row, bool packed, int n_store) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int n0 = nt * 32 + 8 * j + 4 * g;
         int val[4];
-        quad_acc<ASYM, TAPS>(L, T, C, c, j, n0, rs0, zw_s, row, row_ok, val);
+        quad_acc<ASYM, TAPS>(N, T, C, c, j, n0, rs0, zw_s, row, row_ok, val);
         const int4 M = *(const int4*)(C.M0 + n0);
-        const int4 R = *(const int4*)(C.rshift + n0);
-        const int Mv[4] = {M.x, M.y, M.z, M.w}, Rv[4] = {R.x, R.y, R.z, R.w};
+        const int Mv[4] = {M.x, M.y, M.z, M.w};
+        int code[4];
+        if (FAST) {
+            const int4 Z = *(const int4*)(C.rz + n0);
+            const int4 S = *(const int4*)(C.sh + n0);
+            const int Zv[4] = {Z.x, Z.y, Z.z, Z.w}, Sv[4] = {S.x, S.y, S.z, S.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int t = (__mulhi(val[i], Mv[i]) + Zv[i]) >> Sv[i];
+                code[i] = min(max(t, lo), 255);
+            }
+        } else {
+            const int4 R = *(const int4*)(C.rshift + n0);
+            const int Rv[4] = {R.x, R.y, R.z, R.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) code[i] = requant_code(val[i], Mv[i], Rv[i], z_out, lo);
+        }
         uint32_t pack = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            int code = requant_code(val[i], Mv[i], Rv[i], z_out, lo);
-            if (n0 + i >= L.N) code = 128;  // padding features are zero in the signed domain
+            if (n0 + i >= N) code[i] = 128;  // padding features are zero in the signed domain
             if (TAPS) {
-                if (T.act && row_ok && n0 + i < L.N) T.act[row * L.N + n0 + i] = (uint8_t)code;
+                if (T.act && row_ok && n0 + i < N) T.act[(int64_t)row * N + n0 + i] = (uint8_t)code[i];
             }
-            pack |= (uint32_t)((code ^ 0x80) & 255) << (8 * i);
+            pack |= (uint32_t)code[i] << (8 * i);
         }
+        pack ^= 0x80808080u;
         if (out_row) {
             if (packed) {
                 if (n0 < n_store) *(uint32_t*)(out_row + n0) = pack;
@@ -188,13 +229,13 @@ __device__ __forceinline__ void epi_hidden_tile(const LayerDev& L, const LayerTa
 
 // Last layer: y = (float)acc * m[n] for one tile, stored to y_row[n] (n < n_store).
 template <bool ASYM, bool TAPS>
-__device__ __forceinline__ void epi_last_tile(const LayerDev& L, const LayerTaps& T, const CPtrs& C, const v16i& c, int rs0, int zw_s, int nt, int g,
+__device__ __forceinline__ void epi_last_tile(const int N, const LayerTaps& T, const CPtrs& C, const v16i& c, int rs0, int zw_s, int nt, int g,
                                               int64_t row, bool row_ok, float* y_row, int n_store) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int n0 = nt * 32 + 8 * j + 4 * g;
         int val[4];
-        quad_acc<ASYM, TAPS>(L, T, C, c, j, n0, rs0, zw_s, row, row_ok, val);
+        quad_acc<ASYM, TAPS>(N, T, C, c, j, n0, rs0, zw_s, row, row_ok, val);
         const float4 mm = *(const float4*)(C.m + n0);
         const float mv[4] = {mm.x, mm.y, mm.z, mm.w};
 #pragma unroll

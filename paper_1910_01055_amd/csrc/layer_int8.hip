@@ -67,12 +67,12 @@ __global__ __launch_bounds__(256) void k_layer_int8(const NetDev* __restrict__ n
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[nb][mt] = zero16();
     }
-    const v4i* wptr[NB];
+    gv4i_ptr wptr[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         int nt = grp * NB + nb;
         nt = nt < L.NT ? nt : L.NT - 1;
-        wptr[nb] = (const v4i*)L.wp + (int64_t)nt * L.KS * 64 + lane;
+        wptr[nb] = (gv4i_ptr)L.wp + (int64_t)nt * L.KS * 64 + lane;
     }
 
     for (int ks0 = 0; ks0 < L.KS; ks0 += KC) {
@@ -128,6 +128,7 @@ __global__ __launch_bounds__(256) void k_layer_int8(const NetDev* __restrict__ n
 
     if (!active) return;
     const CPtrs C = global_consts(L);
+    const bool fast = !last && !ln && a.fast[l] != 0;
     static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
         constexpr int nb = decltype(nb_c)::value;
         const int nt = grp * NB + nb;
@@ -138,15 +139,18 @@ __global__ __launch_bounds__(256) void k_layer_int8(const NetDev* __restrict__ n
                 const bool row_ok = row < rows;
                 if (ln) {
                     // dequantized accumulators go to the LayerNorm kernel
-                    epi_last_tile<ASYM, TAPS>(L, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
+                    epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
                                               row_ok ? io.ln_x + row * L.N : nullptr, L.N);
                 } else if (last) {
                     // y = (float)acc * m; the head kernel follows
-                    epi_last_tile<ASYM, TAPS>(L, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
+                    epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
                                               row_ok ? io.y + row * L.N : nullptr, L.N);
+                } else if (fast) {
+                    epi_hidden_tile<ASYM, TAPS, true>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok, z_out,
+                                                      lo, row_ok ? io.out + row * L.N : nullptr, (L.N & 3) == 0, L.N);
                 } else {
-                    epi_hidden_tile<ASYM, TAPS>(L, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok, z_out, lo,
-                                                row_ok ? io.out + row * L.N : nullptr, (L.N & 3) == 0, L.N);
+                    epi_hidden_tile<ASYM, TAPS, false>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok, z_out,
+                                                       lo, row_ok ? io.out + row * L.N : nullptr, (L.N & 3) == 0, L.N);
                 }
             });
         }
@@ -233,7 +237,7 @@ aq_status launch_layer_int8(const FwdArgs& a, int l, const LayerIO& io, hipStrea
 aq_status launch_ln_tanh_rows(const FwdArgs& a, int l, const float* x, int8_t* out, int64_t rows, hipStream_t st) {
     const LayerDev& L = a.net.L[l];
     hipLaunchKernelGGL(k_ln_tanh_rows, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, x, rows, L.N, L.gamma,
-                       L.beta, a.net.ln_eps, a.net.actq, l + 1, out, a.t.ln[l], a.t.act[l]);
+                       L.beta, a.net.ln_eps, a.d_net->actq, l + 1, out, a.t.ln[l], a.t.act[l]);
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 

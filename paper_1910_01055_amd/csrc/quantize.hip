@@ -292,6 +292,7 @@ __global__ void k_layer_consts(const ActQ* __restrict__ actq, int layer, int req
                                const float* __restrict__ bias, const int32_t* __restrict__ rowsum, int N, int K,
                                float* __restrict__ m, int32_t* __restrict__ bias_q, int32_t* __restrict__ M0,
                                int32_t* __restrict__ rshift, int32_t* __restrict__ bias_fold,
+                               int32_t* __restrict__ rz, int32_t* __restrict__ sh, int* __restrict__ fast,
                                int* __restrict__ status) {
     int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
@@ -321,6 +322,18 @@ __global__ void k_layer_consts(const ActQ* __restrict__ actq, int layer, int req
         }
         M0[n] = (int32_t)q;
         rshift[n] = r;
+        // Short form of the same requantization for 33 <= r <= 54: the rounding constant 2^(r-1) has a
+        // zero low word, so (acc*M0 + 2^(r-1)) >> r = (mulhi(acc, M0) + 2^(r-33)) >> (r-32), and the
+        // output zero-point can ride along as z_out << (r-32).  One layer-wide flag says whether every
+        // channel qualifies.
+        if (r >= 33 && r <= 54) {
+            sh[n] = r - 32;
+            rz[n] = (1 << (r - 33)) + (actq[layer + 1].z << (r - 32));
+        } else {
+            sh[n] = 0;
+            rz[n] = 0;
+            atomicAnd(fast, 0);
+        }
     } else {
         M0[n] = 0;
         rshift[n] = 0;
@@ -413,10 +426,10 @@ aq_status launch_act_qparams(const RangesArg& r, int n, int in_u8, float qdenom,
 
 aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym, const float* s_w,
                               const int32_t* z_w, const float* bias, const int32_t* rowsum, int N, int K, float* m,
-                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int* status,
-                              hipStream_t st) {
+                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int32_t* rz,
+                              int32_t* sh, int* fast, int* status, hipStream_t st) {
     hipLaunchKernelGGL(k_layer_consts, dim3((N + 255) / 256), dim3(256), 0, st, actq, layer, requant, asym, s_w, z_w,
-                       bias, rowsum, N, K, m, bias_q, M0, rshift, bias_fold, status);
+                       bias, rowsum, N, K, m, bias_q, M0, rshift, bias_fold, rz, sh, fast, status);
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 

@@ -103,6 +103,31 @@ def test_forward_every_stage(aq, name, path, batch):
     P.close()
 
 
+@pytest.mark.parametrize("path", [0, 2])
+@pytest.mark.parametrize("hi1,hi2", [(0.02, 3.0), (3.0, 3e5), (1e-3, 1e-3), (40.0, 0.5)])
+def test_requant_forms(aq, path, hi1, hi2):
+    """Activation ranges far from the calibrated ones push the requantization multiplier out of the
+    window of the kernels' short form (r < 33: multiplier >= 1/4; r > 54: tiny multiplier): the
+    general form must give the same integers as the oracle there too."""
+    _say(f"requant_forms path={path} hi=({hi1},{hi2})")
+    net = synth.small_net([synth.fc(40, 64, "relu"), synth.fc(64, 96, "none"), synth.fc(96, 9, "none")],
+                          head="linear")
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, 70)
+    pol = O.OraclePolicy(net)
+    _, ranges = pol.forward_fp32(params, obs)
+    ranges = [ranges[0], (np.float32(0.0), np.float32(hi1)), (np.float32(-hi2), np.float32(hi2))]
+    pol.quantize_params(params, ranges)
+    r = np.concatenate([pol.q[0]["rshift"], pol.q[1]["rshift"]])
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    U.check_quantized_params(aq, P, pol, net)
+    P.policy_set_path(path)
+    actions, t = U.gpu_forward(P, net, obs)
+    U.compare_forward(net, pol, obs, actions, t)
+    _say(f"  shifts span {r.min()}..{r.max()}")
+    P.close()
+
+
 # ------------------------------------------------------------------ full sizes, launch configuration of the bench
 @pytest.mark.parametrize("name,batch,sample", [("cfg1", 256, None), ("cfg2", 4096, None), ("cfg3", 65536, 2048),
                                                ("cfg3", 16, None), ("cfg5", 16384, 384), ("cfg4", 256, 64)])
@@ -189,6 +214,12 @@ def test_edges(aq):
     bad[1][3, 5] = np.inf
     P.quantize_params([U.to_dev(x) for x in bad], d[1], d[2], d[3], ranges)
     assert P.policy_status() == aq.ENONFINITE
+    # a requantization multiplier that needs a shift beyond 62 is reported, as the oracle does
+    huge = [ranges[0], (np.float32(0), np.float32(1e30)), ranges[2]]
+    with pytest.raises(ValueError):
+        O.OraclePolicy(net).quantize_params(params, huge)
+    P.quantize_params(d[0], d[1], d[2], d[3], huge)
+    assert P.policy_status() == aq.ERANGE
     P.close()
     # all-zero weights: scale 1, codes 0, actions tanh(0) = 0
     zero = [{"w": np.zeros_like(p["w"]), "b": np.zeros_like(p["b"])} for p in params]
