@@ -23,6 +23,7 @@ HBM_PEAK_GBS = 8000.0
 
 
 def _events_ms(torch, fn, n):
+    """Average ms per fn() call, launched one by one from the host (includes host launch cost)."""
     st = torch.cuda.current_stream()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(st)
@@ -31,6 +32,52 @@ def _events_ms(torch, fn, n):
     e1.record(st)
     e1.synchronize()
     return e0.elapsed_time(e1) / n
+
+
+_USE_GRAPHS = True
+
+
+def _capture(torch, body):
+    """Records body() into a HIP graph (the library launches on torch's current stream, which is the
+    capture stream inside torch.cuda.graph).  Returns None if capture is not possible."""
+    if not _USE_GRAPHS:
+        return None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            body()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            body()
+        return g
+    except Exception as e:  # noqa: BLE001
+        print(f"bench.py: graph capture unavailable ({e}); timing eager launches", file=sys.stderr)
+        return None
+
+
+def _graph_ms(torch, fn, n, replays=5):
+    """Average ms per fn() call with n calls replayed from one HIP graph: the device-side rate,
+    free of per-launch host cost.  Falls back to eager launches."""
+    g = _capture(torch, lambda: [fn() for _ in range(n)])
+    if g is None:
+        return _events_ms(torch, fn, n)
+    g.replay()
+    torch.cuda.synchronize()
+    st = torch.cuda.current_stream()
+    best = None
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(replays):
+            g.replay()
+        e1.record(st)
+        e1.synchronize()
+        ms = e0.elapsed_time(e1) / (replays * n)
+        best = ms if best is None else min(best, ms)
+    return best
 
 
 def forward_workload(torch, aq, synth, U, name, batch, iters, warm=20):
@@ -56,7 +103,8 @@ def forward_workload(torch, aq, synth, U, name, batch, iters, warm=20):
     for _ in range(warm):
         fwd()
     torch.cuda.synchronize()
-    ms = min(_events_ms(torch, fwd, iters) for _ in range(3))
+    ms_eager = min(_events_ms(torch, fwd, iters) for _ in range(3))
+    ms = _graph_ms(torch, fwd, min(iters, 200))
     f32 = lambda: P.policy_forward_fp32(w, b, g, be, d_obs, act)
     f32()
     torch.cuda.synchronize()
@@ -64,7 +112,7 @@ def forward_workload(torch, aq, synth, U, name, batch, iters, warm=20):
     ops = 2.0 * synth.macs_per_sample(net) * batch
     out = {"workload": f"{name} batch {batch}", "us_per_launch": ms * 1e3, "inferences_per_s": batch / (ms * 1e-3),
            "tops": ops / (ms * 1e-3) / 1e12, "frac_int8_mfma_peak": ops / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
-           "fp32_actor_us_per_launch": ms32 * 1e3}
+           "us_per_launch_eager": ms_eager * 1e3, "fp32_actor_us_per_launch": ms32 * 1e3}
     return out, (P, w, b, g, be, ranges, d_obs, act, net, params, obs)
 
 
@@ -78,7 +126,7 @@ def quantize_workload(torch, aq, synth, U, scheme, iters=30, n_buf=40):
     dsts = [torch.empty(n, dtype=torch.uint8, device=U.DEV) for _ in range(n_buf)]
     scale = torch.empty(rows, dtype=torch.float32, device=U.DEV)
     zp = torch.empty(rows, dtype=torch.int32, device=U.DEV)
-    ws = torch.zeros(16, dtype=torch.int32, device=U.DEV)
+    ws = torch.zeros(4096, dtype=torch.int32, device=U.DEV)
     i = [0]
 
     def one():
@@ -88,9 +136,12 @@ def quantize_workload(torch, aq, synth, U, scheme, iters=30, n_buf=40):
     for _ in range(n_buf):
         one()
     torch.cuda.synchronize()
-    ms = min(_events_ms(torch, one, iters) for _ in range(3))
+    ms_eager = min(_events_ms(torch, one, iters) for _ in range(3))
+    i[0] = 0
+    ms = _graph_ms(torch, one, n_buf)   # one pass over all the distinct buffers per replay
     gbs = 5.0 * n / (ms * 1e-3) / 1e9
-    return {"workload": f"quantize 4M fp32 params, {scheme}", "us_per_call": ms * 1e3, "GBps_algorithmic": gbs,
+    return {"workload": f"quantize 4M fp32 params, {scheme}, {n_buf} rotating buffers (HBM-resident source)",
+            "us_per_call": ms * 1e3, "us_per_call_eager": ms_eager * 1e3, "GBps_algorithmic": gbs,
             "frac_hbm_peak": gbs / HBM_PEAK_GBS}
 
 
@@ -120,6 +171,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--eager", action="store_true", help="launch from the host instead of replaying HIP graphs "
+                    "(for profiler runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain 64 MiB device-to-device copies (reference for scaling HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path is measured on ONE GPU (the batch is the set of independent actors; "
@@ -128,9 +183,20 @@ def main():
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = 64 << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": 20}))
+        return
     from paper_1910_01055_amd import binding as aq, synth
     import gpu_util as U
     aq.load()
+    global _USE_GRAPHS
+    _USE_GRAPHS = not args.eager
 
     batch = 4096
     head, ctx = forward_workload(torch, aq, synth, U, "cfg2", batch, iters=500)
@@ -144,12 +210,24 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    # the actor loop as a HIP graph: PULL_EVERY steps (one model pull + PULL_EVERY inference calls) per replay
+    n_rep, rest = divmod(args.steps, PULL_EVERY)
+    graph = _capture(torch, lambda: [step(i) for i in range(PULL_EVERY)]) if n_rep else None
+    if graph is not None:
+        graph.replay()
+    torch.cuda.synchronize()
     st = torch.cuda.current_stream()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record(st)
-    for i in range(args.steps):
-        step(i)
+    if graph is not None:
+        for _ in range(n_rep):
+            graph.replay()
+        for i in range(rest):
+            step(i + 1)
+    else:
+        for i in range(args.steps):
+            step(i)
     e1.record(st)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -166,6 +244,8 @@ def main():
         "config": {"workload": "cfg2: D4PG-style actor MLP 67-256(LN+tanh)-256-256-21(tanh), batch 4096, "
                                "per-channel symmetric int8 weights, static uint8 activations",
                    "batch": batch, "pull_every": PULL_EVERY, "quantize_params_us": qp_ms * 1e3,
+                   "launch": "hip graph replay" if graph is not None else "eager",
+                   "eager_us_per_launch": head["us_per_launch_eager"],
                    "device_ms_per_step": e0.elapsed_time(e1) / args.steps},
         "pct_int8_mfma_peak": 100.0 * achieved / INT8_PEAK_TOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",

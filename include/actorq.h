@@ -128,8 +128,10 @@ aq_status aq_policy_status(aq_policy* p, void* stream);
  * d_w[rows][cols] to 8-bit codes in canonical row-major order.
  *   AQ_W_TENSOR_ASYM_U8: one (scale, zero-point) for the whole tensor -> d_scale[1], d_zp[1], uint8 codes.
  *   AQ_W_CHANNEL_SYM_S8: one scale per row -> d_scale[rows], d_zp[rows] = 0, int8 codes.
- * d_workspace: at least 64 bytes of device memory the call may overwrite (cleared by the call).
- * cols must be a multiple of 4 and d_w 16-byte aligned.  Non-finite inputs set d_workspace[2] (int32) to 1. */
+ * d_workspace: at least 16 KiB of device memory the call may overwrite (partial ranges of the
+ * workgroups).  Word 2 of it (int32) is a sticky flag: the call sets it to 1 when it meets a
+ * non-finite input and never clears it, so zero it once before the first call.
+ * cols must be a multiple of 4 and d_w 16-byte aligned. */
 aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int32_t wscheme, int32_t qdenom,
                              void* d_codes, float* d_scale, int32_t* d_zp, void* d_workspace, void* stream);
 

@@ -42,6 +42,62 @@ __device__ __forceinline__ int rint_clamp(float v, int lo, int hi) {
     return (int)r;
 }
 
+// Sec. 3.2's round(W / delta), the quotient formed by IEEE fp32 division, at the price of one
+// multiply in the common case.  m = w * (1/s) differs from the true quotient by a few ulp; unless m
+// sits within a guard band of a half-integer (where that could flip the rounding, or where the
+// fp32-rounded quotient could be an exact tie), round(m) IS round(fl(w / s)).  Lanes inside the band
+// (a few in a million) take the division.  `rcp_ok` is false when 1/s is not usable (s denormal).
+struct QuantScale {
+    float s, inv;
+    bool rcp_ok;
+};
+__device__ __forceinline__ QuantScale make_quant_scale(float s) {
+    QuantScale q;
+    q.s = s;
+    q.inv = 1.0f / s;
+    q.rcp_ok = q.inv <= 3.0e38f && s >= 1.2e-38f;
+    return q;
+}
+__device__ __forceinline__ int quant_code(float w, const QuantScale& q, int lo, int hi) {
+    if (!q.rcp_ok) return rint_clamp(w / q.s, lo, hi);
+    const float m = w * q.inv;
+    const float r = rintf(m);
+    // distance to the nearest half-integer is 0.5 - |m - r|; guard band 2^-20 relative + 2^-20 absolute
+    const float slack = 0.5f - fabsf(m - r);
+    if (slack < fabsf(m) * 9.5367431640625e-7f + 9.5367431640625e-7f) return rint_clamp(w / q.s, lo, hi);
+    if (!(r >= (float)lo)) return lo;
+    if (r > (float)hi) return hi;
+    return (int)r;
+}
+
+// Four codes at once, packed little-endian into one word (code & 255 each): the guard-band test of
+// quant_code is shared by the four elements, so the common case has a single (not taken) branch.
+__device__ __forceinline__ uint32_t quant_code4(float4 v, const QuantScale& q, int lo, int hi, int add) {
+    float r0, r1, r2, r3;
+    bool exact = !q.rcp_ok;
+    if (!exact) {
+        const float m0 = v.x * q.inv, m1 = v.y * q.inv, m2 = v.z * q.inv, m3 = v.w * q.inv;
+        r0 = rintf(m0);
+        r1 = rintf(m1);
+        r2 = rintf(m2);
+        r3 = rintf(m3);
+        const float c = 9.5367431640625e-7f;  // 2^-20
+        exact = (0.5f - fabsf(m0 - r0) < fabsf(m0) * c + c) | (0.5f - fabsf(m1 - r1) < fabsf(m1) * c + c) |
+                (0.5f - fabsf(m2 - r2) < fabsf(m2) * c + c) | (0.5f - fabsf(m3 - r3) < fabsf(m3) * c + c);
+    }
+    if (exact) {
+        r0 = rintf(v.x / q.s);
+        r1 = rintf(v.y / q.s);
+        r2 = rintf(v.z / q.s);
+        r3 = rintf(v.w / q.s);
+    }
+    // fmaxf(NaN, lo) = lo: same saturation rule as rint_clamp
+    const float flo = (float)lo, fhi = (float)hi;
+    const int c0 = (int)fminf(fmaxf(r0, flo), fhi) + add, c1 = (int)fminf(fmaxf(r1, flo), fhi) + add;
+    const int c2 = (int)fminf(fmaxf(r2, flo), fhi) + add, c3 = (int)fminf(fmaxf(r3, flo), fhi) + add;
+    return (uint32_t)(c0 & 255) | ((uint32_t)(c1 & 255) << 8) | ((uint32_t)(c2 & 255) << 16) | ((uint32_t)c3 << 24);
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));

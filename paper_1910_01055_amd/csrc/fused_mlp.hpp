@@ -145,6 +145,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const int K0 = c.K0, Kp = c.Kp0;
         const float s0 = a.actq[0].s;
         const int z0 = a.actq[0].z;
+        const QuantScale qs0 = make_quant_scale(s0);
         if (!c.in_u8 && (K0 & 3) == 0) {
             // four observations per lane: one 16-byte load, one packed 32-bit LDS store
             const int K4 = K0 >> 2;
@@ -154,8 +155,8 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 uint32_t pack = 0;
                 if (row0 + m < c.batch) {
                     const float4 v = src[idx];
-                    const int c0 = rint_clamp(v.x / s0, -z0, 255 - z0) + z0, c1 = rint_clamp(v.y / s0, -z0, 255 - z0) + z0;
-                    const int c2 = rint_clamp(v.z / s0, -z0, 255 - z0) + z0, c3 = rint_clamp(v.w / s0, -z0, 255 - z0) + z0;
+                    const int c0 = quant_code(v.x, qs0, -z0, 255 - z0) + z0, c1 = quant_code(v.y, qs0, -z0, 255 - z0) + z0;
+                    const int c2 = quant_code(v.z, qs0, -z0, 255 - z0) + z0, c3 = quant_code(v.w, qs0, -z0, 255 - z0) + z0;
                     pack = (uint32_t)c0 | ((uint32_t)c1 << 8) | ((uint32_t)c2 << 16) | ((uint32_t)c3 << 24);
                     if (TAPS) {
                         if (t.a0) *(uint32_t*)(t.a0 + (row0 + m) * K0 + 4 * k4) = pack;
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                     if (c.in_u8) {
                         code = ((const uint8_t*)c.obs)[row * K0 + k];
                     } else {
-                        code = rint_clamp(((const float*)c.obs)[row * K0 + k] / s0, -z0, 255 - z0) + z0;
+                        code = quant_code(((const float*)c.obs)[row * K0 + k], qs0, -z0, 255 - z0) + z0;
                     }
                     if (TAPS) {
                         if (t.a0) t.a0[row * K0 + k] = (uint8_t)code;
@@ -209,6 +210,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const int Np = L.NT * 32;
         const float s_out = L.s_out;
         const int z_out = L.z_out, fast = L.fast;
+        const QuantScale qs_out = make_quant_scale(s_out);
         const int lo = (!last && L.act == AQ_ACT_RELU) ? z_out : 0;
         const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
         const int ldy = Np;  // last layer: fp32 row stride of y in LDS
@@ -372,7 +374,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                                     float x = __int_as_float(acc[nb][mt][4 * j + i]);
                                     float y = (x - mean[mt]) * inv[mt] * gv[i] + bv[i];
                                     float tv = tanh_fast(y);
-                                    int code = rint_clamp(tv / s_out, -z_out, 255 - z_out) + z_out;
+                                    int code = quant_code(tv, qs_out, -z_out, 255 - z_out) + z_out;
                                     if (n >= L.N) code = 128;
                                     if (TAPS) {
                                         if (row_ok && n < L.N) {

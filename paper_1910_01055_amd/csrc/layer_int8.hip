@@ -54,6 +54,7 @@ __global__ __launch_bounds__(256) void k_layer_int8(const NetDev* __restrict__ n
         s0 = a.actq[0].s;
         z0 = a.actq[0].z;
     }
+    const QuantScale qs0 = make_quant_scale(s0);
     int z_out = 0;
     if (!last) z_out = a.actq[l + 1].z;
     const int lo = (!last && L.act == AQ_ACT_RELU) ? z_out : 0;
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(256) void k_layer_int8(const NetDev* __restrict__ n
                     if (first) {
                         int code;
                         if (a.in_u8) code = ((const uint8_t*)io.in)[off];
-                        else code = rint_clamp(((const float*)io.in)[off] / s0, -z0, 255 - z0) + z0;
+                        else code = quant_code(((const float*)io.in)[off], qs0, -z0, 255 - z0) + z0;
                         if (TAPS) {
                             if (t.a0 && blockIdx.y == 0) t.a0[off] = (uint8_t)code;
                         }
@@ -168,6 +169,7 @@ __global__ __launch_bounds__(256) void k_ln_tanh_rows(const float* __restrict__ 
     if (row >= rows) return;
     const float s_out = actq[out_idx].s;
     const int z_out = actq[out_idx].z;
+    const QuantScale qs_out = make_quant_scale(s_out);
     const float* xr = x + row * N;
     float s = 0.0f;
     for (int n = lane; n < N; n += 64) s += xr[n];
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(256) void k_ln_tanh_rows(const float* __restrict__ 
         float y = (xr[n] - mean) * inv * gamma[n] + beta[n];
         float t = tanh_fast(y);
         if (tap_ln) tap_ln[row * N + n] = t;
-        int code = rint_clamp(t / s_out, -z_out, 255 - z_out) + z_out;
+        int code = quant_code(t, qs_out, -z_out, 255 - z_out) + z_out;
         if (tap_act) tap_act[row * N + n] = (uint8_t)code;
         out[row * N + n] = (int8_t)(code - 128);
     }

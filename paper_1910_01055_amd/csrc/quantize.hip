@@ -82,27 +82,82 @@ __global__ __launch_bounds__(256) void k_range_nonneg(const float4* __restrict__
     }
 }
 
-// per-tensor asymmetric codes, canonical order, 4 per thread and iteration
+// Pass 1 of the per-tensor scheme for a large flat tensor: every workgroup publishes its partial
+// range (hi bits, -lo bits, non-finite flag) in part[3 * block]; nothing has to be cleared first.
+__global__ __launch_bounds__(256) void k_range_partials(const float4* __restrict__ w4, int64_t n4,
+                                                        uint32_t* __restrict__ part) {
+    float hi = 0.0f, nlo = 0.0f;
+    int bad = 0;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        const float4 v = w4[i];
+        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bad |= !finite_f(e[j]);
+            hi = e[j] > hi ? e[j] : hi;
+            const float t = -e[j];
+            nlo = t > nlo ? t : nlo;
+        }
+    }
+    hi = wave_max(hi);
+    nlo = wave_max(nlo);
+    bad = wave_or_i32(bad);
+    __shared__ float s_hi[4], s_nlo[4];
+    __shared__ int s_bad[4];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) {
+        s_hi[wv] = hi;
+        s_nlo[wv] = nlo;
+        s_bad[wv] = bad;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        part[3 * blockIdx.x + 0] = __float_as_uint(fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3])));
+        part[3 * blockIdx.x + 1] = __float_as_uint(fmaxf(fmaxf(s_nlo[0], s_nlo[1]), fmaxf(s_nlo[2], s_nlo[3])));
+        part[3 * blockIdx.x + 2] = (uint32_t)(s_bad[0] | s_bad[1] | s_bad[2] | s_bad[3]);
+    }
+}
+
+// Pass 2: every workgroup folds the partials (a few KiB, cache resident), then streams its share of
+// the tensor: 16 bytes in, 4 codes out per thread and iteration.  The second read of the tensor
+// comes from the last-level cache for tensors that fit it.
 __global__ __launch_bounds__(256) void k_quant_asym_flat(const float4* __restrict__ w4, int64_t n4,
-                                                         const uint32_t* __restrict__ mm, float qdenom,
+                                                         const uint32_t* __restrict__ part, int n_part, float qdenom,
                                                          uint32_t* __restrict__ codes, float* __restrict__ scale,
-                                                         int32_t* __restrict__ zp) {
+                                                         int32_t* __restrict__ zp, uint32_t* __restrict__ flag) {
+    float hi = 0.0f, nlo = 0.0f;
+    int bad = 0;
+    for (int b = threadIdx.x; b < n_part; b += 256) {
+        hi = fmaxf(hi, __uint_as_float(part[3 * b + 0]));
+        nlo = fmaxf(nlo, __uint_as_float(part[3 * b + 1]));
+        bad |= (int)part[3 * b + 2];
+    }
+    hi = wave_max(hi);
+    nlo = wave_max(nlo);
+    bad = wave_or_i32(bad);
+    __shared__ float s_hi[4], s_nlo[4];
+    __shared__ int s_bad[4];
+    if ((threadIdx.x & 63) == 0) {
+        s_hi[threadIdx.x >> 6] = hi;
+        s_nlo[threadIdx.x >> 6] = nlo;
+        s_bad[threadIdx.x >> 6] = bad;
+    }
+    __syncthreads();
+    hi = fmaxf(fmaxf(s_hi[0], s_hi[1]), fmaxf(s_hi[2], s_hi[3]));
+    nlo = fmaxf(fmaxf(s_nlo[0], s_nlo[1]), fmaxf(s_nlo[2], s_nlo[3]));
     float s;
     int z;
-    asym_qparams(__uint_as_float(mm[0]), __uint_as_float(mm[1]), qdenom, s, z);
+    asym_qparams(hi, nlo, qdenom, s, z);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         scale[0] = s;
         zp[0] = z;
+        if (s_bad[0] | s_bad[1] | s_bad[2] | s_bad[3]) flag[0] = 1u;
     }
+    const QuantScale qs = make_quant_scale(s);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        float4 v = w4[i];
-        uint32_t q0 = rint_clamp(v.x / s, -z, 255 - z) + z;
-        uint32_t q1 = rint_clamp(v.y / s, -z, 255 - z) + z;
-        uint32_t q2 = rint_clamp(v.z / s, -z, 255 - z) + z;
-        uint32_t q3 = rint_clamp(v.w / s, -z, 255 - z) + z;
-        codes[i] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
-    }
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
+        codes[i] = quant_code4(w4[i], qs, -z, 255 - z, z);
 }
 
 // per-channel symmetric codes, canonical order: one wavefront per row, the row lives in
@@ -136,16 +191,57 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_flat(const float4* __res
         if (bad) atomicOr(&mm[2], 1u);
     }
     uint32_t* dst = codes + row * cols4;
+    const QuantScale qs = make_quant_scale(s);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         int c = lane + 64 * r;
         if (c < cols4) {
-            uint32_t q0 = (uint32_t)rint_clamp(v[r].x / s, -127, 127) & 255u;
-            uint32_t q1 = (uint32_t)rint_clamp(v[r].y / s, -127, 127) & 255u;
-            uint32_t q2 = (uint32_t)rint_clamp(v[r].z / s, -127, 127) & 255u;
-            uint32_t q3 = (uint32_t)rint_clamp(v[r].w / s, -127, 127) & 255u;
-            dst[c] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+            dst[c] = quant_code4(v[r], qs, -127, 127, 0);
         }
+    }
+}
+
+// Longer rows: one workgroup per row, R float4 per thread held in registers between the |w|
+// reduction and the rounding (still one pass over HBM).  Many small workgroups keep the memory
+// pipeline of every CU busy while others are in their arithmetic phase.
+template <int R>
+__global__ __launch_bounds__(256) void k_quant_sym_row_wg(const float4* __restrict__ w4, int cols4,
+                                                          uint32_t* __restrict__ codes, float* __restrict__ scale,
+                                                          int32_t* __restrict__ zp, uint32_t* __restrict__ mm) {
+    const int64_t row = blockIdx.x;
+    const float4* src = w4 + row * cols4;
+    float4 v[R];
+    float amax = 0.0f;
+    int bad = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int c = threadIdx.x + 256 * r;
+        v[r] = c < cols4 ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const float a0 = fabsf(v[r].x), a1 = fabsf(v[r].y), a2 = fabsf(v[r].z), a3 = fabsf(v[r].w);
+        bad |= !(a0 <= FLT_MAX) | !(a1 <= FLT_MAX) | !(a2 <= FLT_MAX) | !(a3 <= FLT_MAX);
+        amax = fmaxf(fmaxf(amax, fmaxf(a0, a1)), fmaxf(a2, a3));
+    }
+    amax = wave_max(amax);
+    __shared__ float s_max[4];
+    if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = amax;
+    if (bad) atomicOr(&mm[2], 1u);
+    __syncthreads();
+    amax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+    float s = amax / 127.0f;
+    if (amax == 0.0f) s = 1.0f;
+    if (threadIdx.x == 0) {
+        scale[row] = s;
+        zp[row] = 0;
+    }
+    const QuantScale qs = make_quant_scale(s);
+    uint32_t* dst = codes + row * cols4;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int c = threadIdx.x + 256 * r;
+        if (c < cols4) dst[c] = quant_code4(v[r], qs, -127, 127, 0);
     }
 }
 
@@ -183,13 +279,9 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_long(const float4* __res
         if (bad) atomicOr(&mm[2], 1u);
     }
     uint32_t* dst = codes + row * cols4;
+    const QuantScale qs = make_quant_scale(s);
     for (int c = threadIdx.x; c < cols4; c += 256) {
-        float4 v = src[c];
-        uint32_t q0 = (uint32_t)rint_clamp(v.x / s, -127, 127) & 255u;
-        uint32_t q1 = (uint32_t)rint_clamp(v.y / s, -127, 127) & 255u;
-        uint32_t q2 = (uint32_t)rint_clamp(v.z / s, -127, 127) & 255u;
-        uint32_t q3 = (uint32_t)rint_clamp(v.w / s, -127, 127) & 255u;
-        dst[c] = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+        dst[c] = quant_code4(src[c], qs, -127, 127, 0);
     }
 }
 
@@ -232,8 +324,9 @@ __global__ __launch_bounds__(256) void k_quant_rows_packed(const float* __restri
     }
     int8_t* tile_row = wp + ((int64_t)(n >> 5) * KS * 64 + (n & 31)) * 16;
     int sum = 0;
+    const QuantScale qs = make_quant_scale(s);
     for (int k = lane; k < K; k += 64) {
-        int q = SYM ? rint_clamp(src[k] / s, -127, 127) : rint_clamp(src[k] / s, -z, 255 - z) + z - 128;
+        int q = SYM ? quant_code(src[k], qs, -127, 127) : quant_code(src[k], qs, -z, 255 - z) + z - 128;
         sum += q;
         tile_row[((int64_t)(k >> 5) * 64 + 32 * ((k & 31) >> 4)) * 16 + (k & 15)] = (int8_t)q;
     }
@@ -361,33 +454,33 @@ aq_status launch_fill_u32(uint32_t* p, int n, uint32_t v, hipStream_t st) {
 aq_status launch_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int wscheme, float qdenom,
                                  void* d_codes, float* d_scale, int32_t* d_zp, uint32_t* d_ws, hipStream_t st) {
     const int64_t n = rows * cols;
-    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, d_ws, 16, 0u);
+    const float4* w4 = (const float4*)d_w;
+    uint32_t* c4 = (uint32_t*)d_codes;
     if (wscheme == AQ_W_TENSOR_ASYM_U8) {
         const int64_t n4 = n / 4;
-        // enough workgroups to keep every CU's memory pipeline full, few enough that the
-        // one-atomic-per-block reduction stays negligible
-        int g = grid_for(n4, 256 * 4, 2048);
-        hipLaunchKernelGGL(k_range_nonneg, dim3(g), dim3(256), 0, st, (const float4*)d_w, n4, d_w, n, d_ws);
-        int g2 = grid_for(n4, 256 * 2, 4096);
-        hipLaunchKernelGGL(k_quant_asym_flat, dim3(g2), dim3(256), 0, st, (const float4*)d_w, n4, d_ws, qdenom,
-                           (uint32_t*)d_codes, d_scale, d_zp);
+        // enough workgroups to keep every CU's memory pipeline full; partial ranges go to d_ws[16..]
+        const int g1 = grid_for(n4, 256 * 4, 1024);
+        hipLaunchKernelGGL(k_range_partials, dim3(g1), dim3(256), 0, st, w4, n4, d_ws + 16);
+        const int g2 = grid_for(n4, 256 * 4, 2048);
+        hipLaunchKernelGGL(k_quant_asym_flat, dim3(g2), dim3(256), 0, st, w4, n4, d_ws + 16, g1, qdenom, c4, d_scale,
+                           d_zp, d_ws + 2);
     } else {
         const int cols4 = (int)(cols / 4);
-        const int g = (int)((rows + 3) / 4);
-        const float4* w4 = (const float4*)d_w;
-        uint32_t* c4 = (uint32_t*)d_codes;
-#define AQ_ROWS_FLAT(R)                                                                                         \
-    hipLaunchKernelGGL(k_quant_sym_rows_flat<R>, dim3(g), dim3(256), 0, st, w4, rows, cols4, c4, d_scale, d_zp, \
-                       d_ws)
-        if (cols4 <= 64) AQ_ROWS_FLAT(1);
-        else if (cols4 <= 128) AQ_ROWS_FLAT(2);
-        else if (cols4 <= 256) AQ_ROWS_FLAT(4);
-        else if (cols4 <= 512) AQ_ROWS_FLAT(8);
-        else if (cols4 <= 1024) AQ_ROWS_FLAT(16);
-        else
-            hipLaunchKernelGGL(k_quant_sym_rows_long, dim3((unsigned)rows), dim3(256), 0, st, w4, rows, cols4, c4,
-                               d_scale, d_zp, d_ws);
-#undef AQ_ROWS_FLAT
+        if (cols4 <= 64) {
+            hipLaunchKernelGGL(k_quant_sym_rows_flat<1>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, w4, rows,
+                               cols4, c4, d_scale, d_zp, d_ws);
+        } else {
+#define AQ_ROW_WG(R) \
+    hipLaunchKernelGGL(k_quant_sym_row_wg<R>, dim3((unsigned)rows), dim3(256), 0, st, w4, cols4, c4, d_scale, d_zp, d_ws)
+            if (cols4 <= 256) AQ_ROW_WG(1);
+            else if (cols4 <= 512) AQ_ROW_WG(2);
+            else if (cols4 <= 1024) AQ_ROW_WG(4);
+            else if (cols4 <= 2048) AQ_ROW_WG(8);
+            else
+                hipLaunchKernelGGL(k_quant_sym_rows_long, dim3((unsigned)rows), dim3(256), 0, st, w4, rows, cols4, c4,
+                                   d_scale, d_zp, d_ws);
+#undef AQ_ROW_WG
+        }
     }
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }

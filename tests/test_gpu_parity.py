@@ -29,7 +29,8 @@ def test_quantize_tensor(aq, rows, cols, scheme):
     ns = 1 if asym else rows
     scale = torch.zeros(ns, dtype=torch.float32, device=U.DEV)
     zp = torch.full((ns,), -1, dtype=torch.int32, device=U.DEV)
-    ws = torch.ones(16, dtype=torch.int32, device=U.DEV)
+    ws = torch.ones(4096, dtype=torch.int32, device=U.DEV)
+    ws[2] = 0  # the sticky non-finite flag
     aq.quantize_tensor(d_w, rows, cols, scheme, 255, codes, scale, zp, ws)
     torch.cuda.synchronize()
     if asym:
@@ -48,11 +49,12 @@ def test_quantize_tensor_literal_denominator_and_nonfinite(aq):
     codes = torch.zeros(1, 4, dtype=torch.uint8, device=U.DEV)
     scale = torch.zeros(1, dtype=torch.float32, device=U.DEV)
     zp = torch.zeros(1, dtype=torch.int32, device=U.DEV)
-    ws = torch.zeros(16, dtype=torch.int32, device=U.DEV)
+    ws = torch.zeros(4096, dtype=torch.int32, device=U.DEV)
     aq.quantize_tensor(U.to_dev(w), 1, 4, "tensor_asym_u8", 256, codes, scale, zp, ws)
     assert codes.cpu().numpy().tolist() == [[0, 128, 192, 255]] and float(scale[0]) == 1 / 128 and int(zp[0]) == 128
     for scheme in ("tensor_asym_u8", "channel_sym_s8"):
         w = np.array([[0.5, np.nan, 1.0, 2.0]], np.float32)
+        ws.zero_()
         aq.quantize_tensor(U.to_dev(w), 1, 4, scheme, 255, codes, scale, zp, ws)
         torch.cuda.synchronize()
         assert int(ws[2]) == 1
