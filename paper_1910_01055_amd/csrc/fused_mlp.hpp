@@ -262,27 +262,29 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
             if (g0 == 0) lds_barrier();
             if (!ln) {
                 if (active) {
-                    static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
-                        constexpr int nb = decltype(nb_c)::value;
-                        const int nt = grp * NB + nb;
-                        if (nt < L.NT) {
-                            static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
-                                constexpr int mt = decltype(mt_c)::value;
-                                const int m = mt * 32 + (lane & 31);
-                                const int64_t row = row0 + m;
-                                const bool row_ok = row < c.batch;
-                                if (last)
-                                    epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
-                                                              (float*)out + m * ldy, ldy);
-                                else if (fast)
-                                    epi_hidden_tile<ASYM, TAPS, true>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row,
-                                                                      row_ok, z_out, lo, out + m * ld, true, Np);
-                                else
-                                    epi_hidden_tile<ASYM, TAPS, false>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row,
-                                                                       row_ok, z_out, lo, out + m * ld, true, Np);
-                            });
-                        }
-                    });
+                    const int m0 = lane & 31;
+                    if (last) {
+                        static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
+                            constexpr int nb = decltype(nb_c)::value;
+                            const int nt = grp * NB + nb;
+                            if (nt < L.NT) {
+                                static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
+                                    constexpr int mt = decltype(mt_c)::value;
+                                    const int m = mt * 32 + m0;
+                                    const int64_t row = row0 + m;
+                                    epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row,
+                                                              row < c.batch, (float*)out + m * ldy, ldy, nullptr, 0);
+                                });
+                            }
+                        });
+                    } else if (fast) {
+                        epi_hidden_wave<MT, NB, ASYM, TAPS, true>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row0 + m0, c.batch,
+                                                                  false, z_out, lo, out + m0 * ld, 32 * ld, true, Np);
+                    } else {
+                        epi_hidden_wave<MT, NB, ASYM, TAPS, false>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row0 + m0,
+                                                                   c.batch, false, z_out, lo, out + m0 * ld, 32 * ld, true,
+                                                                   Np);
+                    }
                 }
             } else {
                 // LayerNorm over the layer's N features (all resident in this one pass: ngroups <= FW),

@@ -96,7 +96,10 @@ __device__ __forceinline__ void mma_prefetch(gv4i_ptr (&wptr)[NB], int ks_begin,
 template <int MT, int NB, bool ASYM, int PF>
 __device__ __forceinline__ void mma_run(gv4i_ptr (&wptr)[NB], v4i (&wreg)[PF][NB], const int8_t* xs, int ld,
                                         int ks_begin, int ks_end, int ks_lds0, v16i (&acc)[NB][MT], v16i (&rs)[MT],
-                                        int lane) {
+                                        int lane, int ks_pf_end = -1) {
+    // ks_pf_end: the weight pipeline keeps loading up to this k-step (beyond ks_end when the caller
+    // walks K in chunks and calls again for the next chunk; chunk starts must be multiples of PF)
+    if (ks_pf_end < 0) ks_pf_end = ks_end;
     const int8_t* xrow = xs + (lane & 31) * ld + (lane >> 5) * 16;
     v4i ones;
     ones[0] = ones[1] = ones[2] = ones[3] = 0x01010101;
@@ -227,10 +230,91 @@ __device__ __forceinline__ void epi_hidden_tile(const int N, const LayerTaps& T,
     }
 }
 
-// Last layer: y = (float)acc * m[n] for one tile, stored to y_row[n] (n < n_store).
+// Hidden-layer epilogue of a wave's whole tile set (NB feature tiles x MT row tiles).  The
+// per-channel constants of a feature quad are loaded once and shared by the MT row tiles, and the
+// next quad's constants are requested before the current quad is processed, so the (global or LDS)
+// load latency is paid once, not once per quad.
+//   out0: this lane's row of row tile 0 in the destination (LDS staging buffer or global rows);
+//   out_mt_stride: bytes between consecutive row tiles (32 rows); guard_rows: skip rows >= rows.
+struct QuadConsts {
+    int4 bf, M, Z, S;
+};
+template <bool FAST>
+__device__ __forceinline__ QuadConsts load_quad_consts(const CPtrs& C, int n0) {
+    QuadConsts q;
+    q.bf = *(const int4*)(C.bias_fold + n0);
+    q.M = *(const int4*)(C.M0 + n0);
+    if (FAST) {
+        q.Z = *(const int4*)(C.rz + n0);
+        q.S = *(const int4*)(C.sh + n0);
+    } else {
+        q.Z = make_int4(0, 0, 0, 0);
+        q.S = *(const int4*)(C.rshift + n0);
+    }
+    return q;
+}
+template <int MT, int NB, bool ASYM, bool TAPS, bool FAST>
+__device__ __forceinline__ void epi_hidden_wave(const int N, const int NT, const LayerTaps& T, const CPtrs& C,
+                                                v16i (&acc)[NB][MT], v16i (&rs)[MT], int zw_s, int grp, int g,
+                                                int64_t row_first, int64_t rows, bool guard_rows, int z_out, int lo,
+                                                int8_t* out0, int64_t out_mt_stride, bool packed, int n_store) {
+    constexpr int NQ = NB * 4;
+    auto n0_of = [&](int q) { return (grp * NB + (q >> 2)) * 32 + 8 * (q & 3) + 4 * g; };
+    auto valid = [&](int q) { return grp * NB + (q >> 2) < NT; };
+    QuadConsts cur = load_quad_consts<FAST>(C, valid(0) ? n0_of(0) : 0);
+    static_for<0, NQ>([&](auto q_c) __attribute__((always_inline)) {
+        constexpr int q = decltype(q_c)::value;
+        constexpr int nb = q >> 2, j = q & 3;
+        QuadConsts nxt = cur;
+        if (q + 1 < NQ) nxt = load_quad_consts<FAST>(C, valid(q + 1) ? n0_of(q + 1) : 0);
+        if (valid(q)) {
+            const int n0 = n0_of(q);
+            const int bfv[4] = {cur.bf.x, cur.bf.y, cur.bf.z, cur.bf.w}, Mv[4] = {cur.M.x, cur.M.y, cur.M.z, cur.M.w};
+            const int Zv[4] = {cur.Z.x, cur.Z.y, cur.Z.z, cur.Z.w}, Sv[4] = {cur.S.x, cur.S.y, cur.S.z, cur.S.w};
+            static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
+                constexpr int mt = decltype(mt_c)::value;
+                const int64_t row = row_first + mt * 32;
+                const bool row_ok = row < rows;
+                uint32_t pack = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    int val = acc[nb][mt][4 * j + i] + bfv[i];
+                    if (ASYM) val -= zw_s * rs[mt][0];
+                    if (TAPS) {
+                        if (T.acc && row_ok && n0 + i < N) T.acc[row * N + n0 + i] = val;
+                    }
+                    int code;
+                    if (FAST) code = min(max((__mulhi(val, Mv[i]) + Zv[i]) >> Sv[i], lo), 255);
+                    else code = requant_code(val, Mv[i], Sv[i], z_out, lo);
+                    if (n0 + i >= N) code = 128;  // padding features are zero in the signed domain
+                    if (TAPS) {
+                        if (T.act && row_ok && n0 + i < N) T.act[row * N + n0 + i] = (uint8_t)code;
+                    }
+                    pack |= (uint32_t)code << (8 * i);
+                }
+                pack ^= 0x80808080u;
+                if (out0 && (!guard_rows || row_ok)) {
+                    int8_t* dst = out0 + mt * out_mt_stride + n0;
+                    if (packed) {
+                        if (n0 < n_store) *(uint32_t*)dst = pack;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (n0 + i < n_store) dst[i] = (int8_t)(pack >> (8 * i));
+                    }
+                }
+            });
+        }
+        cur = nxt;
+    });
+}
+
+// Last layer: y = (float)acc * m[n] for one tile, stored to y_row[n] (n < n_store) when y_row is
+// given; when act_row is given the elementwise head (tanh or identity) is applied and stored too.
 template <bool ASYM, bool TAPS>
-__device__ __forceinline__ void epi_last_tile(const int N, const LayerTaps& T, const CPtrs& C, const v16i& c, int rs0, int zw_s, int nt, int g,
-                                              int64_t row, bool row_ok, float* y_row, int n_store) {
+__device__ __forceinline__ void epi_last_tile(const int N, const LayerTaps& T, const CPtrs& C, const v16i& c, int rs0,
+                                              int zw_s, int nt, int g, int64_t row, bool row_ok, float* y_row,
+                                              int n_store, float* act_row, int head) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int n0 = nt * 32 + 8 * j + 4 * g;
@@ -239,10 +323,14 @@ __device__ __forceinline__ void epi_last_tile(const int N, const LayerTaps& T, c
         const float4 mm = *(const float4*)(C.m + n0);
         const float mv[4] = {mm.x, mm.y, mm.z, mm.w};
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (y_row && n0 + i < n_store) y_row[n0 + i] = (float)val[i] * mv[i];
+        for (int i = 0; i < 4; ++i) {
+            const float y = (float)val[i] * mv[i];
+            if (n0 + i < n_store) {
+                if (y_row) y_row[n0 + i] = y;
+                if (act_row) act_row[n0 + i] = head == AQ_HEAD_TANH ? tanh_head(y) : y;
+            }
+        }
     }
 }
-
 
 }  // namespace aq

@@ -1,25 +1,17 @@
-// One launch per layer: FC and implicit-GEMM convolution on int8 MFMA, activations in global memory.
+// One launch per layer: FC and implicit-GEMM convolution on int8 MFMA (Sec. 3.1 actor inference on
+// the quantized policy of Sec. 3.2), activations in global memory between layers.
+//
+// A workgroup of W waves owns ROWS = 32 * MT output rows (rows = batch * oh * ow positions) and, per
+// pass, W * NB feature tiles; the rows' K bytes are staged in LDS (the whole K when it fits, else
+// in chunks), weights stream from L2 straight into MFMA operand registers.  Each wave's tile is
+// (NB*32 features) x (MT*32 rows): with MT = 4 a weight operand is reused for four MFMAs, which
+// keeps the L2 -> register stream of a wide layer under a quarter KiB per MFMA; two waves per SIMD
+// let one wave's epilogue overlap the other's MFMAs.
 #include "int8_device.hpp"
 
 namespace aq {
 
-// ---------------------------------------------------------------------------------------------
-// One layer per launch: FC or convolution as an implicit GEMM (rows = batch * oh * ow output
-// positions, K = kh * kw * Cin gathered from the NHWC input).  A workgroup owns ROWS x (4*NB*32)
-// outputs; the activation rows are staged in LDS KC k-steps at a time.
-// ---------------------------------------------------------------------------------------------
-constexpr int KC = 16;  // k-steps (of 32 bytes) staged per chunk
-
-struct StageSrc {
-    const void* in;
-    int first;   // layer 0: input is the observation (fp32 to be quantized, or uint8 codes)
-    int in_u8;
-    float s0;
-    int z0;
-    uint8_t* tap_a0;
-};
-
-// address of the first of `run` contiguous input bytes that hold k .. k+run-1 of output row `row`
+// address of the first of the contiguous input bytes that hold k .. of output row `row`
 __device__ __forceinline__ int64_t gather_offset(const LayerDev& L, int64_t row, int k) {
     if (L.kh == 1 && L.kw == 1 && L.in_h == 1 && L.in_w == 1) return row * L.K + k;
     const int per_img = L.oh * L.ow;
@@ -31,12 +23,19 @@ __device__ __forceinline__ int64_t gather_offset(const LayerDev& L, int64_t row,
     return ((b * L.in_h + (int64_t)oy * L.stride + ky) * L.in_w + (int64_t)ox * L.stride) * L.in_c + kr;
 }
 
-template <int MT, int NB, bool ASYM, bool TAPS>
-__global__ __launch_bounds__(256) void k_layer_int8(const NetDev* __restrict__ netp, const TapArgs t, const int l, const LayerIO io, const int64_t rows,
-                                                    const int vec_ok) {
+// stage modes
+constexpr int ST_BYTES = 0;   // generic byte gather (any shape; quantizes fp32 observations on the way)
+constexpr int ST_VEC16 = 1;   // 16-byte gathers of 8-bit codes
+constexpr int ST_F32X4 = 2;   // first FC layer on fp32 observations, K a multiple of 4: float4 -> 4 codes
+
+template <int W, int MT, int NB, bool ASYM, bool TAPS>
+__global__ __launch_bounds__(W * 64) void k_layer_int8(const NetDev* __restrict__ netp, const TapArgs t, const int l,
+                                                      const LayerIO io, const int64_t rows, const int stage_mode,
+                                                      const int kc, const void* __restrict__ actions) {
     constexpr int ROWS = 32 * MT;
-    constexpr int LD = KC * 32 + 16;
-    __shared__ __align__(16) int8_t xs[ROWS * LD];
+    constexpr int NT_ = W * 64;
+    extern __shared__ __align__(16) int8_t xs[];
+    const int LD = kc * 32 + 16;
     const NetDev& a = *netp;
     const LayerDev& L = a.L[l];
     LayerTaps T{nullptr, nullptr, nullptr};
@@ -45,7 +44,7 @@ __global__ __launch_bounds__(256) void k_layer_int8(const NetDev* __restrict__ n
     const int64_t row0 = (int64_t)blockIdx.x * ROWS;
     const bool first = l == 0, last = l == a.n_layers - 1;
     const bool ln = !last && L.act == AQ_ACT_LN_TANH;
-    const int grp = blockIdx.y * 4 + wave;
+    const int grp = blockIdx.y * W + wave;
     const int ngroups = (L.NT + NB - 1) / NB;
     const bool active = grp < ngroups;
     float s0 = 1.0f;
@@ -76,32 +75,83 @@ __global__ __launch_bounds__(256) void k_layer_int8(const NetDev* __restrict__ n
         wptr[nb] = (gv4i_ptr)L.wp + (int64_t)nt * L.KS * 64 + lane;
     }
 
-    for (int ks0 = 0; ks0 < L.KS; ks0 += KC) {
-        const int ks1 = ks0 + KC < L.KS ? ks0 + KC : L.KS;
+    for (int ks0 = 0; ks0 < L.KS; ks0 += kc) {
+        const int ks1 = ks0 + kc < L.KS ? ks0 + kc : L.KS;
         if (ks0) __syncthreads();
-        if (vec_ok) {
-            // 16-byte gathers: every 16-byte piece of a row's K range is contiguous in the input
+        // Staging loops keep SU independent loads in flight per thread: with one load per iteration the
+        // block copy would run at one memory latency per 16 bytes per thread.
+        constexpr int SU = 8;
+        if (stage_mode == ST_VEC16) {
+            // every 16-byte piece of a row's K range is contiguous and aligned in the input
             const int chunks = (ks1 - ks0) * 2;
-            for (int idx = tid; idx < ROWS * chunks; idx += 256) {
-                const int m = idx / chunks, c = idx - m * chunks;
-                const int k = ks0 * 32 + c * 16;
-                const int64_t row = row0 + m;
-                v4i v;
-                v[0] = v[1] = v[2] = v[3] = 0;
-                if (row < rows && k < L.K) {
-                    v = *(const v4i*)((const int8_t*)io.in + gather_offset(L, row, k));
-                    if (first) {  // raw unsigned codes -> signed domain
-                        v[0] ^= 0x80808080;
-                        v[1] ^= 0x80808080;
-                        v[2] ^= 0x80808080;
-                        v[3] ^= 0x80808080;
+            const int total = ROWS * chunks;
+            for (int base = tid; base < total; base += NT_ * SU) {
+                v4i v[SU];
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int idx = base + u * NT_;
+                    v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0;
+                    if (idx < total) {
+                        const int m = idx / chunks, c = idx - m * chunks;
+                        const int k = ks0 * 32 + c * 16;
+                        const int64_t row = row0 + m;
+                        if (row < rows && k < L.K) v[u] = *(const v4i*)((const int8_t*)io.in + gather_offset(L, row, k));
                     }
                 }
-                *(v4i*)(xs + m * LD + c * 16) = v;
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int idx = base + u * NT_;
+                    if (idx < total) {
+                        const int m = idx / chunks, c = idx - m * chunks;
+                        const int k = ks0 * 32 + c * 16;
+                        v4i w = v[u];
+                        if (first && row0 + m < rows && k < L.K) {  // raw unsigned codes -> signed domain
+                            w[0] ^= 0x80808080;
+                            w[1] ^= 0x80808080;
+                            w[2] ^= 0x80808080;
+                            w[3] ^= 0x80808080;
+                        }
+                        *(v4i*)(xs + m * LD + c * 16) = w;
+                    }
+                }
+            }
+        } else if (stage_mode == ST_F32X4) {
+            const int K4 = L.K >> 2;
+            const int q0 = ks0 * 8, q1 = ks1 * 8;  // quads of this chunk (zero beyond K4)
+            const int nq = q1 - q0;
+            const int total = ROWS * nq;
+            for (int base = tid; base < total; base += NT_ * SU) {
+                float4 v[SU];
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int idx = base + u * NT_;
+                    v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (idx < total) {
+                        const int m = idx / nq, q = q0 + (idx - m * nq);
+                        if (row0 + m < rows && q < K4) v[u] = ((const float4*)io.in)[(row0 + m) * K4 + q];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int idx = base + u * NT_;
+                    if (idx < total) {
+                        const int m = idx / nq, q = q0 + (idx - m * nq);
+                        const int64_t row = row0 + m;
+                        uint32_t pack = 0;
+                        if (row < rows && q < K4) {
+                            pack = quant_code4(v[u], qs0, -z0, 255 - z0, z0);
+                            if (TAPS) {
+                                if (t.a0 && blockIdx.y == 0) *(uint32_t*)(t.a0 + row * L.K + 4 * q) = pack;
+                            }
+                            pack ^= 0x80808080u;
+                        }
+                        *(uint32_t*)(xs + m * LD + (q - q0) * 4) = pack;
+                    }
+                }
             }
         } else {
             const int kb = (ks1 - ks0) * 32;
-            for (int idx = tid; idx < ROWS * kb; idx += 256) {
+            for (int idx = tid; idx < ROWS * kb; idx += NT_) {
                 const int m = idx / kb, kk = idx - m * kb;
                 const int k = ks0 * 32 + kk;
                 const int64_t row = row0 + m;
@@ -127,35 +177,93 @@ __global__ __launch_bounds__(256) void k_layer_int8(const NetDev* __restrict__ n
         if (active) mma_block<MT, NB, ASYM, 4>(wptr, xs, LD, ks0, ks1, ks0, acc, rs, lane);
     }
 
-    if (!active) return;
     const CPtrs C = global_consts(L);
     const bool fast = !last && !ln && a.fast[l] != 0;
-    static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
-        constexpr int nb = decltype(nb_c)::value;
-        const int nt = grp * NB + nb;
-        if (nt < L.NT) {
-            static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
-                constexpr int mt = decltype(mt_c)::value;
-                const int64_t row = row0 + mt * 32 + (lane & 31);
-                const bool row_ok = row < rows;
-                if (ln) {
-                    // dequantized accumulators go to the LayerNorm kernel
-                    epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
-                                              row_ok ? io.ln_x + row * L.N : nullptr, L.N);
-                } else if (last) {
-                    // y = (float)acc * m; the head kernel follows
-                    epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
-                                              row_ok ? io.y + row * L.N : nullptr, L.N);
-                } else if (fast) {
-                    epi_hidden_tile<ASYM, TAPS, true>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok, z_out,
-                                                      lo, row_ok ? io.out + row * L.N : nullptr, (L.N & 3) == 0, L.N);
-                } else {
-                    epi_hidden_tile<ASYM, TAPS, false>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok, z_out,
-                                                       lo, row_ok ? io.out + row * L.N : nullptr, (L.N & 3) == 0, L.N);
+    const int head = a.head;
+    // Results leave through LDS so that global stores are whole 16-byte pieces of an output row: a lane
+    // owns 4 consecutive features of ONE row, and 64 such 4-byte stores per instruction would each touch
+    // a different cache line.  The activation block is no longer needed once every wave has left the
+    // MFMA loop, so its LDS is reused: [ROWS][BNP + 16] bytes (hidden) or [ROWS][BNP + 4] floats (last).
+    constexpr int BNP = W * NB * 32;                 // features per workgroup pass
+    const int n_base = blockIdx.y * BNP;
+    const bool via_lds = !ln && (last || (L.N & 15) == 0);
+    if (!via_lds) {
+        if (!active) return;
+        const int64_t row_first = row0 + (lane & 31);
+        if (ln) {
+            // dequantized accumulators go to the LayerNorm kernel
+            static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
+                constexpr int nb = decltype(nb_c)::value;
+                const int nt = grp * NB + nb;
+                if (nt < L.NT) {
+                    static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
+                        constexpr int mt = decltype(mt_c)::value;
+                        const int64_t row = row_first + mt * 32;
+                        const bool row_ok = row < rows;
+                        epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row_ok,
+                                                  row_ok ? io.ln_x + row * L.N : nullptr, L.N, nullptr, 0);
+                    });
+                }
+            });
+        } else if (fast) {
+            epi_hidden_wave<MT, NB, ASYM, TAPS, true>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row_first, rows, true, z_out,
+                                                      lo, io.out + row_first * L.N, (int64_t)32 * L.N, false, L.N);
+        } else {
+            epi_hidden_wave<MT, NB, ASYM, TAPS, false>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row_first, rows, true, z_out,
+                                                       lo, io.out + row_first * L.N, (int64_t)32 * L.N, false, L.N);
+        }
+        return;
+    }
+    __syncthreads();  // every wave is done reading the activation block
+    if (last) {
+        constexpr int LDY = BNP + 4;
+        float* ys = (float*)xs;
+        if (active) {
+            static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
+                constexpr int nb = decltype(nb_c)::value;
+                const int nt = grp * NB + nb;
+                if (nt < L.NT) {
+                    static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
+                        constexpr int mt = decltype(mt_c)::value;
+                        const int m = mt * 32 + (lane & 31);
+                        const int64_t row = row0 + m;
+                        epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row, row < rows,
+                                                  ys + m * LDY - n_base, n_base + BNP, nullptr, 0);
+                    });
                 }
             });
         }
-    });
+        __syncthreads();
+        // y tap, elementwise head (tanh / identity) and coalesced stores; argmax is a separate row kernel
+        const int nvalid = L.N - n_base < BNP ? L.N - n_base : BNP;
+        for (int idx = tid; idx < ROWS * nvalid; idx += NT_) {
+            const int m = idx / nvalid, n = idx - m * nvalid;
+            const int64_t row = row0 + m;
+            if (row >= rows) continue;
+            const float y = ys[m * LDY + n];
+            if (io.y) io.y[row * L.N + n_base + n] = y;
+            if (actions) ((float*)actions)[row * L.N + n_base + n] = head == AQ_HEAD_TANH ? tanh_head(y) : y;
+        }
+    } else {
+        constexpr int LDO = BNP + 16;
+        if (active) {
+            const int m0 = lane & 31;
+            if (fast)
+                epi_hidden_wave<MT, NB, ASYM, TAPS, true>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row0 + m0, rows, false,
+                                                          z_out, lo, xs + m0 * LDO - n_base, 32 * LDO, true, n_base + BNP);
+            else
+                epi_hidden_wave<MT, NB, ASYM, TAPS, false>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row0 + m0, rows, false,
+                                                           z_out, lo, xs + m0 * LDO - n_base, 32 * LDO, true, n_base + BNP);
+        }
+        __syncthreads();
+        const int nvalid = L.N - n_base < BNP ? L.N - n_base : BNP;  // a multiple of 16
+        const int chunks = nvalid >> 4;
+        for (int idx = tid; idx < ROWS * chunks; idx += NT_) {
+            const int m = idx / chunks, c = idx - m * chunks;
+            const int64_t row = row0 + m;
+            if (row < rows) *(v4i*)(io.out + row * L.N + n_base + c * 16) = *(const v4i*)(xs + m * LDO + c * 16);
+        }
+    }
 }
 
 // LayerNorm + tanh + re-quantize of fp32 rows (per-layer path): one wavefront per row.
@@ -186,15 +294,15 @@ __global__ __launch_bounds__(256) void k_ln_tanh_rows(const float* __restrict__ 
     const float inv = 1.0f / sqrtf(ss / (float)N + eps);
     for (int n = lane; n < N; n += 64) {
         float y = (xr[n] - mean) * inv * gamma[n] + beta[n];
-        float t = tanh_fast(y);
-        if (tap_ln) tap_ln[row * N + n] = t;
-        int code = quant_code(t, qs_out, -z_out, 255 - z_out) + z_out;
+        float tv = tanh_fast(y);
+        if (tap_ln) tap_ln[row * N + n] = tv;
+        int code = quant_code(tv, qs_out, -z_out, 255 - z_out) + z_out;
         if (tap_act) tap_act[row * N + n] = (uint8_t)code;
         out[row * N + n] = (int8_t)(code - 128);
     }
 }
 
-// action head on the dequantized last-layer rows (per-layer path)
+// argmax head on the dequantized last-layer rows (per-layer path; lowest index wins ties)
 __global__ void k_head_rows(const float* __restrict__ y, int64_t rows, int N, int head, void* __restrict__ actions) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (head == AQ_HEAD_ARGMAX) {
@@ -210,22 +318,52 @@ __global__ void k_head_rows(const float* __restrict__ y, int64_t rows, int N, in
     }
 }
 
-aq_status launch_layer_int8(const FwdArgs& a, int l, const LayerIO& io, hipStream_t st) {
+namespace {
+// Tile configuration of one layer launch.
+struct LayerPlan {
+    int w, mt, nb;
+};
+
+LayerPlan plan_layer(const LayerDev& L, int64_t rows, bool asym) {
+    // Wide layers with many rows: 128-row blocks, 64 features per wave, 8 waves (512 features per
+    // workgroup pass).  Narrow layers: 32-row blocks and as many waves as there are feature tiles,
+    // so that every SIMD of the chip gets work.  Everything else: 64-row blocks, 4 waves.
+    if (!asym && rows >= 8192 && L.NT >= 16) return {8, 4, 2};  // (the asymmetric row-sum tiles would spill)
+    if (rows >= 8192 && L.NT <= 2) return {2, 1, 1};
+    return {4, 2, 2};
+}
+}  // namespace
+
+template <int W, int MT, int NB>
+static aq_status launch_layer_t(const FwdArgs& a, int l, const LayerIO& io, int64_t rows, int stage_mode,
+                                const void* actions, hipStream_t st) {
     const LayerDev& L = a.net.L[l];
-    const int64_t rows = a.c.batch * L.oh * L.ow;
-    const bool first = l == 0;
-    // 16-byte gathers need contiguous, aligned 16-byte pieces of K in the input
-    const bool fc = L.kh == 1 && L.kw == 1 && L.in_h == 1 && L.in_w == 1;
-    const int run = fc ? L.K : L.kw * L.in_c;
-    bool vec_ok = run % 16 == 0 && !(first && !a.net.in_u8) && !(first && a.t.a0);
-    if (!fc && ((L.stride * L.in_c) % 16 != 0 || (L.in_w * L.in_c) % 16 != 0)) vec_ok = false;
-    constexpr int MT = 2, NB = 2;
+    constexpr int ROWS = 32 * MT;
+    // stage as much of K as fits comfortably in LDS (whole K for K <= 2048 at 64 rows, 1024 at 128 rows)
+    int kc = L.KS;
+    const int kc_max = (144 * 1024 / ROWS - 16) / 32;
+    if (kc > kc_max) kc = kc_max;
+    if (kc < 1) kc = 1;
+    size_t lds = (size_t)ROWS * (kc * 32 + 16);
+    const size_t lds_out = (size_t)ROWS * (W * NB * 32 + 16) * (l == a.net.n_layers - 1 ? 4 : 1);
+    if (lds_out > lds) lds = lds_out;
     const int ngroups = (L.NT + NB - 1) / NB;
-    dim3 grid((unsigned)((rows + 32 * MT - 1) / (32 * MT)), (unsigned)((ngroups + 3) / 4));
+    dim3 grid((unsigned)((rows + ROWS - 1) / ROWS), (unsigned)((ngroups + W - 1) / W));
     const bool taps = any_taps(a);
-#define AQ_LAYER(AS, TP) \
-    hipLaunchKernelGGL((k_layer_int8<MT, NB, AS, TP>), grid, dim3(256), 0, st, a.d_net, a.t, l, io, rows, (int)vec_ok)
-    if (a.net.asym) {
+    const bool asym = a.net.asym != 0;
+#define AQ_LAYER(AS, TP)                                                                                            \
+    do {                                                                                                            \
+        static bool attr_set = false;                                                                               \
+        if (!attr_set) {                                                                                            \
+            if (hipFuncSetAttribute((const void*)k_layer_int8<W, MT, NB, AS, TP>,                                   \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)          \
+                return AQ_EHIP;                                                                                     \
+            attr_set = true;                                                                                        \
+        }                                                                                                           \
+        hipLaunchKernelGGL((k_layer_int8<W, MT, NB, AS, TP>), grid, dim3(W * 64), lds, st, a.d_net, a.t, l, io, rows, \
+                           stage_mode, kc, actions);                                                                \
+    } while (0)
+    if (asym) {
         if (taps) AQ_LAYER(true, true);
         else AQ_LAYER(true, false);
     } else {
@@ -234,6 +372,27 @@ aq_status launch_layer_int8(const FwdArgs& a, int l, const LayerIO& io, hipStrea
     }
 #undef AQ_LAYER
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
+aq_status launch_layer_int8(const FwdArgs& a, int l, const LayerIO& io, hipStream_t st) {
+    const LayerDev& L = a.net.L[l];
+    const int64_t rows = a.c.batch * L.oh * L.ow;
+    const bool first = l == 0, last = l == a.net.n_layers - 1;
+    const bool fc = L.kh == 1 && L.kw == 1 && L.in_h == 1 && L.in_w == 1;
+    // 16-byte gathers need contiguous, aligned 16-byte pieces of K in an 8-bit input
+    const int run = fc ? L.K : L.kw * L.in_c;
+    int stage_mode = ST_BYTES;
+    if (run % 16 == 0 && !(first && !a.net.in_u8) && !(first && a.t.a0) &&
+        (fc || ((L.stride * L.in_c) % 16 == 0 && (L.in_w * L.in_c) % 16 == 0)))
+        stage_mode = ST_VEC16;
+    else if (first && !a.net.in_u8 && fc && (L.K & 3) == 0)
+        stage_mode = ST_F32X4;
+    // elementwise heads are applied in the last layer's epilogue; argmax needs the whole row
+    const void* actions = (last && a.net.head != AQ_HEAD_ARGMAX) ? a.c.actions : nullptr;
+    const LayerPlan p = plan_layer(L, rows, a.net.asym != 0);
+    if (p.w == 8) return launch_layer_t<8, 4, 2>(a, l, io, rows, stage_mode, actions, st);
+    if (p.w == 2) return launch_layer_t<2, 1, 1>(a, l, io, rows, stage_mode, actions, st);
+    return launch_layer_t<4, 2, 2>(a, l, io, rows, stage_mode, actions, st);
 }
 
 aq_status launch_ln_tanh_rows(const FwdArgs& a, int l, const float* x, int8_t* out, int64_t rows, hipStream_t st) {

@@ -156,6 +156,26 @@ def test_forward_full_size(aq, name, batch, sample):
     P.close()
 
 
+@pytest.mark.parametrize("name,batch,sample", [("cfg5", 8200, 300), ("cfg2", 9000, 400)])
+def test_per_layer_path_large_batch(aq, name, batch, sample):
+    """The one-launch-per-layer plan at batch sizes where it picks its 128-row / 8-wave and its narrow
+    2-wave tile configurations (MLPs normally run fused; convolution layers always take this path)."""
+    _say(f"per_layer_path_large_batch {name} batch={batch}")
+    net = synth.net_config(name)
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs[:256])
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    P.policy_set_path(2)
+    actions, t = U.gpu_forward(P, net, obs)
+    rng = np.random.default_rng(6)
+    rows = np.unique(np.concatenate([[0, 127, 128, batch - 1], rng.integers(0, batch, sample)]))
+    U.compare_forward(net, pol, obs, actions, t, rows)
+    a2, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(a2, actions)
+    P.close()
+
+
 # ------------------------------------------------------------------ fp32 actor and calibration
 @pytest.mark.parametrize("name,batch", [("cfg1", 256), ("cfg2", 300), ("cfg4", 8), ("cfg5", 96)])
 def test_forward_fp32(aq, name, batch):
