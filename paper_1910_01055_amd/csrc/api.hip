@@ -17,14 +17,19 @@ struct LayerBuf {
     int32_t* z_w;
     int32_t* rowsum;
     int32_t* bias_q;
-    int32_t* bias_fold;
     int32_t* M0;
     int32_t* rshift;
     float* m;
-    float* gamma;
-    float* beta;
+    // The constants an epilogue reads per output channel sit in one contiguous pack of four
+    // [N_pad] arrays, so that the fused kernel stages them with one linear copy:
+    //   [0] bias_fold   [1] M0 (requantized layers) or m (LayerNorm and last layers)
+    //   [2] rz or gamma [3] sh or beta          (a layer is either requantized or normalised)
+    int32_t* bias_fold;
+    int32_t* pack1;
     int32_t* rz;
     int32_t* sh;
+    float* gamma;
+    float* beta;
     int* fast;  // points into the device-resident NetDev
 };
 
@@ -169,7 +174,8 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         if (l < net->n_layers - 1 && prev_elems > p->max_hidden_elems) p->max_hidden_elems = prev_elems;
         if (prev_elems > p->max_out_elems) p->max_out_elems = prev_elems;
         offs.push_back(take((size_t)b.NT * b.KS * 1024));
-        for (int i = 0; i < 12; ++i) offs.push_back(take((size_t)b.N_pad * 4));
+        for (int i = 0; i < 7; ++i) offs.push_back(take((size_t)b.N_pad * 4));
+        offs.push_back(take((size_t)b.N_pad * 4 * 4));  // the epilogue constant pack, see LayerBuf
         p->L.push_back(b);
     }
     size_t off_status = take(256);
@@ -194,14 +200,16 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         b.z_w = (int32_t*)(base + offs[oi++]);
         b.rowsum = (int32_t*)(base + offs[oi++]);
         b.bias_q = (int32_t*)(base + offs[oi++]);
-        b.bias_fold = (int32_t*)(base + offs[oi++]);
         b.M0 = (int32_t*)(base + offs[oi++]);
         b.rshift = (int32_t*)(base + offs[oi++]);
         b.m = (float*)(base + offs[oi++]);
-        b.gamma = (float*)(base + offs[oi++]);
-        b.beta = (float*)(base + offs[oi++]);
-        b.rz = (int32_t*)(base + offs[oi++]);
-        b.sh = (int32_t*)(base + offs[oi++]);
+        int32_t* pack = (int32_t*)(base + offs[oi++]);
+        b.bias_fold = pack;
+        b.pack1 = pack + b.N_pad;
+        b.rz = pack + 2 * b.N_pad;
+        b.sh = pack + 3 * b.N_pad;
+        b.gamma = (float*)b.rz;
+        b.beta = (float*)b.sh;
     }
     p->status = (int*)(base + off_status);
     p->mm = (uint32_t*)(base + off_mm);
@@ -346,7 +354,7 @@ extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w,
         s = launch_fill_u32((uint32_t*)b.fast, 1, requant ? 1u : 0u, st);
         if (s != AQ_OK) return s;
         s = launch_layer_consts(p->actq, l, requant, asym, b.s_w, b.z_w, h_d_b ? h_d_b[l] : nullptr, b.rowsum, b.N,
-                                b.K, b.m, b.bias_q, b.M0, b.rshift, b.bias_fold, b.rz, b.sh, b.fast, p->status, st);
+                                b.K, b.m, b.bias_q, b.M0, b.rshift, b.bias_fold, b.pack1, b.rz, b.sh, b.fast, p->status, st);
         if (s != AQ_OK) return s;
     }
     p->quantized = true;

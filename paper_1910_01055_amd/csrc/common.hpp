@@ -126,6 +126,9 @@ constexpr int kStatRange = 2;
 // Per-layer descriptor handed to the forward kernels by value.
 struct LayerDev {
     const int8_t* wp;          // packed signed-domain weights [NT][KS][64 lanes][16 bytes]
+    // bias_fold heads a contiguous pack of four [N_pad] arrays: bias_fold | M0 or m | rz or gamma |
+    // sh or beta (requantized layers take the first alternative, LayerNorm and last layers the second);
+    // rz, sh, gamma and beta below point into that pack
     const int32_t* bias_fold;  // [N_pad] integer bias with the zero-point terms folded in
     const int32_t* M0;         // [N_pad] requantization multipliers (Q31, normalised)
     const int32_t* rshift;     // [N_pad] requantization right shifts

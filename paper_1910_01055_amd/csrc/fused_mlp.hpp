@@ -39,15 +39,15 @@ __device__ __forceinline__ T* uni_ptr(T* p) {
 // One layer as the kernel needs it: plain scalars, built field by field from the LDS copy.
 struct LayerView {
     const int8_t* wp;
-    gv4i_ptr slot[4];     // sources of the four staged constant arrays (see below), as 16-byte pieces
+    gv4i_ptr pack;        // the layer's epilogue constants: four contiguous [Np] arrays, as 16-byte pieces
     const int32_t* rshift;
     gint_ptr z_w;
-    int N, NT, KS, act, nslots, fast, z_out;
+    int N, NT, KS, act, pieces, fast, z_out;
     float s_out;
     bool last, ln;
 };
-// Constant slots by layer type: slot 0 = bias_fold; requantized: M0, rz, sh (the general requantization
-// form reads its shifts from global memory); LayerNorm: m, gamma, beta; last: m.
+// The pack holds bias_fold, then by layer type: requantized M0, rz, sh (the general requantization
+// form reads its shifts from global memory); LayerNorm m, gamma, beta; last m (two arrays staged).
 __device__ __forceinline__ LayerView layer_view(const NetDev& n, int l, int n_layers) {
     const LayerDev& s = n.L[l];
     LayerView v;
@@ -55,16 +55,13 @@ __device__ __forceinline__ LayerView layer_view(const NetDev& n, int l, int n_la
     v.act = uni(s.act);
     v.ln = !v.last && v.act == AQ_ACT_LN_TANH;
     v.wp = uni_ptr(s.wp);
-    v.slot[0] = (gv4i_ptr)uni_ptr(s.bias_fold);
-    v.slot[1] = (gv4i_ptr)((v.ln || v.last) ? (const void*)uni_ptr(s.m) : (const void*)uni_ptr(s.M0));
-    v.slot[2] = (gv4i_ptr)(v.ln ? (const void*)uni_ptr(s.gamma) : (const void*)uni_ptr(s.rz));
-    v.slot[3] = (gv4i_ptr)(v.ln ? (const void*)uni_ptr(s.beta) : (const void*)uni_ptr(s.sh));
+    v.pack = (gv4i_ptr)uni_ptr(s.bias_fold);
     v.rshift = uni_ptr(s.rshift);
     v.z_w = (gint_ptr)uni_ptr(s.z_w);
     v.N = uni(s.N);
     v.NT = uni(s.NT);
     v.KS = uni(s.KS);
-    v.nslots = v.last ? 2 : 4;
+    v.pieces = (v.last ? 2 : 4) * v.NT * 8;
     v.s_out = 1.0f;
     v.z_out = 0;
     v.fast = 0;
@@ -77,23 +74,12 @@ __device__ __forceinline__ LayerView layer_view(const NetDev& n, int l, int n_la
 }
 // this thread's share of a layer's constants: up to two 16-byte pieces (Np <= CST_MAXN)
 __device__ __forceinline__ void load_consts(const LayerView& v, int tid, v4i& c0, v4i& c1) {
-    const int n4 = v.NT * 8, pieces = v.nslots * n4;
-    const int i0 = tid, i1 = tid + FW * 64;
-    if (i0 < pieces) {
-        const int w = i0 / n4;
-        c0 = (w == 0 ? v.slot[0] : w == 1 ? v.slot[1] : w == 2 ? v.slot[2] : v.slot[3])[i0 - w * n4];
-    }
-    if (i1 < pieces) {
-        const int w = i1 / n4;
-        c1 = (w == 0 ? v.slot[0] : w == 1 ? v.slot[1] : w == 2 ? v.slot[2] : v.slot[3])[i1 - w * n4];
-    }
+    if (tid < v.pieces) c0 = v.pack[tid];
+    if (tid + FT < v.pieces) c1 = v.pack[tid + FT];
 }
-__device__ __forceinline__ void park_consts(const LayerView& v, int tid, int32_t* cst, int cst_n, const v4i& c0,
-                                            const v4i& c1) {
-    const int n4 = v.NT * 8, pieces = v.nslots * n4;
-    const int i0 = tid, i1 = tid + FW * 64;
-    if (i0 < pieces) *(v4i*)(cst + (i0 / n4) * cst_n + (i0 % n4) * 4) = c0;
-    if (i1 < pieces) *(v4i*)(cst + (i1 / n4) * cst_n + (i1 % n4) * 4) = c1;
+__device__ __forceinline__ void park_consts(const LayerView& v, int tid, int32_t* cst, const v4i& c0, const v4i& c1) {
+    if (tid < v.pieces) ((v4i*)cst)[tid] = c0;
+    if (tid + FT < v.pieces) ((v4i*)cst)[tid + FT] = c1;
 }
 
 template <int NB>
@@ -165,28 +151,46 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 }
                 *(uint32_t*)(buf_in + m * ld + 4 * k4) = pack;
             }
+            const int padw = Kp - K0;
+            for (int idx = tid; idx < ROWS * padw; idx += FT) {
+                const int m = idx / padw, k = K0 + (idx - m * padw);
+                buf_in[m * ld + k] = 0;
+            }
         } else {
-            for (int idx = tid; idx < ROWS * K0; idx += FT) {
-                const int m = idx / K0, k = idx - m * K0;
+            // 16 lanes per row; each lane requests up to eight elements before it converts the first,
+            // and the zero padding up to the k-step boundary is written in the same sweep
+            const int r32 = tid >> 4, l16 = tid & 15;
+            for (int mb = 0; mb < ROWS; mb += 32) {
+                const int m = mb + r32;
                 const int64_t row = row0 + m;
-                int code = 128;
-                if (row < c.batch) {
-                    if (c.in_u8) {
-                        code = ((const uint8_t*)c.obs)[row * K0 + k];
-                    } else {
-                        code = quant_code(((const float*)c.obs)[row * K0 + k], qs0, -z0, 255 - z0) + z0;
+                const bool ok = row < c.batch;
+                for (int kb = 0; kb < Kp; kb += 128) {
+                    float xv[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int k = kb + l16 + 16 * u;
+                        xv[u] = 0.0f;
+                        if (ok && k < K0) {
+                            if (c.in_u8) xv[u] = __int_as_float((int)((const uint8_t*)c.obs)[row * K0 + k]);
+                            else xv[u] = ((const float*)c.obs)[row * K0 + k];
+                        }
                     }
-                    if (TAPS) {
-                        if (t.a0) t.a0[row * K0 + k] = (uint8_t)code;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int k = kb + l16 + 16 * u;
+                        if (k < Kp) {
+                            int code = 128;
+                            if (ok && k < K0) {
+                                code = c.in_u8 ? __float_as_int(xv[u]) : quant_code(xv[u], qs0, -z0, 255 - z0) + z0;
+                                if (TAPS) {
+                                    if (t.a0) t.a0[row * K0 + k] = (uint8_t)code;
+                                }
+                            }
+                            buf_in[m * ld + k] = (int8_t)(code - 128);
+                        }
                     }
                 }
-                buf_in[m * ld + k] = (int8_t)(code - 128);
             }
-        }
-        const int padw = Kp - K0;
-        for (int idx = tid; idx < ROWS * padw; idx += FT) {
-            const int m = idx / padw, k = K0 + (idx - m * padw);
-            buf_in[m * ld + k] = 0;
         }
     }
     lds_barrier();
@@ -219,10 +223,10 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 
         // This layer's per-channel constants were requested one layer ago (layer 0: just above);
         // park them in LDS for the epilogue.  The barrier after the first MFMA pass publishes them.
-        park_consts(L, tid, cst, cst_n, cv0, cv1);
-        const CPtrs C{cst, cst + cst_n, L.rshift, cst + 2 * cst_n, cst + 3 * cst_n, (const float*)(cst + cst_n)};
-        const float* c_gamma = (const float*)(cst + 2 * cst_n);
-        const float* c_beta = (const float*)(cst + 3 * cst_n);
+        park_consts(L, tid, cst, cv0, cv1);
+        const CPtrs C{cst, cst + Np, L.rshift, cst + 2 * Np, cst + 3 * Np, (const float*)(cst + Np)};
+        const float* c_gamma = (const float*)(cst + 2 * Np);
+        const float* c_beta = (const float*)(cst + 3 * Np);
 
         for (int g0 = 0; g0 < ngroups; g0 += FW) {
             const int grp = g0 + wave;
@@ -369,22 +373,29 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                                 const float4 ga = *(const float4*)(c_gamma + n0);
                                 const float4 be = *(const float4*)(c_beta + n0);
                                 const float gv[4] = {ga.x, ga.y, ga.z, ga.w}, bv[4] = {be.x, be.y, be.z, be.w};
-                                uint32_t pack = 0;
+                                float tv[4];
 #pragma unroll
                                 for (int i = 0; i < 4; ++i) {
-                                    const int n = n0 + i;
-                                    float x = __int_as_float(acc[nb][mt][4 * j + i]);
-                                    float y = (x - mean[mt]) * inv[mt] * gv[i] + bv[i];
-                                    float tv = tanh_fast(y);
-                                    int code = quant_code(tv, qs_out, -z_out, 255 - z_out) + z_out;
-                                    if (n >= L.N) code = 128;
-                                    if (TAPS) {
+                                    const float x = __int_as_float(acc[nb][mt][4 * j + i]);
+                                    tv[i] = tanh_fast((x - mean[mt]) * inv[mt] * gv[i] + bv[i]);
+                                }
+                                uint32_t pack = quant_code4(float4{tv[0], tv[1], tv[2], tv[3]}, qs_out, -z_out,
+                                                            255 - z_out, z_out);
+                                if (n0 + 4 > L.N) {
+                                    // padding features are zero in the signed domain
+                                    const int keep = L.N - n0;  // < 4, may be <= 0
+                                    const uint32_t kmask = keep <= 0 ? 0u : (1u << (8 * keep)) - 1u;
+                                    pack = (pack & kmask) | (0x80808080u & ~kmask);
+                                }
+                                if (TAPS) {
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) {
+                                        const int n = n0 + i;
                                         if (row_ok && n < L.N) {
-                                            if (T.ln) T.ln[row * L.N + n] = tv;
-                                            if (T.act) T.act[row * L.N + n] = (uint8_t)code;
+                                            if (T.ln) T.ln[row * L.N + n] = tv[i];
+                                            if (T.act) T.act[row * L.N + n] = (uint8_t)(pack >> (8 * i));
                                         }
                                     }
-                                    pack |= (uint32_t)code << (8 * i);
                                 }
                                 *(uint32_t*)(out + m * ld + n0) = pack ^ 0x80808080u;
                             }

@@ -14,8 +14,8 @@ aq_status launch_unpack_weights(const int8_t* wp, int N, int K, int KS, int asym
 aq_status launch_act_qparams(const RangesArg& r, int n, int in_u8, float qdenom, ActQ* actq, hipStream_t st);
 aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym, const float* s_w,
                               const int32_t* z_w, const float* bias, const int32_t* rowsum, int N, int K, float* m,
-                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int32_t* rz,
-                              int32_t* sh, int* fast, int* status, hipStream_t st);
+                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int32_t* pack1,
+                              int32_t* rz, int32_t* sh, int* fast, int* status, hipStream_t st);
 
 // ---- 8-bit forward (forward_int8.hip)
 struct FwdArgs {

@@ -385,7 +385,7 @@ __global__ void k_layer_consts(const ActQ* __restrict__ actq, int layer, int req
                                const float* __restrict__ bias, const int32_t* __restrict__ rowsum, int N, int K,
                                float* __restrict__ m, int32_t* __restrict__ bias_q, int32_t* __restrict__ M0,
                                int32_t* __restrict__ rshift, int32_t* __restrict__ bias_fold,
-                               int32_t* __restrict__ rz, int32_t* __restrict__ sh, int* __restrict__ fast,
+                               int32_t* __restrict__ pack1, int32_t* __restrict__ rz, int32_t* __restrict__ sh, int* __restrict__ fast,
                                int* __restrict__ status) {
     int n = blockIdx.x * blockDim.x + threadIdx.x;
     if (n >= N) return;
@@ -414,6 +414,7 @@ __global__ void k_layer_consts(const ActQ* __restrict__ actq, int layer, int req
             r = 1;
         }
         M0[n] = (int32_t)q;
+        pack1[n] = (int32_t)q;
         rshift[n] = r;
         // Short form of the same requantization for 33 <= r <= 54: the rounding constant 2^(r-1) has a
         // zero low word, so (acc*M0 + 2^(r-1)) >> r = (mulhi(acc, M0) + 2^(r-33)) >> (r-32), and the
@@ -430,6 +431,7 @@ __global__ void k_layer_consts(const ActQ* __restrict__ actq, int layer, int req
     } else {
         M0[n] = 0;
         rshift[n] = 0;
+        pack1[n] = __float_as_int(s_in * s_w[n]);
     }
     const int za_s = z_a - 128;
     const int zw_s = asym ? z_w[n] - 128 : 0;
@@ -519,10 +521,10 @@ aq_status launch_act_qparams(const RangesArg& r, int n, int in_u8, float qdenom,
 
 aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym, const float* s_w,
                               const int32_t* z_w, const float* bias, const int32_t* rowsum, int N, int K, float* m,
-                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int32_t* rz,
-                              int32_t* sh, int* fast, int* status, hipStream_t st) {
+                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int32_t* pack1,
+                              int32_t* rz, int32_t* sh, int* fast, int* status, hipStream_t st) {
     hipLaunchKernelGGL(k_layer_consts, dim3((N + 255) / 256), dim3(256), 0, st, actq, layer, requant, asym, s_w, z_w,
-                       bias, rowsum, N, K, m, bias_q, M0, rshift, bias_fold, rz, sh, fast, status);
+                       bias, rowsum, N, K, m, bias_q, M0, rshift, bias_fold, pack1, rz, sh, fast, status);
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
