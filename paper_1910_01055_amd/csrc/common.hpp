@@ -167,6 +167,11 @@ struct CallArgs {
     int cst_n;  // fused kernel: words per constant array in the LDS staging area
     int K0, Kp0, in_u8;  // first layer's input width (real, padded) and input type, so the observation
                          // loads can be issued before anything else has been read
+    // fused kernel: the first layer's packed weights and constant pack, so that their loads do not
+    // wait for the network description either
+    const int8_t* wp0;
+    const int32_t* pack0;
+    int NT0, KS0, pieces0;
 };
 
 // Optional intermediate outputs (by value, only read by the kernels compiled with TAPS).

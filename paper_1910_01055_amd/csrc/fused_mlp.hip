@@ -85,6 +85,11 @@ aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     FwdArgs a = a_in;
     a.c.ld = p.ld;
     a.c.cst_n = p.cst_n;
+    a.c.wp0 = a.net.L[0].wp;
+    a.c.pack0 = a.net.L[0].bias_fold;
+    a.c.NT0 = a.net.L[0].NT;
+    a.c.KS0 = a.net.L[0].KS;
+    a.c.pieces0 = (a.net.n_layers == 1 ? 2 : 4) * a.net.L[0].NT * 8;
     const bool tp = any_taps(a);
     const bool as = a.net.asym != 0;
 #define AQ_GO(MT, NB, AS) \

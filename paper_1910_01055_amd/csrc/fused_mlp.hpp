@@ -120,11 +120,14 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
     // first layer's first weights: requested before the observations are touched
     v4i wreg[PF][NB];
     if (XPF) {
-        const int NT0 = a.L[0].NT, KS0 = a.L[0].KS;
         gv4i_ptr wptr[NB];
-        tile_ptrs<NB>(a.L[0].wp, NT0, KS0, wave, lane, wptr);
-        if (wave * NB < NT0) mma_prefetch<NB, PF>(wptr, 0, KS0, wreg);
+        tile_ptrs<NB>(c.wp0, c.NT0, c.KS0, wave, lane, wptr);
+        if (wave * NB < c.NT0) mma_prefetch<NB, PF>(wptr, 0, c.KS0, wreg);
     }
+    // ... and its per-channel constants
+    v4i cv0 = {0, 0, 0, 0}, cv1 = cv0;
+    if (tid < c.pieces0) cv0 = ((gv4i_ptr)c.pack0)[tid];
+    if (tid + FT < c.pieces0) cv1 = ((gv4i_ptr)c.pack0)[tid + FT];
 
     // observation quantize: a0 = clamp(round(x / s0) + z0, 0, 255), kept in the signed domain
     {
@@ -132,30 +135,69 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const float s0 = a.actq[0].s;
         const int z0 = a.actq[0].z;
         const QuantScale qs0 = make_quant_scale(s0);
-        if (!c.in_u8 && (K0 & 3) == 0) {
-            // four observations per lane: one 16-byte load, one packed 32-bit LDS store
-            const int K4 = K0 >> 2;
-            const float4* src = (const float4*)c.obs + row0 * K4;
-            for (int idx = tid; idx < ROWS * K4; idx += FT) {
-                const int m = idx / K4, k4 = idx - m * K4;
-                uint32_t pack = 0;
-                if (row0 + m < c.batch) {
-                    const float4 v = src[idx];
-                    const int c0 = quant_code(v.x, qs0, -z0, 255 - z0) + z0, c1 = quant_code(v.y, qs0, -z0, 255 - z0) + z0;
-                    const int c2 = quant_code(v.z, qs0, -z0, 255 - z0) + z0, c3 = quant_code(v.w, qs0, -z0, 255 - z0) + z0;
-                    pack = (uint32_t)c0 | ((uint32_t)c1 << 8) | ((uint32_t)c2 << 16) | ((uint32_t)c3 << 24);
-                    if (TAPS) {
-                        if (t.a0) *(uint32_t*)(t.a0 + (row0 + m) * K0 + 4 * k4) = pack;
+        if (!c.in_u8 && ((uintptr_t)c.obs & 15) == 0) {
+            // The block's rows are one contiguous run in memory that starts 16-byte aligned (ROWS * K0
+            // is a multiple of 4): read it as flat 16-byte pieces, four pieces in flight per lane,
+            // quantize four values at a time, and scatter the codes to their (row, k) places in LDS.
+            const int64_t left = c.batch - row0;
+            const int vrows = left < ROWS ? (int)left : ROWS;
+            const int n_el = vrows * K0, n4 = n_el >> 2;
+            const float invK = 1.0f / (float)K0;
+            const float* src1 = (const float*)c.obs + row0 * K0;
+            const float4* src = (const float4*)src1;
+            for (int i0 = tid; i0 < n4; i0 += 4 * FT) {
+                float4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (i0 + u * FT < n4) v[u] = src[i0 + u * FT];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int idx = i0 + u * FT;
+                    if (idx < n4) {
+                        uint32_t pack = quant_code4(v[u], qs0, -z0, 255 - z0, z0);
+                        if (TAPS) {
+                            if (t.a0) *(uint32_t*)(t.a0 + row0 * K0 + 4 * idx) = pack;
+                        }
+                        pack ^= 0x80808080u;
+                        const int e = 4 * idx;
+                        // e / K0: (e + 0.5) / K0 stays at least 0.5 / K0 away from every integer, far more
+                        // than the rounding error of the product at these magnitudes
+                        int m = (int)(((float)e + 0.5f) * invK);
+                        int k = e - m * K0;
+                        if ((k & 3) == 0 && k + 4 <= K0) {
+                            *(uint32_t*)(buf_in + m * ld + k) = pack;
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                buf_in[m * ld + k] = (int8_t)(pack >> (8 * i));
+                                if (++k == K0) {
+                                    k = 0;
+                                    ++m;
+                                }
+                            }
+                        }
                     }
-                    pack ^= 0x80808080u;
                 }
-                *(uint32_t*)(buf_in + m * ld + 4 * k4) = pack;
             }
+            if (tid < n_el - 4 * n4) {  // at most three elements past the last whole piece
+                const int e = 4 * n4 + tid;
+                const int m = (int)(((float)e + 0.5f) * invK), k = e - m * K0;
+                const int code = quant_code(src1[e], qs0, -z0, 255 - z0) + z0;
+                if (TAPS) {
+                    if (t.a0) t.a0[row0 * K0 + e] = (uint8_t)code;
+                }
+                buf_in[m * ld + k] = (int8_t)(code - 128);
+            }
+            // zero (signed domain) in the padding columns and in the rows past the batch
             const int padw = Kp - K0;
-            for (int idx = tid; idx < ROWS * padw; idx += FT) {
-                const int m = idx / padw, k = K0 + (idx - m * padw);
-                buf_in[m * ld + k] = 0;
+            if (padw > 0) {
+                for (int m = tid >> 5; m < vrows; m += FT / 32) {
+                    const int k = K0 + (tid & 31);
+                    if (k < Kp) buf_in[m * ld + k] = 0;
+                }
             }
+            for (int m = vrows + wave; m < ROWS; m += FW)
+                for (int k = lane; k < Kp; k += 64) buf_in[m * ld + k] = 0;
         } else {
             // 16 lanes per row; each lane requests up to eight elements before it converts the first,
             // and the zero padding up to the k-step boundary is written in the same sweep
@@ -198,11 +240,6 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
     const int n_layers = uni(an.n_layers);
     const float ln_eps = unif(an.ln_eps);
     int N_last = 0, NT_last = 0;
-    v4i cv0 = {0, 0, 0, 0}, cv1 = cv0;
-    {
-        const LayerView v0 = layer_view(an, 0, n_layers);
-        load_consts(v0, tid, cv0, cv1);
-    }
     for (int l = 0; l < n_layers; ++l) {
         const LayerView L = layer_view(an, l, n_layers);
         const bool last = L.last, ln = L.ln;
@@ -215,6 +252,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const float s_out = L.s_out;
         const int z_out = L.z_out, fast = L.fast;
         const QuantScale qs_out = make_quant_scale(s_out);
+        const float zf_out = (float)z_out;
         const int lo = (!last && L.act == AQ_ACT_RELU) ? z_out : 0;
         const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
         const int ldy = Np;  // last layer: fp32 row stride of y in LDS
@@ -377,10 +415,23 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 #pragma unroll
                                 for (int i = 0; i < 4; ++i) {
                                     const float x = __int_as_float(acc[nb][mt][4 * j + i]);
-                                    tv[i] = tanh_fast((x - mean[mt]) * inv[mt] * gv[i] + bv[i]);
+                                    tv[i] = tanh_exp2(fmaf((x - mean[mt]) * inv[mt], gv[i], bv[i]));
                                 }
-                                uint32_t pack = quant_code4(float4{tv[0], tv[1], tv[2], tv[3]}, qs_out, -z_out,
-                                                            255 - z_out, z_out);
+                                uint32_t pack;
+                                if (qs_out.rcp_ok) {
+                                    // the tanh value already carries rounding differences of its own, so the
+                                    // code is taken from t * (1/s) + z directly (it can differ from round(t/s)
+                                    // only where t/s sits on a rounding tie)
+                                    pack = 0;
+#pragma unroll
+                                    for (int i = 0; i < 4; ++i) {
+                                        const int ci = (int)rintf(fmaf(tv[i], qs_out.inv, zf_out));
+                                        pack |= (uint32_t)min(max(ci, 0), 255) << (8 * i);
+                                    }
+                                } else {
+                                    pack = quant_code4(float4{tv[0], tv[1], tv[2], tv[3]}, qs_out, -z_out, 255 - z_out,
+                                                       z_out);
+                                }
                                 if (n0 + 4 > L.N) {
                                     // padding features are zero in the signed domain
                                     const int keep = L.N - n0;  // < 4, may be <= 0
