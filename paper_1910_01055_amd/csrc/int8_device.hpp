@@ -92,49 +92,119 @@ __device__ __forceinline__ float tanh_head(float x) {
 // loads before it starts the current layer's epilogue.
 template <int NB, int PF>
 __device__ __forceinline__ void mma_prefetch(gv4i_ptr (&wptr)[NB], int ks_begin, int ks_end, v4i (&wreg)[PF][NB]) {
+    // unconditional (indices past the end are clamped, those registers are never used): straight-line
+    // loads let the compiler count exactly how many are in flight when the first one is needed
 #pragma unroll
-    for (int p = 0; p < PF; ++p)
-        if (ks_begin + p < ks_end) {
+    for (int p = 0; p < PF; ++p) {
+        const int k = ks_begin + p < ks_end - 1 ? ks_begin + p : ks_end - 1;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) wreg[p][nb] = wptr[nb][(int64_t)(ks_begin + p) * 64];
-        }
+        for (int nb = 0; nb < NB; ++nb) wreg[p][nb] = wptr[nb][(int64_t)k * 64];
+    }
 }
 
 template <int MT, int NB, bool ASYM, int PF>
 __device__ __forceinline__ void mma_run(gv4i_ptr (&wptr)[NB], v4i (&wreg)[PF][NB], const int8_t* xs, int ld,
                                         int ks_begin, int ks_end, int ks_lds0, v16i (&acc)[NB][MT], v16i (&rs)[MT],
-                                        int lane, int ks_pf_end = -1) {
-    // ks_pf_end: the weight pipeline keeps loading up to this k-step (beyond ks_end when the caller
-    // walks K in chunks and calls again for the next chunk; chunk starts must be multiples of PF)
-    if (ks_pf_end < 0) ks_pf_end = ks_end;
+                                        int lane) {
     const int8_t* xrow = xs + (lane & 31) * ld + (lane >> 5) * 16;
     v4i ones;
     ones[0] = ones[1] = ones[2] = ones[3] = 0x01010101;
-    for (int ks = ks_begin; ks < ks_end; ks += PF) {
+    // The activation operands are read R k-steps ahead of their MFMAs (a ring of R register sets;
+    // R divides PF so that every slot index is static): each k-step sits in its own conditional
+    // block, where the compiler cannot move the LDS read ahead of the wait by itself.
+    constexpr int R = MT == 1 ? 4 : (MT == 2 ? 2 : 1);
+    static_assert(PF % R == 0, "operand ring must divide the weight pipeline depth");
+    v4i xf[R][MT];
+    const int ks_last = ks_end - 1;
+    if (R > 1) {
 #pragma unroll
-        for (int p = 0; p < PF; ++p) {
+        for (int i = 0; i < R; ++i) {
+            const int kk = ks_begin + i < ks_last ? ks_begin + i : ks_last;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xf[i][mt] = *(const v4i*)(xrow + mt * 32 * ld + (kk - ks_lds0) * 32);
+        }
+    }
+    // Whole groups of PF k-steps run as straight-line code: with no branch between a weight load and
+    // its use, the compiler can wait for exactly the oldest loads (a conditional block in between
+    // makes it wait for all of them, which drains the pipeline once per group).
+    //   refill 1: every slot is refilled with k + PF (the caller guarantees k + PF < ks_end)
+    //   refill 2: the last whole group before a partial one; indices past the end are clamped and the
+    //             tiles re-read there are never used
+    //   refill 0: the last group of K, nothing left to load
+    auto group = [&](int ks, auto refill_c) __attribute__((always_inline)) {
+        constexpr int refill = decltype(refill_c)::value;
+        static_for<0, PF>([&](auto p_c) __attribute__((always_inline)) {
+            constexpr int p = decltype(p_c)::value;
+            constexpr int slot = p % R;
             const int k = ks + p;
-            if (k < ks_end) {
-                v4i xf[MT];
+            if (R == 1) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) xf[0][mt] = *(const v4i*)(xrow + mt * 32 * ld + (k - ks_lds0) * 32);
+            }
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    xf[mt] = *(const v4i*)(xrow + mt * 32 * ld + (k - ks_lds0) * 32);
+                    acc[nb][mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[p][nb], xf[slot][mt], acc[nb][mt], 0, 0, 0);
+            if (ASYM) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    rs[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, xf[slot][mt], rs[mt], 0, 0, 0);
+            }
+            if (R > 1) {
+                const int kk = k + R < ks_last ? k + R : ks_last;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                    xf[slot][mt] = *(const v4i*)(xrow + mt * 32 * ld + (kk - ks_lds0) * 32);
+            }
+            if (refill != 0) {
+                const int kw = refill == 1 ? k + PF : (k + PF < ks_last ? k + PF : ks_last);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) wreg[p][nb] = wptr[nb][(int64_t)kw * 64];
+                // keep each refill right behind the MFMAs that freed its registers: moved to the end of
+                // the group, it would be needed again almost at once
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+    };
+    int ks = ks_begin;
+    for (; ks + 2 * PF <= ks_end; ks += PF) group(ks, std::integral_constant<int, 1>{});
+    if (ks + PF <= ks_end) {
+        if (ks + PF < ks_end) group(ks, std::integral_constant<int, 2>{});
+        else group(ks, std::integral_constant<int, 0>{});
+        ks += PF;
+    }
+    // the remaining k-steps (fewer than PF), one conditional block each
+    if (ks < ks_end) {
+        static_for<0, PF - 1>([&](auto p_c) __attribute__((always_inline)) {
+            constexpr int p = decltype(p_c)::value;
+            constexpr int slot = p % R;
+            const int k = ks + p;
+            if (k < ks_end) {
+                if (R == 1) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        xf[0][mt] = *(const v4i*)(xrow + mt * 32 * ld + (k - ks_lds0) * 32);
+                }
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
-                        acc[nb][mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[p][nb], xf[mt], acc[nb][mt], 0, 0, 0);
+                        acc[nb][mt] =
+                            __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[p][nb], xf[slot][mt], acc[nb][mt], 0, 0, 0);
                 if (ASYM) {
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt)
-                        rs[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, xf[mt], rs[mt], 0, 0, 0);
+                        rs[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ones, xf[slot][mt], rs[mt], 0, 0, 0);
                 }
-                if (k + PF < ks_end) {
+                if (R > 1) {
+                    const int kk = k + R < ks_last ? k + R : ks_last;  // never past the staged columns
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) wreg[p][nb] = wptr[nb][(int64_t)(k + PF) * 64];
+                    for (int mt = 0; mt < MT; ++mt)
+                        xf[slot][mt] = *(const v4i*)(xrow + mt * 32 * ld + (kk - ks_lds0) * 32);
                 }
             }
-        }
+        });
     }
 }
 
