@@ -98,6 +98,41 @@ __device__ __forceinline__ uint32_t quant_code4(float4 v, const QuantScale& q, i
     return (uint32_t)(c0 & 255) | ((uint32_t)(c1 & 255) << 8) | ((uint32_t)(c2 & 255) << 16) | ((uint32_t)c3 << 24);
 }
 
+// Four unsigned codes clamp(round(v / s) + z, 0, 255) packed little-endian: the form of quant_code4
+// for activations and observations (lo = -z, hi = 255 - z, add = z), with the guard-band test folded
+// into one comparison and the clamp, the conversion and the packing done by the saturating
+// float -> byte conversion (the rounded value plus z is an integer, or saturates either way).
+__device__ __forceinline__ uint32_t quant_u8x4(float4 v, const QuantScale& q, float zf) {
+    float r0, r1, r2, r3;
+    bool exact = !q.rcp_ok;
+    if (!exact) {
+        const float m0 = v.x * q.inv, m1 = v.y * q.inv, m2 = v.z * q.inv, m3 = v.w * q.inv;
+        r0 = rintf(m0);
+        r1 = rintf(m1);
+        r2 = rintf(m2);
+        r3 = rintf(m3);
+        const float c = 9.5367431640625e-7f;  // 2^-20
+        // 0.5 - |m - r| < |m| c + c  <=>  |m - r| + |m| c > 0.5 - c
+        const float t0 = fmaf(fabsf(m0), c, fabsf(m0 - r0)), t1 = fmaf(fabsf(m1), c, fabsf(m1 - r1));
+        const float t2 = fmaf(fabsf(m2), c, fabsf(m2 - r2)), t3 = fmaf(fabsf(m3), c, fabsf(m3 - r3));
+        const float tm = fmaxf(fmaxf(t0, t1), fmaxf(t2, t3));
+        // (a NaN or infinite lane drops out of the maximum; its code is the same on either path)
+        exact = !(tm <= 0.5f - c);
+    }
+    if (exact) {
+        r0 = rintf(v.x / q.s);
+        r1 = rintf(v.y / q.s);
+        r2 = rintf(v.z / q.s);
+        r3 = rintf(v.w / q.s);
+    }
+    uint32_t pack = 0;
+    pack = __builtin_amdgcn_cvt_pk_u8_f32(r0 + zf, 0, pack);
+    pack = __builtin_amdgcn_cvt_pk_u8_f32(r1 + zf, 1, pack);
+    pack = __builtin_amdgcn_cvt_pk_u8_f32(r2 + zf, 2, pack);
+    pack = __builtin_amdgcn_cvt_pk_u8_f32(r3 + zf, 3, pack);
+    return pack;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));

@@ -135,6 +135,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const float s0 = a.actq[0].s;
         const int z0 = a.actq[0].z;
         const QuantScale qs0 = make_quant_scale(s0);
+        const float zf0 = (float)z0;
         if (!c.in_u8 && ((uintptr_t)c.obs & 15) == 0) {
             // The block's rows are one contiguous run in memory that starts 16-byte aligned (ROWS * K0
             // is a multiple of 4): read it as flat 16-byte pieces, four pieces in flight per lane,
@@ -154,22 +155,23 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 for (int u = 0; u < 4; ++u) {
                     const int idx = i0 + u * FT;
                     if (idx < n4) {
-                        uint32_t pack = quant_code4(v[u], qs0, -z0, 255 - z0, z0);
+                        uint32_t pack = quant_u8x4(v[u], qs0, zf0);
                         if (TAPS) {
                             if (t.a0) *(uint32_t*)(t.a0 + row0 * K0 + 4 * idx) = pack;
                         }
                         pack ^= 0x80808080u;
                         const int e = 4 * idx;
                         // e / K0: (e + 0.5) / K0 stays at least 0.5 / K0 away from every integer, far more
-                        // than the rounding error of the product at these magnitudes
+                        // than the rounding error of the product at these magnitudes (all below 2^23, so
+                        // the 24-bit multiplies are exact)
                         int m = (int)(((float)e + 0.5f) * invK);
-                        int k = e - m * K0;
+                        int k = e - __mul24(m, K0);
                         if ((k & 3) == 0 && k + 4 <= K0) {
-                            *(uint32_t*)(buf_in + m * ld + k) = pack;
+                            *(uint32_t*)(buf_in + __mul24(m, ld) + k) = pack;
                         } else {
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                buf_in[m * ld + k] = (int8_t)(pack >> (8 * i));
+                                buf_in[__mul24(m, ld) + k] = (int8_t)(pack >> (8 * i));
                                 if (++k == K0) {
                                     k = 0;
                                     ++m;
@@ -425,8 +427,9 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                                     pack = 0;
 #pragma unroll
                                     for (int i = 0; i < 4; ++i) {
-                                        const int ci = (int)rintf(fmaf(tv[i], qs_out.inv, zf_out));
-                                        pack |= (uint32_t)min(max(ci, 0), 255) << (8 * i);
+                                        // saturating float -> byte conversion: clamp to [0, 255] and pack
+                                        pack = __builtin_amdgcn_cvt_pk_u8_f32(rintf(fmaf(tv[i], qs_out.inv, zf_out)), i,
+                                                                              pack);
                                     }
                                 } else {
                                     pack = quant_code4(float4{tv[0], tv[1], tv[2], tv[3]}, qs_out, -z_out, 255 - z_out,
