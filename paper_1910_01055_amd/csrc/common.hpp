@@ -207,6 +207,9 @@ struct CallArgs {
     const int8_t* wp0;
     const int32_t* pack0;
     int NT0, KS0, pieces0;
+    int narrow0;   // fused kernel: the first layer is also the last and narrow (its weights are split over K)
+    int part_off;  // fused kernel: LDS offset of the partial-sum area of a narrow last layer, or -1 when it
+                   // fits the idle activation buffer
 };
 
 // Optional intermediate outputs (by value, only read by the kernels compiled with TAPS).

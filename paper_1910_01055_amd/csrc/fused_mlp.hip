@@ -23,7 +23,7 @@ AQ_FUSED_DECL(4, 1, true, true);
 
 namespace {
 struct Plan {
-    int mt, nb, ld, cst_n;
+    int mt, nb, ld, cst_n, part_off;
     size_t lds;
 };
 
@@ -53,8 +53,16 @@ bool make_plan(const FwdArgs& a, Plan* p) {
     int mt = 1;
     if (a.c.batch >= 256 * 64) mt = 2;
     if (a.c.batch >= 512 * 128 && p->nb == 1) mt = 4;
+    const bool narrow_last = a.net.L[a.net.n_layers - 1].NT <= NARROW_NT;
     for (; mt >= 1; mt >>= 1) {
         p->lds = fused_lds_bytes(32 * mt, p->ld, p->cst_n);
+        p->part_off = -1;
+        // partial sums of a narrow last layer: in the idle activation buffer if it is large enough,
+        // else in an area of their own behind everything else
+        if (narrow_last && (size_t)32 * mt * p->ld < (size_t)PART_BYTES) {
+            p->part_off = (int)p->lds;
+            p->lds += PART_BYTES;
+        }
         if (p->lds <= 160 * 1024) {
             p->mt = mt;
             return true;
@@ -90,6 +98,8 @@ aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     a.c.NT0 = a.net.L[0].NT;
     a.c.KS0 = a.net.L[0].KS;
     a.c.pieces0 = (a.net.n_layers == 1 ? 2 : 4) * a.net.L[0].NT * 8;
+    a.c.part_off = p.part_off;
+    a.c.narrow0 = a.net.n_layers == 1 && a.net.L[0].NT <= NARROW_NT;
     const bool tp = any_taps(a);
     const bool as = a.net.asym != 0;
 #define AQ_GO(MT, NB, AS) \

@@ -93,6 +93,65 @@ __device__ __forceinline__ void tile_ptrs(const int8_t* wp, int NT, int KS, int 
     }
 }
 
+// A last layer of at most two feature tiles would leave most waves idle.  It is spread over all
+// eight instead: its (feature tile, row tile) pairs go to different waves, and the waves left over
+// split K.  Partial accumulators meet in LDS (PART_WORDS ints per wave: 16 accumulator registers
+// and the row sums of the activations, lane-major).
+constexpr int NARROW_NT = 2;
+constexpr int PART_WORDS = 17 * 64;
+constexpr int PART_BYTES = FW * PART_WORDS * 4;
+struct NarrowMap {
+    int pairs, ksplit, pair, nt, mt, k0, k1;
+};
+template <int MT>
+__device__ __forceinline__ NarrowMap narrow_map(int NT, int KS, int wave) {
+    NarrowMap x;
+    x.pairs = NT * MT;                        // 1, 2, 4 or 8
+    const int lg = 31 - __builtin_clz(x.pairs);
+    x.ksplit = FW >> lg;
+    x.pair = wave & (x.pairs - 1);
+    const int kpart = wave >> lg;
+    x.nt = x.pair & (NT - 1);
+    x.mt = x.pair >> (NT - 1);                // NT is 1 or 2
+    const int kchunk = (KS + x.ksplit - 1) >> (3 - lg);
+    x.k0 = kpart * kchunk;
+    x.k1 = x.k0 + kchunk < KS ? x.k0 + kchunk : KS;
+    return x;
+}
+
+// Sums the K-split partial accumulators of a narrow last layer and dequantizes: every thread owns
+// 2 * NT * MT outputs (lane-major, so its LDS reads are conflict-free) and reads the KSPLIT partial
+// sums of each; all reads of one output are independent and issued together.
+template <int MT, int NT, bool ASYM, bool TAPS>
+__device__ __forceinline__ void narrow_reduce(const int32_t* part, const CPtrs& C, const LayerTaps& T, int N, int zw_s,
+                                              int64_t row0, int64_t batch, float* yrow, int ldy, int tid) {
+    constexpr int PAIRS = NT * MT, KSPLIT = FW / PAIRS;
+    const int ln = tid & 63;
+#pragma unroll
+    for (int it = 0; it < 2 * PAIRS; ++it) {
+        const int e = tid + it * FT;
+        const int pr = it >> 1;                 // FT = 512 outputs per step, 1024 per pair
+        const int reg = (e >> 6) & 15;
+        int v = 0, rsum = 0;
+#pragma unroll
+        for (int kp = 0; kp < KSPLIT; ++kp) {
+            const int32_t* src = part + (kp * PAIRS + pr) * PART_WORDS + ln;
+            v += src[reg * 64];
+            if (ASYM) rsum += src[16 * 64];
+        }
+        const int nt = pr & (NT - 1), mt = pr / NT;
+        const int n = nt * 32 + 8 * (reg >> 2) + 4 * (ln >> 5) + (reg & 3);
+        const int m = mt * 32 + (ln & 31);
+        v += C.bias_fold[n];
+        if (ASYM) v -= zw_s * rsum;
+        const int64_t row = row0 + m;
+        if (TAPS) {
+            if (T.acc && row < batch && n < N) T.acc[row * N + n] = v;
+        }
+        yrow[m * ldy + n] = (float)v * C.m[n];
+    }
+}
+
 template <int MT, int NB, bool ASYM, bool TAPS>
 __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ netp, const CallArgs c,
                                                   const TapArgs t) {
@@ -121,8 +180,10 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
     v4i wreg[PF][NB];
     if (XPF) {
         gv4i_ptr wptr[NB];
-        tile_ptrs<NB>(c.wp0, c.NT0, c.KS0, wave, lane, wptr);
-        if (wave * NB < c.NT0) mma_prefetch<NB, PF>(wptr, 0, c.KS0, wreg);
+        if (!c.narrow0) {
+            tile_ptrs<NB>(c.wp0, c.NT0, c.KS0, wave, lane, wptr);
+            if (wave * NB < c.NT0) mma_prefetch<NB, PF>(wptr, 0, c.KS0, wreg);
+        }
     }
     // ... and its per-channel constants
     v4i cv0 = {0, 0, 0, 0}, cv1 = cv0;
@@ -241,12 +302,16 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 
     const int n_layers = uni(an.n_layers);
     const float ln_eps = unif(an.ln_eps);
-    int N_last = 0, NT_last = 0;
-    for (int l = 0; l < n_layers; ++l) {
+    int N_last = 0;
+    const float* ybuf = nullptr;  // dequantized last-layer rows in LDS and their stride, set by the last layer
+    int ldy_h = 0;
+    // a narrow last layer is handled after the loop, by all waves together
+    const bool narrow = uni(an.L[n_layers - 1].NT) <= NARROW_NT;
+    const int n_loop = narrow ? n_layers - 1 : n_layers;
+    for (int l = 0; l < n_loop; ++l) {
         const LayerView L = layer_view(an, l, n_layers);
         const bool last = L.last, ln = L.ln;
         N_last = L.N;
-        NT_last = L.NT;
         LayerTaps T{nullptr, nullptr, nullptr};
         if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
         const int ngroups = (L.NT + NB - 1) / NB;
@@ -268,6 +333,10 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const float* c_gamma = (const float*)(cst + 2 * Np);
         const float* c_beta = (const float*)(cst + 3 * Np);
 
+        if (last) {
+            ybuf = (const float*)out;
+            ldy_h = ldy;
+        }
         for (int g0 = 0; g0 < ngroups; g0 += FW) {
             const int grp = g0 + wave;
             const bool active = grp < ngroups;
@@ -292,7 +361,9 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 const int8_t* wp_n = uni_ptr(an.L[ln_i].wp);
                 const int NT_n = uni(an.L[ln_i].NT), KS_n = uni(an.L[ln_i].KS);
                 const int grp_n = more ? grp + FW : wave;
-                if ((more || !last) && grp_n * NB < NT_n) {
+                // (a narrow last layer fetches its own weights: its waves split K instead of the tiles)
+                const bool narrow_next = !more && l + 2 == n_layers && NT_n <= NARROW_NT;
+                if ((more || !last) && !narrow_next && grp_n * NB < NT_n) {
                     gv4i_ptr wptr[NB];
                     tile_ptrs<NB>(wp_n, NT_n, KS_n, grp_n, lane, wptr);
                     mma_prefetch<NB, PF>(wptr, 0, KS_n, wreg);
@@ -464,11 +535,55 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         buf_out = sw;
     }
 
+    if (narrow) {
+        const int l = n_layers - 1;
+        const LayerView L = layer_view(an, l, n_layers);
+        N_last = L.N;
+        LayerTaps T{nullptr, nullptr, nullptr};
+        if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
+        const int Np = L.NT * 32;
+        const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
+        const int8_t* in = buf_in;
+        park_consts(L, tid, cst, cv0, cv1);
+        const CPtrs C{cst, cst + Np, L.rshift, cst + 2 * Np, cst + 3 * Np, (const float*)(cst + Np)};
+        // Everything below depends on the thread index only; left alone, the compiler computes it at
+        // the top of the kernel and keeps it in registers through every layer.  The empty asm hides
+        // the index from that motion.
+        int tid_n = tid;
+        asm volatile("" : "+v"(tid_n));
+        const int lane = tid_n & 63, wave = __builtin_amdgcn_readfirstlane(tid_n >> 6);
+        const NarrowMap nm = narrow_map<MT>(L.NT, L.KS, wave);
+        v16i pacc[1][1], prs[1];
+        pacc[0][0] = zero16();
+        prs[0] = zero16();
+        if (nm.k0 < nm.k1) {
+            gv4i_ptr wptr[1];
+            wptr[0] = (gv4i_ptr)L.wp + (int64_t)nm.nt * L.KS * 64 + lane;
+            v4i w1[4][1];
+            mma_prefetch<1, 4>(wptr, nm.k0, nm.k1, w1);
+            mma_run<1, 1, ASYM, 4>(wptr, w1, in + nm.mt * 32 * ld, ld, nm.k0, nm.k1, 0, pacc, prs, lane);
+        }
+        int32_t* part = c.part_off >= 0 ? (int32_t*)(smem + c.part_off) : (int32_t*)buf_out;
+        {
+            int32_t* mine = part + wave * PART_WORDS + lane;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mine[r * 64] = pacc[0][0][r];
+            if (ASYM) mine[16 * 64] = prs[0][0];
+        }
+        lds_barrier();  // partial sums and this layer's constants are in LDS; the layer's input is free
+        // y rows go where the layer's input was (stride Np + 1 floats keeps the banks apart)
+        float* yrow = (float*)buf_in;
+        ybuf = yrow;
+        ldy_h = Np + 1;
+        if (L.NT == 1) narrow_reduce<MT, 1, ASYM, TAPS>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n);
+        else narrow_reduce<MT, 2, ASYM, TAPS>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n);
+        lds_barrier();
+    }
+
     // action head on the dequantized last-layer rows y (fp32, in LDS): tanh / identity / argmax
     {
         const int head = uni(an.head);
-        const float* ybuf = (const float*)buf_in;
-        const int ldy = NT_last * 32;
+        const int ldy = ldy_h;
         const int N = N_last;
         if (head == AQ_HEAD_ARGMAX) {
             for (int m = tid; m < ROWS; m += FT) {

@@ -76,6 +76,14 @@ def _nets():
         "u8_mlp": synth.small_net([fc(48, 64, "relu"), fc(64, 5, "none")], head="tanh", in_type="u8"),
         "literal256": synth.small_net([fc(17, 64, "relu"), fc(64, 6, "none")], head="tanh", qdenom=256,
                                       wscheme="tensor_asym_u8"),
+        # last layers of one, two and more feature tiles, and single-layer networks (the fused kernel
+        # spreads a narrow last layer over its waves by splitting K)
+        "wide_last": synth.small_net([fc(40, 64, "relu"), fc(64, 100, "none")], head="linear"),
+        "two_tile_last_asym": synth.small_net([fc(30, 64, "relu"), fc(64, 60, "none")], head="argmax",
+                                              wscheme="tensor_asym_u8"),
+        "single_narrow": synth.small_net([fc(50, 37, "none")], head="tanh"),
+        "single_wide_asym": synth.small_net([fc(50, 130, "none")], head="linear", wscheme="tensor_asym_u8"),
+        "long_k_narrow": synth.small_net([fc(20, 700, "relu"), fc(700, 10, "none")], head="tanh"),
         "conv_small": synth.small_net([conv(12, 12, 4, 16, 4, 4, 2, "relu"), conv(5, 5, 16, 32, 3, 3, 1, "relu"),
                                        fc(288, 48, "relu"), fc(48, 5, "none")], head="argmax", in_type="u8",
                                       init="he_normal"),
@@ -153,6 +161,27 @@ def test_forward_full_size(aq, name, batch, sample):
         assert np.isfinite(actions).all() and np.abs(actions).max() <= 1.0
     else:
         assert actions.min() >= 0 and actions.max() < synth.action_dim(net)
+    P.close()
+
+
+@pytest.mark.parametrize("name", ["odd_asym", "two_tile_last_asym", "wide_last", "single_narrow", "long_k_narrow",
+                                  "odd_sym_ln"])
+@pytest.mark.parametrize("batch", [16500, 65700])
+def test_fused_row_tiles_large_batch(aq, name, batch):
+    """Small networks at the batch sizes where the fused kernel takes 64 and 128 rows per workgroup
+    (every weight scheme, narrow and wide last layers), on sampled rows."""
+    _say(f"fused_row_tiles_large_batch {name} batch={batch}")
+    net = _nets()[name]
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs[:256])
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    actions, t = U.gpu_forward(P, net, obs)
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([[0, 31, 32, 63, 64, 127, 128, batch - 1], rng.integers(0, batch, 300)]))
+    U.compare_forward(net, pol, obs, actions, t, rows)
+    a2, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(a2, actions, equal_nan=True)
     P.close()
 
 
