@@ -3,6 +3,6 @@
 #include "fused_mlp.hpp"
 
 namespace aq {
-AQ_FUSED_INST(4, 1, false, false);
-AQ_FUSED_INST(4, 1, false, true);
+AQ_FUSED_INST(4, 1, false, false, false);
+AQ_FUSED_INST(4, 1, false, true, false);
 }  // namespace aq

@@ -3,6 +3,6 @@
 #include "fused_mlp.hpp"
 
 namespace aq {
-AQ_FUSED_INST(1, 1, true, false);
-AQ_FUSED_INST(1, 1, true, true);
+AQ_FUSED_INST(1, 1, true, false, false);
+AQ_FUSED_INST(1, 1, true, true, false);
 }  // namespace aq

@@ -4,26 +4,31 @@
 
 namespace aq {
 
-AQ_FUSED_DECL(1, 1, false, false);
-AQ_FUSED_DECL(1, 1, false, true);
-AQ_FUSED_DECL(2, 1, false, false);
-AQ_FUSED_DECL(2, 1, false, true);
-AQ_FUSED_DECL(4, 1, false, false);
-AQ_FUSED_DECL(4, 1, false, true);
-AQ_FUSED_DECL(1, 2, false, false);
-AQ_FUSED_DECL(1, 2, false, true);
-AQ_FUSED_DECL(2, 2, false, false);
-AQ_FUSED_DECL(2, 2, false, true);
-AQ_FUSED_DECL(1, 1, true, false);
-AQ_FUSED_DECL(1, 1, true, true);
-AQ_FUSED_DECL(2, 1, true, false);
-AQ_FUSED_DECL(2, 1, true, true);
-AQ_FUSED_DECL(4, 1, true, false);
-AQ_FUSED_DECL(4, 1, true, true);
+AQ_FUSED_DECL(1, 1, false, false, false);
+AQ_FUSED_DECL(1, 1, false, true, false);
+AQ_FUSED_DECL(2, 1, false, false, false);
+AQ_FUSED_DECL(2, 1, false, true, false);
+AQ_FUSED_DECL(4, 1, false, false, false);
+AQ_FUSED_DECL(4, 1, false, true, false);
+AQ_FUSED_DECL(1, 2, false, false, false);
+AQ_FUSED_DECL(1, 2, false, true, false);
+AQ_FUSED_DECL(2, 2, false, false, false);
+AQ_FUSED_DECL(2, 2, false, true, false);
+AQ_FUSED_DECL(1, 1, true, false, false);
+AQ_FUSED_DECL(1, 1, true, true, false);
+AQ_FUSED_DECL(2, 1, true, false, false);
+AQ_FUSED_DECL(2, 1, true, true, false);
+AQ_FUSED_DECL(4, 1, true, false, false);
+AQ_FUSED_DECL(4, 1, true, true, false);
+AQ_FUSED_DECL(1, 1, false, false, true);
+AQ_FUSED_DECL(1, 1, false, true, true);
+AQ_FUSED_DECL(1, 1, true, false, true);
+AQ_FUSED_DECL(1, 1, true, true, true);
 
 namespace {
 struct Plan {
     int mt, nb, ld, cst_n, part_off;
+    bool half;  // 16 rows per workgroup
     size_t lds;
 };
 
@@ -46,12 +51,21 @@ bool make_plan(const FwdArgs& a, Plan* p) {
     // feature tiles per wave: wide layers take 2 (two passes of the 8 waves cover 32 tiles); more would
     // not leave registers for the operand pipeline at two waves per SIMD
     p->nb = (max_nt >= 32 && !a.net.asym) ? 2 : 1;
-    for (int l = 0; l < a.net.n_layers - 1; ++l)  // LayerNorm needs its whole row resident in one pass
-        if (a.net.L[l].act == AQ_ACT_LN_TANH && (a.net.L[l].NT + p->nb - 1) / p->nb > FW) return false;
+    // Up to 4096 rows, 32-row workgroups would leave CUs idle: 16-row workgroups (one tile per wave)
+    // halve the epilogue work per CU instead.
+    p->half = a.c.batch <= 16 * 256;
+    auto ln_fits = [&](int nb) {  // LayerNorm needs its whole row resident in one pass
+        for (int l = 0; l < a.net.n_layers - 1; ++l)
+            if (a.net.L[l].act == AQ_ACT_LN_TANH && (a.net.L[l].NT + nb - 1) / nb > FW) return false;
+        return true;
+    };
+    if (p->half && ln_fits(1)) p->nb = 1;
+    else p->half = false;
+    if (!ln_fits(p->nb)) return false;
     // rows per workgroup: enough workgroups to cover the 256 CUs first, more rows per workgroup
     // (fewer weight re-reads from L2) once the batch is large enough
     int mt = 1;
-    if (a.c.batch >= 256 * 64) mt = 2;
+    if (a.c.batch >= 256 * 64) mt = 2;  // (never with 16-row workgroups: those are for small batches)
     if (a.c.batch >= 512 * 128 && p->nb == 1) mt = 4;
     const bool narrow_last = a.net.L[a.net.n_layers - 1].NT <= NARROW_NT;
     for (; mt >= 1; mt >>= 1) {
@@ -82,7 +96,7 @@ bool any_taps(const FwdArgs& a) {
 bool fused_mlp_supported(const FwdArgs& a, int* rows_out, size_t* lds_out) {
     Plan p;
     if (!make_plan(a, &p)) return false;
-    *rows_out = 32 * p.mt;
+    *rows_out = p.half ? 16 : 32 * p.mt;
     *lds_out = p.lds;
     return true;
 }
@@ -102,20 +116,25 @@ aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     a.c.narrow0 = a.net.n_layers == 1 && a.net.L[0].NT <= NARROW_NT;
     const bool tp = any_taps(a);
     const bool as = a.net.asym != 0;
-#define AQ_GO(MT, NB, AS) \
-    return tp ? launch_fused_t<MT, NB, AS, true>(a, p.lds, st) : launch_fused_t<MT, NB, AS, false>(a, p.lds, st)
+#define AQ_GO(MT, NB, AS, HF)                                                   \
+    return tp ? launch_fused_t<MT, NB, AS, true, HF>(a, p.lds, st) \
+              : launch_fused_t<MT, NB, AS, false, HF>(a, p.lds, st)
+    if (p.half) {
+        if (as) AQ_GO(1, 1, true, true);
+        AQ_GO(1, 1, false, true);
+    }
     if (p.nb == 2) {
-        if (p.mt == 1) AQ_GO(1, 2, false);
-        AQ_GO(2, 2, false);
+        if (p.mt == 1) AQ_GO(1, 2, false, false);
+        AQ_GO(2, 2, false, false);
     }
     if (as) {
-        if (p.mt == 1) AQ_GO(1, 1, true);
-        if (p.mt == 2) AQ_GO(2, 1, true);
-        AQ_GO(4, 1, true);
+        if (p.mt == 1) AQ_GO(1, 1, true, false);
+        if (p.mt == 2) AQ_GO(2, 1, true, false);
+        AQ_GO(4, 1, true, false);
     }
-    if (p.mt == 1) AQ_GO(1, 1, false);
-    if (p.mt == 2) AQ_GO(2, 1, false);
-    AQ_GO(4, 1, false);
+    if (p.mt == 1) AQ_GO(1, 1, false, false);
+    if (p.mt == 2) AQ_GO(2, 1, false, false);
+    AQ_GO(4, 1, false, false);
 #undef AQ_GO
 }
 

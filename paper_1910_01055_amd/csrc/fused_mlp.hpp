@@ -122,7 +122,7 @@ __device__ __forceinline__ NarrowMap narrow_map(int NT, int KS, int wave) {
 // Sums the K-split partial accumulators of a narrow last layer and dequantizes: every thread owns
 // 2 * NT * MT outputs (lane-major, so its LDS reads are conflict-free) and reads the KSPLIT partial
 // sums of each; all reads of one output are independent and issued together.
-template <int MT, int NT, bool ASYM, bool TAPS>
+template <int MT, int NT, bool ASYM, bool TAPS, bool HALF>
 __device__ __forceinline__ void narrow_reduce(const int32_t* part, const CPtrs& C, const LayerTaps& T, int N, int zw_s,
                                               int64_t row0, int64_t batch, float* yrow, int ldy, int tid) {
     constexpr int PAIRS = NT * MT, KSPLIT = FW / PAIRS;
@@ -145,6 +145,7 @@ __device__ __forceinline__ void narrow_reduce(const int32_t* part, const CPtrs& 
         v += C.bias_fold[n];
         if (ASYM) v -= zw_s * rsum;
         const int64_t row = row0 + m;
+        if (HALF && m >= 16) continue;  // a 16-row workgroup: the upper half of the MFMA tile is don't-care
         if (TAPS) {
             if (T.acc && row < batch && n < N) T.acc[row * N + n] = v;
         }
@@ -152,23 +153,32 @@ __device__ __forceinline__ void narrow_reduce(const int32_t* part, const CPtrs& 
     }
 }
 
-template <int MT, int NB, bool ASYM, bool TAPS>
+// HALF (MT = NB = 1 only): the workgroup owns 16 rows instead of 32, for batches too small to give
+// every CU a 32-row workgroup.  The MFMAs still run on 32-row tiles (the upper 16 rows of the LDS
+// buffers are don't-care); fold_rows16 then spreads the 16 valid rows over all 64 lanes, so that the
+// epilogues, which are what bounds small networks, do half the work per lane.
+template <int MT, int NB, bool ASYM, bool TAPS, bool HALF>
 __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ netp, const CallArgs c,
                                                   const TapArgs t) {
     extern __shared__ __align__(16) int8_t smem[];
-    constexpr int ROWS = 32 * MT;
+    static_assert(!HALF || (MT == 1 && NB == 1), "16-row workgroups use one tile per wave");
+    constexpr int ROWS = HALF ? 16 : 32 * MT;  // rows this workgroup owns
+    constexpr int BROWS = 32 * MT;             // rows of each LDS activation buffer
+    constexpr int QT = HALF ? 2 : 4;           // register quads per tile and lane in the epilogues
     constexpr int PF = NB == 1 ? 8 : 4;
     // requesting the next weights ahead of the epilogue keeps PF*NB operand registers alive through
     // it; the wide variant (NB = 2) has no registers to spare and fetches at the start of each pass
     constexpr bool XPF = NB == 1;
     const NetDev& a = *netp;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+    const int hh = HALF ? (lane >> 4) & 1 : 0;        // which half of the feature quads (after the fold)
+    const int mrow = HALF ? lane & 15 : lane & 31;    // this lane's row within a row tile in the epilogues
     const int64_t row0 = (int64_t)blockIdx.x * ROWS;
     const int ld = c.ld, cst_n = c.cst_n;
     int8_t* buf_in = smem;
-    int8_t* buf_out = smem + ROWS * ld;
-    float* red = (float*)(smem + 2 * ROWS * ld);
-    int32_t* cst = (int32_t*)(red + 2 * FW * ROWS);
+    int8_t* buf_out = smem + BROWS * ld;
+    float* red = (float*)(smem + 2 * BROWS * ld);
+    int32_t* cst = (int32_t*)(red + 2 * FW * BROWS);
     int32_t* net_lds = cst + 4 * cst_n;
     const NetDev& an = *(const NetDev*)net_lds;  // valid after the first barrier
 
@@ -269,7 +279,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 const int m = mb + r32;
                 const int64_t row = row0 + m;
                 const bool ok = row < c.batch;
-                for (int kb = 0; kb < Kp; kb += 128) {
+                for (int kb = 0; kb < (m < ROWS ? Kp : 0); kb += 128) {
                     float xv[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
@@ -353,6 +363,10 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 tile_ptrs<NB>(L.wp, L.NT, L.KS, grp, lane, wptr);
                 if (!XPF) mma_prefetch<NB, PF>(wptr, 0, L.KS, wreg);
                 mma_run<MT, NB, ASYM, PF>(wptr, wreg, in, ld, 0, L.KS, 0, acc, rs, lane);
+                if (HALF) {
+                    fold_rows16(acc[0][0], lane);
+                    if (ASYM) rs[0][0] = fold_rows16_scalar(rs[0][0], lane);
+                }
             }
             // request the next pass's (or the next layer's) first weights before the epilogue
             if (XPF) {
@@ -377,7 +391,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
             if (g0 == 0) lds_barrier();
             if (!ln) {
                 if (active) {
-                    const int m0 = lane & 31;
+                    const int m0 = mrow;
                     if (last) {
                         static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
                             constexpr int nb = decltype(nb_c)::value;
@@ -387,37 +401,39 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                                     constexpr int mt = decltype(mt_c)::value;
                                     const int m = mt * 32 + m0;
                                     const int64_t row = row0 + m;
-                                    epi_last_tile<ASYM, TAPS>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row,
-                                                              row < c.batch, (float*)out + m * ldy, ldy, nullptr, 0);
+                                    epi_last_tile<ASYM, TAPS, HALF>(L.N, T, C, acc[nb][mt], rs[mt][0], zw_s, nt, g, row,
+                                                                    row < c.batch, (float*)out + m * ldy, ldy, nullptr,
+                                                                    0, hh);
                                 });
                             }
                         });
                     } else if (fast) {
-                        epi_hidden_wave<MT, NB, ASYM, TAPS, true>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row0 + m0, c.batch,
-                                                                  false, z_out, lo, out + m0 * ld, 32 * ld, true, Np);
+                        epi_hidden_wave<MT, NB, ASYM, TAPS, true, HALF>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row0 + m0,
+                                                                        c.batch, false, z_out, lo, out + m0 * ld, 32 * ld,
+                                                                        true, Np, hh);
                     } else {
-                        epi_hidden_wave<MT, NB, ASYM, TAPS, false>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row0 + m0,
-                                                                   c.batch, false, z_out, lo, out + m0 * ld, 32 * ld, true,
-                                                                   Np);
+                        epi_hidden_wave<MT, NB, ASYM, TAPS, false, HALF>(L.N, L.NT, T, C, acc, rs, zw_s, grp, g, row0 + m0,
+                                                                         c.batch, false, z_out, lo, out + m0 * ld, 32 * ld,
+                                                                         true, Np, hh);
                     }
                 }
             } else {
                 // LayerNorm over the layer's N features (all resident in this one pass: ngroups <= FW),
                 // tanh, re-quantize.  Row statistics: in-lane sums, lane ^ 32, then across waves via LDS.
                 float* red1 = red;
-                float* red2 = red + FW * ROWS;
+                float* red2 = red + FW * BROWS;
                 float mean[MT], inv[MT];
                 static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
                     constexpr int mt = decltype(mt_c)::value;
                     float s = 0.0f;
-                    const int64_t row = row0 + mt * 32 + (lane & 31);
+                    const int64_t row = row0 + mt * 32 + mrow;
                     const bool row_ok = row < c.batch;
                     static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
                         constexpr int nb = decltype(nb_c)::value;
                         const int nt = grp * NB + nb;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int n0 = nt * 32 + 8 * j + 4 * g;
+                        for (int j = 0; j < QT; ++j) {
+                            const int n0 = nt * 32 + 8 * (j + 2 * hh) + 4 * g;
                             if (active && n0 < Np) {
                                 int val[4];
                                 quad_acc<ASYM, TAPS>(L.N, T, C, acc[nb][mt], j, n0, rs[mt][0], zw_s, row, row_ok, val);
@@ -436,25 +452,26 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                         }
                     });
                     s += __shfl_xor(s, 32, 64);
-                    if (g == 0) red1[wave * ROWS + mt * 32 + lane] = s;
+                    if (HALF) s += __shfl_xor(s, 16, 64);
+                    if (g == 0 && hh == 0) red1[wave * BROWS + mt * 32 + mrow] = s;
                 });
                 lds_barrier();
                 static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
                     constexpr int mt = decltype(mt_c)::value;
-                    const int m = mt * 32 + (lane & 31);
+                    const int m = mt * 32 + mrow;
                     float tot = 0.0f;
 #pragma unroll
-                    for (int w = 0; w < FW; ++w) tot += red1[w * ROWS + m];
+                    for (int w = 0; w < FW; ++w) tot += red1[w * BROWS + m];
                     mean[mt] = tot / (float)L.N;
                     float ss = 0.0f;
                     static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
                         constexpr int nb = decltype(nb_c)::value;
                         const int nt = grp * NB + nb;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
+                        for (int j = 0; j < QT; ++j)
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                const int n = nt * 32 + 8 * j + 4 * g + i;
+                                const int n = nt * 32 + 8 * (j + 2 * hh) + 4 * g + i;
                                 if (active && n < L.N) {
                                     float d = __int_as_float(acc[nb][mt][4 * j + i]) - mean[mt];
                                     ss += d * d;
@@ -462,15 +479,16 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                             }
                     });
                     ss += __shfl_xor(ss, 32, 64);
-                    if (g == 0) red2[wave * ROWS + mt * 32 + lane] = ss;
+                    if (HALF) ss += __shfl_xor(ss, 16, 64);
+                    if (g == 0 && hh == 0) red2[wave * BROWS + mt * 32 + mrow] = ss;
                 });
                 lds_barrier();
                 static_for<0, MT>([&](auto mt_c) __attribute__((always_inline)) {
                     constexpr int mt = decltype(mt_c)::value;
-                    const int m = mt * 32 + (lane & 31);
+                    const int m = mt * 32 + mrow;
                     float tot = 0.0f;
 #pragma unroll
-                    for (int w = 0; w < FW; ++w) tot += red2[w * ROWS + m];
+                    for (int w = 0; w < FW; ++w) tot += red2[w * BROWS + m];
                     inv[mt] = 1.0f / sqrtf(tot / (float)L.N + ln_eps);
                     const int64_t row = row0 + m;
                     const bool row_ok = row < c.batch;
@@ -479,8 +497,8 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                         const int nt = grp * NB + nb;
                         if (active && nt < L.NT) {
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const int n0 = nt * 32 + 8 * j + 4 * g;
+                            for (int j = 0; j < QT; ++j) {
+                                const int n0 = nt * 32 + 8 * (j + 2 * hh) + 4 * g;
                                 const float4 ga = *(const float4*)(c_gamma + n0);
                                 const float4 be = *(const float4*)(c_beta + n0);
                                 const float gv[4] = {ga.x, ga.y, ga.z, ga.w}, bv[4] = {be.x, be.y, be.z, be.w};
@@ -575,8 +593,8 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         float* yrow = (float*)buf_in;
         ybuf = yrow;
         ldy_h = Np + 1;
-        if (L.NT == 1) narrow_reduce<MT, 1, ASYM, TAPS>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n);
-        else narrow_reduce<MT, 2, ASYM, TAPS>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n);
+        if (L.NT == 1) narrow_reduce<MT, 1, ASYM, TAPS, HALF>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n);
+        else narrow_reduce<MT, 2, ASYM, TAPS, HALF>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n);
         lds_barrier();
     }
 
@@ -614,25 +632,25 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
     }
 }
 
-template <int MT, int NB, bool ASYM, bool TAPS>
+template <int MT, int NB, bool ASYM, bool TAPS, bool HALF>
 aq_status launch_fused_t(const FwdArgs& a, size_t lds, hipStream_t st) {
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)k_mlp_fused<MT, NB, ASYM, TAPS>,
+        if (hipFuncSetAttribute((const void*)k_mlp_fused<MT, NB, ASYM, TAPS, HALF>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
             return AQ_EHIP;
         attr_set = true;
     }
-    const int rows = 32 * MT;
+    const int rows = HALF ? 16 : 32 * MT;
     const unsigned grid = (unsigned)((a.c.batch + rows - 1) / rows);
-    hipLaunchKernelGGL((k_mlp_fused<MT, NB, ASYM, TAPS>), dim3(grid), dim3(FT), lds, st, a.d_net, a.c, a.t);
+    hipLaunchKernelGGL((k_mlp_fused<MT, NB, ASYM, TAPS, HALF>), dim3(grid), dim3(FT), lds, st, a.d_net, a.c, a.t);
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
 // one explicit instantiation per translation unit, so the variants compile in parallel
-#define AQ_FUSED_DECL(MT, NB, AS, TP) \
-    extern template aq_status launch_fused_t<MT, NB, AS, TP>(const FwdArgs&, size_t, hipStream_t)
-#define AQ_FUSED_INST(MT, NB, AS, TP) \
-    template aq_status launch_fused_t<MT, NB, AS, TP>(const FwdArgs&, size_t, hipStream_t)
+#define AQ_FUSED_DECL(MT, NB, AS, TP, HF) \
+    extern template aq_status launch_fused_t<MT, NB, AS, TP, HF>(const FwdArgs&, size_t, hipStream_t)
+#define AQ_FUSED_INST(MT, NB, AS, TP, HF) \
+    template aq_status launch_fused_t<MT, NB, AS, TP, HF>(const FwdArgs&, size_t, hipStream_t)
 
 }  // namespace aq

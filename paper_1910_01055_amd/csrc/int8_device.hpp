@@ -307,6 +307,24 @@ __device__ __forceinline__ void epi_hidden_tile(const int N, const LayerTaps& T,
     }
 }
 
+// 16-row workgroups still run 32x32x32 MFMAs (rows 16..31 of the operand are don't-care), then fold
+// the tile: lanes that hold rows 16..31 take over feature quads 2 and 3 of the row 16 below them.
+// Afterwards lane l owns row l & 15, half h = (l >> 4) & 1, and registers 4j+i (j = 0, 1) hold feature
+// 8 (j + 2h) + 4 (l >> 5) + i of the tile: every lane does useful epilogue work on half the registers.
+__device__ __forceinline__ void fold_rows16(v16i& c, int lane) {
+    const int src = (lane ^ 16) << 2;
+    const bool up = (lane & 16) != 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int t = __builtin_amdgcn_ds_bpermute(src, c[r + 8]);
+        c[r] = up ? t : c[r];
+    }
+}
+__device__ __forceinline__ int fold_rows16_scalar(int v, int lane) {
+    const int t = __builtin_amdgcn_ds_bpermute((lane ^ 16) << 2, v);
+    return (lane & 16) ? t : v;
+}
+
 // Hidden-layer epilogue of a wave's whole tile set (NB feature tiles x MT row tiles).  The
 // per-channel constants of a feature quad are loaded once and shared by the MT row tiles, and the
 // next quad's constants are requested before the current quad is processed, so the (global or LDS)
@@ -330,18 +348,21 @@ __device__ __forceinline__ QuadConsts load_quad_consts(const CPtrs& C, int n0) {
     }
     return q;
 }
-template <int MT, int NB, bool ASYM, bool TAPS, bool FAST>
+// HALF: the tiles were folded by fold_rows16 (two quads per tile, `hh` = this lane's half).
+template <int MT, int NB, bool ASYM, bool TAPS, bool FAST, bool HALF = false>
 __device__ __forceinline__ void epi_hidden_wave(const int N, const int NT, const LayerTaps& T, const CPtrs& C,
                                                 v16i (&acc)[NB][MT], v16i (&rs)[MT], int zw_s, int grp, int g,
                                                 int64_t row_first, int64_t rows, bool guard_rows, int z_out, int lo,
-                                                int8_t* out0, int64_t out_mt_stride, bool packed, int n_store) {
-    constexpr int NQ = NB * 4;
-    auto n0_of = [&](int q) { return (grp * NB + (q >> 2)) * 32 + 8 * (q & 3) + 4 * g; };
-    auto valid = [&](int q) { return grp * NB + (q >> 2) < NT; };
+                                                int8_t* out0, int64_t out_mt_stride, bool packed, int n_store,
+                                                int hh = 0) {
+    constexpr int QT = HALF ? 2 : 4;  // quads per tile
+    constexpr int NQ = NB * QT;
+    auto n0_of = [&](int q) { return (grp * NB + q / QT) * 32 + 8 * (q % QT + (HALF ? 2 * hh : 0)) + 4 * g; };
+    auto valid = [&](int q) { return grp * NB + q / QT < NT; };
     QuadConsts cur = load_quad_consts<FAST>(C, valid(0) ? n0_of(0) : 0);
     static_for<0, NQ>([&](auto q_c) __attribute__((always_inline)) {
         constexpr int q = decltype(q_c)::value;
-        constexpr int nb = q >> 2, j = q & 3;
+        constexpr int nb = q / QT, j = q % QT;
         QuadConsts nxt = cur;
         if (q + 1 < NQ) nxt = load_quad_consts<FAST>(C, valid(q + 1) ? n0_of(q + 1) : 0);
         if (valid(q)) {
@@ -388,13 +409,13 @@ __device__ __forceinline__ void epi_hidden_wave(const int N, const int NT, const
 
 // Last layer: y = (float)acc * m[n] for one tile, stored to y_row[n] (n < n_store) when y_row is
 // given; when act_row is given the elementwise head (tanh or identity) is applied and stored too.
-template <bool ASYM, bool TAPS>
+template <bool ASYM, bool TAPS, bool HALF = false>
 __device__ __forceinline__ void epi_last_tile(const int N, const LayerTaps& T, const CPtrs& C, const v16i& c, int rs0,
                                               int zw_s, int nt, int g, int64_t row, bool row_ok, float* y_row,
-                                              int n_store, float* act_row, int head) {
+                                              int n_store, float* act_row, int head, int hh = 0) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int n0 = nt * 32 + 8 * j + 4 * g;
+    for (int j = 0; j < (HALF ? 2 : 4); ++j) {
+        const int n0 = nt * 32 + 8 * (j + (HALF ? 2 * hh : 0)) + 4 * g;
         int val[4];
         quad_acc<ASYM, TAPS>(N, T, C, c, j, n0, rs0, zw_s, row, row_ok, val);
         const float4 mm = *(const float4*)(C.m + n0);
