@@ -82,37 +82,57 @@ __global__ __launch_bounds__(W * 64) void k_layer_int8(const NetDev* __restrict_
         // block copy would run at one memory latency per 16 bytes per thread.
         constexpr int SU = 8;
         if (stage_mode == ST_VEC16) {
-            // every 16-byte piece of a row's K range is contiguous and aligned in the input
+            // Every 16-byte piece of a row's K range is contiguous and aligned in the input.  Four threads
+            // share a row (NT_ = 4 * ROWS for every tile configuration), so the row's position in the
+            // input (a 64-bit division for convolutions) is worked out once per thread, and each piece
+            // costs one small division by the length of a kernel row, done in floating point (exact:
+            // (k + 0.5) / run is never within 0.5 / run of an integer and k stays far below 2^21).
+            static_assert(NT_ == 4 * ROWS, "four staging threads per row");
             const int chunks = (ks1 - ks0) * 2;
-            const int total = ROWS * chunks;
-            for (int base = tid; base < total; base += NT_ * SU) {
+            const int m = tid >> 2, j = tid & 3;
+            const int64_t row = row0 + m;
+            const bool row_ok = row < rows;
+            const bool fc = L.kh == 1 && L.kw == 1 && L.in_h == 1 && L.in_w == 1;
+            int64_t base = 0;     // offset of the row's k = 0
+            int run = L.K;        // contiguous K bytes per kernel row; the next kernel row is row_pitch further
+            int64_t row_pitch = 0;
+            if (row_ok) {
+                if (fc) {
+                    base = row * L.K;
+                } else {
+                    const int per_img = L.oh * L.ow;
+                    const int64_t b = row / per_img;
+                    const int r = (int)(row - b * per_img);
+                    const int oy = r / L.ow, ox = r - oy * L.ow;
+                    base = ((b * L.in_h + (int64_t)oy * L.stride) * L.in_w + (int64_t)ox * L.stride) * L.in_c;
+                    run = L.kw * L.in_c;
+                    row_pitch = (int64_t)L.in_w * L.in_c;
+                }
+            }
+            const float inv_run = 1.0f / (float)run;
+            for (int c0 = j; c0 < chunks; c0 += 4 * SU) {
                 v4i v[SU];
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
-                    const int idx = base + u * NT_;
+                    const int c = c0 + 4 * u;
                     v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0;
-                    if (idx < total) {
-                        const int m = idx / chunks, c = idx - m * chunks;
-                        const int k = ks0 * 32 + c * 16;
-                        const int64_t row = row0 + m;
-                        if (row < rows && k < L.K) v[u] = *(const v4i*)((const int8_t*)io.in + gather_offset(L, row, k));
+                    const int k = ks0 * 32 + c * 16;
+                    if (c < chunks && row_ok && k < L.K) {
+                        const int ky = fc ? 0 : (int)(((float)k + 0.5f) * inv_run);
+                        const int kr = k - ky * run;
+                        v[u] = *(const v4i*)((const int8_t*)io.in + base + ky * row_pitch + kr);
+                        if (first) {  // raw unsigned codes -> signed domain
+                            v[u][0] ^= 0x80808080;
+                            v[u][1] ^= 0x80808080;
+                            v[u][2] ^= 0x80808080;
+                            v[u][3] ^= 0x80808080;
+                        }
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
-                    const int idx = base + u * NT_;
-                    if (idx < total) {
-                        const int m = idx / chunks, c = idx - m * chunks;
-                        const int k = ks0 * 32 + c * 16;
-                        v4i w = v[u];
-                        if (first && row0 + m < rows && k < L.K) {  // raw unsigned codes -> signed domain
-                            w[0] ^= 0x80808080;
-                            w[1] ^= 0x80808080;
-                            w[2] ^= 0x80808080;
-                            w[3] ^= 0x80808080;
-                        }
-                        *(v4i*)(xs + m * LD + c * 16) = w;
-                    }
+                    const int c = c0 + 4 * u;
+                    if (c < chunks) *(v4i*)(xs + m * LD + c * 16) = v[u];
                 }
             }
         } else if (stage_mode == ST_F32X4) {
@@ -330,6 +350,9 @@ LayerPlan plan_layer(const LayerDev& L, int64_t rows, bool asym) {
     // so that every SIMD of the chip gets work.  Everything else: 64-row blocks, 4 waves.
     if (!asym && rows >= 8192 && L.NT >= 16) return {8, 4, 2};  // (the asymmetric row-sum tiles would spill)
     if (rows >= 8192 && L.NT <= 2) return {2, 1, 1};
+    // few rows: the 64-row configuration would leave most CUs without a workgroup; take the smallest tile
+    const int64_t wg_mid = ((rows + 63) / 64) * (((L.NT + 1) / 2 + 3) / 4);
+    if (wg_mid < 128) return {2, 1, 1};
     return {4, 2, 2};
 }
 }  // namespace
