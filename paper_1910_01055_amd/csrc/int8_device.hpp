@@ -168,11 +168,18 @@ __device__ __forceinline__ void mma_run(gv4i_ptr (&wptr)[NB], v4i (&wreg)[PF][NB
         });
     };
     int ks = ks_begin;
-    for (; ks + 2 * PF <= ks_end; ks += PF) group(ks, std::integral_constant<int, 1>{});
-    if (ks + PF <= ks_end) {
-        if (ks + PF < ks_end) group(ks, std::integral_constant<int, 2>{});
-        else group(ks, std::integral_constant<int, 0>{});
-        ks += PF;
+    if (MT * NB <= 4) {
+        for (; ks + 2 * PF <= ks_end; ks += PF) group(ks, std::integral_constant<int, 1>{});
+        if (ks + PF <= ks_end) {
+            if (ks + PF < ks_end) group(ks, std::integral_constant<int, 2>{});
+            else group(ks, std::integral_constant<int, 0>{});
+            ks += PF;
+        }
+    } else {
+        // eight accumulator tiles per wave: a second copy of the group body makes the register
+        // allocator spill accumulators between the copies, so every whole group takes the clamped
+        // form (the tiles re-read at the end of K hit in the vector L1)
+        for (; ks + PF <= ks_end; ks += PF) group(ks, std::integral_constant<int, 2>{});
     }
     // the remaining k-steps (fewer than PF), one conditional block each
     if (ks < ks_end) {

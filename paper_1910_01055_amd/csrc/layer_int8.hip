@@ -28,7 +28,11 @@ constexpr int ST_BYTES = 0;   // generic byte gather (any shape; quantizes fp32 
 constexpr int ST_VEC16 = 1;   // 16-byte gathers of 8-bit codes
 constexpr int ST_F32X4 = 2;   // first FC layer on fp32 observations, K a multiple of 4: float4 -> 4 codes
 
-template <int W, int MT, int NB, bool ASYM, bool TAPS>
+// DEEP (single-tile waves only): 16 weight k-steps in flight per wave, requested before the
+// activations are staged - for a long K at few rows, where few workgroups each walk a long weight
+// stream and its latency, not bandwidth, sets the pace.  It costs registers, hence occupancy, so
+// layers with many workgroups keep the shallow pipeline.
+template <int W, int MT, int NB, bool ASYM, bool TAPS, bool DEEP>
 __global__ __launch_bounds__(W * 64) void k_layer_int8(const NetDev* __restrict__ netp, const TapArgs t, const int l,
                                                       const LayerIO io, const int64_t rows, const int stage_mode,
                                                       const int kc, const void* __restrict__ actions) {
@@ -75,9 +79,13 @@ __global__ __launch_bounds__(W * 64) void k_layer_int8(const NetDev* __restrict_
         wptr[nb] = (gv4i_ptr)L.wp + (int64_t)nt * L.KS * 64 + lane;
     }
 
+    static_assert(!DEEP || (NB == 1 && MT == 1), "deep weight pipeline: single-tile waves only");
+    constexpr int PF = DEEP ? 16 : 4;
+    v4i wreg[PF][NB];
     for (int ks0 = 0; ks0 < L.KS; ks0 += kc) {
         const int ks1 = ks0 + kc < L.KS ? ks0 + kc : L.KS;
         if (ks0) __syncthreads();
+        if (DEEP && active) mma_prefetch<NB, PF>(wptr, ks0, ks1, wreg);
         // Staging loops keep SU independent loads in flight per thread: with one load per iteration the
         // block copy would run at one memory latency per 16 bytes per thread.
         constexpr int SU = 8;
@@ -194,7 +202,10 @@ __global__ __launch_bounds__(W * 64) void k_layer_int8(const NetDev* __restrict_
             }
         }
         __syncthreads();
-        if (active) mma_block<MT, NB, ASYM, 4>(wptr, xs, LD, ks0, ks1, ks0, acc, rs, lane);
+        if (active) {
+            if (!DEEP) mma_prefetch<NB, PF>(wptr, ks0, ks1, wreg);
+            mma_run<MT, NB, ASYM, PF>(wptr, wreg, xs, LD, ks0, ks1, ks0, acc, rs, lane);
+        }
     }
 
     const CPtrs C = global_consts(L);
@@ -342,22 +353,24 @@ namespace {
 // Tile configuration of one layer launch.
 struct LayerPlan {
     int w, mt, nb;
+    bool deep;
 };
 
 LayerPlan plan_layer(const LayerDev& L, int64_t rows, bool asym) {
     // Wide layers with many rows: 128-row blocks, 64 features per wave, 8 waves (512 features per
     // workgroup pass).  Narrow layers: 32-row blocks and as many waves as there are feature tiles,
     // so that every SIMD of the chip gets work.  Everything else: 64-row blocks, 4 waves.
-    if (!asym && rows >= 8192 && L.NT >= 16) return {8, 4, 2};  // (the asymmetric row-sum tiles would spill)
-    if (rows >= 8192 && L.NT <= 2) return {2, 1, 1};
-    // few rows: the 64-row configuration would leave most CUs without a workgroup; take the smallest tile
+    if (!asym && rows >= 8192 && L.NT >= 16) return {8, 4, 2, false};  // (the asymmetric row-sum tiles would spill)
+    if (rows >= 8192 && L.NT <= 2) return {2, 1, 1, false};
+    // few rows: the 64-row configuration would leave most CUs without a workgroup; take the smallest
+    // tile, and with a long K the deep weight pipeline
     const int64_t wg_mid = ((rows + 63) / 64) * (((L.NT + 1) / 2 + 3) / 4);
-    if (wg_mid < 128) return {2, 1, 1};
-    return {4, 2, 2};
+    if (wg_mid < 128) return {2, 1, 1, L.KS >= 32};
+    return {4, 2, 2, false};
 }
 }  // namespace
 
-template <int W, int MT, int NB>
+template <int W, int MT, int NB, bool DEEP = false>
 static aq_status launch_layer_t(const FwdArgs& a, int l, const LayerIO& io, int64_t rows, int stage_mode,
                                 const void* actions, hipStream_t st) {
     const LayerDev& L = a.net.L[l];
@@ -378,12 +391,12 @@ static aq_status launch_layer_t(const FwdArgs& a, int l, const LayerIO& io, int6
     do {                                                                                                            \
         static bool attr_set = false;                                                                               \
         if (!attr_set) {                                                                                            \
-            if (hipFuncSetAttribute((const void*)k_layer_int8<W, MT, NB, AS, TP>,                                   \
+            if (hipFuncSetAttribute((const void*)k_layer_int8<W, MT, NB, AS, TP, DEEP>,                                   \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)          \
                 return AQ_EHIP;                                                                                     \
             attr_set = true;                                                                                        \
         }                                                                                                           \
-        hipLaunchKernelGGL((k_layer_int8<W, MT, NB, AS, TP>), grid, dim3(W * 64), lds, st, a.d_net, a.t, l, io, rows, \
+        hipLaunchKernelGGL((k_layer_int8<W, MT, NB, AS, TP, DEEP>), grid, dim3(W * 64), lds, st, a.d_net, a.t, l, io, rows, \
                            stage_mode, kc, actions);                                                                \
     } while (0)
     if (asym) {
@@ -414,6 +427,7 @@ aq_status launch_layer_int8(const FwdArgs& a, int l, const LayerIO& io, hipStrea
     const void* actions = (last && a.net.head != AQ_HEAD_ARGMAX) ? a.c.actions : nullptr;
     const LayerPlan p = plan_layer(L, rows, a.net.asym != 0);
     if (p.w == 8) return launch_layer_t<8, 4, 2>(a, l, io, rows, stage_mode, actions, st);
+    if (p.w == 2 && p.deep) return launch_layer_t<2, 1, 1, true>(a, l, io, rows, stage_mode, actions, st);
     if (p.w == 2) return launch_layer_t<2, 1, 1>(a, l, io, rows, stage_mode, actions, st);
     return launch_layer_t<4, 2, 2>(a, l, io, rows, stage_mode, actions, st);
 }
