@@ -19,6 +19,10 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PULL_EVERY = 100           # actor steps between model pulls (the paper's smaller pull frequency)
 INT8_PEAK_TOPS = 5000.0    # MI355X dense int8 MFMA, TOP/s
+# HBM bytes per launch of the fused kernel on the headline workload, from the FETCH_SIZE and WRITE_SIZE
+# hardware counters scaled by what they read on a plain 64 MiB copy (profiles/k_mlp_fused_cfg2_b4096.md).
+# Set to None whenever that kernel changes, until the counters have been taken again.
+FUSED_HBM_BYTES_PER_LAUNCH = 3201016
 HBM_PEAK_GBS = 8000.0
 
 
@@ -249,7 +253,8 @@ def main():
                    "device_ms_per_step": e0.elapsed_time(e1) / args.steps},
         "pct_int8_mfma_peak": 100.0 * achieved / INT8_PEAK_TOPS,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": achieved / INT8_PEAK_TOPS, "traffic": None,
+                     "frac": achieved / INT8_PEAK_TOPS, "traffic": FUSED_HBM_BYTES_PER_LAUNCH,
+                     "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE counters, copy-calibrated)",
                      "kernel": "k_mlp_fused (whole-network int8 MLP)", "us_per_launch": head["us_per_launch"]},
         "fp32_actor_us_per_launch": head["fp32_actor_us_per_launch"],
     }
