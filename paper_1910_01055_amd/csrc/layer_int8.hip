@@ -418,10 +418,12 @@ aq_status launch_layer_int8(const FwdArgs& a, int l, const LayerIO& io, hipStrea
     // 16-byte gathers need contiguous, aligned 16-byte pieces of K in an 8-bit input
     const int run = fc ? L.K : L.kw * L.in_c;
     int stage_mode = ST_BYTES;
-    if (run % 16 == 0 && !(first && !a.net.in_u8) && !(first && a.t.a0) &&
+    // (a caller's observation buffer may sit at any address; the library's own buffers are aligned)
+    const bool aligned = ((uintptr_t)io.in & 15) == 0;
+    if (aligned && run % 16 == 0 && !(first && !a.net.in_u8) && !(first && a.t.a0) &&
         (fc || ((L.stride * L.in_c) % 16 == 0 && (L.in_w * L.in_c) % 16 == 0)))
         stage_mode = ST_VEC16;
-    else if (first && !a.net.in_u8 && fc && (L.K & 3) == 0)
+    else if (aligned && first && !a.net.in_u8 && fc && (L.K & 3) == 0)
         stage_mode = ST_F32X4;
     // elementwise heads are applied in the last layer's epilogue; argmax needs the whole row
     const void* actions = (last && a.net.head != AQ_HEAD_ARGMAX) ? a.c.actions : nullptr;

@@ -85,9 +85,16 @@ def check_quantized_params(aq, P, pol, net):
         assert np.array_equal(fm.cpu().numpy().view(np.uint32), q["m"].view(np.uint32)), f"layer {l} m"
 
 
-def gpu_forward(P, net, obs, taps=True):
+def gpu_forward(P, net, obs, taps=True, misalign=0):
+    """misalign: place the observations this many elements past a fresh allocation's start, so that
+    their address is not 16-byte aligned (the kernels' vector loads must then not be used)."""
     batch = obs.shape[0]
     d_obs = to_dev(obs)
+    if misalign:
+        flat = torch.empty(d_obs.numel() + misalign, dtype=d_obs.dtype, device=DEV)
+        flat[misalign:].copy_(d_obs.reshape(-1))
+        d_obs = flat[misalign:].reshape(d_obs.shape)
+        assert d_obs.data_ptr() % 16 != 0 and d_obs.is_contiguous()
     nl = len(net["layers"])
     A = synth.action_dim(net)
     if net["head"] == "argmax":

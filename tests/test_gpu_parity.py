@@ -113,6 +113,32 @@ def test_forward_every_stage(aq, name, path, batch):
     P.close()
 
 
+@pytest.mark.parametrize("name", ["cfg2", "odd_asym", "u8_mlp", "single_narrow"])
+@pytest.mark.parametrize("path", [0, 2])
+@pytest.mark.parametrize("batch", [15, 16, 17, 33, 4096, 4097])
+def test_forward_unaligned_observations_and_tile_edges(aq, name, path, batch):
+    """Observation buffers that are not 16-byte aligned (fp32: 4 bytes off, uint8: 1 byte off) take the
+    element-wise staging path; batch sizes sit on both sides of the 16- and 32-row workgroup sizes and
+    of the switch between them."""
+    _say(f"forward_unaligned {name} path={path} batch={batch}")
+    net = _nets()[name]
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs[:256])
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    P.policy_set_path(path)
+    rows = None if batch <= 64 else np.unique(np.concatenate([[0, 15, 16, 31, 32, batch - 2, batch - 1],
+                                                               np.random.default_rng(8).integers(0, batch, 200)]))
+    a_ref, t = U.gpu_forward(P, net, obs)
+    U.compare_forward(net, pol, obs, a_ref, t, rows)
+    a_mis, t = U.gpu_forward(P, net, obs, misalign=1)
+    U.compare_forward(net, pol, obs, a_mis, t, rows)
+    assert np.array_equal(a_mis, a_ref, equal_nan=True)
+    a_mis2, _ = U.gpu_forward(P, net, obs, taps=False, misalign=3)
+    assert np.array_equal(a_mis2, a_ref, equal_nan=True)
+    P.close()
+
+
 @pytest.mark.parametrize("path", [0, 2])
 @pytest.mark.parametrize("hi1,hi2", [(0.02, 3.0), (3.0, 3e5), (1e-3, 1e-3), (40.0, 0.5)])
 def test_requant_forms(aq, path, hi1, hi2):
