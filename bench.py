@@ -114,19 +114,26 @@ def forward_workload(torch, aq, synth, U, name, batch, iters, warm=20):
     torch.cuda.synchronize()
     ms32 = _events_ms(torch, f32, max(2, iters // 20))
     ops = 2.0 * synth.macs_per_sample(net) * batch
+    # algorithmic HBM bytes: observations in, actions out, 8-bit weights once
+    n_w = sum(int(p["w"].size) for p in params)
+    hbm = float(obs.nbytes + act.numel() * act.element_size() + n_w)
     out = {"workload": f"{name} batch {batch}", "us_per_launch": ms * 1e3, "inferences_per_s": batch / (ms * 1e-3),
            "tops": ops / (ms * 1e-3) / 1e12, "frac_int8_mfma_peak": ops / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+           "GBps_algorithmic": hbm / (ms * 1e-3) / 1e9, "frac_hbm_peak": hbm / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
            "us_per_launch_eager": ms_eager * 1e3, "fp32_actor_us_per_launch": ms32 * 1e3}
     return out, (P, w, b, g, be, ranges, d_obs, act, net, params, obs)
 
 
-def quantize_workload(torch, aq, synth, U, scheme, iters=30, n_buf=40):
-    """Learner->actor weight quantize pass over 4M fp32 params, rotating over distinct buffers so
-    that the source comes from HBM, not from the 256 MB last-level cache."""
-    n = synth.QUANT_TENSOR_ELEMS
+def quantize_workload(torch, aq, synth, U, scheme, iters=30, n_buf=40, repeat=1):
+    """Learner->actor weight quantize pass over 4M fp32 params (times `repeat`: the same values tiled
+    into a larger tensor, for the asymptotic rate), rotating over distinct buffers so that the
+    source comes from HBM, not from the 256 MB last-level cache."""
+    n = synth.QUANT_TENSOR_ELEMS * repeat
     src = U.to_dev(synth.quant_tensor())
+    if repeat > 1:
+        src = src.reshape(-1).repeat(repeat)
     srcs = [src.clone() for _ in range(n_buf)]
-    rows, cols = (1, n) if scheme == "tensor_asym_u8" else (2048, 2048)
+    rows, cols = (1, n) if scheme == "tensor_asym_u8" else (2048 * repeat, 2048)
     dsts = [torch.empty(n, dtype=torch.uint8, device=U.DEV) for _ in range(n_buf)]
     scale = torch.empty(rows, dtype=torch.float32, device=U.DEV)
     zp = torch.empty(rows, dtype=torch.int32, device=U.DEV)
@@ -144,7 +151,7 @@ def quantize_workload(torch, aq, synth, U, scheme, iters=30, n_buf=40):
     i[0] = 0
     ms = _graph_ms(torch, one, n_buf)   # one pass over all the distinct buffers per replay
     gbs = 5.0 * n / (ms * 1e-3) / 1e9
-    return {"workload": f"quantize 4M fp32 params, {scheme}, {n_buf} rotating buffers (HBM-resident source)",
+    return {"workload": f"quantize {4 * repeat}M fp32 params, {scheme}, {n_buf} rotating buffers (HBM-resident source)",
             "us_per_call": ms * 1e3, "us_per_call_eager": ms_eager * 1e3, "GBps_algorithmic": gbs,
             "frac_hbm_peak": gbs / HBM_PEAK_GBS}
 
@@ -177,6 +184,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--eager", action="store_true", help="launch from the host instead of replaying HIP graphs "
                     "(for profiler runs)")
+    ap.add_argument("--only", metavar="CFG:BATCH", help="time one secondary forward workload only, e.g. cfg5:16384 "
+                    "(for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain 64 MiB device-to-device copies (reference for scaling HBM byte counters)")
     args = ap.parse_args()
@@ -201,6 +210,13 @@ def main():
     aq.load()
     global _USE_GRAPHS
     _USE_GRAPHS = not args.eager
+
+    if args.only:
+        name, bsz = args.only.split(":")
+        o, c = forward_workload(torch, aq, synth, U, name, int(bsz), 100)
+        c[0].close()
+        print(json.dumps(o))
+        return
 
     batch = 4096
     head, ctx = forward_workload(torch, aq, synth, U, "cfg2", batch, iters=500)
@@ -268,6 +284,8 @@ def main():
             extra.append(o)
         for scheme in ("channel_sym_s8", "tensor_asym_u8"):
             extra.append(quantize_workload(torch, aq, synth, U, scheme))
+        # informational: a 64 M-parameter tensor (256 MB in, 64 MB out per call) shows the asymptotic rate
+        extra.append(quantize_workload(torch, aq, synth, U, "channel_sym_s8", iters=6, n_buf=4, repeat=16))
         result["other_workloads"] = extra
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(synth, U, net, params, obs, ranges)
