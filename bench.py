@@ -156,6 +156,37 @@ def quantize_workload(torch, aq, synth, U, scheme, iters=30, n_buf=40, repeat=1)
             "frac_hbm_peak": gbs / HBM_PEAK_GBS}
 
 
+def blob_workload(torch, aq, synth, U, name):
+    """Learner -> actor hand-off of a quantized policy as one packed blob: export from one handle, import
+    into another (device to device, no repacking), next to the cost of quantizing the fp32 parameters."""
+    net = synth.net_config(name)
+    params = synth.make_params(net)
+    obs = synth.make_obs(net, 512)
+    P, Q = aq.Policy(net), aq.Policy(net)
+    w, b, g, be = U.upload_params(params)
+    A = synth.action_dim(net)
+    act = torch.zeros((512,) if net["head"] == "argmax" else (512, A),
+                      dtype=torch.int32 if net["head"] == "argmax" else torch.float32, device=U.DEV)
+    nl = len(net["layers"])
+    r = torch.zeros(2 * nl, dtype=torch.float32, device=U.DEV)
+    P.policy_forward_fp32(w, b, g, be, U.to_dev(obs), act, r)
+    ranges = r.cpu().numpy().reshape(nl, 2).tolist()
+    P.quantize_params(w, b, g, be, ranges)
+    assert P.policy_status() == aq.OK
+    n = P.policy_blob_size()
+    blob = torch.empty(n, dtype=torch.uint8, device=U.DEV)
+    P.policy_export_blob(blob)
+    Q.policy_import_blob(blob)
+    assert Q.policy_status() == aq.OK
+    ms_q = _graph_ms(torch, lambda: P.quantize_params(w, b, g, be, ranges), 20)
+    ms_e = _graph_ms(torch, lambda: P.policy_export_blob(blob), 50)
+    ms_i = _graph_ms(torch, lambda: Q.policy_import_blob(blob), 50)
+    P.close()
+    Q.close()
+    return {"workload": f"{name} policy blob hand-off", "blob_bytes": n, "us_export": ms_e * 1e3, "us_import": ms_i * 1e3,
+            "us_quantize_params": ms_q * 1e3, "GBps_import": 2.0 * n / (ms_i * 1e-3) / 1e9}
+
+
 def cpu_baseline(synth, U, net, params, obs, ranges, budget_s=12.0):
     """The CPU oracle, as it stands, on batches of the same workload for about budget_s seconds."""
     from oracle import policy as O
@@ -286,6 +317,8 @@ def main():
             extra.append(quantize_workload(torch, aq, synth, U, scheme))
         # informational: a 64 M-parameter tensor (256 MB in, 64 MB out per call) shows the asymptotic rate
         extra.append(quantize_workload(torch, aq, synth, U, "channel_sym_s8", iters=6, n_buf=4, repeat=16))
+        for name in ("cfg2", "cfg5"):
+            extra.append(blob_workload(torch, aq, synth, U, name))
         result["other_workloads"] = extra
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(synth, U, net, params, obs, ranges)

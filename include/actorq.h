@@ -121,8 +121,28 @@ aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch);
 aq_status aq_policy_set_path(aq_policy* p, int32_t path);
 
 /* Synchronizes `stream` and returns the sticky device-side error of the last
- * aq_quantize_params (AQ_OK, AQ_ENONFINITE or AQ_ERANGE). */
+ * aq_quantize_params or aq_policy_import_blob (AQ_OK, AQ_ENONFINITE, AQ_ERANGE, or AQ_EINVAL for a
+ * blob whose header does not match). */
 aq_status aq_policy_status(aq_policy* p, void* stream);
+
+/* The quantized policy as one contiguous blob, for the learner-to-actor broadcast of Sec. 3.1 (the
+ * step whose cost Sec. 5.3 breaks out; the paper notes that loading the quantized parameters into the
+ * actor's model re-packs the weights).  The blob holds the 8-bit weights already in the forward
+ * kernels' operand order, every per-channel constant and the activation quantization parameters,
+ * behind a 64-byte header (magic, format version, a hash of the network description, payload size):
+ * importing it is two device-to-device copies and no arithmetic.  A blob is valid only for a handle
+ * created from the same aq_net on the same library version.
+ *   aq_policy_blob_size: *bytes = size of the blob for this handle's network (no GPU work).
+ *   aq_policy_export_blob: writes the blob to d_blob (caller-owned device memory, 16-byte aligned,
+ *     at least `bytes` long; AQ_EINVAL if shorter than the blob, AQ_ENOTQUANT before any
+ *     aq_quantize_params / import).  Enqueues on `stream`.
+ *   aq_policy_import_blob: installs a blob (same size rules).  Enqueues on `stream`; a header that does
+ *     not match this handle's network sets a device-side flag that aq_policy_status() reports as
+ *     AQ_EINVAL (the payload is then unspecified, as after non-finite weights).  The handle counts as
+ *     quantized afterwards. */
+aq_status aq_policy_blob_size(const aq_policy* p, uint64_t* bytes);
+aq_status aq_policy_export_blob(const aq_policy* p, void* d_blob, uint64_t bytes, void* stream);
+aq_status aq_policy_import_blob(aq_policy* p, const void* d_blob, uint64_t bytes, void* stream);
 
 /* Sec. 3.2 applied to one tensor, for the learner-to-actor broadcast: quantizes fp32
  * d_w[rows][cols] to 8-bit codes in canonical row-major order.

@@ -22,7 +22,8 @@ INTYPE = {"f32": 0, "u8": 1}
 
 EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_policy_set_path", "aq_policy_status",
            "aq_quantize_tensor", "aq_quantize_params", "aq_policy_export_layer", "aq_policy_export_act_qparams",
-           "aq_policy_forward_int8", "aq_policy_forward_fp32", "aq_status_string"]
+           "aq_policy_forward_int8", "aq_policy_forward_fp32", "aq_status_string",
+           "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob"]
 
 
 class AqLayer(C.Structure):
@@ -78,6 +79,9 @@ def load():
     lib.aq_policy_export_act_qparams.argtypes = [vp, vp, vp, vp]
     lib.aq_policy_forward_int8.argtypes = [vp, vp, i64, vp, C.POINTER(AqTaps), vp]
     lib.aq_policy_forward_fp32.argtypes = [vp, pp, pp, pp, pp, vp, i64, vp, vp, vp]
+    lib.aq_policy_blob_size.argtypes = [vp, C.POINTER(C.c_uint64)]
+    lib.aq_policy_export_blob.argtypes = [vp, vp, C.c_uint64, vp]
+    lib.aq_policy_import_blob.argtypes = [vp, vp, C.c_uint64, vp]
     for name in EXPORTS:
         if name != "aq_status_string":
             getattr(lib, name).restype = C.c_int
@@ -153,6 +157,20 @@ class Policy:
 
     def policy_status(self):
         return load().aq_policy_status(self._h, _stream())
+
+    def policy_blob_size(self):
+        n = C.c_uint64(0)
+        _check(load().aq_policy_blob_size(self._h, C.byref(n)), "aq_policy_blob_size")
+        return int(n.value)
+
+    def policy_export_blob(self, blob):
+        """blob: a uint8 device tensor of at least policy_blob_size() bytes."""
+        _check(load().aq_policy_export_blob(self._h, _ptr(blob), blob.numel() * blob.element_size(), _stream()),
+               "aq_policy_export_blob")
+
+    def policy_import_blob(self, blob):
+        _check(load().aq_policy_import_blob(self._h, _ptr(blob), blob.numel() * blob.element_size(), _stream()),
+               "aq_policy_import_blob")
 
     def quantize_params(self, w, b, gamma, beta, ranges):
         """w, b, gamma, beta: per-layer lists of device tensors (entries or lists may be None);

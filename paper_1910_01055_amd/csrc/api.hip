@@ -46,6 +46,8 @@ struct aq_policy {
     NetDev h_net{};            // host copy of the device-resident network description
     NetDev* d_net = nullptr;
     bool quantized = false;
+    size_t layer_bytes = 0;    // the slab's leading part: every layer's packed weights and constants
+    uint64_t net_hash = 0;     // of the network description (blob header)
     int path = 0;  // 0 auto, 1 fused only, 2 one launch per layer
     // activation scratch of the per-layer path and of the fp32 actor (grown on demand)
     int64_t cap_i8 = 0, cap_f32 = 0;
@@ -178,6 +180,7 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         offs.push_back(take((size_t)b.N_pad * 4 * 4));  // the epilogue constant pack, see LayerBuf
         p->L.push_back(b);
     }
+    p->layer_bytes = bytes;
     size_t off_status = take(256);
     size_t off_mm = take(256);
     size_t off_keys = take(sizeof(uint32_t) * 2 * (AQ_MAX_LAYERS + 1));
@@ -225,6 +228,26 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     p->h_net.in_u8 = net->in_type == AQ_IN_U8;
     p->h_net.asym = net->wscheme == AQ_W_TENSOR_ASYM_U8;
     p->h_net.ln_eps = net->ln_eps;
+    {   // FNV-1a over everything that fixes the blob's layout and meaning
+        uint64_t h = 1469598103934665603ull;
+        auto mix = [&](int64_t v) {
+            for (int i = 0; i < 8; ++i) {
+                h ^= (uint64_t)(v >> (8 * i)) & 0xffu;
+                h *= 1099511628211ull;
+            }
+        };
+        mix(net->n_layers);
+        mix(net->head);
+        mix(net->wscheme);
+        mix(net->in_type);
+        mix(net->qdenom);
+        for (const auto& b : p->L) {
+            mix(b.d.kind); mix(b.d.in_h); mix(b.d.in_w); mix(b.d.in_c); mix(b.d.out_c);
+            mix(b.d.kh); mix(b.d.kw); mix(b.d.stride); mix(b.d.act);
+        }
+        mix((int64_t)p->layer_bytes);
+        p->net_hash = h;
+    }
     if (hipMemcpy(p->d_net, &p->h_net, sizeof(NetDev), hipMemcpyHostToDevice) != hipSuccess) {
         (void)hipFree(p->slab);
         delete p;
@@ -296,6 +319,66 @@ extern "C" aq_status aq_policy_status(aq_policy* p, void* stream) {
     AQ_HIP_CHECK(hipMemcpy(&h, p->status, sizeof(int), hipMemcpyDeviceToHost));
     if (h & kStatNonFinite) return AQ_ENONFINITE;
     if (h & kStatRange) return AQ_ERANGE;
+    if (h & kStatBlob) return AQ_EINVAL;
+    return AQ_OK;
+}
+
+// ---- policy blob: [64-byte header][128-byte tail: activation (scale, zero-point) pairs and
+// short-form flags][the slab's layer part]
+namespace {
+constexpr size_t kBlobHeader = 64, kBlobTail = 128;
+constexpr uint32_t kBlobMagic = 0x42515141u;  // "AQQB"
+constexpr uint32_t kBlobVersion = 1;
+static_assert(sizeof(ActQ) * (AQ_MAX_LAYERS + 1) + sizeof(int) * AQ_MAX_LAYERS <= kBlobTail, "tail fits");
+static_assert(offsetof(NetDev, fast) == offsetof(NetDev, actq) + sizeof(ActQ) * (AQ_MAX_LAYERS + 1),
+              "scales, zero-points and flags are contiguous");
+void blob_words(const aq_policy* p, uint32_t (&w)[6]) {
+    const uint64_t payload = kBlobTail + p->layer_bytes;
+    w[0] = kBlobMagic;
+    w[1] = kBlobVersion;
+    w[2] = (uint32_t)p->net_hash;
+    w[3] = (uint32_t)(p->net_hash >> 32);
+    w[4] = (uint32_t)payload;
+    w[5] = (uint32_t)(payload >> 32);
+}
+constexpr size_t kTailBytes = sizeof(ActQ) * (AQ_MAX_LAYERS + 1) + sizeof(int) * AQ_MAX_LAYERS;
+}  // namespace
+
+extern "C" aq_status aq_policy_blob_size(const aq_policy* p, uint64_t* bytes) {
+    if (!p || !bytes) return AQ_EINVAL;
+    *bytes = kBlobHeader + kBlobTail + p->layer_bytes;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_export_blob(const aq_policy* p, void* d_blob, uint64_t bytes, void* stream) {
+    if (!p || !d_blob || ((uintptr_t)d_blob & 15)) return AQ_EINVAL;
+    if (bytes < kBlobHeader + kBlobTail + p->layer_bytes) return AQ_EINVAL;
+    if (!p->quantized) return AQ_ENOTQUANT;
+    hipStream_t st = as_stream(stream);
+    uint32_t w[6];
+    blob_words(p, w);
+    char* dst = (char*)d_blob;
+    aq_status s = launch_blob_header_write((uint32_t*)dst, w, st);
+    if (s != AQ_OK) return s;
+    AQ_HIP_CHECK(hipMemcpyAsync(dst + kBlobHeader, p->d_net->actq, kTailBytes, hipMemcpyDeviceToDevice, st));
+    AQ_HIP_CHECK(hipMemcpyAsync(dst + kBlobHeader + kBlobTail, p->slab, p->layer_bytes, hipMemcpyDeviceToDevice, st));
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_import_blob(aq_policy* p, const void* d_blob, uint64_t bytes, void* stream) {
+    if (!p || !d_blob || ((uintptr_t)d_blob & 15)) return AQ_EINVAL;
+    if (bytes < kBlobHeader + kBlobTail + p->layer_bytes) return AQ_EINVAL;
+    hipStream_t st = as_stream(stream);
+    uint32_t w[6];
+    blob_words(p, w);
+    const char* src = (const char*)d_blob;
+    aq_status s = launch_fill_u32((uint32_t*)p->status, 1, 0u, st);
+    if (s != AQ_OK) return s;
+    s = launch_blob_header_check((const uint32_t*)src, w, p->status, st);
+    if (s != AQ_OK) return s;
+    AQ_HIP_CHECK(hipMemcpyAsync(p->d_net->actq, src + kBlobHeader, kTailBytes, hipMemcpyDeviceToDevice, st));
+    AQ_HIP_CHECK(hipMemcpyAsync(p->slab, src + kBlobHeader + kBlobTail, p->layer_bytes, hipMemcpyDeviceToDevice, st));
+    p->quantized = true;
     return AQ_OK;
 }
 

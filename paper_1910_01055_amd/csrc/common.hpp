@@ -157,6 +157,7 @@ __device__ __forceinline__ int wave_or_i32(int v) {
 // Device status bits kept in the handle (sticky until the next aq_quantize_params).
 constexpr int kStatNonFinite = 1;
 constexpr int kStatRange = 2;
+constexpr int kStatBlob = 4;  // an imported blob's header did not match the handle
 
 // Per-layer descriptor handed to the forward kernels by value.
 struct LayerDev {

@@ -17,6 +17,10 @@ aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym
                               int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int32_t* pack1,
                               int32_t* rz, int32_t* sh, int* fast, int* status, hipStream_t st);
 
+// ---- policy blob (quantize.hip): header words [0..15] = magic, version, hash lo/hi, payload bytes lo/hi, 0...
+aq_status launch_blob_header_write(uint32_t* d_hdr, const uint32_t* h_words, hipStream_t st);
+aq_status launch_blob_header_check(const uint32_t* d_hdr, const uint32_t* h_words, int* status, hipStream_t st);
+
 // ---- 8-bit forward (forward_int8.hip)
 struct FwdArgs {
     NetDev net;           // host copy, for planning

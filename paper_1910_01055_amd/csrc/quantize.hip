@@ -439,8 +439,39 @@ __global__ void k_layer_consts(const ActQ* __restrict__ actq, int layer, int req
 }
 
 // ---------------------------------------------------------------------------------------------
+// policy blob header: six words written / compared by one small launch (the expected words travel
+// as kernel arguments, so neither call needs a host round trip)
+// ---------------------------------------------------------------------------------------------
+struct BlobWords {
+    uint32_t w[6];
+};
+__global__ void k_blob_header_write(uint32_t* __restrict__ hdr, const BlobWords b) {
+    // the 16 header words, and zeros over the 32 words behind them (the tail's padding; its
+    // contents are copied in afterwards)
+    const int i = threadIdx.x;
+    if (i < 48) hdr[i] = i < 6 ? b.w[i] : 0u;
+}
+__global__ void k_blob_header_check(const uint32_t* __restrict__ hdr, const BlobWords b, int* __restrict__ status) {
+    const int i = threadIdx.x;
+    if (i < 6 && hdr[i] != b.w[i]) atomicOr(status, kStatBlob);
+}
+
+// ---------------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------------
+aq_status launch_blob_header_write(uint32_t* d_hdr, const uint32_t* h_words, hipStream_t st) {
+    BlobWords b;
+    for (int i = 0; i < 6; ++i) b.w[i] = h_words[i];
+    hipLaunchKernelGGL(k_blob_header_write, dim3(1), dim3(64), 0, st, d_hdr, b);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+aq_status launch_blob_header_check(const uint32_t* d_hdr, const uint32_t* h_words, int* status, hipStream_t st) {
+    BlobWords b;
+    for (int i = 0; i < 6; ++i) b.w[i] = h_words[i];
+    hipLaunchKernelGGL(k_blob_header_check, dim3(1), dim3(64), 0, st, d_hdr, b, status);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
 static int grid_for(int64_t work_items, int per_block, int cap) {
     int64_t g = (work_items + per_block - 1) / per_block;
     if (g < 1) g = 1;

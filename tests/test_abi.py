@@ -42,6 +42,9 @@ def test_status_strings_and_argument_errors_without_gpu():
     assert lib.aq_policy_create(None, None) == b.EINVAL
     assert lib.aq_policy_destroy(None) == b.EINVAL
     assert lib.aq_quantize_tensor(None, 1, 4, 0, 255, None, None, None, None, None) == b.EINVAL
+    assert lib.aq_policy_blob_size(None, None) == b.EINVAL
+    assert lib.aq_policy_export_blob(None, None, 0, None) == b.EINVAL
+    assert lib.aq_policy_import_blob(None, None, 0, None) == b.EINVAL
 
 
 def test_synth_configs_match_the_stated_workloads():

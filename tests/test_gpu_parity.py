@@ -263,6 +263,56 @@ def test_forward_fp32(aq, name, batch):
     P.close()
 
 
+# ------------------------------------------------------------------ policy blob (learner -> actor hand-off)
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "odd_sym_ln", "conv_small", "two_tile_last_asym"])
+def test_policy_blob_round_trip(aq, name):
+    """A policy exported as one blob and imported into a fresh handle of the same network computes what
+    the oracle computes, bit for bit, and exposes the oracle's codes and constants; a blob from another
+    network is refused through the status flag; size errors are refused at once."""
+    _say(f"policy_blob_round_trip {name}")
+    net = _nets()[name]
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, 70)
+    pol, ranges = U.make_oracle(net, params, obs)
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    nbytes = P.policy_blob_size()
+    assert nbytes > 192
+    blob = torch.full((nbytes,), 0xAB, dtype=torch.uint8, device=U.DEV)
+    Q = aq.Policy(net)
+    with pytest.raises(aq.AqError) as e:
+        Q.policy_export_blob(blob)
+    assert e.value.status == aq.ENOTQUANT
+    with pytest.raises(aq.AqError) as e:
+        P.policy_export_blob(blob[:nbytes - 16])
+    assert e.value.status == aq.EINVAL
+    P.policy_export_blob(blob)
+    torch.cuda.synchronize()
+    with pytest.raises(aq.AqError) as e:
+        Q.policy_import_blob(blob[:nbytes - 16])
+    assert e.value.status == aq.EINVAL
+    Q.policy_import_blob(blob)
+    assert Q.policy_status() == aq.OK
+    P.close()  # the imported copy owns everything it needs
+    blob2 = torch.zeros_like(blob)
+    Q.policy_export_blob(blob2)
+    torch.cuda.synchronize()
+    assert torch.equal(blob, blob2)
+    U.check_quantized_params(aq, Q, pol, net)
+    for path in (0, 2):
+        Q.policy_set_path(path)
+        actions, t = U.gpu_forward(Q, net, obs)
+        U.compare_forward(net, pol, obs, actions, t)
+    # a blob of a different network: flagged, not installed silently
+    other = synth.small_net([synth.fc(12, 40, "relu"), synth.fc(40, 3, "none")], head="tanh")
+    R = aq.Policy(other)
+    big = torch.zeros(max(nbytes, R.policy_blob_size()), dtype=torch.uint8, device=U.DEV)
+    big[:nbytes] = blob
+    R.policy_import_blob(big)
+    assert R.policy_status() == aq.EINVAL
+    R.close()
+    Q.close()
+
+
 # ------------------------------------------------------------------ edge cases and error paths
 def test_edges(aq):
     net = synth.net_config("cfg1")
