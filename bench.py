@@ -308,7 +308,8 @@ def main():
     if not args.no_extra:
         extra = []
         for name, bsz, it in (("cfg5", 16384, 100), ("cfg3", 65536, 100), ("cfg3", 256, 500), ("cfg3", 1, 500),
-                              ("cfg1", 256, 500), ("cfg4", 256, 100)):
+                              ("cfg1", 256, 500), ("cfg4", 256, 100), ("paper_fc2048", 1, 200),
+                              ("paper_fc2048", 16, 200)):
             o, c = forward_workload(torch, aq, synth, U, name, bsz, it)
             c[0].close()
             del c

@@ -1,0 +1,223 @@
+// Fully connected layer at few rows (Sec. 3.1: the paper's actors run their policy on one observation
+// at a time; Sec. 4.1: three hidden layers of 2048 units): the time goes into streaming the layer's
+// 8-bit weights once, so the layer is cut into as many independent weight streams as possible.
+//
+// One workgroup of 8 waves owns one 32-row x 32-feature output tile; its waves split K eight ways.
+// Each wave requests its whole share of the weights at once (up to 16 KiB in flight), stages its own
+// K-slice of the activations in a private LDS region (no barrier before the MFMAs), and leaves a
+// partial accumulator tile in LDS; after one barrier the 512 threads sum the eight partial sums of two
+// outputs each and run the layer's epilogue (requantize, or dequantize for a LayerNorm / last layer).
+// A 2048 x 2048 layer at batch 1 is 64 workgroups x 8 waves with all 4 MiB of weights in flight.
+#include "int8_device.hpp"
+
+namespace aq {
+
+namespace {
+constexpr int SK_W = 8;                    // waves per workgroup = K split
+constexpr int SK_PF = 16;                  // weight k-steps in flight per wave
+constexpr int SK_MAX_KCHUNK = 15;          // k-steps per wave that fit the LDS budget below
+constexpr int SK_PART_LD = 65;             // words per register row of a partial tile (64 lanes + 1: the
+                                           // feature-major reduction then spreads over the banks)
+constexpr int SK_PART_WORDS = 17 * SK_PART_LD;
+
+__host__ __device__ inline size_t skinny_lds_bytes(int kchunk) {
+    return (size_t)SK_W * 32 * (kchunk * 32 + 16) + (size_t)SK_W * SK_PART_WORDS * 4;
+}
+}  // namespace
+
+template <bool ASYM, bool TAPS>
+__global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __restrict__ netp, const TapArgs t, const int l,
+                                                           const LayerIO io, const int64_t rows, const int kchunk,
+                                                           const int in_mode, const void* __restrict__ actions) {
+    extern __shared__ __align__(16) int8_t smem[];
+    const NetDev& a = *netp;
+    const LayerDev& L = a.L[l];
+    LayerTaps T{nullptr, nullptr, nullptr};
+    if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nt = blockIdx.x;
+    const int64_t row0 = (int64_t)blockIdx.y * 32;
+    const bool first = l == 0, last = l == a.n_layers - 1;
+    const bool ln = !last && L.act == AQ_ACT_LN_TANH;
+    const int K = L.K, KS = L.KS, N = L.N;
+    const int k0 = wave * kchunk, k1 = k0 + kchunk < KS ? k0 + kchunk : KS;
+    const int LDX = kchunk * 32 + 16;
+    int8_t* xs = smem + (size_t)wave * 32 * LDX;  // this wave's rows x its K slice
+    int32_t* part = (int32_t*)(smem + (size_t)SK_W * 32 * LDX);
+
+    // this thread's epilogue constants (its two outputs share one feature): requested up front, they
+    // arrive behind the weights
+    const int n_e = nt * 32 + (tid & 31);  // < N_pad: the constant arrays are padded
+    const int c_bias = L.bias_fold[n_e], c_M0 = L.M0[n_e], c_rz = L.rz[n_e], c_sh = L.sh[n_e], c_r = L.rshift[n_e];
+    const float c_m = L.m[n_e];
+    const int z_out = last ? 0 : a.actq[l + 1].z;
+    const int lo = (!last && L.act == AQ_ACT_RELU) ? z_out : 0;
+    const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
+    const bool fast = !last && !ln && a.fast[l] != 0;
+    const int head = a.head;
+
+    v16i pacc[1][1], prs[1];
+    pacc[0][0] = zero16();
+    prs[0] = zero16();
+    if (k0 < k1) {
+        // the wave's whole weight share goes out first
+        gv4i_ptr wptr[1];
+        wptr[0] = (gv4i_ptr)L.wp + (int64_t)nt * KS * 64 + lane;
+        v4i wreg[SK_PF][1];
+        mma_prefetch<1, SK_PF>(wptr, k0, k1, wreg);
+
+        // this wave's K slice of the 32 rows -> LDS (signed domain; zero beyond the batch and beyond K)
+        const int kb0 = k0 * 32, kb1 = k1 * 32;  // byte range of K
+        if (in_mode == 1) {
+            // 8-bit activations, rows of K bytes with K a multiple of 16, 16-byte aligned: whole pieces
+            const int ppr = (kb1 - kb0) >> 4;  // pieces per row
+            const int total = 32 * ppr;
+            constexpr int SU = 8;
+            for (int base = lane; base < total; base += 64 * SU) {
+                v4i v[SU];
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int idx = base + u * 64;
+                    v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0;
+                    if (idx < total) {
+                        const int m = idx / ppr, c = idx - m * ppr;
+                        const int k = kb0 + c * 16;
+                        if (row0 + m < rows && k < K) v[u] = *(const v4i*)((const int8_t*)io.in + (row0 + m) * K + k);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < SU; ++u) {
+                    const int idx = base + u * 64;
+                    if (idx < total) {
+                        const int m = idx / ppr, c = idx - m * ppr;
+                        *(v4i*)(xs + m * LDX + c * 16) = v[u];
+                    }
+                }
+            }
+        } else {
+            float s0 = 1.0f;
+            int z0 = 0;
+            if (first) {
+                s0 = a.actq[0].s;
+                z0 = a.actq[0].z;
+            }
+            const QuantScale qs0 = make_quant_scale(s0);
+            const int kb = kb1 - kb0;
+            for (int idx = lane; idx < 32 * kb; idx += 64) {
+                const int m = idx / kb, kk = idx - m * kb;
+                const int k = kb0 + kk;
+                const int64_t row = row0 + m;
+                int sv = 0;
+                if (row < rows && k < K) {
+                    const int64_t off = row * K + k;
+                    if (first) {
+                        int code;
+                        if (a.in_u8) code = ((const uint8_t*)io.in)[off];
+                        else code = quant_code(((const float*)io.in)[off], qs0, -z0, 255 - z0) + z0;
+                        if (TAPS) {
+                            if (t.a0 && nt == 0) t.a0[off] = (uint8_t)code;
+                        }
+                        sv = code - 128;
+                    } else {
+                        sv = ((const int8_t*)io.in)[off];
+                    }
+                }
+                xs[m * LDX + kk] = (int8_t)sv;
+            }
+        }
+        // the slice is private to this wave: its own LDS writes only have to land
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+        mma_run<1, 1, ASYM, SK_PF>(wptr, wreg, xs, LDX, k0, k1, k0, pacc, prs, lane);
+    }
+    {
+        int32_t* mine = part + wave * SK_PART_WORDS + lane;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mine[r * SK_PART_LD] = pacc[0][0][r];
+        if (ASYM) mine[16 * SK_PART_LD] = prs[0][0];
+    }
+    __syncthreads();
+
+    // reduction + epilogue: thread -> (row m, feature n) with the feature index fastest, so that the
+    // global stores of a row are contiguous
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int m = (tid >> 5) + 16 * it, nl = tid & 31;
+        const int reg = 4 * (nl >> 3) + (nl & 3), lsrc = m + 32 * ((nl >> 2) & 1);
+        int v = 0, rsum = 0;
+#pragma unroll
+        for (int kp = 0; kp < SK_W; ++kp) {
+            const int32_t* src = part + kp * SK_PART_WORDS + lsrc;
+            v += src[reg * SK_PART_LD];
+            if (ASYM) rsum += src[16 * SK_PART_LD];
+        }
+        const int n = nt * 32 + nl;
+        const int64_t row = row0 + m;
+        if (row >= rows || n >= N) continue;
+        v += c_bias;
+        if (ASYM) v -= zw_s * rsum;
+        if (TAPS) {
+            if (T.acc) T.acc[row * N + n] = v;
+        }
+        if (ln) {
+            io.ln_x[row * N + n] = (float)v * c_m;
+        } else if (last) {
+            const float y = (float)v * c_m;
+            if (io.y) io.y[row * N + n] = y;
+            if (actions) ((float*)actions)[row * N + n] = head == AQ_HEAD_TANH ? tanh_head(y) : y;
+        } else {
+            int code;
+            if (fast) code = min(max((__mulhi(v, c_M0) + c_rz) >> c_sh, lo), 255);
+            else code = requant_code(v, c_M0, c_r, z_out, lo);
+            if (TAPS) {
+                if (T.act) T.act[row * N + n] = (uint8_t)code;
+            }
+            io.out[row * N + n] = (int8_t)(code - 128);
+        }
+    }
+}
+
+bool skinny_layer_supported(const LayerDev& L, int64_t rows) {
+    const bool fc = L.kh == 1 && L.kw == 1 && L.in_h == 1 && L.in_w == 1;
+    if (!fc) return false;
+    const int kchunk = (L.KS + SK_W - 1) / SK_W;
+    if (kchunk > SK_MAX_KCHUNK) return false;
+    return (rows + 31) / 32 <= 65535;
+}
+
+aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStream_t st) {
+    const LayerDev& L = a.net.L[l];
+    const int64_t rows = a.c.batch;
+    const bool first = l == 0, last = l == a.net.n_layers - 1;
+    const int kchunk = (L.KS + SK_W - 1) / SK_W;
+    const size_t lds = skinny_lds_bytes(kchunk);
+    // whole 16-byte pieces need 8-bit rows whose length is a multiple of 16, at an aligned address
+    const int in_mode = (!first && (L.K & 15) == 0 && ((uintptr_t)io.in & 15) == 0) ? 1 : 0;
+    const void* actions = (last && a.net.head != AQ_HEAD_ARGMAX) ? a.c.actions : nullptr;
+    dim3 grid((unsigned)L.NT, (unsigned)((rows + 31) / 32));
+    const bool taps = any_taps(a);
+    const bool asym = a.net.asym != 0;
+#define AQ_SKINNY(AS, TP)                                                                                           \
+    do {                                                                                                            \
+        static bool attr_set = false;                                                                               \
+        if (!attr_set) {                                                                                            \
+            if (hipFuncSetAttribute((const void*)k_layer_skinny<AS, TP>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                    160 * 1024) != hipSuccess)                                                      \
+                return AQ_EHIP;                                                                                     \
+            attr_set = true;                                                                                        \
+        }                                                                                                           \
+        hipLaunchKernelGGL((k_layer_skinny<AS, TP>), grid, dim3(SK_W * 64), lds, st, a.d_net, a.t, l, io, rows, kchunk, \
+                           in_mode, actions);                                                                       \
+    } while (0)
+    if (asym) {
+        if (taps) AQ_SKINNY(true, true);
+        else AQ_SKINNY(true, false);
+    } else {
+        if (taps) AQ_SKINNY(false, true);
+        else AQ_SKINNY(false, false);
+    }
+#undef AQ_SKINNY
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
+}  // namespace aq

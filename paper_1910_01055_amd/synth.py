@@ -50,6 +50,13 @@ CONFIGS = {
                                                           _fc(1024, 1024, "relu"), _fc(1024, 64, "none")],
              "head": "tanh", "wscheme": "channel_sym_s8", "qdenom": 255, "ln_eps": 1e-5, "batch": 16384,
              "init": "glorot_uniform", "obs_seed": 1005, "w_seed": 2501},
+    # the paper's own actor (Sec. 4.1: three hidden layers of 2048 units, plain fully connected) on a
+    # 67-dimensional observation and 21-dimensional action; the paper runs it one observation at a time
+    "paper_fc2048": {"name": "paper_fc2048", "in_type": "f32",
+                     "layers": [_fc(67, 2048, "relu"), _fc(2048, 2048, "relu"), _fc(2048, 2048, "relu"),
+                                _fc(2048, 21, "none")],
+                     "head": "tanh", "wscheme": "channel_sym_s8", "qdenom": 255, "ln_eps": 1e-5, "batch": 16,
+                     "init": "glorot_uniform", "obs_seed": 1006, "w_seed": 2601},
 }
 # batch sweep of cfg2's network
 CONFIGS["cfg3"] = dict(copy.deepcopy(CONFIGS["cfg2"]), name="cfg3", batch=65536, obs_seed=1003)

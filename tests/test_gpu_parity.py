@@ -211,6 +211,23 @@ def test_fused_row_tiles_large_batch(aq, name, batch):
     P.close()
 
 
+@pytest.mark.parametrize("batch", [1, 16, 40, 300])
+def test_paper_scale_actor_small_batches(aq, batch):
+    """The paper's own actor shape (three hidden layers of 2048 units) at the batch sizes of its actors:
+    too wide for the fused kernel, so every layer runs as a K-split launch (or the tiled kernel)."""
+    _say(f"paper_scale_actor batch={batch}")
+    net = synth.net_config("paper_fc2048")
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, synth.make_obs(net, 64))
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    actions, t = U.gpu_forward(P, net, obs)
+    U.compare_forward(net, pol, obs, actions, t)
+    a2, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(a2, actions)
+    P.close()
+
+
 @pytest.mark.parametrize("name,batch,sample", [("cfg5", 8200, 300), ("cfg2", 9000, 400)])
 def test_per_layer_path_large_batch(aq, name, batch, sample):
     """The one-launch-per-layer plan at batch sizes where it picks its 128-row / 8-wave and its narrow
