@@ -318,18 +318,16 @@ __device__ __forceinline__ void epi_hidden_tile(const int N, const LayerTaps& T,
 // the tile: lanes that hold rows 16..31 take over feature quads 2 and 3 of the row 16 below them.
 // Afterwards lane l owns row l & 15, half h = (l >> 4) & 1, and registers 4j+i (j = 0, 1) hold feature
 // 8 (j + 2h) + 4 (l >> 5) + i of the tile: every lane does useful epilogue work on half the registers.
+// v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of its
+// second: (c[r], c[r+8]) -> c[r] = [own row 0 | c[r+8] row 0 | own row 2 | c[r+8] row 2], which is the fold.
 __device__ __forceinline__ void fold_rows16(v16i& c, int lane) {
-    const int src = (lane ^ 16) << 2;
-    const bool up = (lane & 16) != 0;
+    (void)lane;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-        const int t = __builtin_amdgcn_ds_bpermute(src, c[r + 8]);
-        c[r] = up ? t : c[r];
-    }
+    for (int r = 0; r < 8; ++r) c[r] = (int)__builtin_amdgcn_permlane16_swap((unsigned)c[r], (unsigned)c[r + 8], false, false)[0];
 }
 __device__ __forceinline__ int fold_rows16_scalar(int v, int lane) {
-    const int t = __builtin_amdgcn_ds_bpermute((lane ^ 16) << 2, v);
-    return (lane & 16) ? t : v;
+    (void)lane;
+    return (int)__builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false)[0];
 }
 
 // Hidden-layer epilogue of a wave's whole tile set (NB feature tiles x MT row tiles).  The
