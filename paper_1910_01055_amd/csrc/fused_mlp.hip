@@ -27,7 +27,7 @@ AQ_FUSED_DECL(1, 1, true, true, true);
 
 namespace {
 struct Plan {
-    int mt, nb, ld, cst_n, part_off;
+    int mt, nb, ld, cst_n, part_off, cst_dbl;
     bool half;  // 16 rows per workgroup
     size_t lds;
 };
@@ -69,7 +69,10 @@ bool make_plan(const FwdArgs& a, Plan* p) {
     if (a.c.batch >= 512 * 128 && p->nb == 1) mt = 4;
     const bool narrow_last = a.net.L[a.net.n_layers - 1].NT <= NARROW_NT;
     for (; mt >= 1; mt >>= 1) {
-        p->lds = fused_lds_bytes(32 * mt, p->ld, p->cst_n);
+        // (a doubled constant area when everything still fits in 64 KB: small networks, where the
+        // barrier it saves per layer is a visible share of the time)
+        p->cst_dbl = fused_lds_bytes(32 * mt, p->ld, p->cst_n, true) + PART_BYTES <= 64 * 1024;
+        p->lds = fused_lds_bytes(32 * mt, p->ld, p->cst_n, p->cst_dbl != 0);
         p->part_off = -1;
         // partial sums of a narrow last layer: in the idle activation buffer if it is large enough,
         // else in an area of their own behind everything else
@@ -113,6 +116,7 @@ aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     a.c.KS0 = a.net.L[0].KS;
     a.c.pieces0 = (a.net.n_layers == 1 ? 2 : 4) * a.net.L[0].NT * 8;
     a.c.part_off = p.part_off;
+    a.c.cst_dbl = p.cst_dbl;
     a.c.narrow0 = a.net.n_layers == 1 && a.net.L[0].NT <= NARROW_NT;
     const bool tp = any_taps(a);
     const bool as = a.net.asym != 0;

@@ -21,8 +21,9 @@ constexpr int CST_MAXN = 1024;   // widest layer whose constants fit the LDS sta
 constexpr int NET_WORDS = (sizeof(NetDev) + 15) / 16 * 4;
 
 // LDS layout (bytes): [buf_in ROWS*ld][buf_out ROWS*ld][red 2*FW*ROWS floats][cst 4*cst_n words][net]
-__host__ __device__ inline size_t fused_lds_bytes(int rows, int ld, int cst_n) {
-    return (size_t)2 * rows * ld + (size_t)2 * FW * rows * 4 + (size_t)4 * cst_n * 4 + (size_t)NET_WORDS * 4;
+__host__ __device__ inline size_t fused_lds_bytes(int rows, int ld, int cst_n, bool cst_dbl = false) {
+    return (size_t)2 * rows * ld + (size_t)2 * FW * rows * 4 + (size_t)4 * cst_n * 4 * (cst_dbl ? 2 : 1) +
+           (size_t)NET_WORDS * 4;
 }
 
 // Values read from the LDS copy of the network description arrive in vector registers;
@@ -77,9 +78,9 @@ __device__ __forceinline__ void load_consts(const LayerView& v, int tid, v4i& c0
     if (tid < v.pieces) c0 = v.pack[tid];
     if (tid + FT < v.pieces) c1 = v.pack[tid + FT];
 }
-__device__ __forceinline__ void park_consts(const LayerView& v, int tid, int32_t* cst, const v4i& c0, const v4i& c1) {
-    if (tid < v.pieces) ((v4i*)cst)[tid] = c0;
-    if (tid + FT < v.pieces) ((v4i*)cst)[tid + FT] = c1;
+__device__ __forceinline__ void park_consts(int pieces, int tid, int32_t* cst, const v4i& c0, const v4i& c1) {
+    if (tid < pieces) ((v4i*)cst)[tid] = c0;
+    if (tid + FT < pieces) ((v4i*)cst)[tid + FT] = c1;
 }
 
 template <int NB>
@@ -179,7 +180,11 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
     int8_t* buf_out = smem + BROWS * ld;
     float* red = (float*)(smem + 2 * BROWS * ld);
     int32_t* cst = (int32_t*)(red + 2 * FW * BROWS);
-    int32_t* net_lds = cst + 4 * cst_n;
+    // With LDS to spare the constant area is doubled: the next layer's constants are parked in the other
+    // half before the barrier that ends the current layer, which saves the barrier that would publish them.
+    const int cst_dbl = c.cst_dbl;
+    const int cst_half = cst_dbl ? 4 * cst_n : 0;  // words between the two halves
+    int32_t* net_lds = cst + 4 * cst_n + cst_half;
     const NetDev& an = *(const NetDev*)net_lds;  // valid after the first barrier
 
     // the network description: one coalesced read into LDS, so that no layer starts by chasing
@@ -308,6 +313,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
             }
         }
     }
+    if (cst_dbl) park_consts(c.pieces0, tid, cst, cv0, cv1);
     lds_barrier();
 
     const int n_layers = uni(an.n_layers);
@@ -338,10 +344,12 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 
         // This layer's per-channel constants were requested one layer ago (layer 0: just above);
         // park them in LDS for the epilogue.  The barrier after the first MFMA pass publishes them.
-        park_consts(L, tid, cst, cv0, cv1);
-        const CPtrs C{cst, cst + Np, L.rshift, cst + 2 * Np, cst + 3 * Np, (const float*)(cst + Np)};
-        const float* c_gamma = (const float*)(cst + 2 * Np);
-        const float* c_beta = (const float*)(cst + 3 * Np);
+        int32_t* cstl = cst + (l & 1) * cst_half;
+        if (!cst_dbl) park_consts(L.pieces, tid, cstl, cv0, cv1);
+        const CPtrs C{cstl, cstl + Np, L.rshift, cstl + 2 * Np, cstl + 3 * Np, (const float*)(cstl + Np)};
+        const float* c_gamma = (const float*)(cstl + 2 * Np);
+        const float* c_beta = (const float*)(cstl + 3 * Np);
+        int pieces_next = 0;
 
         if (last) {
             ybuf = (const float*)out;
@@ -387,8 +395,9 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
             if (!last && g0 + FW >= ngroups) {
                 const LayerView vn = layer_view(an, l + 1, n_layers);
                 load_consts(vn, tid, cv0, cv1);
+                pieces_next = vn.pieces;
             }
-            if (g0 == 0) lds_barrier();
+            if (g0 == 0 && !cst_dbl) lds_barrier();
             if (!ln) {
                 if (active) {
                     const int m0 = mrow;
@@ -547,6 +556,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 });
             }
         }
+        if (cst_dbl) park_consts(pieces_next, tid, cst + ((l + 1) & 1) * cst_half, cv0, cv1);
         lds_barrier();
         int8_t* sw = buf_in;
         buf_in = buf_out;
@@ -562,8 +572,9 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const int Np = L.NT * 32;
         const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
         const int8_t* in = buf_in;
-        park_consts(L, tid, cst, cv0, cv1);
-        const CPtrs C{cst, cst + Np, L.rshift, cst + 2 * Np, cst + 3 * Np, (const float*)(cst + Np)};
+        int32_t* cstl = cst + (l & 1) * cst_half;
+        if (!cst_dbl) park_consts(L.pieces, tid, cstl, cv0, cv1);
+        const CPtrs C{cstl, cstl + Np, L.rshift, cstl + 2 * Np, cstl + 3 * Np, (const float*)(cstl + Np)};
         // Everything below depends on the thread index only; left alone, the compiler computes it at
         // the top of the kernel and keeps it in registers through every layer.  The empty asm hides
         // the index from that motion.
