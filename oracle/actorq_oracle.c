@@ -266,6 +266,85 @@ void orc_argmax_rows(const float* y, int64_t rows, int64_t N, int32_t* idx) {
 }
 
 /* ------------------------------------------------------------------------
+ * Exploration on the actor (Sec. 4.1): Gaussian noise on the policy output
+ * with a per-actor sigma (continuous control), epsilon-greedy on the argmax
+ * action (discrete control; the paper names DQN, epsilon-greedy is that
+ * algorithm's exploration rule).
+ *
+ * The random numbers come from the counter-based generator Philox4x32-10 as
+ * defined by Salmon, Moraes, Dror and Shaw, "Parallel random numbers: as easy
+ * as 1, 2, 3" (SC'11): ten rounds of
+ *     (hi0, lo0) = M0 * c0      (32 x 32 -> 64 bit products)
+ *     (hi1, lo1) = M1 * c2
+ *     c <- (hi1 ^ c1 ^ k0,  lo1,  hi0 ^ c3 ^ k1,  lo0)
+ * with the key advanced by the Weyl constants (W0, W1) before every round
+ * but the first.  Readings taken here (the paper fixes none of this):
+ *   key     = (seed low word, seed high word)
+ *   counter = (batch row, block, step low word, step high word)
+ *   Gaussian noise: block = feature index / 4; the four output words give two
+ *     Box-Muller pairs, u1 = ((x >> 8) + 1) / 2^24 in (0, 1], u2 = (y >> 8) / 2^24
+ *     in [0, 1); z_even = sqrt(-2 ln u1) cos(2 pi u2), z_odd = ... sin(2 pi u2);
+ *     action' = action + sigma[row] * z, evaluated in fp64, rounded to fp32.
+ *     No clipping (the paper states none).
+ *   epsilon-greedy: block = 0xFFFFFFFF; u = (x0 >> 8) / 2^24 as fp32 (exact);
+ *     if u < epsilon (fp32 compare) the action becomes floor(x1 * A / 2^32).
+ * ---------------------------------------------------------------------- */
+void orc_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) {
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0;
+        c1 = n1;
+        c2 = n2;
+        c3 = n3;
+    }
+    out[0] = c0;
+    out[1] = c1;
+    out[2] = c2;
+    out[3] = c3;
+}
+
+void orc_explore_gaussian(float* actions, int64_t rows, int64_t A, const float* sigma, uint64_t seed,
+                          uint64_t step) {
+    const double two_pi = 6.283185307179586476925286766559;
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (int64_t b = 0; b < rows; ++b) {
+        for (int64_t n = 0; n < A; ++n) {
+            const uint32_t ctr[4] = {(uint32_t)b, (uint32_t)(n / 4), (uint32_t)step, (uint32_t)(step >> 32)};
+            uint32_t r[4];
+            orc_philox4x32_10(ctr, key, r);
+            const int j = (int)(n % 4), pair = j / 2;
+            const double u1 = ((double)(r[2 * pair] >> 8) + 1.0) / 16777216.0;
+            const double u2 = (double)(r[2 * pair + 1] >> 8) / 16777216.0;
+            const double rad = sqrt(-2.0 * log(u1));
+            const double z = (j % 2 == 0) ? rad * cos(two_pi * u2) : rad * sin(two_pi * u2);
+            actions[b * A + n] = (float)((double)actions[b * A + n] + (double)sigma[b] * z);
+        }
+    }
+}
+
+void orc_explore_eps_greedy(int32_t* idx, int64_t rows, int64_t A, float epsilon, uint64_t seed, uint64_t step) {
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    for (int64_t b = 0; b < rows; ++b) {
+        const uint32_t ctr[4] = {(uint32_t)b, 0xFFFFFFFFu, (uint32_t)step, (uint32_t)(step >> 32)};
+        uint32_t r[4];
+        orc_philox4x32_10(ctr, key, r);
+        const float u = (float)(r[0] >> 8) * (1.0f / 16777216.0f);
+        if (u < epsilon) idx[b] = (int32_t)(((uint64_t)r[1] * (uint64_t)A) >> 32);
+    }
+}
+
+/* ------------------------------------------------------------------------
  * Full-precision policy (the learner's / the fp32 actor's network), evaluated
  * in fp64 from fp32 parameters: textbook affine layer, VALID convolution,
  * ReLU, LayerNorm and tanh.  Activations stay fp64 between layers.

@@ -161,6 +161,30 @@ def c_argmax_rows(y):
     return idx
 
 
+def c_philox4x32_10(ctr, key):
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().orc_philox4x32_10(c.ctypes.data_as(C.c_void_p), k.ctypes.data_as(C.c_void_p), out.ctypes.data_as(C.c_void_p))
+    return out
+
+
+def c_explore_gaussian(actions, sigma, seed, step):
+    """actions fp32 [rows][A] -> a copy with the exploration noise added (Sec. 4.1)."""
+    a = np.array(actions, dtype=np.float32, order="C", copy=True)
+    rows, A = a.shape
+    sg = np.ascontiguousarray(sigma, dtype=np.float32)
+    assert sg.shape == (rows,)
+    lib().orc_explore_gaussian(_p(a, _f32), _i64(rows), _i64(A), _p(sg, _f32), C.c_uint64(seed), C.c_uint64(step))
+    return a
+
+
+def c_explore_eps_greedy(idx, A, epsilon, seed, step):
+    i = np.array(idx, dtype=np.int32, order="C", copy=True)
+    lib().orc_explore_eps_greedy(_p(i, _i32), _i64(i.size), _i64(A), _f32(epsilon), C.c_uint64(seed), C.c_uint64(step))
+    return i
+
+
 def c_fc_f64(x, w, b):
     x = np.ascontiguousarray(x, np.float64)
     B, K = x.shape

@@ -439,3 +439,83 @@ def test_conv_policy_runs_and_start_layer_resumes():
     assert (taps["actions"] == ref).mean() >= 0.8
     again = pol.forward_int8(start_layer=2, start_codes=taps["act"][1])
     assert np.array_equal(again["acc"][3], taps["acc"][3]) and np.array_equal(again["actions"], taps["actions"])
+
+
+# ------------------------------------------------------------------ exploration (Sec. 4.1)
+def test_philox_matches_the_published_known_answers():
+    """Pins the counter-based generator to the known-answer vectors of its reference implementation
+    (tests/golden/philox4x32_10_kat.txt); a wrong multiplier, Weyl constant, round count or output
+    word order fails every line."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    n = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        w = [int(x, 16) for x in line.split()]
+        assert len(w) == 10
+        got = O.c_philox4x32_10(w[0:4], w[4:6])
+        assert [int(x) for x in got] == w[6:10]
+        n += 1
+    assert n == 3
+
+
+def _py_philox(ctr, key):
+    # the same published definition in plain Python integers, for cross-checking counters other than the three above
+    c, k = list(ctr), list(key)
+    for r in range(10):
+        if r:
+            k = [(k[0] + 0x9E3779B9) & 0xFFFFFFFF, (k[1] + 0xBB67AE85) & 0xFFFFFFFF]
+        p0, p1 = 0xD2511F53 * c[0], 0xCD9E8D57 * c[2]
+        c = [(p1 >> 32) ^ c[1] ^ k[0], p1 & 0xFFFFFFFF, (p0 >> 32) ^ c[3] ^ k[1], p0 & 0xFFFFFFFF]
+    return c
+
+
+def test_gaussian_exploration_noise():
+    rows, A, seed, step = 2000, 21, 0x1234567887654321, (7 << 32) + 5
+    base = np.zeros((rows, A), dtype=np.float32)
+    sigma = np.full(rows, 1.0, dtype=np.float32)
+    z = O.c_explore_gaussian(base, sigma, seed, step).astype(np.float64)
+    # standard normal moments (42 000 samples: 5 sigma bounds)
+    assert abs(z.mean()) < 5 / math.sqrt(z.size)
+    assert abs(z.var() - 1.0) < 5 * math.sqrt(2.0 / z.size)
+    assert abs((z ** 4).mean() - 3.0) < 0.25
+    # one element against the definition evaluated with Python integers and math: row 3, feature 6
+    r = _py_philox([3, 6 // 4, step & 0xFFFFFFFF, step >> 32], [seed & 0xFFFFFFFF, seed >> 32])
+    u1, u2 = ((r[2] >> 8) + 1) / 2.0 ** 24, (r[3] >> 8) / 2.0 ** 24          # feature 6 -> second pair, even member
+    assert abs(z[3, 6] - math.sqrt(-2 * math.log(u1)) * math.cos(2 * math.pi * u2)) < 1e-6
+    r = _py_philox([1999, 20 // 4, step & 0xFFFFFFFF, step >> 32], [seed & 0xFFFFFFFF, seed >> 32])
+    u1, u2 = ((r[0] >> 8) + 1) / 2.0 ** 24, (r[1] >> 8) / 2.0 ** 24          # feature 20 -> first pair, even member
+    assert abs(z[1999, 20] - math.sqrt(-2 * math.log(u1)) * math.cos(2 * math.pi * u2)) < 1e-6
+    # scaling by the actor's sigma, additivity, determinism, sigma = 0 leaves the action alone
+    a = np.random.default_rng(1).uniform(-1, 1, (rows, A)).astype(np.float32)
+    sg = np.random.default_rng(2).uniform(0, 0.2, rows).astype(np.float32)
+    out = O.c_explore_gaussian(a, sg, seed, step)
+    assert np.allclose(out, a + sg[:, None].astype(np.float64) * z, rtol=0, atol=1e-6)
+    assert np.array_equal(out, O.c_explore_gaussian(a, sg, seed, step))
+    assert not np.array_equal(out, O.c_explore_gaussian(a, sg, seed, step + 1))
+    assert not np.array_equal(out, O.c_explore_gaussian(a, sg, seed + 1, step))
+    assert np.array_equal(O.c_explore_gaussian(a, np.zeros(rows, np.float32), seed, step), a)
+
+
+def test_epsilon_greedy_exploration():
+    rows, A, seed, step = 20000, 18, 99, 3
+    greedy = np.random.default_rng(3).integers(0, A, rows).astype(np.int32)
+    assert np.array_equal(O.c_explore_eps_greedy(greedy, A, 0.0, seed, step), greedy)
+    allrand = O.c_explore_eps_greedy(greedy, A, 1.0, seed, step)
+    assert allrand.min() >= 0 and allrand.max() < A
+    counts = np.bincount(allrand, minlength=A)
+    assert np.abs(counts - rows / A).max() < 5 * math.sqrt(rows / A)      # uniform over the actions
+    eps = 0.1
+    out = O.c_explore_eps_greedy(greedy, A, eps, seed, step)
+    changed_or_same = out != greedy
+    # a replaced action equals the old one with probability 1/A: count replacements through the definition instead
+    repl = 0
+    for b in (0, 1, 17, 19999):
+        r = _py_philox([b, 0xFFFFFFFF, step, 0], [seed, 0])
+        u = np.float32(r[0] >> 8) * np.float32(2.0 ** -24)
+        want = (r[1] * A) >> 32 if u < np.float32(eps) else int(greedy[b])
+        assert int(out[b]) == want
+    frac = np.mean(out == allrand)          # rows where the random action was taken (or coincides)
+    expect = eps + (1 - eps) / A
+    assert abs(frac - expect) < 5 * math.sqrt(expect * (1 - expect) / rows)
+    assert changed_or_same.mean() <= eps + 5 * math.sqrt(eps / rows)
