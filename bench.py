@@ -307,6 +307,17 @@ def main():
     }
     if not args.no_extra:
         extra = []
+        # the full actor step of Sec. 4.1: 8-bit forward, then Gaussian exploration noise with per-actor sigma
+        sg = torch.rand(batch, device=U.DEV) * 0.2
+        ctr = [0]
+
+        def actor_step():
+            P.policy_forward_int8(d_obs, act)
+            ctr[0] += 1
+            P.policy_explore(act, 2024, ctr[0], sigma=sg)
+        ms_step = _graph_ms(torch, actor_step, 100)
+        extra.append({"workload": "cfg2 batch 4096 forward + exploration noise", "us_per_step": ms_step * 1e3,
+                      "inferences_per_s": batch / (ms_step * 1e-3)})
         for name, bsz, it in (("cfg5", 16384, 100), ("cfg3", 65536, 100), ("cfg3", 256, 500), ("cfg3", 1, 500),
                               ("cfg1", 256, 500), ("cfg4", 256, 100), ("paper_fc2048", 1, 200),
                               ("paper_fc2048", 16, 200)):

@@ -144,6 +144,28 @@ aq_status aq_policy_blob_size(const aq_policy* p, uint64_t* bytes);
 aq_status aq_policy_export_blob(const aq_policy* p, void* d_blob, uint64_t bytes, void* stream);
 aq_status aq_policy_import_blob(aq_policy* p, const void* d_blob, uint64_t bytes, void* stream);
 
+/* Exploration on the actor (Sec. 4.1: a Gaussian noise layer on the policy output whose sigma
+ * depends on the actor; for the discrete-control policies, epsilon-greedy), applied in place to the
+ * actions of a preceding forward on the same stream.
+ *   tanh / linear heads: actions[b][n] += d_sigma[b] * z, z ~ N(0, 1); d_sigma: device fp32 [batch]
+ *     (the paper draws each actor's sigma from U(0, 0.2)); no clipping.
+ *   argmax head: with probability epsilon actions[b] becomes a uniform action index (d_sigma unused).
+ * Random numbers come from the counter-based generator Philox4x32-10 (Salmon et al., SC'11) with
+ * key = seed and counter = (row, block, step): the same (seed, step, row) always gives the same
+ * draw, different steps give independent draws, no generator state is kept.  z comes from
+ * Box-Muller on 24-bit uniforms: block = n / 4, words (0, 1) -> features 4 block + (0, 1) as
+ * (cos, sin), words (2, 3) -> features 4 block + (2, 3); epsilon-greedy uses block 0xFFFFFFFF,
+ * word 0 for the test u < epsilon (u = (word >> 8) / 2^24) and word 1 for the index
+ * floor(word * A / 2^32).  batch must be below 2^32.  AQ_EINVAL for a NULL d_sigma with a
+ * continuous head or an epsilon outside [0, 1]. */
+typedef struct {
+    uint64_t seed;
+    uint64_t step;
+    const float* d_sigma;
+    float epsilon;
+} aq_explore;
+aq_status aq_policy_explore(const aq_policy* p, void* d_actions, int64_t batch, const aq_explore* ex, void* stream);
+
 /* Sec. 3.2 applied to one tensor, for the learner-to-actor broadcast: quantizes fp32
  * d_w[rows][cols] to 8-bit codes in canonical row-major order.
  *   AQ_W_TENSOR_ASYM_U8: one (scale, zero-point) for the whole tensor -> d_scale[1], d_zp[1], uint8 codes.

@@ -23,7 +23,7 @@ INTYPE = {"f32": 0, "u8": 1}
 EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_policy_set_path", "aq_policy_status",
            "aq_quantize_tensor", "aq_quantize_params", "aq_policy_export_layer", "aq_policy_export_act_qparams",
            "aq_policy_forward_int8", "aq_policy_forward_fp32", "aq_status_string",
-           "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob"]
+           "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore"]
 
 
 class AqLayer(C.Structure):
@@ -39,6 +39,10 @@ class AqNet(C.Structure):
 
 class AqRange(C.Structure):
     _fields_ = [("lo", C.c_float), ("hi", C.c_float)]
+
+
+class AqExplore(C.Structure):
+    _fields_ = [("seed", C.c_uint64), ("step", C.c_uint64), ("d_sigma", C.c_void_p), ("epsilon", C.c_float)]
 
 
 class AqTaps(C.Structure):
@@ -82,6 +86,7 @@ def load():
     lib.aq_policy_blob_size.argtypes = [vp, C.POINTER(C.c_uint64)]
     lib.aq_policy_export_blob.argtypes = [vp, vp, C.c_uint64, vp]
     lib.aq_policy_import_blob.argtypes = [vp, vp, C.c_uint64, vp]
+    lib.aq_policy_explore.argtypes = [vp, vp, i64, C.POINTER(AqExplore), vp]
     for name in EXPORTS:
         if name != "aq_status_string":
             getattr(lib, name).restype = C.c_int
@@ -157,6 +162,13 @@ class Policy:
 
     def policy_status(self):
         return load().aq_policy_status(self._h, _stream())
+
+    def policy_explore(self, actions, seed, step, sigma=None, epsilon=0.0):
+        """In place on the actions of a forward: Gaussian noise with per-row sigma (device fp32 [batch]) for
+        continuous heads, epsilon-greedy for argmax heads."""
+        ex = AqExplore(int(seed), int(step), 0 if sigma is None else sigma.data_ptr(), float(epsilon))
+        _check(load().aq_policy_explore(self._h, _ptr(actions), int(actions.shape[0]), C.byref(ex), _stream()),
+               "aq_policy_explore")
 
     def policy_blob_size(self):
         n = C.c_uint64(0)

@@ -382,6 +382,18 @@ extern "C" aq_status aq_policy_import_blob(aq_policy* p, const void* d_blob, uin
     return AQ_OK;
 }
 
+extern "C" aq_status aq_policy_explore(const aq_policy* p, void* d_actions, int64_t batch, const aq_explore* ex,
+                                       void* stream) {
+    if (!p || !d_actions || !ex || batch < 0 || batch > 0xffffffffLL) return AQ_EINVAL;
+    const bool discrete = p->net.head == AQ_HEAD_ARGMAX;
+    if (!discrete && !ex->d_sigma) return AQ_EINVAL;
+    if (discrete && !(ex->epsilon >= 0.0f && ex->epsilon <= 1.0f)) return AQ_EINVAL;
+    if (batch == 0) return AQ_OK;
+    const int A = p->L.back().N * p->L.back().oh * p->L.back().ow;
+    return launch_explore(d_actions, batch, A, p->net.head, ex->d_sigma, ex->epsilon, ex->seed, ex->step,
+                          as_stream(stream));
+}
+
 extern "C" aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int32_t wscheme,
                                         int32_t qdenom, void* d_codes, float* d_scale, int32_t* d_zp,
                                         void* d_workspace, void* stream) {

@@ -21,6 +21,10 @@ aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym
 aq_status launch_blob_header_write(uint32_t* d_hdr, const uint32_t* h_words, hipStream_t st);
 aq_status launch_blob_header_check(const uint32_t* d_hdr, const uint32_t* h_words, int* status, hipStream_t st);
 
+// ---- exploration on the produced actions (explore.hip)
+aq_status launch_explore(void* d_actions, int64_t rows, int A, int head, const float* d_sigma, float epsilon,
+                         uint64_t seed, uint64_t step, hipStream_t st);
+
 // ---- 8-bit forward (forward_int8.hip)
 struct FwdArgs {
     NetDev net;           // host copy, for planning

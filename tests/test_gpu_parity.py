@@ -330,6 +330,78 @@ def test_policy_blob_round_trip(aq, name):
     Q.close()
 
 
+# ------------------------------------------------------------------ exploration (Sec. 4.1)
+@pytest.mark.parametrize("rows,A", [(1, 1), (77, 21), (4096, 6), (1000, 64)])
+def test_explore_gaussian_matches_oracle(aq, rows, A):
+    _say(f"explore_gaussian rows={rows} A={A}")
+    net = synth.small_net([synth.fc(8, A, "none")], head="tanh")
+    P = aq.Policy(net)
+    rng = np.random.default_rng(11)
+    a = rng.uniform(-1, 1, (rows, A)).astype(np.float32)
+    sg = rng.uniform(0, 0.2, rows).astype(np.float32)
+    sg[0] = 0.0
+    for seed, step in ((5, 0), (0xFEDCBA9876543210, (3 << 32) + 17)):
+        d_a = U.to_dev(a)
+        P.policy_explore(d_a, seed, step, sigma=U.to_dev(sg))
+        torch.cuda.synchronize()
+        got = d_a.cpu().numpy()
+        want = O.c_explore_gaussian(a, sg, seed, step)
+        assert U.close(got, want).all()
+        assert np.array_equal(got[0], a[0])          # sigma = 0: untouched
+        if rows * A > 100:
+            assert not np.array_equal(got, a)
+    with pytest.raises(aq.AqError) as e:
+        P.policy_explore(U.to_dev(a), 1, 1, sigma=None)
+    assert e.value.status == aq.EINVAL
+    P.close()
+
+
+@pytest.mark.parametrize("rows,A", [(1, 2), (300, 18), (5000, 7)])
+def test_explore_eps_greedy_matches_oracle(aq, rows, A):
+    _say(f"explore_eps_greedy rows={rows} A={A}")
+    net = synth.small_net([synth.fc(8, A, "none")], head="argmax")
+    P = aq.Policy(net)
+    idx = np.random.default_rng(12).integers(0, A, rows).astype(np.int32)
+    for eps in (0.0, 0.05, 0.5, 1.0):
+        for seed, step in ((9, 1), (1 << 40, 1 << 35)):
+            d_i = U.to_dev(idx)
+            P.policy_explore(d_i, seed, step, epsilon=eps)
+            torch.cuda.synchronize()
+            assert np.array_equal(d_i.cpu().numpy(), O.c_explore_eps_greedy(idx, A, eps, seed, step))
+    with pytest.raises(aq.AqError) as e:
+        P.policy_explore(U.to_dev(idx), 1, 1, epsilon=1.5)
+    assert e.value.status == aq.EINVAL
+    P.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "argmax_mlp"])
+def test_forward_then_explore_end_to_end(aq, name):
+    """The actor step: 8-bit forward, then exploration, against the oracle doing the same on its own actions."""
+    _say(f"forward_then_explore {name}")
+    net = _nets()[name]
+    params = synth.make_params(net, nonzero_bias=True)
+    batch = 200
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs)
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    ref = pol.forward_int8(obs)["actions"]
+    d_obs = U.to_dev(obs)
+    sg = np.random.default_rng(13).uniform(0, 0.2, batch).astype(np.float32)
+    if net["head"] == "argmax":
+        act = torch.zeros(batch, dtype=torch.int32, device=U.DEV)
+        P.policy_forward_int8(d_obs, act)
+        P.policy_explore(act, 77, 4, epsilon=0.25)
+        torch.cuda.synchronize()
+        assert np.array_equal(act.cpu().numpy(), O.c_explore_eps_greedy(ref, synth.action_dim(net), 0.25, 77, 4))
+    else:
+        act = torch.zeros(batch, synth.action_dim(net), dtype=torch.float32, device=U.DEV)
+        P.policy_forward_int8(d_obs, act)
+        P.policy_explore(act, 77, 4, sigma=U.to_dev(sg))
+        torch.cuda.synchronize()
+        assert U.close(act.cpu().numpy(), O.c_explore_gaussian(ref, sg, 77, 4)).all()
+    P.close()
+
+
 # ------------------------------------------------------------------ edge cases and error paths
 def test_edges(aq):
     net = synth.net_config("cfg1")
