@@ -125,14 +125,24 @@ __device__ __forceinline__ NarrowMap narrow_map(int NT, int KS, int wave) {
 // sums of each; all reads of one output are independent and issued together.
 template <int MT, int NT, bool ASYM, bool TAPS, bool HALF>
 __device__ __forceinline__ void narrow_reduce(const int32_t* part, const CPtrs& C, const LayerTaps& T, int N, int zw_s,
-                                              int64_t row0, int64_t batch, float* yrow, int ldy, int tid) {
+                                              int64_t row0, int64_t batch, float* yrow, int ldy, int tid, int head,
+                                              float* actions, float* tap_y) {
     constexpr int PAIRS = NT * MT, KSPLIT = FW / PAIRS;
-    const int ln = tid & 63;
+    // a 16-row workgroup enumerates only the lower half of the MFMA tile's rows (the rest is don't-care)
+    constexpr int STEPS = HALF ? PAIRS : 2 * PAIRS;
 #pragma unroll
-    for (int it = 0; it < 2 * PAIRS; ++it) {
-        const int e = tid + it * FT;
-        const int pr = it >> 1;                 // FT = 512 outputs per step, 1024 per pair
-        const int reg = (e >> 6) & 15;
+    for (int it = 0; it < STEPS; ++it) {
+        int pr, reg, ln;
+        if (HALF) {
+            pr = it;
+            reg = (tid >> 5) & 15;
+            ln = (tid & 15) + 32 * ((tid >> 4) & 1);
+        } else {
+            const int e = tid + it * FT;
+            pr = it >> 1;  // FT = 512 outputs per step, 1024 per pair
+            reg = (e >> 6) & 15;
+            ln = tid & 63;
+        }
         int v = 0, rsum = 0;
 #pragma unroll
         for (int kp = 0; kp < KSPLIT; ++kp) {
@@ -146,11 +156,22 @@ __device__ __forceinline__ void narrow_reduce(const int32_t* part, const CPtrs& 
         v += C.bias_fold[n];
         if (ASYM) v -= zw_s * rsum;
         const int64_t row = row0 + m;
-        if (HALF && m >= 16) continue;  // a 16-row workgroup: the upper half of the MFMA tile is don't-care
+        const bool ok = row < batch && n < N;
         if (TAPS) {
-            if (T.acc && row < batch && n < N) T.acc[row * N + n] = v;
+            if (T.acc && ok) T.acc[row * N + n] = v;
         }
-        yrow[m * ldy + n] = (float)v * C.m[n];
+        const float y = (float)v * C.m[n];
+        if (actions) {
+            // elementwise heads leave from here; only argmax needs the whole row in one place
+            if (ok) {
+                if (TAPS) {
+                    if (tap_y) tap_y[row * N + n] = y;
+                }
+                actions[row * N + n] = head == AQ_HEAD_TANH ? tanh_head(y) : y;
+            }
+        } else {
+            yrow[m * ldy + n] = y;
+        }
     }
 }
 
@@ -604,8 +625,16 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         float* yrow = (float*)buf_in;
         ybuf = yrow;
         ldy_h = Np + 1;
-        if (L.NT == 1) narrow_reduce<MT, 1, ASYM, TAPS, HALF>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n);
-        else narrow_reduce<MT, 2, ASYM, TAPS, HALF>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n);
+        const int head_n = uni(an.head);
+        float* direct = head_n != AQ_HEAD_ARGMAX ? (float*)c.actions : nullptr;
+        float* tap_y = TAPS ? t.y : nullptr;
+        if (L.NT == 1)
+            narrow_reduce<MT, 1, ASYM, TAPS, HALF>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n, head_n, direct,
+                                                   tap_y);
+        else
+            narrow_reduce<MT, 2, ASYM, TAPS, HALF>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n, head_n, direct,
+                                                   tap_y);
+        if (direct) return;  // actions are written; nothing below applies
         lds_barrier();
     }
 
