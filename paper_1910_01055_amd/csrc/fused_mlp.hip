@@ -51,41 +51,51 @@ bool make_plan(const FwdArgs& a, Plan* p) {
     // feature tiles per wave: wide layers take 2 (two passes of the 8 waves cover 32 tiles); more would
     // not leave registers for the operand pipeline at two waves per SIMD
     p->nb = (max_nt >= 32 && !a.net.asym) ? 2 : 1;
-    // Up to 4096 rows, 32-row workgroups would leave CUs idle: 16-row workgroups (one tile per wave)
-    // halve the epilogue work per CU instead.
-    p->half = a.c.batch <= 16 * 256;
     auto ln_fits = [&](int nb) {  // LayerNorm needs its whole row resident in one pass
         for (int l = 0; l < a.net.n_layers - 1; ++l)
             if (a.net.L[l].act == AQ_ACT_LN_TANH && (a.net.L[l].NT + nb - 1) / nb > FW) return false;
         return true;
     };
-    if (p->half && ln_fits(1)) p->nb = 1;
-    else p->half = false;
-    if (!ln_fits(p->nb)) return false;
-    // rows per workgroup: enough workgroups to cover the 256 CUs first, more rows per workgroup
-    // (fewer weight re-reads from L2) once the batch is large enough
-    int mt = 1;
-    if (a.c.batch >= 256 * 64) mt = 2;  // (never with 16-row workgroups: those are for small batches)
-    if (a.c.batch >= 512 * 128 && p->nb == 1) mt = 4;
     const bool narrow_last = a.net.L[a.net.n_layers - 1].NT <= NARROW_NT;
-    for (; mt >= 1; mt >>= 1) {
+    const int nb_full = p->nb;
+    // Rows per workgroup: 16 (one tile per wave only), 32, 64 or 128 (the latter with one tile per wave
+    // only).  A workgroup's time grows roughly like 1 + rows/32 (a fixed latency chain plus epilogue work
+    // per row), the 256 CUs take one workgroup each per round: take the cheapest rounds x time.
+    struct Cand {
+        int rows, mt, nb;
+        bool half;
+    };
+    const Cand cands[4] = {{16, 1, 1, true}, {32, 1, nb_full, false}, {64, 2, nb_full, false}, {128, 4, 1, false}};
+    double best = 0.0;
+    bool found = false;
+    for (const Cand& cd : cands) {
+        if (cd.mt == 4 && nb_full != 1) continue;
+        if (!ln_fits(cd.nb)) continue;
+        Plan q = *p;
+        q.mt = cd.mt;
+        q.nb = cd.nb;
+        q.half = cd.half;
         // (a doubled constant area when everything still fits in 64 KB: small networks, where the
         // barrier it saves per layer is a visible share of the time)
-        p->cst_dbl = fused_lds_bytes(32 * mt, p->ld, p->cst_n, true) + PART_BYTES <= 64 * 1024;
-        p->lds = fused_lds_bytes(32 * mt, p->ld, p->cst_n, p->cst_dbl != 0);
-        p->part_off = -1;
+        q.cst_dbl = fused_lds_bytes(32 * cd.mt, q.ld, q.cst_n, true) + PART_BYTES <= 64 * 1024;
+        q.lds = fused_lds_bytes(32 * cd.mt, q.ld, q.cst_n, q.cst_dbl != 0);
+        q.part_off = -1;
         // partial sums of a narrow last layer: in the idle activation buffer if it is large enough,
         // else in an area of their own behind everything else
-        if (narrow_last && (size_t)32 * mt * p->ld < (size_t)PART_BYTES) {
-            p->part_off = (int)p->lds;
-            p->lds += PART_BYTES;
+        if (narrow_last && (size_t)32 * cd.mt * q.ld < (size_t)PART_BYTES) {
+            q.part_off = (int)q.lds;
+            q.lds += PART_BYTES;
         }
-        if (p->lds <= 160 * 1024) {
-            p->mt = mt;
-            return true;
+        if (q.lds > 160 * 1024) continue;
+        const int64_t wgs = (a.c.batch + cd.rows - 1) / cd.rows;
+        const double cost = (double)((wgs + 255) / 256) * (1.0 + cd.rows / 32.0);
+        if (!found || cost < best) {
+            best = cost;
+            found = true;
+            *p = q;
         }
     }
-    return false;
+    return found;
 }
 }  // namespace
 
