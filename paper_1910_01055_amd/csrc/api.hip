@@ -45,6 +45,8 @@ struct aq_policy {
     uint32_t* keys = nullptr;
     NetDev h_net{};            // host copy of the device-resident network description
     NetDev* d_net = nullptr;
+    QTab h_qtab{};             // the quantizer's table of the policy, host copy and device copy
+    QTab* d_qtab = nullptr;
     bool quantized = false;
     size_t layer_bytes = 0;    // the slab's leading part: every layer's packed weights and constants
     uint64_t net_hash = 0;     // of the network description (blob header)
@@ -185,6 +187,7 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     size_t off_mm = take(256);
     size_t off_keys = take(sizeof(uint32_t) * 2 * (AQ_MAX_LAYERS + 1));
     size_t off_net = take(sizeof(NetDev));
+    size_t off_qtab = take(sizeof(QTab));
     if (hipMalloc(&p->slab, bytes) != hipSuccess) {
         delete p;
         return AQ_ENOMEM;
@@ -218,6 +221,7 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     p->mm = (uint32_t*)(base + off_mm);
     p->keys = (uint32_t*)(base + off_keys);
     p->d_net = (NetDev*)(base + off_net);
+    p->d_qtab = (QTab*)(base + off_qtab);
     p->actq = p->d_net->actq;  // device address arithmetic only
     for (int l = 0; l < net->n_layers; ++l) {
         fill_layer_dev(p, l, p->h_net.L[l]);
@@ -228,6 +232,40 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     p->h_net.in_u8 = net->in_type == AQ_IN_U8;
     p->h_net.asym = net->wscheme == AQ_W_TENSOR_ASYM_U8;
     p->h_net.ln_eps = net->ln_eps;
+    {   // the quantizer's table: outputs per layer and each layer's first workgroup in the shared grids
+        QTab& q = p->h_qtab;
+        q.n_layers = net->n_layers;
+        q.asym = p->h_net.asym;
+        q.in_u8 = p->h_net.in_u8;
+        q.qdenom = (float)net->qdenom;
+        int row_blk = 0, cst_blk = 0, rng_blk = 0;
+        for (int l = 0; l < net->n_layers; ++l) {
+            const LayerBuf& b = p->L[l];
+            QLayerTab& t = q.L[l];
+            t.wp = b.wp; t.s_w = b.s_w; t.z_w = b.z_w; t.rowsum = b.rowsum; t.bias_q = b.bias_q; t.M0 = b.M0;
+            t.rshift = b.rshift; t.m = b.m; t.bias_fold = b.bias_fold; t.pack1 = b.pack1; t.rz = b.rz; t.sh = b.sh;
+            t.N = b.N; t.K = b.K; t.KS = b.KS;
+            t.ln = b.d.act == AQ_ACT_LN_TANH;
+            t.requant = l < net->n_layers - 1 && !t.ln;
+            t.row_blk0 = row_blk;
+            t.cst_blk0 = cst_blk;
+            t.rng_blk0 = rng_blk;
+            const int64_t n4 = (int64_t)b.N * b.K / 4 + 1;
+            int64_t rb = (n4 + 255) / 256;
+            t.rng_blks = (int)(rb < 1 ? 1 : (rb > 256 ? 256 : rb));
+            row_blk += (b.N + 3) / 4;
+            cst_blk += (b.N + 255) / 256;
+            rng_blk += t.rng_blks;
+        }
+        q.row_blks = row_blk;
+        q.cst_blks = cst_blk;
+        q.rng_blks_total = rng_blk;
+        if (hipMemcpy(p->d_qtab, &q, sizeof(QTab), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(p->slab);
+            delete p;
+            return AQ_EHIP;
+        }
+    }
     {   // FNV-1a over everything that fixes the blob's layout and meaning
         uint64_t h = 1469598103934665603ull;
         auto mix = [&](int64_t v) {
@@ -415,43 +453,19 @@ extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w,
     for (int l = 0; l < nl; ++l)
         if (!h_d_w[l]) return AQ_EINVAL;
     hipStream_t st = as_stream(stream);
-    const bool asym = p->net.wscheme == AQ_W_TENSOR_ASYM_U8;
-    const float qd = (float)p->net.qdenom;
     RangesArg r{};
+    QPtrs ptrs{};
     for (int l = 0; l < nl; ++l) {
         r.lo[l] = h_ranges[l].lo;
         r.hi[l] = h_ranges[l].hi;
+        ptrs.w[l] = h_d_w[l];
+        ptrs.b[l] = h_d_b ? h_d_b[l] : nullptr;
+        ptrs.gamma[l] = h_d_gamma ? h_d_gamma[l] : nullptr;
+        ptrs.beta[l] = h_d_beta ? h_d_beta[l] : nullptr;
     }
-    aq_status s = launch_fill_u32((uint32_t*)p->status, 1, 0u, st);
+    const aq_status s = launch_quantize_policy(p->d_qtab, p->h_qtab, ptrs, r, p->actq, p->d_net->fast, p->status,
+                                               p->mm, st);
     if (s != AQ_OK) return s;
-    s = launch_act_qparams(r, nl, p->net.in_type == AQ_IN_U8, qd, p->actq, st);
-    if (s != AQ_OK) return s;
-    for (int l = 0; l < nl; ++l) {
-        LayerBuf& b = p->L[l];
-        s = launch_quantize_layer(h_d_w[l], b.N, b.K, b.KS, p->net.wscheme, qd, p->mm, b.wp, b.s_w, b.z_w, b.rowsum,
-                                  p->status, st);
-        if (s != AQ_OK) return s;
-        if (b.d.act == AQ_ACT_LN_TANH) {
-            if (h_d_gamma && h_d_gamma[l]) {
-                AQ_HIP_CHECK(hipMemcpyAsync(b.gamma, h_d_gamma[l], sizeof(float) * b.N, hipMemcpyDeviceToDevice, st));
-            } else {
-                s = launch_fill_u32((uint32_t*)b.gamma, b.N, 0x3f800000u, st);
-                if (s != AQ_OK) return s;
-            }
-            if (h_d_beta && h_d_beta[l]) {
-                AQ_HIP_CHECK(hipMemcpyAsync(b.beta, h_d_beta[l], sizeof(float) * b.N, hipMemcpyDeviceToDevice, st));
-            } else {
-                s = launch_fill_u32((uint32_t*)b.beta, b.N, 0u, st);
-                if (s != AQ_OK) return s;
-            }
-        }
-        const bool requant = l < nl - 1 && b.d.act != AQ_ACT_LN_TANH;
-        s = launch_fill_u32((uint32_t*)b.fast, 1, requant ? 1u : 0u, st);
-        if (s != AQ_OK) return s;
-        s = launch_layer_consts(p->actq, l, requant, asym, b.s_w, b.z_w, h_d_b ? h_d_b[l] : nullptr, b.rowsum, b.N,
-                                b.K, b.m, b.bias_q, b.M0, b.rshift, b.bias_fold, b.pack1, b.rz, b.sh, b.fast, p->status, st);
-        if (s != AQ_OK) return s;
-    }
     p->quantized = true;
     return AQ_OK;
 }

@@ -194,6 +194,43 @@ struct NetDev {
     float ln_eps;
 };
 
+// The quantizer's view of a policy (device-resident, built once per handle): where every layer's
+// outputs go, and where each layer starts in the three grids that cover all layers at once.
+struct QLayerTab {
+    int8_t* wp;
+    float* s_w;
+    int32_t* z_w;
+    int32_t* rowsum;
+    int32_t* bias_q;
+    int32_t* M0;
+    int32_t* rshift;
+    float* m;
+    int32_t* bias_fold;
+    int32_t* pack1;
+    int32_t* rz;  // LayerNorm layers: the gain slot of the constant pack
+    int32_t* sh;  // LayerNorm layers: the offset slot
+    int N, K, KS;
+    int requant;  // hidden layer without LayerNorm
+    int ln;
+    int row_blk0;  // first workgroup of the row-quantize grid (4 output channels per workgroup)
+    int cst_blk0;  // first workgroup of the constants grid (256 channels per workgroup)
+    int rng_blk0;  // first workgroup of the range grid (per-tensor scheme)
+    int rng_blks;
+};
+struct QTab {
+    QLayerTab L[AQ_MAX_LAYERS];
+    int n_layers, asym, in_u8;
+    float qdenom;
+    int row_blks, cst_blks, rng_blks_total;
+};
+// The caller's fp32 parameters of one quantize pass (by value: they change from call to call).
+struct QPtrs {
+    const float* w[AQ_MAX_LAYERS];
+    const float* b[AQ_MAX_LAYERS];
+    const float* gamma[AQ_MAX_LAYERS];
+    const float* beta[AQ_MAX_LAYERS];
+};
+
 // Per-call arguments (small, by value).
 struct CallArgs {
     const void* obs;

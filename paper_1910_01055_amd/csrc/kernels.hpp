@@ -8,14 +8,11 @@ namespace aq {
 aq_status launch_fill_u32(uint32_t* p, int n, uint32_t v, hipStream_t st);
 aq_status launch_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int wscheme, float qdenom,
                                  void* d_codes, float* d_scale, int32_t* d_zp, uint32_t* d_ws, hipStream_t st);
-aq_status launch_quantize_layer(const float* d_w, int N, int K, int KS, int wscheme, float qdenom, uint32_t* d_mm,
-                                int8_t* wp, float* s_w, int32_t* z_w, int32_t* rowsum, int* status, hipStream_t st);
+// The whole policy: activation parameters, weight ranges (per-tensor scheme), packed 8-bit weights and
+// per-channel constants of every layer, in three or four launches.
+aq_status launch_quantize_policy(const QTab* d_tab, const QTab& h_tab, const QPtrs& ptrs, const RangesArg& r,
+                                 ActQ* actq, int* fast, int* status, uint32_t* mm, hipStream_t st);
 aq_status launch_unpack_weights(const int8_t* wp, int N, int K, int KS, int asym, uint8_t* codes, hipStream_t st);
-aq_status launch_act_qparams(const RangesArg& r, int n, int in_u8, float qdenom, ActQ* actq, hipStream_t st);
-aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym, const float* s_w,
-                              const int32_t* z_w, const float* bias, const int32_t* rowsum, int N, int K, float* m,
-                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int32_t* pack1,
-                              int32_t* rz, int32_t* sh, int* fast, int* status, hipStream_t st);
 
 // ---- policy blob (quantize.hip): header words [0..15] = magic, version, hash lo/hi, payload bytes lo/hi, 0...
 aq_status launch_blob_header_write(uint32_t* d_hdr, const uint32_t* h_words, hipStream_t st);

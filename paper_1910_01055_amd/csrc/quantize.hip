@@ -33,13 +33,13 @@ __device__ __forceinline__ void asym_qparams(float hi, float nlo, float qdenom, 
 // patterns order like unsigned integers, so the grid-wide reduction is one atomicMax each.
 // mm[0] = hi bits, mm[1] = nlo bits, mm[2] = status flag; mm must be zero before the launch.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_range_nonneg(const float4* __restrict__ w4, int64_t n4,
-                                                      const float* __restrict__ w, int64_t n,
-                                                      uint32_t* __restrict__ mm) {
+__device__ __forceinline__ void range_nonneg_block(const float4* __restrict__ w4, int64_t n4,
+                                                   const float* __restrict__ w, int64_t n,
+                                                   uint32_t* __restrict__ mm, int blk, int nblk) {
     float hi = 0.0f, nlo = 0.0f;
     int bad = 0;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    const int64_t stride = (int64_t)nblk * blockDim.x;
+    for (int64_t i = (int64_t)blk * blockDim.x + threadIdx.x; i < n4; i += stride) {
         float4 v = w4[i];
         float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void k_range_nonneg(const float4* __restrict__
         }
     }
     // scalar tail (tensor length not a multiple of 4)
-    for (int64_t i = n4 * 4 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    for (int64_t i = n4 * 4 + (int64_t)blk * blockDim.x + threadIdx.x; i < n; i += stride) {
         float e = w[i];
         bad |= !finite_f(e);
         hi = e > hi ? e : hi;
@@ -294,13 +294,12 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_long(const float4* __res
 // fold the activation zero-point into the integer bias).
 // ---------------------------------------------------------------------------------------------
 template <bool SYM>
-__global__ __launch_bounds__(256) void k_quant_rows_packed(const float* __restrict__ w, int N, int K, int KS,
-                                                           float qdenom, const uint32_t* __restrict__ mm,
-                                                           int8_t* __restrict__ wp, float* __restrict__ s_w,
-                                                           int32_t* __restrict__ z_w, int32_t* __restrict__ rowsum,
-                                                           int* __restrict__ status) {
+__device__ __forceinline__ void quant_row_packed(const float* __restrict__ w, int n, int N, int K, int KS,
+                                                 float qdenom, const uint32_t* __restrict__ mm,
+                                                 int8_t* __restrict__ wp, float* __restrict__ s_w,
+                                                 int32_t* __restrict__ z_w, int32_t* __restrict__ rowsum,
+                                                 int* __restrict__ status) {
     const int lane = threadIdx.x & 63;
-    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (n >= N) return;
     const float* src = w + (int64_t)n * K;
     float s;
@@ -352,10 +351,18 @@ __global__ void k_unpack_weights(const int8_t* __restrict__ wp, int N, int K, in
 // activation (scale, zero-point) from the supplied ranges: the same formula as for weights,
 // the range being extended to contain zero.
 // ---------------------------------------------------------------------------------------------
-__global__ void k_act_qparams(RangesArg r, int n, int in_u8, float qdenom, ActQ* __restrict__ actq) {
-    int i = threadIdx.x;
-    if (i >= n) return;
-    if (i == 0 && in_u8) {
+// One small launch opens a quantize pass: it also clears the status word and the per-layer range
+// words, and presets the short-form flags (1 for requantized layers; a channel that does not
+// qualify clears its layer's flag later).
+__global__ void k_qp_prep(const QTab* __restrict__ tab, RangesArg r, ActQ* __restrict__ actq, int* __restrict__ fast,
+                          int* __restrict__ status, uint32_t* __restrict__ mm) {
+    const int i = threadIdx.x;
+    const int nl = tab->n_layers;
+    if (i == 63) *status = 0;
+    if (i < 4 * AQ_MAX_LAYERS) mm[i] = 0u;
+    if (i >= 32 && i < 32 + nl) fast[i - 32] = tab->L[i - 32].requant;
+    if (i >= nl) return;
+    if (i == 0 && tab->in_u8) {
         actq[0].s = 1.0f;
         actq[0].z = 0;
         return;
@@ -364,7 +371,7 @@ __global__ void k_act_qparams(RangesArg r, int n, int in_u8, float qdenom, ActQ*
     float nlo = -r.lo[i] > 0.0f ? -r.lo[i] : 0.0f;
     float s;
     int z;
-    asym_qparams(hi, nlo, qdenom, s, z);
+    asym_qparams(hi, nlo, tab->qdenom, s, z);
     actq[i].s = s;
     actq[i].z = z;
 }
@@ -380,15 +387,14 @@ __global__ void k_act_qparams(RangesArg r, int n, int in_u8, float qdenom, ActQ*
 //   z_w' = z_w - 128 (symmetric codes: w_s = w, z_w' = 0).  The "- z_w' sum_k a_s" term depends on
 //   the batch row and is applied inside the forward kernel.
 // ---------------------------------------------------------------------------------------------
-__global__ void k_layer_consts(const ActQ* __restrict__ actq, int layer, int requant, int asym,
-                               const float* __restrict__ s_w, const int32_t* __restrict__ z_w,
-                               const float* __restrict__ bias, const int32_t* __restrict__ rowsum, int N, int K,
-                               float* __restrict__ m, int32_t* __restrict__ bias_q, int32_t* __restrict__ M0,
-                               int32_t* __restrict__ rshift, int32_t* __restrict__ bias_fold,
-                               int32_t* __restrict__ pack1, int32_t* __restrict__ rz, int32_t* __restrict__ sh, int* __restrict__ fast,
-                               int* __restrict__ status) {
-    int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= N) return;
+__device__ __forceinline__ void layer_consts_channel(const ActQ* __restrict__ actq, int layer, int requant, int asym,
+                                                     const float* __restrict__ s_w, const int32_t* __restrict__ z_w,
+                                                     const float* __restrict__ bias, const int32_t* __restrict__ rowsum,
+                                                     int n, int K, float* __restrict__ m, int32_t* __restrict__ bias_q,
+                                                     int32_t* __restrict__ M0, int32_t* __restrict__ rshift,
+                                                     int32_t* __restrict__ bias_fold, int32_t* __restrict__ pack1,
+                                                     int32_t* __restrict__ rz, int32_t* __restrict__ sh,
+                                                     int* __restrict__ fast, int* __restrict__ status) {
     const float s_in = actq[layer].s;
     const int z_a = actq[layer].z;
     m[n] = s_in * s_w[n];
@@ -436,6 +442,50 @@ __global__ void k_layer_consts(const ActQ* __restrict__ actq, int layer, int req
     const int za_s = z_a - 128;
     const int zw_s = asym ? z_w[n] - 128 : 0;
     bias_fold[n] = bqi - za_s * rowsum[n] + K * za_s * zw_s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The whole policy in three or four launches: each grid covers every layer, a workgroup finds its
+// layer from the table's first-workgroup indices (at most 8 compares).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int layer_of_block(const QTab& t, int blk, int which) {
+    int l = t.n_layers - 1;
+    while (l > 0 && blk < (which == 0 ? t.L[l].row_blk0 : which == 1 ? t.L[l].cst_blk0 : t.L[l].rng_blk0)) --l;
+    return l;
+}
+
+__global__ __launch_bounds__(256) void k_qp_ranges(const QTab* __restrict__ tab, const QPtrs p, uint32_t* __restrict__ mm) {
+    const QTab& t = *tab;
+    const int l = layer_of_block(t, blockIdx.x, 2);
+    const QLayerTab& L = t.L[l];
+    const int64_t n = (int64_t)L.N * L.K;
+    range_nonneg_block((const float4*)p.w[l], n / 4, p.w[l], n, mm + 4 * l, blockIdx.x - L.rng_blk0, L.rng_blks);
+}
+
+template <bool SYM>
+__global__ __launch_bounds__(256) void k_qp_rows(const QTab* __restrict__ tab, const QPtrs p,
+                                                 const uint32_t* __restrict__ mm, int* __restrict__ status) {
+    const QTab& t = *tab;
+    const int l = layer_of_block(t, blockIdx.x, 0);
+    const QLayerTab& L = t.L[l];
+    const int n = (blockIdx.x - L.row_blk0) * 4 + (threadIdx.x >> 6);
+    quant_row_packed<SYM>(p.w[l], n, L.N, L.K, L.KS, t.qdenom, mm + 4 * l, L.wp, L.s_w, L.z_w, L.rowsum, status);
+}
+
+__global__ __launch_bounds__(256) void k_qp_consts(const QTab* __restrict__ tab, const QPtrs p,
+                                                   const ActQ* __restrict__ actq, int* __restrict__ fast,
+                                                   int* __restrict__ status) {
+    const QTab& t = *tab;
+    const int l = layer_of_block(t, blockIdx.x, 1);
+    const QLayerTab& L = t.L[l];
+    const int n = (blockIdx.x - L.cst_blk0) * 256 + threadIdx.x;
+    if (n >= L.N) return;
+    layer_consts_channel(actq, l, L.requant, t.asym, L.s_w, L.z_w, p.b[l], L.rowsum, n, L.K, L.m, L.bias_q, L.M0,
+                         L.rshift, L.bias_fold, L.pack1, L.rz, L.sh, fast + l, status);
+    if (L.ln) {  // LayerNorm gain and offset (defaults 1 and 0) into their slots of the constant pack
+        L.rz[n] = __float_as_int(p.gamma[l] ? p.gamma[l][n] : 1.0f);
+        L.sh[n] = __float_as_int(p.beta[l] ? p.beta[l][n] : 0.0f);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -518,26 +568,6 @@ aq_status launch_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, i
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
-aq_status launch_quantize_layer(const float* d_w, int N, int K, int KS, int wscheme, float qdenom, uint32_t* d_mm,
-                                int8_t* wp, float* s_w, int32_t* z_w, int32_t* rowsum, int* status,
-                                hipStream_t st) {
-    const int g = (N + 3) / 4;
-    if (wscheme == AQ_W_TENSOR_ASYM_U8) {
-        const int64_t n = (int64_t)N * K;
-        // weights of a policy layer are small; the vector path needs 16-byte alignment only
-        const int64_t n4 = n / 4;
-        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, d_mm, 4, 0u);
-        hipLaunchKernelGGL(k_range_nonneg, dim3(grid_for(n4 + 1, 256, 1024)), dim3(256), 0, st, (const float4*)d_w,
-                           n4, d_w, n, d_mm);
-        hipLaunchKernelGGL(k_quant_rows_packed<false>, dim3(g), dim3(256), 0, st, d_w, N, K, KS, qdenom, d_mm, wp,
-                           s_w, z_w, rowsum, status);
-    } else {
-        hipLaunchKernelGGL(k_quant_rows_packed<true>, dim3(g), dim3(256), 0, st, d_w, N, K, KS, qdenom, d_mm, wp,
-                           s_w, z_w, rowsum, status);
-    }
-    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
-}
-
 aq_status launch_unpack_weights(const int8_t* wp, int N, int K, int KS, int asym, uint8_t* codes, hipStream_t st) {
     const int64_t n = (int64_t)N * K;
     hipLaunchKernelGGL(k_unpack_weights, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, wp, N, K, KS, asym,
@@ -545,17 +575,16 @@ aq_status launch_unpack_weights(const int8_t* wp, int N, int K, int KS, int asym
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
-aq_status launch_act_qparams(const RangesArg& r, int n, int in_u8, float qdenom, ActQ* actq, hipStream_t st) {
-    hipLaunchKernelGGL(k_act_qparams, dim3(1), dim3(64), 0, st, r, n, in_u8, qdenom, actq);
-    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
-}
-
-aq_status launch_layer_consts(const ActQ* actq, int layer, int requant, int asym, const float* s_w,
-                              const int32_t* z_w, const float* bias, const int32_t* rowsum, int N, int K, float* m,
-                              int32_t* bias_q, int32_t* M0, int32_t* rshift, int32_t* bias_fold, int32_t* pack1,
-                              int32_t* rz, int32_t* sh, int* fast, int* status, hipStream_t st) {
-    hipLaunchKernelGGL(k_layer_consts, dim3((N + 255) / 256), dim3(256), 0, st, actq, layer, requant, asym, s_w, z_w,
-                       bias, rowsum, N, K, m, bias_q, M0, rshift, bias_fold, pack1, rz, sh, fast, status);
+aq_status launch_quantize_policy(const QTab* d_tab, const QTab& h_tab, const QPtrs& ptrs, const RangesArg& r,
+                                 ActQ* actq, int* fast, int* status, uint32_t* mm, hipStream_t st) {
+    hipLaunchKernelGGL(k_qp_prep, dim3(1), dim3(64), 0, st, d_tab, r, actq, fast, status, mm);
+    if (h_tab.asym) {
+        hipLaunchKernelGGL(k_qp_ranges, dim3(h_tab.rng_blks_total), dim3(256), 0, st, d_tab, ptrs, mm);
+        hipLaunchKernelGGL(k_qp_rows<false>, dim3(h_tab.row_blks), dim3(256), 0, st, d_tab, ptrs, mm, status);
+    } else {
+        hipLaunchKernelGGL(k_qp_rows<true>, dim3(h_tab.row_blks), dim3(256), 0, st, d_tab, ptrs, mm, status);
+    }
+    hipLaunchKernelGGL(k_qp_consts, dim3(h_tab.cst_blks), dim3(256), 0, st, d_tab, ptrs, actq, fast, status);
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
