@@ -30,7 +30,6 @@ struct LayerBuf {
     int32_t* sh;
     float* gamma;
     float* beta;
-    int* fast;  // points into the device-resident NetDev
 };
 
 }  // namespace
@@ -225,7 +224,6 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     p->actq = p->d_net->actq;  // device address arithmetic only
     for (int l = 0; l < net->n_layers; ++l) {
         fill_layer_dev(p, l, p->h_net.L[l]);
-        p->L[l].fast = &p->d_net->fast[l];
     }
     p->h_net.n_layers = net->n_layers;
     p->h_net.head = net->head;

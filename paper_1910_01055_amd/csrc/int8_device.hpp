@@ -215,14 +215,6 @@ __device__ __forceinline__ void mma_run(gv4i_ptr (&wptr)[NB], v4i (&wreg)[PF][NB
     }
 }
 
-template <int MT, int NB, bool ASYM, int PF>
-__device__ __forceinline__ void mma_block(gv4i_ptr (&wptr)[NB], const int8_t* xs, int ld, int ks_begin,
-                                          int ks_end, int ks_lds0, v16i (&acc)[NB][MT], v16i (&rs)[MT], int lane) {
-    v4i wreg[PF][NB];
-    mma_prefetch<NB, PF>(wptr, ks_begin, ks_end, wreg);
-    mma_run<MT, NB, ASYM, PF>(wptr, wreg, xs, ld, ks_begin, ks_end, ks_lds0, acc, rs, lane);
-}
-
 // where an epilogue reads the per-channel constants from (global memory or a copy staged in LDS)
 struct CPtrs {
     const int32_t* bias_fold;
@@ -257,59 +249,6 @@ __device__ __forceinline__ void quad_acc(const int N, const LayerTaps& T, const 
         if (ASYM) val[i] -= zw_s * rs0;
         if (TAPS) {
             if (T.acc && row_ok && n0 + i < N) T.acc[(int64_t)row * N + n0 + i] = val[i];
-        }
-    }
-}
-
-// Hidden layer: requantize (+ReLU through the clamp) one 32x32 tile and store the codes, signed
-// domain, four per 32-bit word (packed) or bytewise, for features below n_store.
-// FAST: every channel has 33 <= r <= 54, so (acc*M0 + 2^(r-1)) >> r + z_out collapses to
-// (mulhi(acc, M0) + rz) >> sh with rz = 2^(r-33) + (z_out << sh), sh = r - 32 (same integers).
-template <bool ASYM, bool TAPS, bool FAST>
-__device__ __forceinline__ void epi_hidden_tile(const int N, const LayerTaps& T, const CPtrs& C, const v16i& c,
-                                                int rs0, int zw_s, int nt, int g, int64_t row, bool row_ok, int z_out,
-                                                int lo, int8_t* out_row, bool packed, int n_store) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int n0 = nt * 32 + 8 * j + 4 * g;
-        int val[4];
-        quad_acc<ASYM, TAPS>(N, T, C, c, j, n0, rs0, zw_s, row, row_ok, val);
-        const int4 M = *(const int4*)(C.M0 + n0);
-        const int Mv[4] = {M.x, M.y, M.z, M.w};
-        int code[4];
-        if (FAST) {
-            const int4 Z = *(const int4*)(C.rz + n0);
-            const int4 S = *(const int4*)(C.sh + n0);
-            const int Zv[4] = {Z.x, Z.y, Z.z, Z.w}, Sv[4] = {S.x, S.y, S.z, S.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int t = (__mulhi(val[i], Mv[i]) + Zv[i]) >> Sv[i];
-                code[i] = min(max(t, lo), 255);
-            }
-        } else {
-            const int4 R = *(const int4*)(C.rshift + n0);
-            const int Rv[4] = {R.x, R.y, R.z, R.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) code[i] = requant_code(val[i], Mv[i], Rv[i], z_out, lo);
-        }
-        uint32_t pack = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (n0 + i >= N) code[i] = 128;  // padding features are zero in the signed domain
-            if (TAPS) {
-                if (T.act && row_ok && n0 + i < N) T.act[(int64_t)row * N + n0 + i] = (uint8_t)code[i];
-            }
-            pack |= (uint32_t)code[i] << (8 * i);
-        }
-        pack ^= 0x80808080u;
-        if (out_row) {
-            if (packed) {
-                if (n0 < n_store) *(uint32_t*)(out_row + n0) = pack;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (n0 + i < n_store) out_row[n0 + i] = (int8_t)(pack >> (8 * i));
-            }
         }
     }
 }
@@ -353,6 +292,8 @@ __device__ __forceinline__ QuadConsts load_quad_consts(const CPtrs& C, int n0) {
     }
     return q;
 }
+// FAST: every channel has 33 <= r <= 54, so (acc*M0 + 2^(r-1)) >> r + z_out collapses to
+// (mulhi(acc, M0) + rz) >> sh with rz = 2^(r-33) + (z_out << sh), sh = r - 32 (same integers).
 // HALF: the tiles were folded by fold_rows16 (two quads per tile, `hh` = this lane's half).
 template <int MT, int NB, bool ASYM, bool TAPS, bool FAST, bool HALF = false>
 __device__ __forceinline__ void epi_hidden_wave(const int N, const int NT, const LayerTaps& T, const CPtrs& C,
