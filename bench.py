@@ -312,9 +312,8 @@ def main():
         ctr = [0]
 
         def actor_step():
-            P.policy_forward_int8(d_obs, act)
             ctr[0] += 1
-            P.policy_explore(act, 2024, ctr[0], sigma=sg)
+            P.policy_step_int8(d_obs, act, 2024, ctr[0], sigma=sg)
         ms_step = _graph_ms(torch, actor_step, 100)
         extra.append({"workload": "cfg2 batch 4096 forward + exploration noise", "us_per_step": ms_step * 1e3,
                       "inferences_per_s": batch / (ms_step * 1e-3)})

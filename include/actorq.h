@@ -166,6 +166,13 @@ typedef struct {
 } aq_explore;
 aq_status aq_policy_explore(const aq_policy* p, void* d_actions, int64_t batch, const aq_explore* ex, void* stream);
 
+/* One actor step: aq_policy_forward_int8 followed by aq_policy_explore with the same arguments (ex may
+ * be NULL: no exploration).  The Gaussian noise is added inside the forward kernel where that kernel
+ * writes the actions itself (fused plan, tanh / linear head, at most 64 actions); otherwise the
+ * exploration runs as a second launch on the same stream.  Same results either way. */
+aq_status aq_policy_step_int8(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                              const aq_explore* ex, const aq_taps* taps_or_null, void* stream);
+
 /* Sec. 3.2 applied to one tensor, for the learner-to-actor broadcast: quantizes fp32
  * d_w[rows][cols] to 8-bit codes in canonical row-major order.
  *   AQ_W_TENSOR_ASYM_U8: one (scale, zero-point) for the whole tensor -> d_scale[1], d_zp[1], uint8 codes.

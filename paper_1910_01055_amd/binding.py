@@ -23,7 +23,7 @@ INTYPE = {"f32": 0, "u8": 1}
 EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_policy_set_path", "aq_policy_status",
            "aq_quantize_tensor", "aq_quantize_params", "aq_policy_export_layer", "aq_policy_export_act_qparams",
            "aq_policy_forward_int8", "aq_policy_forward_fp32", "aq_status_string",
-           "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore"]
+           "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore", "aq_policy_step_int8"]
 
 
 class AqLayer(C.Structure):
@@ -87,6 +87,7 @@ def load():
     lib.aq_policy_export_blob.argtypes = [vp, vp, C.c_uint64, vp]
     lib.aq_policy_import_blob.argtypes = [vp, vp, C.c_uint64, vp]
     lib.aq_policy_explore.argtypes = [vp, vp, i64, C.POINTER(AqExplore), vp]
+    lib.aq_policy_step_int8.argtypes = [vp, vp, i64, vp, C.POINTER(AqExplore), C.POINTER(AqTaps), vp]
     for name in EXPORTS:
         if name != "aq_status_string":
             getattr(lib, name).restype = C.c_int
@@ -162,6 +163,12 @@ class Policy:
 
     def policy_status(self):
         return load().aq_policy_status(self._h, _stream())
+
+    def policy_step_int8(self, obs, actions, seed, step, sigma=None, epsilon=0.0):
+        """8-bit forward plus exploration in one call (fused into the forward kernel where possible)."""
+        ex = AqExplore(int(seed), int(step), 0 if sigma is None else sigma.data_ptr(), float(epsilon))
+        _check(load().aq_policy_step_int8(self._h, _ptr(obs), int(obs.shape[0]), _ptr(actions), C.byref(ex), None,
+                                          _stream()), "aq_policy_step_int8")
 
     def policy_explore(self, actions, seed, step, sigma=None, epsilon=0.0):
         """In place on the actions of a forward: Gaussian noise with per-row sigma (device fp32 [batch]) for

@@ -418,12 +418,19 @@ extern "C" aq_status aq_policy_import_blob(aq_policy* p, const void* d_blob, uin
     return AQ_OK;
 }
 
-extern "C" aq_status aq_policy_explore(const aq_policy* p, void* d_actions, int64_t batch, const aq_explore* ex,
-                                       void* stream) {
-    if (!p || !d_actions || !ex || batch < 0 || batch > 0xffffffffLL) return AQ_EINVAL;
+static aq_status explore_args_ok(const aq_policy* p, const aq_explore* ex, int64_t batch) {
+    if (batch > 0xffffffffLL) return AQ_EINVAL;
     const bool discrete = p->net.head == AQ_HEAD_ARGMAX;
     if (!discrete && !ex->d_sigma) return AQ_EINVAL;
     if (discrete && !(ex->epsilon >= 0.0f && ex->epsilon <= 1.0f)) return AQ_EINVAL;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_explore(const aq_policy* p, void* d_actions, int64_t batch, const aq_explore* ex,
+                                       void* stream) {
+    if (!p || !d_actions || !ex || batch < 0) return AQ_EINVAL;
+    const aq_status es = explore_args_ok(p, ex, batch);
+    if (es != AQ_OK) return es;
     if (batch == 0) return AQ_OK;
     const int A = p->L.back().N * p->L.back().oh * p->L.back().ow;
     return launch_explore(d_actions, batch, A, p->net.head, ex->d_sigma, ex->epsilon, ex->seed, ex->step,
@@ -506,9 +513,13 @@ extern "C" aq_status aq_policy_export_act_qparams(const aq_policy* p, float* d_s
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
-extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
-                                            const aq_taps* taps, void* stream) {
+static aq_status forward_int8_impl(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                   const aq_taps* taps, const aq_explore* ex, void* stream) {
     if (!p || batch < 0) return AQ_EINVAL;
+    if (ex) {
+        const aq_status es = explore_args_ok(p, ex, batch);
+        if (es != AQ_OK) return es;
+    }
     if (!p->quantized) return AQ_ENOTQUANT;
     if (batch == 0) return AQ_OK;
     if (!d_obs || !d_actions) return AQ_EINVAL;
@@ -540,7 +551,22 @@ extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int
     if (p->path == 1 && !can_fuse) return AQ_ESHAPE;
     // an MLP that fits the fused kernel always runs fused: measured faster than one launch per layer at
     // every batch size (activations stay in LDS, one launch)
-    if (can_fuse && p->path != 2) return launch_fused_mlp(a, st);
+    const int A = p->L.back().N * p->L.back().oh * p->L.back().ow;
+    if (can_fuse && p->path != 2) {
+        // Gaussian noise rides in the kernel where it writes the actions itself (an elementwise head on
+        // a narrow last layer); every other case takes the separate exploration launch below
+        const bool fuse_ex = ex && p->net.head != AQ_HEAD_ARGMAX && p->L.back().NT <= 2;
+        if (fuse_ex) {
+            a.c.ex_sigma = ex->d_sigma;
+            a.c.ex_k0 = (uint32_t)ex->seed;
+            a.c.ex_k1 = (uint32_t)(ex->seed >> 32);
+            a.c.ex_s0 = (uint32_t)ex->step;
+            a.c.ex_s1 = (uint32_t)(ex->step >> 32);
+        }
+        const aq_status fs = launch_fused_mlp(a, st);
+        if (fs != AQ_OK || !ex || fuse_ex) return fs;
+        return launch_explore(d_actions, batch, A, p->net.head, ex->d_sigma, ex->epsilon, ex->seed, ex->step, st);
+    }
 
     // one launch per layer
     aq_status s = ensure_i8(p, batch);
@@ -574,7 +600,18 @@ extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int
             if (s != AQ_OK) return s;
         }
     }
+    if (ex) return launch_explore(d_actions, batch, A, p->net.head, ex->d_sigma, ex->epsilon, ex->seed, ex->step, st);
     return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                            const aq_taps* taps, void* stream) {
+    return forward_int8_impl(p, d_obs, batch, d_actions, taps, nullptr, stream);
+}
+
+extern "C" aq_status aq_policy_step_int8(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                         const aq_explore* ex, const aq_taps* taps, void* stream) {
+    return forward_int8_impl(p, d_obs, batch, d_actions, taps, ex, stream);
 }
 
 extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,

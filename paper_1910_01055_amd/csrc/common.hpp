@@ -249,6 +249,9 @@ struct CallArgs {
     int narrow0;   // fused kernel: the first layer is also the last and narrow (its weights are split over K)
     int part_off;  // fused kernel: LDS offset of the partial-sum area of a narrow last layer, or -1 when it
                    // fits the idle activation buffer
+    // fused kernel: Gaussian exploration noise added where the actions are written (ex_sigma != NULL)
+    const float* ex_sigma;
+    uint32_t ex_k0, ex_k1, ex_s0, ex_s1;
 };
 
 // Optional intermediate outputs (by value, only read by the kernels compiled with TAPS).

@@ -3,41 +3,12 @@
 // Random numbers: the counter-based generator Philox4x32-10 (Salmon, Moraes, Dror, Shaw, "Parallel
 // random numbers: as easy as 1, 2, 3", SC'11), key = the caller's seed, counter = (batch row, block,
 // step low word, step high word): every (row, step) has its own stream, nothing is stored.
+#include "explore_device.hpp"
 #include "kernels.hpp"
 
 namespace aq {
 
 namespace {
-struct U4 {
-    uint32_t x, y, z, w;
-};
-
-// ten rounds; the key advances by the Weyl constants before every round but the first
-__device__ __forceinline__ U4 philox4x32_10(U4 c, uint32_t k0, uint32_t k1) {
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        if (r > 0) {
-            k0 += 0x9E3779B9u;
-            k1 += 0xBB67AE85u;
-        }
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
-        c = U4{hi1 ^ c.y ^ k0, lo1, hi0 ^ c.w ^ k1, lo0};
-    }
-    return c;
-}
-
-// Box-Muller on 24-bit uniforms: u1 in (0, 1], u2 in [0, 1)
-__device__ __forceinline__ void box_muller(uint32_t a, uint32_t b, float& z_cos, float& z_sin) {
-    const float u1 = (float)((a >> 8) + 1u) * 5.9604644775390625e-8f;
-    const float u2 = (float)(b >> 8) * 5.9604644775390625e-8f;
-    const float rad = sqrtf(-2.0f * logf(u1));
-    float sn, cs;
-    sincosf(6.283185307179586f * u2, &sn, &cs);
-    z_cos = rad * cs;
-    z_sin = rad * sn;
-}
-
 // one thread per (row, block of four features)
 __global__ __launch_bounds__(256) void k_explore_gaussian(float* __restrict__ actions, int64_t rows, int A, int blocks,
                                                           const float* __restrict__ sigma, uint32_t k0, uint32_t k1,

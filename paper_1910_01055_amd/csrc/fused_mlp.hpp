@@ -10,6 +10,7 @@
 //   - epilogues: requantize(+ReLU) / LayerNorm+tanh+requantize in registers, last layer dequantize,
 //     then a coalesced head pass (tanh / identity / argmax)
 #pragma once
+#include "explore_device.hpp"
 #include "int8_device.hpp"
 
 namespace aq {
@@ -126,7 +127,7 @@ __device__ __forceinline__ NarrowMap narrow_map(int NT, int KS, int wave) {
 template <int MT, int NT, bool ASYM, bool TAPS, bool HALF>
 __device__ __forceinline__ void narrow_reduce(const int32_t* part, const CPtrs& C, const LayerTaps& T, int N, int zw_s,
                                               int64_t row0, int64_t batch, float* yrow, int ldy, int tid, int head,
-                                              float* actions, float* tap_y) {
+                                              float* actions, float* tap_y, const CallArgs& c) {
     constexpr int PAIRS = NT * MT, KSPLIT = FW / PAIRS;
     // a 16-row workgroup enumerates only the lower half of the MFMA tile's rows (the rest is don't-care)
     constexpr int STEPS = HALF ? PAIRS : 2 * PAIRS;
@@ -167,7 +168,10 @@ __device__ __forceinline__ void narrow_reduce(const int32_t* part, const CPtrs& 
                 if (TAPS) {
                     if (tap_y) tap_y[row * N + n] = y;
                 }
-                actions[row * N + n] = head == AQ_HEAD_TANH ? tanh_head(y) : y;
+                float act = head == AQ_HEAD_TANH ? tanh_head(y) : y;
+                if (c.ex_sigma)  // exploration noise of Sec. 4.1, sigma per actor (= per batch row)
+                    act = act + c.ex_sigma[row] * gaussian_draw((uint32_t)row, n, c.ex_k0, c.ex_k1, c.ex_s0, c.ex_s1);
+                actions[row * N + n] = act;
             }
         } else {
             yrow[m * ldy + n] = y;
@@ -630,10 +634,10 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         float* tap_y = TAPS ? t.y : nullptr;
         if (L.NT == 1)
             narrow_reduce<MT, 1, ASYM, TAPS, HALF>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n, head_n, direct,
-                                                   tap_y);
+                                                   tap_y, c);
         else
             narrow_reduce<MT, 2, ASYM, TAPS, HALF>(part, C, T, L.N, zw_s, row0, c.batch, yrow, ldy_h, tid_n, head_n, direct,
-                                                   tap_y);
+                                                   tap_y, c);
         if (direct) return;  // actions are written; nothing below applies
         lds_barrier();
     }

@@ -402,6 +402,46 @@ def test_forward_then_explore_end_to_end(aq, name):
     P.close()
 
 
+@pytest.mark.parametrize("name,path", [("cfg1", 0), ("cfg1", 2), ("single_narrow", 0), ("wide_last", 0), ("long_k_narrow", 0),
+                                       ("argmax_mlp", 0), ("two_tile_last_asym", 2), ("conv_odd", 0)])
+@pytest.mark.parametrize("batch", [5, 300])
+def test_actor_step_entry_point(aq, name, path, batch):
+    """aq_policy_step_int8 (noise added inside the forward kernel where that kernel writes the actions, a
+    second launch otherwise) equals forward followed by explore, and both equal the oracle's step."""
+    _say(f"actor_step {name} path={path} batch={batch}")
+    net = _nets()[name]
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs)
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    P.policy_set_path(path)
+    ref = pol.forward_int8(obs)["actions"]
+    d_obs = U.to_dev(obs)
+    A = synth.action_dim(net)
+    sg = np.random.default_rng(14).uniform(0, 0.2, batch).astype(np.float32)
+    seed, step = 0xABCDEF0123, (1 << 33) + 9
+    if net["head"] == "argmax":
+        a1 = torch.zeros(batch, dtype=torch.int32, device=U.DEV)
+        a2 = torch.zeros_like(a1)
+        P.policy_step_int8(d_obs, a1, seed, step, epsilon=0.3)
+        P.policy_forward_int8(d_obs, a2)
+        P.policy_explore(a2, seed, step, epsilon=0.3)
+        torch.cuda.synchronize()
+        assert torch.equal(a1, a2)
+        assert np.array_equal(a1.cpu().numpy(), O.c_explore_eps_greedy(ref, A, 0.3, seed, step))
+    else:
+        a1 = torch.zeros(batch, A, dtype=torch.float32, device=U.DEV)
+        a2 = torch.zeros_like(a1)
+        d_sg = U.to_dev(sg)
+        P.policy_step_int8(d_obs, a1, seed, step, sigma=d_sg)
+        P.policy_forward_int8(d_obs, a2)
+        P.policy_explore(a2, seed, step, sigma=d_sg)
+        torch.cuda.synchronize()
+        assert torch.equal(a1, a2)                      # the same arithmetic on both routes
+        assert U.close(a1.cpu().numpy(), O.c_explore_gaussian(ref, sg, seed, step)).all()
+    P.close()
+
+
 # ------------------------------------------------------------------ edge cases and error paths
 def test_edges(aq):
     net = synth.net_config("cfg1")
