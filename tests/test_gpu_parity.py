@@ -442,6 +442,67 @@ def test_actor_step_entry_point(aq, name, path, batch):
     P.close()
 
 
+# ------------------------------------------------------------------ HIP graph capture
+@pytest.mark.parametrize("name", ["cfg2", "cfg1", "conv_small"])
+def test_graph_replays_match_eager(aq, name):
+    """The benchmark replays the library's launches from a HIP graph: quantize, forward, actor step and the
+    blob hand-off are captured once and replayed several times, with eager work and synchronizations in
+    between; every replay must reproduce the eager results bit for bit."""
+    _say(f"graph_replays {name}")
+    net = _nets()[name]
+    params = synth.make_params(net, nonzero_bias=True)
+    batch = 260
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs)
+    P, d = U.gpu_quantize(aq, net, params, ranges)
+    Q = aq.Policy(net)
+    A = synth.action_dim(net)
+    argmax = net["head"] == "argmax"
+    shape, dt = ((batch,), torch.int32) if argmax else ((batch, A), torch.float32)
+    d_obs = U.to_dev(obs)
+    sg = U.to_dev(np.random.default_rng(15).uniform(0, 0.2, batch).astype(np.float32))
+    blob = torch.zeros(P.policy_blob_size(), dtype=torch.uint8, device=U.DEV)
+    out = {k: torch.zeros(shape, dtype=dt, device=U.DEV) for k in ("fwd", "step", "imported")}
+
+    def body():
+        P.quantize_params(d[0], d[1], d[2], d[3], ranges)
+        P.policy_forward_int8(d_obs, out["fwd"])
+        P.policy_step_int8(d_obs, out["step"], 31, 7, sigma=None if argmax else sg, epsilon=0.2)
+        P.policy_export_blob(blob)
+        Q.policy_import_blob(blob)
+        Q.policy_forward_int8(d_obs, out["imported"])
+
+    P.policy_reserve(batch)
+    Q.policy_reserve(batch)
+    body()
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in out.items()}
+    assert torch.equal(eager["fwd"], eager["imported"])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        body()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        body()
+    for rep in range(4):
+        for v in out.values():
+            v.zero_()
+        # eager work of the program's own between the replays
+        scratch = torch.zeros(shape, dtype=dt, device=U.DEV)
+        P.policy_forward_int8(d_obs, scratch)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for k in out:
+            assert torch.equal(out[k], eager[k]), f"replay {rep}: {k}"
+        assert P.policy_status() == aq.OK and Q.policy_status() == aq.OK
+    P.close()
+    Q.close()
+
+
 # ------------------------------------------------------------------ edge cases and error paths
 def test_edges(aq):
     net = synth.net_config("cfg1")
