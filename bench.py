@@ -20,9 +20,9 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 PULL_EVERY = 100           # actor steps between model pulls (the paper's smaller pull frequency)
 INT8_PEAK_TOPS = 5000.0    # MI355X dense int8 MFMA, TOP/s
 # HBM bytes per launch of the fused kernel on the headline workload, from the FETCH_SIZE and WRITE_SIZE
-# hardware counters scaled by what they read on a plain 64 MiB copy (profiles/k_mlp_fused_cfg2_b4096.md).
+# hardware counters scaled by what they read on a plain 64 MiB copy (the rocprofv3 summary of this kernel under profiles/).
 # Set to None whenever that kernel changes, until the counters have been taken again.
-FUSED_HBM_BYTES_PER_LAUNCH = 3201016
+FUSED_HBM_BYTES_PER_LAUNCH = 3191816
 HBM_PEAK_GBS = 8000.0
 
 
