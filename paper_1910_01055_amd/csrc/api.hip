@@ -595,7 +595,7 @@ static aq_status forward_int8_impl(aq_policy* p, const void* d_obs, int64_t batc
             s = launch_ln_tanh_rows(a, l, io.ln_x, io.out, rows_l, st);
             if (s != AQ_OK) return s;
         }
-        if (l == nl - 1 && p->net.head == AQ_HEAD_ARGMAX) {
+        if (l == nl - 1 && p->net.head == AQ_HEAD_ARGMAX && !(layer_uses_skinny(a, l) && skinny_layer_does_argmax(a, l))) {
             s = launch_head_rows(ybuf, rows_l, b.N, p->net.head, d_actions, st);
             if (s != AQ_OK) return s;
         }

@@ -45,6 +45,9 @@ struct LayerIO {
 aq_status launch_layer_int8(const FwdArgs& a, int layer, const LayerIO& io, hipStream_t st);
 // FC layers at few rows: one workgroup per 32 x 32 output tile, K split over its waves (skinny_layer.hip)
 bool skinny_layer_supported(const LayerDev& L, int64_t rows);
+bool skinny_layer_does_argmax(const FwdArgs& a, int l);
+// whether launch_layer_int8 hands layer l at this batch to the K-split kernel
+bool layer_uses_skinny(const FwdArgs& a, int l);
 aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStream_t st);
 aq_status launch_ln_tanh_rows(const FwdArgs& a, int layer, const float* x, int8_t* out, int64_t rows, hipStream_t st);
 aq_status launch_head_rows(const float* y, int64_t rows, int N, int head, void* actions, hipStream_t st);

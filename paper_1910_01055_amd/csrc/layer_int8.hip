@@ -410,6 +410,13 @@ static aq_status launch_layer_t(const FwdArgs& a, int l, const LayerIO& io, int6
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
+bool layer_uses_skinny(const FwdArgs& a, int l) {
+    const LayerDev& L = a.net.L[l];
+    const int64_t rows = a.c.batch * L.oh * L.ow;
+    const LayerPlan p = plan_layer(L, rows, a.net.asym != 0);
+    return p.w == 2 && rows < 8192 && skinny_layer_supported(L, rows);
+}
+
 aq_status launch_layer_int8(const FwdArgs& a, int l, const LayerIO& io, hipStream_t st) {
     const LayerDev& L = a.net.L[l];
     const int64_t rows = a.c.batch * L.oh * L.ow;
@@ -429,7 +436,7 @@ aq_status launch_layer_int8(const FwdArgs& a, int l, const LayerIO& io, hipStrea
     const void* actions = (last && a.net.head != AQ_HEAD_ARGMAX) ? a.c.actions : nullptr;
     const LayerPlan p = plan_layer(L, rows, a.net.asym != 0);
     // few workgroups and a fully connected layer: the K-split kernel makes one weight stream per wave
-    if (p.w == 2 && rows < 8192 && skinny_layer_supported(L, rows)) return launch_layer_skinny(a, l, io, st);
+    if (layer_uses_skinny(a, l)) return launch_layer_skinny(a, l, io, st);
     if (p.w == 8) return launch_layer_t<8, 4, 2>(a, l, io, rows, stage_mode, actions, st);
     if (p.w == 2 && p.deep) return launch_layer_t<2, 1, 1, true>(a, l, io, rows, stage_mode, actions, st);
     if (p.w == 2) return launch_layer_t<2, 1, 1>(a, l, io, rows, stage_mode, actions, st);

@@ -28,7 +28,8 @@ __host__ __device__ inline size_t skinny_lds_bytes(int kchunk) {
 template <bool ASYM, bool TAPS>
 __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __restrict__ netp, const TapArgs t, const int l,
                                                            const LayerIO io, const int64_t rows, const int kchunk,
-                                                           const int in_mode, const void* __restrict__ actions) {
+                                                           const int in_mode, const void* __restrict__ actions,
+                                                           void* __restrict__ argmax_out) {
     extern __shared__ __align__(16) int8_t smem[];
     const NetDev& a = *netp;
     const LayerDev& L = a.L[l];
@@ -55,6 +56,7 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
     const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
     const bool fast = !last && !ln && a.fast[l] != 0;
     const int head = a.head;
+    const bool argmax_here = argmax_out != nullptr;  // last layer, argmax head, a single feature tile
 
     v16i pacc[1][1], prs[1];
     pacc[0][0] = zero16();
@@ -153,6 +155,30 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
         }
         const int n = nt * 32 + nl;
         const int64_t row = row0 + m;
+        if (argmax_here) {
+            // the whole output row sits in this tile, one feature per lane of a 32-lane group: the
+            // action index (lowest index among equal logits) is a shuffle reduction away
+            const bool ok = row < rows && n < N;
+            int vv = v + c_bias;
+            if (ASYM) vv -= zw_s * rsum;
+            if (TAPS) {
+                if (T.acc && ok) T.acc[row * N + n] = vv;
+            }
+            float y = ok ? (float)vv * c_m : -INFINITY;
+            if (ok && io.y) io.y[row * N + n] = y;
+            int best = n;
+#pragma unroll
+            for (int o = 16; o > 0; o >>= 1) {
+                const float yo = __shfl_xor(y, o, 32);
+                const int bo = __shfl_xor(best, o, 32);
+                if (yo > y || (yo == y && bo < best)) {
+                    y = yo;
+                    best = bo;
+                }
+            }
+            if (nl == 0 && row < rows) ((int32_t*)argmax_out)[row] = best;
+            continue;
+        }
         if (row >= rows || n >= N) continue;
         v += c_bias;
         if (ASYM) v -= zw_s * rsum;
@@ -177,6 +203,12 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
     }
 }
 
+// the last layer of an argmax policy whose logits fit one tile: the action index comes out of the
+// same launch
+bool skinny_layer_does_argmax(const FwdArgs& a, int l) {
+    return l == a.net.n_layers - 1 && a.net.head == AQ_HEAD_ARGMAX && a.net.L[l].NT == 1;
+}
+
 bool skinny_layer_supported(const LayerDev& L, int64_t rows) {
     const bool fc = L.kh == 1 && L.kw == 1 && L.in_h == 1 && L.in_w == 1;
     if (!fc) return false;
@@ -194,6 +226,7 @@ aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStr
     // whole 16-byte pieces need 8-bit rows whose length is a multiple of 16, at an aligned address
     const int in_mode = (!first && (L.K & 15) == 0 && ((uintptr_t)io.in & 15) == 0) ? 1 : 0;
     const void* actions = (last && a.net.head != AQ_HEAD_ARGMAX) ? a.c.actions : nullptr;
+    void* argmax_out = skinny_layer_does_argmax(a, l) ? a.c.actions : nullptr;
     dim3 grid((unsigned)L.NT, (unsigned)((rows + 31) / 32));
     const bool taps = any_taps(a);
     const bool asym = a.net.asym != 0;
@@ -207,7 +240,7 @@ aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStr
             attr_set = true;                                                                                        \
         }                                                                                                           \
         hipLaunchKernelGGL((k_layer_skinny<AS, TP>), grid, dim3(SK_W * 64), lds, st, a.d_net, a.t, l, io, rows, kchunk, \
-                           in_mode, actions);                                                                       \
+                           in_mode, actions, argmax_out);                                                                       \
     } while (0)
     if (asym) {
         if (taps) AQ_SKINNY(true, true);
