@@ -33,7 +33,7 @@ constexpr int ST_F32X4 = 2;   // first FC layer on fp32 observations, K a multip
 // stream and its latency, not bandwidth, sets the pace.  It costs registers, hence occupancy, so
 // layers with many workgroups keep the shallow pipeline.
 template <int W, int MT, int NB, bool ASYM, bool TAPS, bool DEEP>
-__global__ __launch_bounds__(W * 64) void k_layer_int8(const NetDev* __restrict__ netp, const TapArgs t, const int l,
+__global__ __launch_bounds__(W * 64, (W == 2 && !DEEP) ? 4 : 1) void k_layer_int8(const NetDev* __restrict__ netp, const TapArgs t, const int l,
                                                       const LayerIO io, const int64_t rows, const int stage_mode,
                                                       const int kc, const void* __restrict__ actions) {
     constexpr int ROWS = 32 * MT;
