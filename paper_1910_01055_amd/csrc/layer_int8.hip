@@ -33,7 +33,7 @@ constexpr int ST_F32X4 = 2;   // first FC layer on fp32 observations, K a multip
 // stream and its latency, not bandwidth, sets the pace.  It costs registers, hence occupancy, so
 // layers with many workgroups keep the shallow pipeline.
 template <int W, int MT, int NB, bool ASYM, bool TAPS, bool DEEP>
-__global__ __launch_bounds__(W * 64, (W == 2 && !DEEP) ? 4 : 1) void k_layer_int8(const NetDev* __restrict__ netp, const TapArgs t, const int l,
+__global__ __launch_bounds__(W * 64, (W <= 2 && !DEEP) ? 4 : 1) void k_layer_int8(const NetDev* __restrict__ netp, const TapArgs t, const int l,
                                                       const LayerIO io, const int64_t rows, const int stage_mode,
                                                       const int kc, const void* __restrict__ actions) {
     constexpr int ROWS = 32 * MT;
@@ -90,14 +90,15 @@ __global__ __launch_bounds__(W * 64, (W == 2 && !DEEP) ? 4 : 1) void k_layer_int
         // block copy would run at one memory latency per 16 bytes per thread.
         constexpr int SU = 8;
         if (stage_mode == ST_VEC16) {
-            // Every 16-byte piece of a row's K range is contiguous and aligned in the input.  Four threads
-            // share a row (NT_ = 4 * ROWS for every tile configuration), so the row's position in the
+            // Every 16-byte piece of a row's K range is contiguous and aligned in the input.  A few threads
+            // share a row (NT_ = 4 or 2 times ROWS), so the row's position in the
             // input (a 64-bit division for convolutions) is worked out once per thread, and each piece
             // costs one small division by the length of a kernel row, done in floating point (exact:
             // (k + 0.5) / run is never within 0.5 / run of an integer and k stays far below 2^21).
-            static_assert(NT_ == 4 * ROWS, "four staging threads per row");
+            constexpr int TPR = NT_ / ROWS;  // staging threads per row: 4, or 2 for the single-wave tile
+            static_assert(TPR * ROWS == NT_ && (TPR == 4 || TPR == 2), "whole staging threads per row");
             const int chunks = (ks1 - ks0) * 2;
-            const int m = tid >> 2, j = tid & 3;
+            const int m = tid / TPR, j = tid % TPR;
             const int64_t row = row0 + m;
             const bool row_ok = row < rows;
             const bool fc = L.kh == 1 && L.kw == 1 && L.in_h == 1 && L.in_w == 1;
@@ -118,11 +119,11 @@ __global__ __launch_bounds__(W * 64, (W == 2 && !DEEP) ? 4 : 1) void k_layer_int
                 }
             }
             const float inv_run = 1.0f / (float)run;
-            for (int c0 = j; c0 < chunks; c0 += 4 * SU) {
+            for (int c0 = j; c0 < chunks; c0 += TPR * SU) {
                 v4i v[SU];
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
-                    const int c = c0 + 4 * u;
+                    const int c = c0 + TPR * u;
                     v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0;
                     const int k = ks0 * 32 + c * 16;
                     if (c < chunks && row_ok && k < L.K) {
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(W * 64, (W == 2 && !DEEP) ? 4 : 1) void k_layer_int
                 }
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
-                    const int c = c0 + 4 * u;
+                    const int c = c0 + TPR * u;
                     if (c < chunks) *(v4i*)(xs + m * LD + c * 16) = v[u];
                 }
             }
@@ -361,6 +362,8 @@ LayerPlan plan_layer(const LayerDev& L, int64_t rows, bool asym) {
     // workgroup pass).  Narrow layers: 32-row blocks and as many waves as there are feature tiles,
     // so that every SIMD of the chip gets work.  Everything else: 64-row blocks, 4 waves.
     if (!asym && rows >= 8192 && L.NT >= 16) return {8, 4, 2, false};  // (the asymmetric row-sum tiles would spill)
+    // one feature tile and a short K: a second wave would only help staging, and idle afterwards
+    if (rows >= 8192 && L.NT == 1 && L.KS <= 16) return {1, 1, 1, false};
     if (rows >= 8192 && L.NT <= 2) return {2, 1, 1, false};
     // few rows: the 64-row configuration would leave most CUs without a workgroup; take the smallest
     // tile, and with a long K the deep weight pipeline
@@ -438,6 +441,7 @@ aq_status launch_layer_int8(const FwdArgs& a, int l, const LayerIO& io, hipStrea
     // few workgroups and a fully connected layer: the K-split kernel makes one weight stream per wave
     if (layer_uses_skinny(a, l)) return launch_layer_skinny(a, l, io, st);
     if (p.w == 8) return launch_layer_t<8, 4, 2>(a, l, io, rows, stage_mode, actions, st);
+    if (p.w == 1) return launch_layer_t<1, 1, 1>(a, l, io, rows, stage_mode, actions, st);
     if (p.w == 2 && p.deep) return launch_layer_t<2, 1, 1, true>(a, l, io, rows, stage_mode, actions, st);
     if (p.w == 2) return launch_layer_t<2, 1, 1>(a, l, io, rows, stage_mode, actions, st);
     return launch_layer_t<4, 2, 2>(a, l, io, rows, stage_mode, actions, st);
