@@ -211,6 +211,31 @@ def test_fused_row_tiles_large_batch(aq, name, batch):
     P.close()
 
 
+@pytest.mark.parametrize("name,batch,sample", [("cfg2", 262149, 400), ("paper_fc2048", 8200, 200), ("cfg4", 1100, 24)])
+def test_very_large_batches(aq, name, batch, sample):
+    """Sizes well past the benchmark's: many rounds of workgroups per CU in the fused kernel, the 8-wave
+    tile of the per-layer kernel on 2048-wide layers, and the convolution path at several hundred
+    thousand output positions; sampled rows against the oracle, every row for the stated invariants."""
+    _say(f"very_large_batches {name} batch={batch}")
+    net = synth.net_config(name)
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs[:128])
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    actions, t = U.gpu_forward(P, net, obs)
+    rng = np.random.default_rng(9)
+    rows = np.unique(np.concatenate([[0, 127, 128, batch - 129, batch - 1], rng.integers(0, batch, sample)]))
+    U.compare_forward(net, pol, obs, actions, t, rows)
+    del t
+    a2, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(a2, actions)
+    if net["head"] == "argmax":
+        assert actions.min() >= 0 and actions.max() < synth.action_dim(net)
+    else:
+        assert np.isfinite(actions).all() and np.abs(actions).max() <= 1.0
+    P.close()
+
+
 @pytest.mark.parametrize("batch", [1, 16, 40, 300])
 def test_paper_scale_actor_small_batches(aq, batch):
     """The paper's own actor shape (three hidden layers of 2048 units) at the batch sizes of its actors:
