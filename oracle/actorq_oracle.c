@@ -398,3 +398,48 @@ void orc_layernorm_f64(double* x, int64_t rows, int64_t N, const float* gamma, c
         for (int64_t n = 0; n < N; ++n) x[b * N + n] = (x[b * N + n] - mu) * inv * (double)gamma[n] + (double)beta[n];
     }
 }
+
+/* ------------------------------------------------------------------------
+ * Half-precision actor (the paper's fp16 policies: Sec. 3.2 quantizes trained
+ * policies "to fp16 and int8", Sec. 5 / App. runtime breakdown runs actors at
+ * q = 16).  Reading: every tensor of the half-precision policy - parameters,
+ * the observation, and the output of every operator (affine layer, LayerNorm,
+ * tanh, action head) - is an IEEE binary16 value; an operator's arithmetic is
+ * exact (fp64 here) and its result is rounded once, to nearest, ties to even.
+ * The only new arithmetic is that rounding, written out from the format:
+ * 1 sign, 5 exponent (bias 15), 10 fraction bits, gradual underflow below
+ * 2^-14, overflow to infinity at and above 65520.
+ * The rounded value is returned widened to fp32 (exactly representable).
+ * -------------------------------------------------------------------- */
+static double round_half_even_int(double v) {
+    /* v >= 0, below 2^52: nearest integer, ties to the even one */
+    double f = floor(v);
+    double d = v - f;
+    if (d > 0.5) return f + 1.0;
+    if (d < 0.5) return f;
+    return fmod(f, 2.0) == 0.0 ? f : f + 1.0;
+}
+
+static float round_binary16(double x) {
+    if (isnan(x)) return NAN;
+    double a = fabs(x);
+    double r;
+    if (a == 0.0) {
+        r = 0.0;
+    } else if (isinf(a)) {
+        r = INFINITY;
+    } else {
+        int e;
+        (void)frexp(a, &e); /* a = m * 2^e, m in [0.5, 1): a in [2^(e-1), 2^e) */
+        int exp2 = e - 1;   /* floor(log2 a) */
+        if (exp2 < -14) exp2 = -14; /* subnormal range shares the spacing of the lowest binade */
+        double ulp = ldexp(1.0, exp2 - 10); /* spacing of binary16 values in this binade */
+        r = round_half_even_int(a / ulp) * ulp; /* a / ulp < 2^11 + 1: exact in fp64 */
+        if (r >= 65520.0) r = INFINITY; /* 65504 is the largest finite value; halfway to 2^16 rounds up */
+    }
+    return (float)(x < 0.0 || (x == 0.0 && signbit(x)) ? -r : r);
+}
+
+void orc_round_fp16(const double* x, int64_t n, float* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = round_binary16(x[i]);
+}

@@ -228,6 +228,14 @@ def c_layernorm_f64(x, gamma, beta, eps):
     return x
 
 
+def c_round_fp16(x):
+    """IEEE binary16 rounding (nearest, ties to even) of fp64 values; returned widened to fp32."""
+    x = np.ascontiguousarray(x, np.float64)
+    out = np.empty(x.shape, np.float32)
+    lib().orc_round_fp16(_p(x, _f64), _i64(x.size), _p(out, _f32))
+    return out
+
+
 class OraclePolicy:
     """The whole path, one layer at a time, every intermediate kept.
 
@@ -269,6 +277,42 @@ class OraclePolicy:
         else:
             out = y.astype(np.float32)
         return out, ranges
+
+    # -- half-precision actor (Sec. 3.2 fp16 policies; actors at q = 16) ------------------------
+    def forward_fp16(self, params, obs=None, start_layer=0, start_x=None):
+        """Every parameter, the observation and every operator's output is a binary16 value;
+        operators compute exactly (fp64) and round once.  Runs layers start_layer.. on `obs`
+        (start_layer = 0) or on the given binary16-valued input of that layer.  Returns
+        dict(pre=[...], out=[...], actions): pre[i] is layer i's exact (unrounded, fp64) affine
+        result, out[i] the binary16 tensor the layer hands on (after its activation), as fp32."""
+        nl = len(self.layers)
+        r16 = c_round_fp16
+        x = r16(obs) if start_x is None else np.asarray(start_x, np.float32)
+        taps = {"x0": x if start_layer == 0 else None, "pre": [None] * nl, "out": [None] * nl}
+        for i in range(start_layer, nl):
+            l, p = self.layers[i], params[i]
+            w16, b16 = r16(p["w"]), r16(p["b"])
+            if l["kind"] == "fc":
+                pre = c_fc_f64(x.reshape(x.shape[0], -1), w16, b16)
+            else:
+                pre = c_conv_f64(x.reshape(x.shape[0], l["in_h"], l["in_w"], l["in_c"]), w16, b16, l["stride"])
+            taps["pre"][i] = pre
+            y = r16(pre)
+            if i < nl - 1:
+                if l["act"] == "relu":
+                    y = r16(c_relu_f64(y))
+                elif l["act"] == "ln_tanh":
+                    y = r16(c_layernorm_f64(y, r16(p["gamma"]), r16(p["beta"]), self.net["ln_eps"]))
+                    y = r16(c_tanh_f64(y))
+            taps["out"][i] = x = y
+        y = x.reshape(x.shape[0], -1)
+        if self.net["head"] == "tanh":
+            taps["actions"] = r16(c_tanh_f64(y))
+        elif self.net["head"] == "argmax":
+            taps["actions"] = c_argmax_rows(y)
+        else:
+            taps["actions"] = y
+        return taps
 
     # -- quantizer block (Sec. 3.2) ---------------------------------------------------------
     def quantize_params(self, params, act_ranges):

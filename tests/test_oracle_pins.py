@@ -519,3 +519,109 @@ def test_epsilon_greedy_exploration():
     expect = eps + (1 - eps) / A
     assert abs(frac - expect) < 5 * math.sqrt(expect * (1 - expect) / rows)
     assert changed_or_same.mean() <= eps + 5 * math.sqrt(eps / rows)
+
+
+# ---------------------------------------------------------------- half-precision actor (Sec. 3.2: fp16 policies)
+def _all_nonneg_binary16():
+    """Every finite non-negative binary16 value, ascending, decoded by numpy from the bit pattern."""
+    bits = np.arange(0, 0x7C00, dtype=np.uint16)  # 0x7C00 = +inf
+    return bits.view(np.float16).astype(np.float64)
+
+
+def test_binary16_rounding_on_every_value_and_midpoint():
+    v = _all_nonneg_binary16()
+    assert np.all(np.diff(v) > 0)
+    # the format's values are fixed points, with either sign
+    assert np.array_equal(O.c_round_fp16(v), v.astype(np.float32))
+    assert np.array_equal(O.c_round_fp16(-v), (-v).astype(np.float32))
+    # halfway between neighbours (exact in fp64): ties go to the even bit pattern
+    mid = 0.5 * (v[:-1] + v[1:])
+    even = np.where(np.arange(len(v) - 1) % 2 == 0, v[:-1], v[1:])
+    assert np.array_equal(O.c_round_fp16(mid), even.astype(np.float32))
+    assert np.array_equal(O.c_round_fp16(-mid), (-even).astype(np.float32))
+    # one fp64 step to either side of the midpoint decides for that side
+    assert np.array_equal(O.c_round_fp16(np.nextafter(mid, 0.0)), v[:-1].astype(np.float32))
+    assert np.array_equal(O.c_round_fp16(np.nextafter(mid, np.inf)), v[1:].astype(np.float32))
+    # the top of the range: 65504 is the largest finite value, 65520 is halfway to 2^16 and overflows
+    top = O.c_round_fp16(np.array([65504.0, np.nextafter(65520.0, 0.0), 65520.0, 1e9, -65520.0, np.inf]))
+    assert np.array_equal(top, np.array([65504.0, 65504.0, np.inf, np.inf, -np.inf, np.inf], np.float32))
+    # gradual underflow: half of the smallest subnormal (2^-24) ties to zero, anything above goes up
+    tiny = O.c_round_fp16(np.array([2.0 ** -25, np.nextafter(2.0 ** -25, 1.0), 2.0 ** -24, 1.5 * 2.0 ** -24]))
+    assert np.array_equal(tiny, np.array([0.0, 2.0 ** -24, 2.0 ** -24, 2.0 ** -23], np.float32))
+    assert np.isnan(O.c_round_fp16(np.array([np.nan]))[0])
+    assert np.signbit(O.c_round_fp16(np.array([-0.0, -1e-30]))).all()
+
+
+def test_binary16_rounding_matches_numpy_cast():
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal(400000) * np.exp2(rng.integers(-30, 18, 400000))
+    x = np.concatenate([x, x.astype(np.float32).astype(np.float64)])
+    with np.errstate(over="ignore"):
+        ref = x.astype(np.float16).astype(np.float32)
+    assert np.array_equal(O.c_round_fp16(x), ref)
+
+
+def test_fp16_actor_is_exact_on_small_integers():
+    """Integer parameters and observations small enough that every intermediate is a binary16
+    value (|v| <= 2048): the half-precision policy must equal plain integer arithmetic."""
+    rng = np.random.default_rng(5)
+    net = {"layers": [{"kind": "fc", "in": 9, "out": 7, "act": "relu"}, {"kind": "fc", "in": 7, "out": 5, "act": "relu"},
+                      {"kind": "fc", "in": 5, "out": 3, "act": "none"}], "head": "linear", "ln_eps": 1e-5}
+    params, Wi = [], []
+    for l in net["layers"]:
+        w = rng.integers(-3, 4, (l["out"], l["in"]))
+        b = rng.integers(-4, 5, l["out"])
+        Wi.append((w, b))
+        params.append({"w": w.astype(np.float32), "b": b.astype(np.float32)})
+    obs = rng.integers(-3, 4, (11, 9))
+    t = O.OraclePolicy(net).forward_fp16(params, obs.astype(np.float32))
+    x = obs.astype(np.int64)
+    for i, (w, b) in enumerate(Wi):
+        x = x @ w.T + b
+        assert np.abs(x).max() <= 2048
+        assert np.array_equal(t["pre"][i], x.astype(np.float64))
+        if i < 2:
+            x = np.maximum(x, 0)
+        assert np.array_equal(t["out"][i], x.astype(np.float32))
+    assert np.array_equal(t["actions"], x.astype(np.float32))
+
+
+def test_fp16_actor_rounds_parameters_observation_and_every_operator_output():
+    h = 2.0 ** -11  # 1 + h lies halfway between 1 and the next binary16 value: ties to 1
+    net = {"layers": [{"kind": "fc", "in": 4, "out": 2, "act": "none"}], "head": "linear", "ln_eps": 1e-5}
+    pol = O.OraclePolicy(net)
+    ones = np.ones((1, 4), np.float32)
+    # parameters are rounded before use (unrounded, the sums would be 4 + 4h and 4 + 12h, i.e. 4.00195 / 4.00586)
+    p = [{"w": np.array([[1 + h] * 4, [1 + 3 * h] * 4], np.float32), "b": np.zeros(2, np.float32)}]
+    t = pol.forward_fp16(p, ones)
+    assert np.array_equal(t["pre"][0], [[4.0, 4.0 * (1 + 4 * h)]])
+    # the observation is rounded before use
+    p1 = [{"w": np.ones((2, 4), np.float32), "b": np.zeros(2, np.float32)}]
+    t = pol.forward_fp16(p1, ones * np.float32(1 + 3 * h))
+    assert np.array_equal(t["pre"][0], [[4.0 * (1 + 4 * h)] * 2])
+    # the affine result is rounded once: 2049 is not a binary16 value (spacing 2 above 2048, tie to even)
+    p2 = [{"w": np.ones((2, 4), np.float32), "b": np.array([2045.0, 2047.0], np.float32)}]
+    t = pol.forward_fp16(p2, ones)
+    assert np.array_equal(t["pre"][0], [[2049.0, 2051.0]])
+    assert np.array_equal(t["out"][0], [[2048.0, 2052.0]])
+    # tanh head and LayerNorm + tanh: outputs are binary16 values within half a spacing of the exact result
+    name = "cfg2"
+    net = synth.net_config(name)
+    params = synth.make_params(net)
+    obs = synth.make_obs(net, 8)
+    t = O.OraclePolicy(net).forward_fp16(params, obs)
+    for a in t["out"] + [t["actions"]]:
+        assert np.array_equal(a.astype(np.float16).astype(np.float32), a)
+    g16 = params[0]["gamma"].astype(np.float16).astype(np.float32)
+    b16 = params[0]["beta"].astype(np.float16).astype(np.float32)
+    y0 = t["pre"][0].astype(np.float16).astype(np.float64)
+    ln = torch.nn.functional.layer_norm(torch.from_numpy(y0), (y0.shape[1],), torch.from_numpy(g16).double(),
+                                        torch.from_numpy(b16).double(), net["ln_eps"]).numpy()
+    ln16 = ln.astype(np.float16).astype(np.float64)
+    ref = np.tanh(ln16).astype(np.float16).astype(np.float32)
+    # (a value that sits within rounding error of a tie may legitimately land on either neighbour)
+    assert np.mean(ref == t["out"][0]) > 0.999
+    assert np.abs(ref.astype(np.float64) - t["out"][0]).max() <= 2.0 ** -11
+    # ... and the half-precision actions track the full-precision policy's
+    a32, _ = O.OraclePolicy(net).forward_fp32(params, obs)
+    assert 0 < np.abs(t["actions"] - a32).max() < 2e-2
