@@ -221,6 +221,28 @@ aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_d_w, const 
                                  const void* d_obs, int64_t batch, void* d_actions, float* d_ranges_out,
                                  void* stream);
 
+/* ---- Half-precision actor (Sec. 3.2: trained policies are also quantized "to fp16"; the run-time
+ * breakdown of Sec. 5 runs actors at q = 16 next to q = 8 and q = 32).  Every tensor of this policy is an
+ * IEEE binary16 value: parameters, the observation and the output of every operator (affine layer,
+ * LayerNorm, tanh, action head), each rounded once to nearest-even from a result accumulated in fp32 on
+ * the fp16 matrix cores.
+ *
+ * aq_convert_params_fp16: rounds the learner's fp32 parameters (same arrays and layouts as
+ * aq_quantize_params; biases, gains, offsets may be NULL as there) to binary16 and stores the weights in
+ * matrix-core operand order inside the policy.  The first call allocates that storage (hipMalloc);
+ * later calls overwrite it asynchronously on `stream`.  A parameter that is not finite after rounding
+ * (|v| >= 65520) is reported as AQ_ENONFINITE by aq_policy_status.
+ *
+ * aq_policy_forward_fp16: d_obs (fp32 or uint8 as declared by the policy) -> d_actions (fp32 [batch][A]
+ * holding binary16 values, or int32 [batch] for AQ_HEAD_ARGMAX; ties go to the lowest index).
+ * taps_out (may be NULL): n_layers device pointers (each may be NULL) that receive layer l's binary16
+ * output after its activation, [batch * oh * ow][out_c].  AQ_ENOTQUANT before the first
+ * aq_convert_params_fp16.  Grows internal activation buffers on demand like aq_policy_forward_int8. */
+aq_status aq_convert_params_fp16(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                 const float* const* h_d_gamma, const float* const* h_d_beta, void* stream);
+aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                 void* const* taps_out, void* stream);
+
 const char* aq_status_string(aq_status s);
 
 #ifdef __cplusplus

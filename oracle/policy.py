@@ -279,17 +279,18 @@ class OraclePolicy:
         return out, ranges
 
     # -- half-precision actor (Sec. 3.2 fp16 policies; actors at q = 16) ------------------------
-    def forward_fp16(self, params, obs=None, start_layer=0, start_x=None):
+    def forward_fp16(self, params, obs=None, start_layer=0, start_x=None, stop_layer=None):
         """Every parameter, the observation and every operator's output is a binary16 value;
         operators compute exactly (fp64) and round once.  Runs layers start_layer.. on `obs`
-        (start_layer = 0) or on the given binary16-valued input of that layer.  Returns
+        (start_layer = 0) or on the given binary16-valued input of that layer; with stop_layer, stops
+        before that layer and applies no head.  Returns
         dict(pre=[...], out=[...], actions): pre[i] is layer i's exact (unrounded, fp64) affine
         result, out[i] the binary16 tensor the layer hands on (after its activation), as fp32."""
         nl = len(self.layers)
         r16 = c_round_fp16
         x = r16(obs) if start_x is None else np.asarray(start_x, np.float32)
         taps = {"x0": x if start_layer == 0 else None, "pre": [None] * nl, "out": [None] * nl}
-        for i in range(start_layer, nl):
+        for i in range(start_layer, nl if stop_layer is None else stop_layer):
             l, p = self.layers[i], params[i]
             w16, b16 = r16(p["w"]), r16(p["b"])
             if l["kind"] == "fc":
@@ -305,6 +306,8 @@ class OraclePolicy:
                     y = r16(c_layernorm_f64(y, r16(p["gamma"]), r16(p["beta"]), self.net["ln_eps"]))
                     y = r16(c_tanh_f64(y))
             taps["out"][i] = x = y
+        if stop_layer is not None:
+            return taps
         y = x.reshape(x.shape[0], -1)
         if self.net["head"] == "tanh":
             taps["actions"] = r16(c_tanh_f64(y))

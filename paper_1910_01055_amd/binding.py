@@ -23,7 +23,8 @@ INTYPE = {"f32": 0, "u8": 1}
 EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_policy_set_path", "aq_policy_status",
            "aq_quantize_tensor", "aq_quantize_params", "aq_policy_export_layer", "aq_policy_export_act_qparams",
            "aq_policy_forward_int8", "aq_policy_forward_fp32", "aq_status_string",
-           "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore", "aq_policy_step_int8"]
+           "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore", "aq_policy_step_int8",
+           "aq_convert_params_fp16", "aq_policy_forward_fp16"]
 
 
 class AqLayer(C.Structure):
@@ -229,6 +230,16 @@ class Policy:
         _check(load().aq_policy_forward_fp32(self._h, _ptr_array(w, n), _ptr_array(b, n), _ptr_array(gamma, n),
                                              _ptr_array(beta, n), _ptr(obs), int(obs.shape[0]), _ptr(actions),
                                              _ptr(ranges_out), _stream()), "aq_policy_forward_fp32")
+
+    def convert_params_fp16(self, w, b, gamma, beta):
+        n = self.n_layers
+        _check(load().aq_convert_params_fp16(self._h, _ptr_array(w, n), _ptr_array(b, n), _ptr_array(gamma, n),
+                                             _ptr_array(beta, n), _stream()), "aq_convert_params_fp16")
+
+    def policy_forward_fp16(self, obs, actions, taps_out=None):
+        taps = _ptr_array(taps_out, self.n_layers) if taps_out is not None else None
+        _check(load().aq_policy_forward_fp16(self._h, _ptr(obs), int(obs.shape[0]), _ptr(actions), taps, _stream()),
+               "aq_policy_forward_fp16")
 
 
 def quantize_tensor(w, rows, cols, wscheme, qdenom, codes, scale, zp, workspace):

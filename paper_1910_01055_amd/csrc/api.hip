@@ -54,6 +54,14 @@ struct aq_policy {
     int64_t cap_i8 = 0, cap_f32 = 0;
     int8_t* act_i8[2] = {nullptr, nullptr};
     float* act_f32[2] = {nullptr, nullptr};
+    // half-precision actor: binary16 weights in operand order and rounded bias / gain / offset per layer
+    // (one allocation, made by the first aq_convert_params_fp16), and its activation scratch
+    void* h16_slab = nullptr;
+    std::vector<void*> h16_wp;
+    std::vector<float*> h16_bias, h16_gamma, h16_beta;
+    bool h16_ready = false;
+    int64_t cap_f16 = 0;
+    void* act_f16[2] = {nullptr, nullptr};
     int64_t max_hidden_elems = 0;  // per sample, over hidden layer outputs
     int64_t max_out_elems = 0;     // per sample, over all layer outputs
 };
@@ -300,7 +308,9 @@ extern "C" aq_status aq_policy_destroy(aq_policy* p) {
     for (int i = 0; i < 2; ++i) {
         if (p->act_i8[i]) (void)hipFree(p->act_i8[i]);
         if (p->act_f32[i]) (void)hipFree(p->act_f32[i]);
+        if (p->act_f16[i]) (void)hipFree(p->act_f16[i]);
     }
+    if (p->h16_slab) (void)hipFree(p->h16_slab);
     delete p;
     return AQ_OK;
 }
@@ -335,10 +345,29 @@ static aq_status ensure_f32(aq_policy* p, int64_t batch) {
     return AQ_OK;
 }
 
+static aq_status ensure_f16(aq_policy* p, int64_t batch) {
+    if (batch <= p->cap_f16) return AQ_OK;
+    (void)hipDeviceSynchronize();
+    for (int i = 0; i < 2; ++i) {
+        if (p->act_f16[i]) (void)hipFree(p->act_f16[i]);
+        p->act_f16[i] = nullptr;
+    }
+    p->cap_f16 = 0;
+    size_t n = ((size_t)batch * (size_t)p->max_out_elems + 64) * 2;
+    for (int i = 0; i < 2; ++i)
+        if (hipMalloc(&p->act_f16[i], n) != hipSuccess) return AQ_ENOMEM;
+    p->cap_f16 = batch;
+    return AQ_OK;
+}
+
 extern "C" aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch) {
     if (!p || max_batch < 0) return AQ_EINVAL;
     aq_status s = ensure_i8(p, max_batch);
     if (s != AQ_OK) return s;
+    if (p->h16_ready) {
+        s = ensure_f16(p, max_batch);
+        if (s != AQ_OK) return s;
+    }
     return ensure_f32(p, max_batch);
 }
 
@@ -350,9 +379,10 @@ extern "C" aq_status aq_policy_set_path(aq_policy* p, int32_t path) {
 
 extern "C" aq_status aq_policy_status(aq_policy* p, void* stream) {
     if (!p) return AQ_EINVAL;
-    int h = 0;
+    int h2[2] = {0, 0};  // [0] the 8-bit policy's status word, [1] the half-precision policy's
     AQ_HIP_CHECK(hipStreamSynchronize(as_stream(stream)));
-    AQ_HIP_CHECK(hipMemcpy(&h, p->status, sizeof(int), hipMemcpyDeviceToHost));
+    AQ_HIP_CHECK(hipMemcpy(h2, p->status, sizeof(h2), hipMemcpyDeviceToHost));
+    const int h = h2[0] | (h2[1] & kStatNonFinite);
     if (h & kStatNonFinite) return AQ_ENONFINITE;
     if (h & kStatRange) return AQ_ERANGE;
     if (h & kStatBlob) return AQ_EINVAL;
@@ -675,6 +705,109 @@ extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_
     if (d_ranges_out) {
         s = launch_keys_to_ranges(p->keys, 2 * nl, d_ranges_out, st);
         if (s != AQ_OK) return s;
+    }
+    return AQ_OK;
+}
+
+// ---- half-precision actor
+extern "C" aq_status aq_convert_params_fp16(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                            const float* const* h_d_gamma, const float* const* h_d_beta,
+                                            void* stream) {
+    if (!p || !h_d_w) return AQ_EINVAL;
+    const int nl = p->net.n_layers;
+    for (int l = 0; l < nl; ++l)
+        if (!h_d_w[l]) return AQ_EINVAL;
+    hipStream_t st = as_stream(stream);
+    if (!p->h16_slab) {
+        size_t bytes = 0;
+        std::vector<size_t> offs;
+        auto take = [&](size_t n) {
+            size_t off = bytes;
+            bytes += (n + 255) / 256 * 256;
+            return off;
+        };
+        for (const LayerBuf& b : p->L) {
+            const int ks16 = round_up(b.K, 64) / 16;
+            offs.push_back(take((size_t)b.NT * ks16 * 1024));
+            for (int i = 0; i < 3; ++i) offs.push_back(take((size_t)b.N_pad * 4));
+        }
+        if (hipMalloc(&p->h16_slab, bytes) != hipSuccess) return AQ_ENOMEM;
+        char* base = (char*)p->h16_slab;
+        size_t oi = 0;
+        for (int l = 0; l < nl; ++l) {
+            p->h16_wp.push_back(base + offs[oi++]);
+            p->h16_bias.push_back((float*)(base + offs[oi++]));
+            p->h16_gamma.push_back((float*)(base + offs[oi++]));
+            p->h16_beta.push_back((float*)(base + offs[oi++]));
+        }
+    }
+    int* st16 = p->status + 1;
+    aq_status s = launch_fill_u32((uint32_t*)st16, 1, 0u, st);
+    if (s != AQ_OK) return s;
+    for (int l = 0; l < nl; ++l) {
+        const LayerBuf& b = p->L[l];
+        const int ks16 = round_up(b.K, 64) / 16;
+        s = launch_fp16_pack_weights(h_d_w[l], b.N, b.K, ks16, b.NT, p->h16_wp[l], st16, st);
+        if (s != AQ_OK) return s;
+        s = launch_fp16_round_vec(h_d_b ? h_d_b[l] : nullptr, b.N, b.N_pad, 0.0f, p->h16_bias[l], st16, st);
+        if (s != AQ_OK) return s;
+        if (b.d.act == AQ_ACT_LN_TANH) {
+            s = launch_fp16_round_vec(h_d_gamma ? h_d_gamma[l] : nullptr, b.N, b.N_pad, 1.0f, p->h16_gamma[l], st16, st);
+            if (s != AQ_OK) return s;
+            s = launch_fp16_round_vec(h_d_beta ? h_d_beta[l] : nullptr, b.N, b.N_pad, 0.0f, p->h16_beta[l], st16, st);
+            if (s != AQ_OK) return s;
+        }
+    }
+    p->h16_ready = true;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                            void* const* taps_out, void* stream) {
+    if (!p || batch < 0) return AQ_EINVAL;
+    if (!p->h16_ready) return AQ_ENOTQUANT;
+    if (batch == 0) return AQ_OK;
+    if (!d_obs || !d_actions) return AQ_EINVAL;
+    hipStream_t st = as_stream(stream);
+    aq_status s = ensure_f16(p, batch);
+    if (s != AQ_OK) return s;
+    const int nl = p->net.n_layers;
+    const int in_mode0 = p->net.in_type == AQ_IN_U8 ? 2 : 1;
+    for (int l = 0; l < nl; ++l) {
+        const LayerBuf& b = p->L[l];
+        const bool last = l == nl - 1;
+        Fp16Layer L{};
+        L.wp = p->h16_wp[l];
+        L.bias = p->h16_bias[l];
+        L.K = b.K;
+        L.N = b.N;
+        L.KS16 = round_up(b.K, 64) / 16;
+        L.NT = b.NT;
+        L.fc = b.fc;
+        L.relu = !last && b.d.act == AQ_ACT_RELU;
+        L.in_h = b.d.in_h;
+        L.in_w = b.d.in_w;
+        L.in_c = b.d.in_c;
+        L.kh = b.d.kh;
+        L.kw = b.d.kw;
+        L.stride = b.d.stride;
+        L.oh = b.oh;
+        L.ow = b.ow;
+        const int64_t rows_l = batch * b.oh * b.ow;
+        const void* in = l == 0 ? d_obs : (const void*)p->act_f16[(l - 1) & 1];
+        void* out = p->act_f16[l & 1];
+        s = launch_layer_fp16(L, in, l == 0 ? in_mode0 : 0, out, rows_l, st);
+        if (s != AQ_OK) return s;
+        if (!last && b.d.act == AQ_ACT_LN_TANH) {
+            s = launch_fp16_ln_tanh(out, rows_l, b.N, p->h16_gamma[l], p->h16_beta[l], p->net.ln_eps, st);
+            if (s != AQ_OK) return s;
+        }
+        if (taps_out && taps_out[l])
+            AQ_HIP_CHECK(hipMemcpyAsync(taps_out[l], out, (size_t)rows_l * b.N * 2, hipMemcpyDeviceToDevice, st));
+        if (last) {
+            s = launch_fp16_head(out, rows_l, b.N, p->net.head, d_actions, st);
+            if (s != AQ_OK) return s;
+        }
     }
     return AQ_OK;
 }

@@ -70,4 +70,23 @@ aq_status launch_init_keys(uint32_t* keys, int n_pairs, hipStream_t st);
 aq_status launch_minmax_keys(const void* x, int is_u8, int64_t n, uint32_t* keys, hipStream_t st);
 aq_status launch_keys_to_ranges(const uint32_t* keys, int n, float* out, hipStream_t st);
 
+
+// ---- half-precision actor (fp16_actor.hip)
+struct Fp16Layer {
+    const void* wp;     // binary16 weights in MFMA operand order, [NT][KS16] tiles of 1 KiB
+    const float* bias;  // binary16 values widened to fp32, padded to NT * 32
+    int K, N, KS16, NT, fc, relu;
+    int in_h, in_w, in_c, kh, kw, stride, oh, ow;
+};
+aq_status launch_fp16_pack_weights(const float* w, int N, int K, int KS16, int NT, void* wp, int* status,
+                                   hipStream_t st);
+aq_status launch_fp16_round_vec(const float* src, int n, int n_pad, float fill, float* dst, int* status,
+                                hipStream_t st);
+// in_mode: 0 = binary16 activations, 1 = fp32 observations, 2 = uint8 observations
+aq_status launch_layer_fp16(const Fp16Layer& L, const void* in, int in_mode, void* out, int64_t rows,
+                            hipStream_t st);
+aq_status launch_fp16_ln_tanh(void* x, int64_t rows, int N, const float* gamma, const float* beta, float eps,
+                              hipStream_t st);
+aq_status launch_fp16_head(const void* y, int64_t rows, int N, int head, void* actions, hipStream_t st);
+
 }  // namespace aq
