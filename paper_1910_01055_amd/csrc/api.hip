@@ -796,6 +796,12 @@ extern "C" aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int
         const int64_t rows_l = batch * b.oh * b.ow;
         const void* in = l == 0 ? d_obs : (const void*)p->act_f16[(l - 1) & 1];
         void* out = p->act_f16[l & 1];
+        // (the layer kernel writes actions in 16-byte pieces)
+        const bool fused_head = last && p->net.head != AQ_HEAD_ARGMAX && ((uintptr_t)d_actions & 15) == 0;
+        if (fused_head) {
+            L.head_actions = (float*)d_actions;
+            L.head_tanh = p->net.head == AQ_HEAD_TANH;
+        }
         s = launch_layer_fp16(L, in, l == 0 ? in_mode0 : 0, out, rows_l, st);
         if (s != AQ_OK) return s;
         if (!last && b.d.act == AQ_ACT_LN_TANH) {
@@ -804,7 +810,7 @@ extern "C" aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int
         }
         if (taps_out && taps_out[l])
             AQ_HIP_CHECK(hipMemcpyAsync(taps_out[l], out, (size_t)rows_l * b.N * 2, hipMemcpyDeviceToDevice, st));
-        if (last) {
+        if (last && !fused_head) {
             s = launch_fp16_head(out, rows_l, b.N, p->net.head, d_actions, st);
             if (s != AQ_OK) return s;
         }

@@ -18,9 +18,7 @@ typedef float f16acc __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int HR = 64;    // rows per workgroup (two 32-row MFMA tiles)
 constexpr int HW = 4;     // waves per workgroup
-constexpr int HNB = 2;    // feature tiles per wave
 constexpr int HKC = 64;   // k per staged chunk
 constexpr int HLD = HKC + 8;  // LDS row stride in halfs (144 bytes: 16-byte reads of 8 rows hit 32 banks)
 
@@ -53,6 +51,23 @@ __global__ __launch_bounds__(256) void k_fp16_round_vec(const float* __restrict_
     dst[i] = v;
 }
 
+// tanh with relative error below 1e-6 (far inside half a binary16 spacing, 2.4e-4): odd polynomial
+// near zero, where the exponential form would cancel, 1 - 2 / (e^{2|x|} + 1) elsewhere
+__device__ __forceinline__ float tanh_rel(float x) {
+    const float ax = fabsf(x);
+    const float u = x * x;
+    float p = 0.0035921280f;         // Taylor series of tanh(x) / x in u = x^2 up to u^6
+    p = fmaf(p, u, -0.0088632355f);  // (remainder below 2e-7 relative at |x| = 0.5)
+    p = fmaf(p, u, 0.0218694885f);
+    p = fmaf(p, u, -0.0539682540f);
+    p = fmaf(p, u, 0.1333333333f);
+    p = fmaf(p, u, -0.3333333333f);
+    const float small = fmaf(x * u, p, x);
+    const float e = __builtin_amdgcn_exp2f(fminf(ax, 20.0f) * 2.885390081777927f);  // e^{2|x|}
+    const float big = copysignf(fmaf(__builtin_amdgcn_rcpf(e + 1.0f), -2.0f, 1.0f), x);
+    return ax < 0.5f ? small : big;
+}
+
 struct RowPos {
     int64_t base;  // element offset of (row, k = 0) in the layer's input
     bool ok;
@@ -82,136 +97,219 @@ __device__ __forceinline__ int64_t k_offset(const Fp16Layer& L, int k) {
 }
 
 // IN: 0 = binary16 activations, 1 = fp32 observations, 2 = uint8 observations (exact in binary16)
-// VEC: 16-byte pieces of 8 consecutive k are contiguous and aligned in the input (binary16 input only)
-template <int IN, bool VEC>
-__global__ __launch_bounds__(256) void k_layer_fp16(const Fp16Layer L, const void* __restrict__ in,
+// PIECE: every run of 8 consecutive k starting at a multiple of 8 is contiguous in the input, whole
+//        (K is a multiple of 8) and aligned for vector loads (16 bytes for binary16 and fp32, 4 for uint8)
+// One workgroup = 4 waves = 32*MT rows x 128*NB features; a wave owns NB feature tiles and all MT row tiles.
+// Operands are requested one chunk ahead: weights straight into registers in operand order, the
+// activation chunk into registers and from there into the other LDS buffer after the chunk's MFMAs.
+// Loads are unconditional from clamped addresses (a row past the end reads the last row, a piece
+// past K reads piece 0) and the value is zeroed afterwards, so that no branch separates a load from
+// its use.
+// (compiled for two waves per SIMD: within 256 registers the accumulators stay in ordinary vector
+// registers; with more the compiler parks them in accumulation registers and copies them back and
+// forth around every chunk)
+template <int MT, int NB, int IN, bool PIECE>
+__global__ __launch_bounds__(256, 2) void k_layer_fp16(const Fp16Layer L, const void* __restrict__ in,
                                                     _Float16* __restrict__ out, const int64_t rows) {
-    __shared__ __align__(16) _Float16 xs[2][HR * HLD];
+    constexpr int ROWS = 32 * MT;
+    constexpr int SW = NB * 32 + 8;  // row stride (halfs) of a wave's output staging tile
+    constexpr int XBUF = ROWS * HLD;
+    constexpr int XS = 2 * XBUF > HW * 32 * SW ? 2 * XBUF : HW * 32 * SW;
+    __shared__ __align__(16) _Float16 xs[XS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t row0 = (int64_t)blockIdx.x * HR;
-    const int nt0 = (blockIdx.y * HW + wave) * HNB;  // this wave's first feature tile
+    const int64_t row0 = (int64_t)blockIdx.x * ROWS;
+    const int nt0 = (blockIdx.y * HW + wave) * NB;  // this wave's first feature tile
     const bool wave_on = nt0 < L.NT;
     const int KC = L.KS16 / 4;  // chunks of 64
 
-    // staging: thread -> rows (tid >> 3) and (tid >> 3) + 32, k piece (tid & 7) * 8 of each chunk
+    // staging: thread -> rows (tid >> 3) + 32 j, k piece (tid & 7) * 8 of each chunk
     const int sr = tid >> 3, sk = (tid & 7) * 8;
-    const RowPos rp0 = row_pos(L, row0 + sr, rows), rp1 = row_pos(L, row0 + sr + 32, rows);
-
-    auto load_x = [&](int c, h8& x0, h8& x1) __attribute__((always_inline)) {
-        const int k0 = c * HKC + sk;
-        if (VEC) {
-            const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-            const int64_t off = k_offset(L, k0);
-            const bool kok = k0 < L.K;  // K is a multiple of 8 here, so a piece is whole or empty
-            x0 = (rp0.ok && kok) ? *(const h8*)((const _Float16*)in + rp0.base + off) : z;
-            x1 = (rp1.ok && kok) ? *(const h8*)((const _Float16*)in + rp1.base + off) : z;
-        } else {
+    RowPos rp[MT];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int k = k0 + j;
-                _Float16 a = (_Float16)0.0f, b = (_Float16)0.0f;
-                if (k < L.K) {
-                    const int64_t off = k_offset(L, k);
+    for (int j = 0; j < MT; ++j) {
+        const int64_t row = row0 + sr + 32 * j;
+        rp[j] = row_pos(L, row < rows ? row : rows - 1, rows);
+        rp[j].ok = row < rows;
+    }
+
+    auto load_x = [&](int c, h8 (&x)[MT]) __attribute__((always_inline)) {
+        const int k0 = c * HKC + sk;
+        if (PIECE) {
+            const bool kok = k0 < L.K;
+            const int64_t off = k_offset(L, kok ? k0 : 0);
+            const h8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < MT; ++j) {
+                h8 v;
+                {
                     if (IN == 0) {
-                        if (rp0.ok) a = ((const _Float16*)in)[rp0.base + off];
-                        if (rp1.ok) b = ((const _Float16*)in)[rp1.base + off];
+                        v = *(const h8*)((const _Float16*)in + rp[j].base + off);
                     } else if (IN == 1) {
-                        if (rp0.ok) a = (_Float16)((const float*)in)[rp0.base + off];
-                        if (rp1.ok) b = (_Float16)((const float*)in)[rp1.base + off];
+                        const float4* s4 = (const float4*)((const float*)in + rp[j].base + off);
+                        const float4 a = s4[0], b = s4[1];
+                        v[0] = (_Float16)a.x; v[1] = (_Float16)a.y; v[2] = (_Float16)a.z; v[3] = (_Float16)a.w;
+                        v[4] = (_Float16)b.x; v[5] = (_Float16)b.y; v[6] = (_Float16)b.z; v[7] = (_Float16)b.w;
                     } else {
-                        if (rp0.ok) a = (_Float16)(float)((const uint8_t*)in)[rp0.base + off];
-                        if (rp1.ok) b = (_Float16)(float)((const uint8_t*)in)[rp1.base + off];
+                        const uint32_t* s1 = (const uint32_t*)((const uint8_t*)in + rp[j].base + off);
+                        const uint32_t a = s1[0], b = s1[1];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            v[i] = (_Float16)(float)((a >> (8 * i)) & 0xffu);
+                            v[4 + i] = (_Float16)(float)((b >> (8 * i)) & 0xffu);
+                        }
                     }
                 }
-                x0[j] = a;
-                x1[j] = b;
+                x[j] = (rp[j].ok && kok) ? v : z;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int k = k0 + i;
+                const bool kok = k < L.K;
+                const int64_t off = k_offset(L, kok ? k : 0);
+#pragma unroll
+                for (int j = 0; j < MT; ++j) {
+                    _Float16 a;
+                    if (IN == 0) a = ((const _Float16*)in)[rp[j].base + off];
+                    else if (IN == 1) a = (_Float16)((const float*)in)[rp[j].base + off];
+                    else a = (_Float16)(float)((const uint8_t*)in)[rp[j].base + off];
+                    x[j][i] = (kok && rp[j].ok) ? a : (_Float16)0.0f;
+                }
             }
         }
     };
-    auto store_x = [&](int buf, const h8& x0, const h8& x1) __attribute__((always_inline)) {
-        *(h8*)&xs[buf][sr * HLD + sk] = x0;
-        *(h8*)&xs[buf][(sr + 32) * HLD + sk] = x1;
+    auto store_x = [&](int buf, const h8 (&x)[MT]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < MT; ++j) *(h8*)&xs[buf * XBUF + (sr + 32 * j) * HLD + sk] = x[j];
     };
-    // this wave's weights of one chunk: 4 k-steps x HNB tiles, 16 bytes per lane each
+    // this wave's weights of one chunk: 4 k-steps x NB tiles, 16 bytes per lane each
     const h8* wbase = (const h8*)L.wp + lane;
-    auto load_w = [&](int c, h8 (&wr)[4][HNB]) __attribute__((always_inline)) {
+    auto load_w = [&](int c, h8 (&wr)[4][NB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int nb = 0; nb < HNB; ++nb) {
+            for (int nb = 0; nb < NB; ++nb) {
                 const int nt = nt0 + nb < L.NT ? nt0 + nb : L.NT - 1;  // (clamped: the tile is not stored)
                 wr[s][nb] = wbase[((int64_t)nt * L.KS16 + c * 4 + s) * 64];
             }
     };
 
-    f16acc acc[HNB][2];
+    f16acc acc[NB][MT];
 #pragma unroll
-    for (int nb = 0; nb < HNB; ++nb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[nb][mt][i] = 0.0f;
 
-    h8 wc[4][HNB], wn[4][HNB];
-    h8 x0, x1;
-    if (wave_on) load_w(0, wc);
-    load_x(0, x0, x1);
-    store_x(0, x0, x1);
+    h8 wc[4][NB], wn[4][NB];  // weights of chunks c, c + 1
+    h8 xn[MT];                 // activations of chunk c + 1
+    load_w(0, wc);
+    load_x(0, xn);
+    store_x(0, xn);
     __syncthreads();
     for (int c = 0; c < KC; ++c) {
         const bool more = c + 1 < KC;
-        if (more) {
-            if (wave_on) load_w(c + 1, wn);
-            load_x(c + 1, x0, x1);
+        {
+            const int cn = more ? c + 1 : c;  // (clamped: loaded again, not used)
+            load_w(cn, wn);
+            load_x(cn, xn);
         }
         if (wave_on) {
-            const _Float16* xb = xs[c & 1];
+            const _Float16* xb = xs + (c & 1) * XBUF;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                h8 bx[2];
+                h8 bx[MT];
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
+                for (int mt = 0; mt < MT; ++mt)
                     bx[mt] = *(const h8*)&xb[(mt * 32 + (lane & 31)) * HLD + s * 16 + 8 * (lane >> 5)];
 #pragma unroll
-                for (int nb = 0; nb < HNB; ++nb)
+                for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
+                    for (int mt = 0; mt < MT; ++mt)
                         acc[nb][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wc[s][nb], bx[mt], acc[nb][mt], 0, 0, 0);
             }
         }
-        if (more) {
-            store_x((c + 1) & 1, x0, x1);
+        if (more) store_x((c + 1) & 1, xn);
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int nb = 0; nb < HNB; ++nb) wc[s][nb] = wn[s][nb];
-        }
+            for (int nb = 0; nb < NB; ++nb) wc[s][nb] = wn[s][nb];
         __syncthreads();
     }
     if (!wave_on) return;
 
-    // epilogue: + bias, rounded to binary16 once, ReLU; lane = one row, four consecutive features per quad
+    // epilogue: + bias, rounded to binary16 once, ReLU; lane = one row, four consecutive features per quad.
+    // An elementwise action head (tanh / identity) is applied to the rounded value in the same sweep.
+    auto quad_out = [&](int nb, int mt, int q, int n0) __attribute__((always_inline)) {
+        const float4 bv = *(const float4*)(L.bias + n0);  // padded to the tile
+        const float b4[4] = {bv.x, bv.y, bv.z, bv.w};
+        h4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            _Float16 v = (_Float16)(acc[nb][mt][4 * q + i] + b4[i]);
+            if (L.relu) v = v > (_Float16)0.0f ? v : (_Float16)0.0f;
+            o[i] = v;
+        }
+        return o;
+    };
+    if ((L.N & 7) == 0) {
+        // Rows of 16-byte pieces: each tile goes through a wave-private LDS region (the activation
+        // buffers are idle after the last barrier) and leaves as whole contiguous runs of an output row,
+        // NB * 64 bytes per row and wave, instead of 8 bytes per lane 2 * N bytes apart.
+        _Float16* wsp = xs + wave * (32 * SW);
+        constexpr int LPR = NB * 4;      // lanes per row on the way out
+        constexpr int RPI = 64 / LPR;    // rows per store instruction
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n0 = (nt0 + nb) * 32 + 8 * q + 4 * (lane >> 5);
+                    h4 o = {0, 0, 0, 0};
+                    if (nt0 + nb < L.NT) o = quad_out(nb, mt, q, n0);
+                    *(h4*)&wsp[(lane & 31) * SW + nb * 32 + 8 * q + 4 * (lane >> 5)] = o;
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < 32 / RPI; ++j) {
+                const int r = j * RPI + lane / LPR, pc = lane % LPR;
+                const h8 v = *(const h8*)&wsp[r * SW + pc * 8];
+                const int64_t row = row0 + mt * 32 + r;
+                const int n = nt0 * 32 + pc * 8;
+                if (row < rows && n < L.N) {
+                    *(h8*)(out + row * L.N + n) = v;
+                    if (L.head_actions) {
+                        float a8[8];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            a8[i] = L.head_tanh ? (float)(_Float16)tanh_rel((float)v[i]) : (float)v[i];
+                        float4* ad = (float4*)(L.head_actions + row * L.N + n);
+                        ad[0] = make_float4(a8[0], a8[1], a8[2], a8[3]);
+                        ad[1] = make_float4(a8[4], a8[5], a8[6], a8[7]);
+                    }
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
     const bool vec_out = (L.N & 3) == 0;
 #pragma unroll
-    for (int nb = 0; nb < HNB; ++nb) {
+    for (int nb = 0; nb < NB; ++nb) {
         if (nt0 + nb >= L.NT) continue;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
+        for (int mt = 0; mt < MT; ++mt) {
             const int64_t row = row0 + mt * 32 + (lane & 31);
             if (row >= rows) continue;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int n0 = (nt0 + nb) * 32 + 8 * q + 4 * (lane >> 5);
                 if (n0 >= L.N) continue;
-                const float4 bv = *(const float4*)(L.bias + n0);  // padded to the tile
-                const float b4[4] = {bv.x, bv.y, bv.z, bv.w};
-                h4 o;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    _Float16 v = (_Float16)(acc[nb][mt][4 * q + i] + b4[i]);
-                    if (L.relu) v = v > (_Float16)0.0f ? v : (_Float16)0.0f;
-                    o[i] = v;
-                }
+                const h4 o = quad_out(nb, mt, q, n0);
                 _Float16* dst = out + row * L.N + n0;
                 if (vec_out) {
                     *(h4*)dst = o;
@@ -220,16 +318,106 @@ __global__ __launch_bounds__(256) void k_layer_fp16(const Fp16Layer L, const voi
                     for (int i = 0; i < 4; ++i)
                         if (n0 + i < L.N) dst[i] = o[i];
                 }
+                if (L.head_actions) {
+                    float* ad = L.head_actions + row * L.N + n0;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (n0 + i < L.N)
+                            ad[i] = L.head_tanh ? (float)(_Float16)tanh_rel((float)o[i]) : (float)o[i];
+                }
             }
         }
     }
 }
 
-// LayerNorm (biased variance, eps inside the root) rounded to binary16, then tanh rounded to binary16;
-// one wavefront per row, in place
+// LayerNorm (biased variance, eps inside the root) rounded to binary16, then tanh rounded to binary16,
+// in place.  One wavefront per LN_R rows, the rows in registers between the statistics and the result,
+// all of a wave's loads requested before the first is used (8-byte pieces when N is a multiple of 4).
+constexpr int LN_R = 4;     // rows per wavefront
+constexpr int LN_MAXV = 16; // elements per lane and row held in registers (N <= 1024)
+template <bool VEC4>
 __global__ __launch_bounds__(256) void k_fp16_ln_tanh(_Float16* __restrict__ x, int64_t rows, int N,
                                                       const float* __restrict__ gamma, const float* __restrict__ beta,
                                                       float eps) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * LN_R;
+    if (r0 >= rows) return;
+    float v[LN_R][LN_MAXV];
+    // element index of register i: VEC4: 4 * lane + 256 * (i / 4) + i % 4, else lane + 64 * i
+#pragma unroll
+    for (int r = 0; r < LN_R; ++r) {
+        const int64_t row = r0 + r < rows ? r0 + r : rows - 1;
+        const _Float16* xr = x + row * N;
+        if (VEC4) {
+#pragma unroll
+            for (int i = 0; i < LN_MAXV / 4; ++i) {
+                const int n = 4 * lane + 256 * i;
+                h4 t = {0, 0, 0, 0};
+                if (n < N) t = *(const h4*)(xr + n);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[r][4 * i + j] = (float)t[j];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LN_MAXV; ++i) {
+                const int n = lane + 64 * i;
+                v[r][i] = n < N ? (float)xr[n] : 0.0f;
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < LN_R; ++r) {
+        if (r0 + r >= rows) break;
+        _Float16* xr = x + (r0 + r) * N;
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < LN_MAXV; ++i) s += v[r][i];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+        const float mean = s / (float)N;
+        float ss = 0.0f;
+#pragma unroll
+        for (int i = 0; i < LN_MAXV; ++i) {
+            const int n = VEC4 ? 4 * lane + 256 * (i / 4) + i % 4 : lane + 64 * i;
+            const float d = n < N ? v[r][i] - mean : 0.0f;
+            ss += d * d;
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        const float inv = 1.0f / sqrtf(ss / (float)N + eps);
+        if (VEC4) {
+#pragma unroll
+            for (int i = 0; i < LN_MAXV / 4; ++i) {
+                const int n = 4 * lane + 256 * i;
+                if (n < N) {
+                    const float4 g4 = *(const float4*)(gamma + n), b4 = *(const float4*)(beta + n);
+                    const float gg[4] = {g4.x, g4.y, g4.z, g4.w}, bb[4] = {b4.x, b4.y, b4.z, b4.w};
+                    h4 o;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const _Float16 ln = (_Float16)((v[r][4 * i + j] - mean) * inv * gg[j] + bb[j]);
+                        o[j] = (_Float16)tanh_rel((float)ln);
+                    }
+                    *(h4*)(xr + n) = o;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < LN_MAXV; ++i) {
+                const int n = lane + 64 * i;
+                if (n < N) {
+                    const _Float16 ln = (_Float16)((v[r][i] - mean) * inv * gamma[n] + beta[n]);
+                    xr[n] = (_Float16)tanh_rel((float)ln);
+                }
+            }
+        }
+    }
+}
+
+// rows wider than 64 * LN_MAXV: one wavefront per row, the row is read three times
+__global__ __launch_bounds__(256) void k_fp16_ln_tanh_long(_Float16* __restrict__ x, int64_t rows, int N,
+                                                           const float* __restrict__ gamma,
+                                                           const float* __restrict__ beta, float eps) {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
@@ -249,7 +437,7 @@ __global__ __launch_bounds__(256) void k_fp16_ln_tanh(_Float16* __restrict__ x, 
     const float inv = 1.0f / sqrtf(ss / (float)N + eps);
     for (int n = lane; n < N; n += 64) {
         const _Float16 ln = (_Float16)(((float)xr[n] - mean) * inv * gamma[n] + beta[n]);
-        xr[n] = (_Float16)tanhf((float)ln);
+        xr[n] = (_Float16)tanh_rel((float)ln);
     }
 }
 
@@ -272,7 +460,7 @@ __global__ __launch_bounds__(256) void k_fp16_head(const _Float16* __restrict__ 
     } else {
         if (i >= rows * N) return;
         const float v = (float)y[i];
-        ((float*)actions)[i] = head == AQ_HEAD_TANH ? (float)(_Float16)tanhf(v) : v;
+        ((float*)actions)[i] = head == AQ_HEAD_TANH ? (float)(_Float16)tanh_rel(v) : v;
     }
 }
 
@@ -293,29 +481,68 @@ aq_status launch_fp16_round_vec(const float* src, int n, int n_pad, float fill, 
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
+namespace {
+template <int MT, int NB>
+void launch_layer_cfg(const Fp16Layer& L, const void* in, int in_mode, bool piece, _Float16* o, int64_t rows,
+                      hipStream_t st) {
+    const dim3 grid((unsigned)((rows + 32 * MT - 1) / (32 * MT)), (unsigned)((L.NT + HW * NB - 1) / (HW * NB)));
+#define AQ_F16_GO(IN, PC) hipLaunchKernelGGL((k_layer_fp16<MT, NB, IN, PC>), grid, dim3(256), 0, st, L, in, o, rows)
+    if constexpr (MT == 4) {  // (the 128-row tile serves hidden layers only)
+        if (piece) AQ_F16_GO(0, true);
+        else AQ_F16_GO(0, false);
+    } else {
+        if (in_mode == 0) {
+            if (piece) AQ_F16_GO(0, true);
+            else AQ_F16_GO(0, false);
+        } else if (in_mode == 1) {
+            if (piece) AQ_F16_GO(1, true);
+            else AQ_F16_GO(1, false);
+        } else {
+            if (piece) AQ_F16_GO(2, true);
+            else AQ_F16_GO(2, false);
+        }
+    }
+#undef AQ_F16_GO
+}
+}  // namespace
+
 aq_status launch_layer_fp16(const Fp16Layer& L, const void* in, int in_mode, void* out, int64_t rows,
                             hipStream_t st) {
     if (rows < 1) return AQ_OK;
     if (L.KS16 % 4 != 0 || L.NT < 1) return AQ_ESHAPE;
-    const dim3 grid((unsigned)((rows + HR - 1) / HR), (unsigned)((L.NT + HW * HNB - 1) / (HW * HNB)));
     _Float16* o = (_Float16*)out;
-    // 16-byte pieces: binary16 input whose runs of consecutive k start and end on multiples of 8
-    const bool vec = in_mode == 0 && ((uintptr_t)in & 15) == 0 && (L.fc ? L.K % 8 == 0 : L.in_c % 8 == 0);
-    if (in_mode == 0) {
-        if (vec) hipLaunchKernelGGL((k_layer_fp16<0, true>), grid, dim3(256), 0, st, L, in, o, rows);
-        else hipLaunchKernelGGL((k_layer_fp16<0, false>), grid, dim3(256), 0, st, L, in, o, rows);
-    } else if (in_mode == 1) {
-        hipLaunchKernelGGL((k_layer_fp16<1, false>), grid, dim3(256), 0, st, L, in, o, rows);
-    } else {
-        hipLaunchKernelGGL((k_layer_fp16<2, false>), grid, dim3(256), 0, st, L, in, o, rows);
-    }
+    // whole aligned pieces of 8 consecutive k: runs of consecutive k are multiples of 8 long, and every
+    // run starts at an element offset that is a multiple of 8 (binary16: 16 bytes) or 4 (fp32: 16 bytes,
+    // uint8: 4 bytes)
+    const int unit = in_mode == 0 ? 8 : 4;
+    const bool piece = ((uintptr_t)in & 15) == 0 &&
+                       (L.fc ? L.K % 8 == 0 : ((L.kw * L.in_c) % 8 == 0 && L.in_c % unit == 0));
+    // Tile: 128 rows x 256 features (hidden layers: the conversion of an fp32 observation piece does not
+    // fit the register budget beside 128 accumulators) when that still gives every CU two workgroups,
+    // 64 x 256 when it gives one, else 32 x 128 (few rows or few features: as many workgroups as possible).
+    auto wgs = [&](int mt, int nb) {
+        return ((rows + 32 * mt - 1) / (32 * mt)) * (int64_t)((L.NT + HW * nb - 1) / (HW * nb));
+    };
+    if (in_mode == 0 && L.NT > HW && wgs(4, 2) >= 512) launch_layer_cfg<4, 2>(L, in, in_mode, piece, o, rows, st);
+    else if (L.NT > HW && wgs(2, 2) >= 256) launch_layer_cfg<2, 2>(L, in, in_mode, piece, o, rows, st);
+    else launch_layer_cfg<1, 1>(L, in, in_mode, piece, o, rows, st);
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
 aq_status launch_fp16_ln_tanh(void* x, int64_t rows, int N, const float* gamma, const float* beta, float eps,
                               hipStream_t st) {
-    hipLaunchKernelGGL(k_fp16_ln_tanh, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, (_Float16*)x, rows, N, gamma,
-                       beta, eps);
+    if (rows < 1) return AQ_OK;
+    _Float16* xh = (_Float16*)x;
+    if (N > 64 * LN_MAXV) {
+        hipLaunchKernelGGL(k_fp16_ln_tanh_long, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, xh, rows, N, gamma,
+                           beta, eps);
+    } else {
+        const dim3 grid((unsigned)((rows + 4 * LN_R - 1) / (4 * LN_R)));
+        if (N % 4 == 0 && ((uintptr_t)x & 7) == 0)
+            hipLaunchKernelGGL(k_fp16_ln_tanh<true>, grid, dim3(256), 0, st, xh, rows, N, gamma, beta, eps);
+        else
+            hipLaunchKernelGGL(k_fp16_ln_tanh<false>, grid, dim3(256), 0, st, xh, rows, N, gamma, beta, eps);
+    }
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 

@@ -77,6 +77,8 @@ struct Fp16Layer {
     const float* bias;  // binary16 values widened to fp32, padded to NT * 32
     int K, N, KS16, NT, fc, relu;
     int in_h, in_w, in_c, kh, kw, stride, oh, ow;
+    float* head_actions;  // last layer with an elementwise head: fp32 actions [rows][N], else NULL
+    int head_tanh;
 };
 aq_status launch_fp16_pack_weights(const float* w, int N, int K, int KS16, int NT, void* wp, int* status,
                                    hipStream_t st);

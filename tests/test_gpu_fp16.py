@@ -53,6 +53,9 @@ def _nets():
         "cfg2": synth.net_config("cfg2"),
         "cfg5": synth.net_config("cfg5"),
         "odd_ln": synth.small_net([fc(67, 200, "ln_tanh"), fc(200, 72, "relu"), fc(72, 21, "none")], head="tanh"),
+        "ln_odd70": synth.small_net([fc(20, 70, "ln_tanh"), fc(70, 5, "none")], head="tanh"),
+        "ln_wide": synth.small_net([fc(16, 1100, "ln_tanh"), fc(1100, 4, "none")], head="linear"),
+        "wide_last": synth.small_net([fc(40, 64, "relu"), fc(64, 104, "none")], head="tanh"),
         "argmax_mlp": synth.small_net([fc(33, 64, "relu"), fc(64, 18, "none")], head="argmax"),
         "u8_mlp": synth.small_net([fc(48, 64, "relu"), fc(64, 5, "none")], head="linear", in_type="u8"),
         "long_k": synth.small_net([fc(20, 700, "relu"), fc(700, 10, "none")], head="tanh"),
@@ -143,6 +146,21 @@ def test_fp16_actor_every_layer(aq, name, batch):
     obs = synth.make_obs(net, batch)
     actions, outs = _run_gpu(aq, net, params, obs)
     _check(net, params, obs, actions, outs)
+
+
+@pytest.mark.parametrize("name,batch", [("cfg5", 16384), ("cfg5", 4200), ("cfg2", 4096), ("cfg3", 65536),
+                                        ("cfg4", 256)])
+def test_fp16_actor_full_size(aq, name, batch):
+    """The benchmark's shapes and tile configurations; the oracle checks a sample of the rows."""
+    _say(f"fp16_actor_full_size {name} batch={batch}")
+    net = synth.net_config(name)
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    actions, outs = _run_gpu(aq, net, params, obs)
+    rng = np.random.default_rng(9)
+    n_s = 6 if name == "cfg4" else 48
+    rows = np.unique(np.concatenate([[0, 31, 32, 127, 128, batch - 1], rng.integers(0, batch, n_s)]))
+    _check(net, params, obs[rows], actions[rows], [o.reshape(batch, -1)[rows] for o in outs])
 
 
 def test_fp16_actor_conv_policy(aq):
