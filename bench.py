@@ -19,6 +19,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PULL_EVERY = 100           # actor steps between model pulls (the paper's smaller pull frequency)
 INT8_PEAK_TOPS = 5000.0    # MI355X dense int8 MFMA, TOP/s
+FP16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, TFLOP/s
 # HBM bytes per launch of the fused kernel on the headline workload, from the FETCH_SIZE and WRITE_SIZE
 # hardware counters scaled by what they read on a plain 64 MiB copy (the rocprofv3 summary of this kernel under profiles/).
 # Set to None whenever that kernel changes, until the counters have been taken again.
@@ -113,6 +114,14 @@ def forward_workload(torch, aq, synth, U, name, batch, iters, warm=20):
     f32()
     torch.cuda.synchronize()
     ms32 = _events_ms(torch, f32, max(2, iters // 20))
+    # the half-precision actor (q = 16 in the paper's run-time breakdown) on the same inputs
+    P.convert_params_fp16(w, b, g, be)
+    f16 = lambda: P.policy_forward_fp16(d_obs, act)
+    for _ in range(3):
+        f16()
+    torch.cuda.synchronize()
+    ms16 = _graph_ms(torch, f16, min(iters, 50))
+    fwd()  # leave the 8-bit policy's actions in the buffer
     ops = 2.0 * synth.macs_per_sample(net) * batch
     # algorithmic HBM bytes: observations in, actions out, 8-bit weights once
     n_w = sum(int(p["w"].size) for p in params)
@@ -120,7 +129,9 @@ def forward_workload(torch, aq, synth, U, name, batch, iters, warm=20):
     out = {"workload": f"{name} batch {batch}", "us_per_launch": ms * 1e3, "inferences_per_s": batch / (ms * 1e-3),
            "tops": ops / (ms * 1e-3) / 1e12, "frac_int8_mfma_peak": ops / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
            "GBps_algorithmic": hbm / (ms * 1e-3) / 1e9, "frac_hbm_peak": hbm / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-           "us_per_launch_eager": ms_eager * 1e3, "fp32_actor_us_per_launch": ms32 * 1e3}
+           "us_per_launch_eager": ms_eager * 1e3, "fp32_actor_us_per_launch": ms32 * 1e3,
+           "fp16_actor_us_per_launch": ms16 * 1e3, "fp16_actor_tflops": ops / (ms16 * 1e-3) / 1e12,
+           "fp16_actor_frac_fp16_mfma_peak": ops / (ms16 * 1e-3) / 1e12 / FP16_PEAK_TFLOPS}
     return out, (P, w, b, g, be, ranges, d_obs, act, net, params, obs)
 
 
@@ -304,6 +315,7 @@ def main():
                      "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE counters, copy-calibrated)",
                      "kernel": "k_mlp_fused (whole-network int8 MLP)", "us_per_launch": head["us_per_launch"]},
         "fp32_actor_us_per_launch": head["fp32_actor_us_per_launch"],
+        "fp16_actor_us_per_launch": head["fp16_actor_us_per_launch"],
     }
     if not args.no_extra:
         extra = []
