@@ -172,6 +172,34 @@ def test_fp16_actor_conv_policy(aq):
     _check(net, params, obs, actions, outs)
 
 
+@pytest.mark.parametrize("name", ["cfg5", "cfg2", "u8_mlp"])
+def test_fp16_actor_unaligned_buffers(aq, name):
+    """Observation and action buffers that start off a 16-byte boundary take the element-wise input path
+    and the separate head kernel; the results must not change."""
+    _say(f"fp16_actor_unaligned_buffers {name}")
+    net = _nets()[name]
+    batch = 130
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    ref, _ = _run_gpu(aq, net, params, obs)
+    P = aq.Policy(net)
+    w, b, g, be = U.upload_params(params)
+    P.convert_params_fp16(w, b, g, be)
+    flat = torch.from_numpy(np.ascontiguousarray(obs)).reshape(-1)
+    pad = torch.zeros(flat.numel() + 8, dtype=flat.dtype, device=U.DEV)
+    pad[1:1 + flat.numel()] = flat.to(U.DEV)
+    d_obs = pad[1:1 + flat.numel()].view(obs.shape)
+    A = synth.action_dim(net)
+    abuf = torch.zeros(batch * A + 8, dtype=torch.float32, device=U.DEV)
+    actions = abuf[1:1 + batch * A].view(batch, A)
+    assert d_obs.data_ptr() % 16 != 0 and actions.data_ptr() % 16 != 0
+    P.policy_forward_fp16(d_obs, actions, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(actions.cpu().numpy(), ref)
+    assert float(abuf[0]) == 0.0 and float(abuf[1 + batch * A]) == 0.0  # nothing written outside
+    P.close()
+
+
 def test_fp16_actor_errors_and_nonfinite(aq):
     _say("fp16_actor_errors")
     net = _nets()["argmax_mlp"]
