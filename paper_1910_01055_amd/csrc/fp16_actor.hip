@@ -330,6 +330,72 @@ __global__ __launch_bounds__(256, 2) void k_layer_fp16(const Fp16Layer L, const 
     }
 }
 
+// Fully connected hidden layer at few rows (the paper's actors run one observation at a time, Sec. 3.1,
+// on layers of 2048 units, Sec. 4.1): the time goes into streaming the binary16 weights once, so one
+// workgroup of 8 waves owns a single 32-row x 32-feature output tile and its waves split K.  Both MFMA
+// operands come straight from global memory, 16 bytes per lane and k-step (the activation rows are a
+// few KB and stay in cache), SKH_PF k-steps of each in flight; partial tiles meet in LDS, then the 512
+// threads reduce eight partial sums for two outputs each, add the bias, round once and store.
+constexpr int SKH_W = 8;
+constexpr int SKH_PF = 8;
+constexpr int SKH_LD = 65;  // words per register row of a partial tile (conflict-free feature-major reads)
+
+__global__ __launch_bounds__(SKH_W * 64) void k_layer_fp16_skinny(const Fp16Layer L, const _Float16* __restrict__ in,
+                                                                   _Float16* __restrict__ out, const int64_t rows) {
+    __shared__ float part[SKH_W * 16 * SKH_LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nt = blockIdx.x;
+    const int64_t row0 = (int64_t)blockIdx.y * 32;
+    const int KSr = (L.K + 15) / 16;                  // k-steps that hold real columns
+    const int kc = (KSr + SKH_W - 1) / SKH_W;
+    const int k0 = wave * kc, k1 = k0 + kc < KSr ? k0 + kc : KSr;
+    const int64_t xrow = row0 + (lane & 31) < rows ? row0 + (lane & 31) : rows - 1;  // (clamped, zeroed below)
+    const bool row_ok = row0 + (lane & 31) < rows;
+    const h8* wsrc = (const h8*)L.wp + (int64_t)nt * L.KS16 * 64 + lane;
+    const _Float16* xsrc = in + xrow * L.K + 8 * (lane >> 5);
+    const h8 z8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    f16acc acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+    for (int g0 = k0; g0 < k1; g0 += SKH_PF) {
+        h8 a[SKH_PF], b[SKH_PF];
+#pragma unroll
+        for (int u = 0; u < SKH_PF; ++u) {
+            const int ks = g0 + u < k1 ? g0 + u : k1 - 1;
+            a[u] = wsrc[(int64_t)ks * 64];
+            // K is a multiple of 8: a piece of 8 columns is whole or lies entirely in the zero padding
+            const int kcol = ks * 16 + 8 * (lane >> 5);
+            b[u] = *(const h8*)(xsrc + (kcol < L.K ? ks * 16 : 0));
+            if (!(row_ok && kcol < L.K && g0 + u < k1)) b[u] = z8;
+        }
+#pragma unroll
+        for (int u = 0; u < SKH_PF; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[u], b[u], acc, 0, 0, 0);
+    }
+    {
+        float* mine = part + wave * 16 * SKH_LD + lane;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mine[r * SKH_LD] = acc[r];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int m = (tid >> 5) + 16 * it, nl = tid & 31;
+        // accumulator register and lane that hold (feature nl, row m) of the tile
+        const int reg = 4 * (nl >> 3) + (nl & 3), lsrc = m + 32 * ((nl >> 2) & 1);
+        float v = 0.0f;
+#pragma unroll
+        for (int kp = 0; kp < SKH_W; ++kp) v += part[kp * 16 * SKH_LD + reg * SKH_LD + lsrc];
+        const int n = nt * 32 + nl;
+        const int64_t row = row0 + m;
+        if (row >= rows || n >= L.N) continue;
+        _Float16 o = (_Float16)(v + L.bias[n]);
+        if (L.relu) o = o > (_Float16)0.0f ? o : (_Float16)0.0f;
+        out[row * L.N + n] = o;
+        if (L.head_actions)
+            L.head_actions[row * L.N + n] = L.head_tanh ? (float)(_Float16)tanh_rel((float)o) : (float)o;
+    }
+}
+
 // LayerNorm (biased variance, eps inside the root) rounded to binary16, then tanh rounded to binary16,
 // in place.  One wavefront per LN_R rows, the rows in registers between the statistics and the result,
 // all of a wave's loads requested before the first is used (8-byte pieces when N is a multiple of 4).
@@ -523,6 +589,14 @@ aq_status launch_layer_fp16(const Fp16Layer& L, const void* in, int in_mode, voi
     auto wgs = [&](int mt, int nb) {
         return ((rows + 32 * mt - 1) / (32 * mt)) * (int64_t)((L.NT + HW * nb - 1) / (HW * nb));
     };
+    // few rows: one workgroup per output tile with K split over its waves, whenever the tiled kernel would
+    // leave most CUs without a workgroup (binary16 rows of whole, aligned 16-byte pieces)
+    if (in_mode == 0 && L.fc && L.K % 8 == 0 && ((uintptr_t)in & 15) == 0 && L.K >= 128 && wgs(1, 1) < 128 &&
+        (rows + 31) / 32 <= 65535) {
+        const dim3 grid((unsigned)L.NT, (unsigned)((rows + 31) / 32));
+        hipLaunchKernelGGL(k_layer_fp16_skinny, grid, dim3(SKH_W * 64), 0, st, L, (const _Float16*)in, o, rows);
+        return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+    }
     if (in_mode == 0 && L.NT > HW && wgs(4, 2) >= 512) launch_layer_cfg<4, 2>(L, in, in_mode, piece, o, rows, st);
     else if (L.NT > HW && wgs(2, 2) >= 256) launch_layer_cfg<2, 2>(L, in, in_mode, piece, o, rows, st);
     else launch_layer_cfg<1, 1>(L, in, in_mode, piece, o, rows, st);

@@ -149,7 +149,7 @@ def test_fp16_actor_every_layer(aq, name, batch):
 
 
 @pytest.mark.parametrize("name,batch", [("cfg5", 16384), ("cfg5", 4200), ("cfg2", 4096), ("cfg3", 65536),
-                                        ("cfg4", 256)])
+                                        ("cfg4", 256), ("paper_fc2048", 16), ("paper_fc2048", 1)])
 def test_fp16_actor_full_size(aq, name, batch):
     """The benchmark's shapes and tile configurations; the oracle checks a sample of the rows."""
     _say(f"fp16_actor_full_size {name} batch={batch}")
@@ -159,7 +159,8 @@ def test_fp16_actor_full_size(aq, name, batch):
     actions, outs = _run_gpu(aq, net, params, obs)
     rng = np.random.default_rng(9)
     n_s = 6 if name == "cfg4" else 48
-    rows = np.unique(np.concatenate([[0, 31, 32, 127, 128, batch - 1], rng.integers(0, batch, n_s)]))
+    rows = np.unique(np.concatenate([np.minimum([0, 31, 32, 127, 128, batch - 1], batch - 1),
+                                     rng.integers(0, batch, n_s)]))
     _check(net, params, obs[rows], actions[rows], [o.reshape(batch, -1)[rows] for o in outs])
 
 
