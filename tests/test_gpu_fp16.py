@@ -201,6 +201,52 @@ def test_fp16_actor_unaligned_buffers(aq, name):
     P.close()
 
 
+@pytest.mark.parametrize("name", ["cfg2", "conv_small"])
+def test_fp16_actor_graph_replays_match_eager(aq, name):
+    """The benchmark replays conversion + forward from a HIP graph; every replay, with eager work of the
+    program's own in between, must reproduce the eager actions bit for bit."""
+    _say(f"fp16_actor_graph_replays {name}")
+    net = _nets()[name]
+    batch = 260
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    P = aq.Policy(net)
+    w, b, g, be = U.upload_params(params)
+    A = synth.action_dim(net)
+    argmax = net["head"] == "argmax"
+    shape, dt = ((batch,), torch.int32) if argmax else ((batch, A), torch.float32)
+    d_obs = U.to_dev(obs)
+    out = torch.zeros(shape, dtype=dt, device=U.DEV)
+
+    def body():
+        P.convert_params_fp16(w, b, g, be)
+        P.policy_forward_fp16(d_obs, out, None)
+
+    body()  # allocates the parameter storage and the activation buffers
+    torch.cuda.synchronize()
+    eager = out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        body()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr):
+        body()
+    for rep in range(3):
+        out.zero_()
+        scratch = torch.zeros(shape, dtype=dt, device=U.DEV)
+        P.policy_forward_fp16(d_obs, scratch, None)
+        torch.cuda.synchronize()
+        gr.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep}"
+        assert torch.equal(scratch, eager)
+        assert P.policy_status() == aq.OK
+    P.close()
+
+
 def test_fp16_actor_errors_and_nonfinite(aq):
     _say("fp16_actor_errors")
     net = _nets()["argmax_mlp"]
