@@ -204,38 +204,57 @@ __global__ __launch_bounds__(256, 2) void k_layer_fp16(const Fp16Layer L, const 
 
     h8 wc[4][NB], wn[4][NB];  // weights of chunks c, c + 1
     h8 xn[MT];                 // activations of chunk c + 1
-    load_w(0, wc);
-    load_x(0, xn);
-    store_x(0, xn);
-    __syncthreads();
-    for (int c = 0; c < KC; ++c) {
-        const bool more = c + 1 < KC;
-        {
-            const int cn = more ? c + 1 : c;  // (clamped: loaded again, not used)
-            load_w(cn, wn);
-            load_x(cn, xn);
-        }
-        if (wave_on) {
-            const _Float16* xb = xs + (c & 1) * XBUF;
+    auto compute = [&](int buf, const h8 (&w)[4][NB]) __attribute__((always_inline)) {
+        const _Float16* xb = xs + buf * XBUF;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                h8 bx[MT];
+        for (int s = 0; s < 4; ++s) {
+            h8 bx[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                bx[mt] = *(const h8*)&xb[(mt * 32 + (lane & 31)) * HLD + s * 16 + 8 * (lane >> 5)];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                    bx[mt] = *(const h8*)&xb[(mt * 32 + (lane & 31)) * HLD + s * 16 + 8 * (lane >> 5)];
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-                        acc[nb][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wc[s][nb], bx[mt], acc[nb][mt], 0, 0, 0);
-            }
+                    acc[nb][mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w[s][nb], bx[mt], acc[nb][mt], 0, 0, 0);
         }
-        if (more) store_x((c + 1) & 1, xn);
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) wc[s][nb] = wn[s][nb];
+    };
+    if (MT < 4 && KC <= 2) {  // (the 128-row tile has no registers for it and never meets a short K)
+        // short K (first layers: 17 or 67 observation features): everything is requested at once and both
+        // LDS buffers are filled before the only barrier
+        h8 x1[MT];
+        load_w(0, wc);
+        load_w(KC - 1, wn);
+        load_x(0, xn);
+        load_x(KC - 1, x1);
+        store_x(0, xn);
+        store_x(1, x1);
         __syncthreads();
+        if (wave_on) {
+            compute(0, wc);
+            if (KC == 2) compute(1, wn);
+        }
+        __syncthreads();  // the epilogue reuses the buffers
+    } else {
+        load_w(0, wc);
+        load_x(0, xn);
+        store_x(0, xn);
+        __syncthreads();
+        for (int c = 0; c < KC; ++c) {
+            const bool more = c + 1 < KC;
+            {
+                const int cn = more ? c + 1 : c;  // (clamped: loaded again, not used)
+                load_w(cn, wn);
+                load_x(cn, xn);
+            }
+            if (wave_on) compute(c & 1, wc);
+            if (more) store_x((c + 1) & 1, xn);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) wc[s][nb] = wn[s][nb];
+            __syncthreads();
+        }
     }
     if (!wave_on) return;
 
@@ -598,7 +617,7 @@ aq_status launch_layer_fp16(const Fp16Layer& L, const void* in, int in_mode, voi
         return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
     }
     if (in_mode == 0 && L.NT > HW && wgs(4, 2) >= 512) launch_layer_cfg<4, 2>(L, in, in_mode, piece, o, rows, st);
-    else if (L.NT > HW && wgs(2, 2) >= 256) launch_layer_cfg<2, 2>(L, in, in_mode, piece, o, rows, st);
+    else if (in_mode == 0 && L.NT > HW && wgs(2, 2) >= 256) launch_layer_cfg<2, 2>(L, in, in_mode, piece, o, rows, st);
     else launch_layer_cfg<1, 1>(L, in, in_mode, piece, o, rows, st);
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
