@@ -367,10 +367,15 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const int8_t* in = buf_in;
         int8_t* out = buf_out;
 
-        // This layer's per-channel constants were requested one layer ago (layer 0: just above);
-        // park them in LDS for the epilogue.  The barrier after the first MFMA pass publishes them.
+        // This layer's per-channel constants.  Doubled constant area: they were parked in the other half
+        // before the barrier that ended the previous layer.  Single area (wide layers): it still held
+        // the previous layer's constants until that barrier, so they are requested now (layer 0: at the
+        // top of the kernel), ride in registers through the first MFMA pass only, and are parked after
+        // it; the barrier there publishes them.  (Requested before the previous layer's epilogue they
+        // would have to be kept across it, which the register budget turns into a scratch store that
+        // waits for the load.)
         int32_t* cstl = cst + (l & 1) * cst_half;
-        if (!cst_dbl) park_consts(L.pieces, tid, cstl, cv0, cv1);
+        if (!cst_dbl && l > 0) load_consts(L, tid, cv0, cv1);
         const CPtrs C{cstl, cstl + Np, L.rshift, cstl + 2 * Np, cstl + 3 * Np, (const float*)(cstl + Np)};
         const float* c_gamma = (const float*)(cstl + 2 * Np);
         const float* c_beta = (const float*)(cstl + 3 * Np);
@@ -417,12 +422,15 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 }
             }
             // ... and, on the last pass, the next layer's constants
-            if (!last && g0 + FW >= ngroups) {
+            if (cst_dbl && !last && g0 + FW >= ngroups) {
                 const LayerView vn = layer_view(an, l + 1, n_layers);
                 load_consts(vn, tid, cv0, cv1);
                 pieces_next = vn.pieces;
             }
-            if (g0 == 0 && !cst_dbl) lds_barrier();
+            if (g0 == 0 && !cst_dbl) {
+                park_consts(L.pieces, tid, cstl, cv0, cv1);
+                lds_barrier();
+            }
             if (!ln) {
                 if (active) {
                     const int m0 = mrow;
@@ -598,7 +606,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
         const int8_t* in = buf_in;
         int32_t* cstl = cst + (l & 1) * cst_half;
-        if (!cst_dbl) park_consts(L.pieces, tid, cstl, cv0, cv1);
+        if (!cst_dbl && l > 0) load_consts(L, tid, cv0, cv1);  // parked below, after the MFMAs
         const CPtrs C{cstl, cstl + Np, L.rshift, cstl + 2 * Np, cstl + 3 * Np, (const float*)(cstl + Np)};
         // Everything below depends on the thread index only; left alone, the compiler computes it at
         // the top of the kernel and keeps it in registers through every layer.  The empty asm hides
@@ -624,6 +632,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
             for (int r = 0; r < 16; ++r) mine[r * 64] = pacc[0][0][r];
             if (ASYM) mine[16 * 64] = prs[0][0];
         }
+        if (!cst_dbl) park_consts(L.pieces, tid, cstl, cv0, cv1);
         lds_barrier();  // partial sums and this layer's constants are in LDS; the layer's input is free
         // y rows go where the layer's input was (stride Np + 1 floats keeps the banks apart)
         float* yrow = (float*)buf_in;
