@@ -226,9 +226,12 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         }
     }
     // ... and its per-channel constants
+    // (doubled constant area only; with a single area every wave fetches its own constants, see below)
     v4i cv0 = {0, 0, 0, 0}, cv1 = cv0;
-    if (tid < c.pieces0) cv0 = ((gv4i_ptr)c.pack0)[tid];
-    if (tid + FT < c.pieces0) cv1 = ((gv4i_ptr)c.pack0)[tid + FT];
+    if (cst_dbl) {
+        if (tid < c.pieces0) cv0 = ((gv4i_ptr)c.pack0)[tid];
+        if (tid + FT < c.pieces0) cv1 = ((gv4i_ptr)c.pack0)[tid + FT];
+    }
 
     // observation quantize: a0 = clamp(round(x / s0) + z0, 0, 255), kept in the signed domain
     {
@@ -368,14 +371,12 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         int8_t* out = buf_out;
 
         // This layer's per-channel constants.  Doubled constant area: they were parked in the other half
-        // before the barrier that ended the previous layer.  Single area (wide layers): it still held
-        // the previous layer's constants until that barrier, so they are requested now (layer 0: at the
-        // top of the kernel), ride in registers through the first MFMA pass only, and are parked after
-        // it; the barrier there publishes them.  (Requested before the previous layer's epilogue they
-        // would have to be kept across it, which the register budget turns into a scratch store that
-        // waits for the load.)
+        // before the barrier that ended the previous layer.  Single area (wide layers): an epilogue only
+        // reads the constants of its own wave's features, so every wave requests that slice (one
+        // 16-byte piece per lane) at the start of each MFMA pass and parks it after the pass: nothing
+        // is shared, no barrier is needed, and a wave that finishes its MFMA pass early goes straight
+        // on to its epilogue while the other wave of its SIMD still has the matrix pipe.
         int32_t* cstl = cst + (l & 1) * cst_half;
-        if (!cst_dbl && l > 0) load_consts(L, tid, cv0, cv1);
         const CPtrs C{cstl, cstl + Np, L.rshift, cstl + 2 * Np, cstl + 3 * Np, (const float*)(cstl + Np)};
         const float* c_gamma = (const float*)(cstl + 2 * Np);
         const float* c_beta = (const float*)(cstl + 3 * Np);
@@ -395,6 +396,16 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 rs[mt] = zero16();
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) acc[nb][mt] = zero16();
+            }
+            v4i cw = {0, 0, 0, 0};
+            int cw_off = -1;  // word offset of this lane's piece within the constant pack, or none
+            if (!cst_dbl && active) {
+                constexpr int PER = 8 * NB;  // pieces per array in the slice of this wave's NB tiles
+                const int arr = lane / PER, w0 = 32 * NB * grp + 4 * (lane % PER);
+                if (arr < 4 && w0 < Np) {
+                    cw_off = arr * Np + w0;
+                    cw = L.pack[cw_off >> 2];
+                }
             }
             if (active) {
                 gv4i_ptr wptr[NB];
@@ -427,9 +438,10 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 load_consts(vn, tid, cv0, cv1);
                 pieces_next = vn.pieces;
             }
-            if (g0 == 0 && !cst_dbl) {
-                park_consts(L.pieces, tid, cstl, cv0, cv1);
-                lds_barrier();
+            if (!cst_dbl) {
+                if (cw_off >= 0) *(v4i*)(cstl + cw_off) = cw;
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_wave_barrier();
             }
             if (!ln) {
                 if (active) {
@@ -606,7 +618,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
         const int8_t* in = buf_in;
         int32_t* cstl = cst + (l & 1) * cst_half;
-        if (!cst_dbl && l > 0) load_consts(L, tid, cv0, cv1);  // parked below, after the MFMAs
+        if (!cst_dbl) load_consts(L, tid, cv0, cv1);  // parked below, after the MFMAs
         const CPtrs C{cstl, cstl + Np, L.rshift, cstl + 2 * Np, cstl + 3 * Np, (const float*)(cstl + Np)};
         // Everything below depends on the thread index only; left alone, the compiler computes it at
         // the top of the kernel and keeps it in registers through every layer.  The empty asm hides
