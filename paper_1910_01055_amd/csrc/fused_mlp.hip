@@ -77,7 +77,7 @@ bool make_plan(const FwdArgs& a, Plan* p) {
         q.half = cd.half;
         // (a doubled constant area when everything still fits in 64 KB: small networks, where the
         // barrier it saves per layer is a visible share of the time)
-        q.cst_dbl = fused_lds_bytes(32 * cd.mt, q.ld, q.cst_n, true) + PART_BYTES <= 64 * 1024;
+        q.cst_dbl = cd.nb != 2 && fused_lds_bytes(32 * cd.mt, q.ld, q.cst_n, true) + PART_BYTES <= 64 * 1024;
         q.lds = fused_lds_bytes(32 * cd.mt, q.ld, q.cst_n, q.cst_dbl != 0);
         q.part_off = -1;
         // partial sums of a narrow last layer: in the idle activation buffer if it is large enough,
