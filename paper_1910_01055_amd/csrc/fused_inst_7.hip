@@ -1,8 +1,8 @@
-// Explicit instantiation of one fused-MLP kernel variant (rows = 32 * 4, 1 feature tile(s) per wave,
-// per-tensor asymmetric weights), with and without intermediate taps.
+// Explicit instantiation of one fused-MLP kernel variant (16 rows per workgroup, symmetric weights),
+// with and without intermediate taps.
 #include "fused_mlp.hpp"
 
 namespace aq {
-AQ_FUSED_INST(4, 1, true, false, false);
-AQ_FUSED_INST(4, 1, true, true, false);
+AQ_FUSED_INST(1, 1, false, false, true);
+AQ_FUSED_INST(1, 1, false, true, true);
 }  // namespace aq

@@ -18,8 +18,6 @@ AQ_FUSED_DECL(1, 1, true, false, false);
 AQ_FUSED_DECL(1, 1, true, true, false);
 AQ_FUSED_DECL(2, 1, true, false, false);
 AQ_FUSED_DECL(2, 1, true, true, false);
-AQ_FUSED_DECL(4, 1, true, false, false);
-AQ_FUSED_DECL(4, 1, true, true, false);
 AQ_FUSED_DECL(1, 1, false, false, true);
 AQ_FUSED_DECL(1, 1, false, true, true);
 AQ_FUSED_DECL(1, 1, true, false, true);
@@ -69,7 +67,7 @@ bool make_plan(const FwdArgs& a, Plan* p) {
     double best = 0.0;
     bool found = false;
     for (const Cand& cd : cands) {
-        if (cd.mt == 4 && nb_full != 1) continue;
+        if (cd.mt == 4 && (nb_full != 1 || a.net.asym)) continue;  // (the asymmetric 128-row variant does not fit the registers)
         if (!ln_fits(cd.nb)) continue;
         Plan q = *p;
         q.mt = cd.mt;
@@ -77,7 +75,7 @@ bool make_plan(const FwdArgs& a, Plan* p) {
         q.half = cd.half;
         // (a doubled constant area when everything still fits in 64 KB: small networks, where the
         // barrier it saves per layer is a visible share of the time)
-        q.cst_dbl = cd.nb != 2 && fused_lds_bytes(32 * cd.mt, q.ld, q.cst_n, true) + PART_BYTES <= 64 * 1024;
+        q.cst_dbl = cd.nb != 2 && cd.mt != 4 && fused_lds_bytes(32 * cd.mt, q.ld, q.cst_n, true) + PART_BYTES <= 64 * 1024;
         q.lds = fused_lds_bytes(32 * cd.mt, q.ld, q.cst_n, q.cst_dbl != 0);
         q.part_off = -1;
         // partial sums of a narrow last layer: in the idle activation buffer if it is large enough,
@@ -144,7 +142,7 @@ aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     if (as) {
         if (p.mt == 1) AQ_GO(1, 1, true, false);
         if (p.mt == 2) AQ_GO(2, 1, true, false);
-        AQ_GO(4, 1, true, false);
+        return AQ_ESHAPE;  // (no 128-row asymmetric variant: make_plan never picks it)
     }
     if (p.mt == 1) AQ_GO(1, 1, false, false);
     if (p.mt == 2) AQ_GO(2, 1, false, false);

@@ -207,8 +207,9 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
     int32_t* cst = (int32_t*)(red + 2 * FW * BROWS);
     // With LDS to spare the constant area is doubled: the next layer's constants are parked in the other
     // half before the barrier that ends the current layer, which saves the barrier that would publish them.
-    // (two feature tiles per wave are only planned for layers too wide for a doubled constant area)
-    const int cst_dbl = NB == 2 ? 0 : c.cst_dbl;
+    // (two feature tiles per wave are only planned for layers too wide for a doubled constant area, and
+    // 128-row workgroups never fit one)
+    const int cst_dbl = (NB == 2 || MT == 4) ? 0 : c.cst_dbl;
     const int cst_half = cst_dbl ? 4 * cst_n : 0;  // words between the two halves
     int32_t* net_lds = cst + 4 * cst_n + cst_half;
     const NetDev& an = *(const NetDev*)net_lds;  // valid after the first barrier

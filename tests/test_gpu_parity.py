@@ -211,11 +211,12 @@ def test_fused_row_tiles_large_batch(aq, name, batch):
     P.close()
 
 
-@pytest.mark.parametrize("name,batch,sample", [("cfg2", 262149, 400), ("paper_fc2048", 8200, 200), ("cfg4", 1100, 24)])
+@pytest.mark.parametrize("name,batch,sample", [("cfg2", 262149, 400), ("paper_fc2048", 8200, 200), ("cfg4", 1100, 24),
+                                               ("cfg1", 70001, 300)])
 def test_very_large_batches(aq, name, batch, sample):
     """Sizes well past the benchmark's: many rounds of workgroups per CU in the fused kernel, the 8-wave
-    tile of the per-layer kernel on 2048-wide layers, and the convolution path at several hundred
-    thousand output positions; sampled rows against the oracle, every row for the stated invariants."""
+    tile of the per-layer kernel on 2048-wide layers, the convolution path at several hundred
+    thousand output positions, and per-tensor asymmetric weights on 64-row workgroups; sampled rows against the oracle, every row for the stated invariants."""
     _say(f"very_large_batches {name} batch={batch}")
     net = synth.net_config(name)
     params = synth.make_params(net, nonzero_bias=True)
