@@ -330,7 +330,10 @@ __device__ __forceinline__ void epi_hidden_wave(const int N, const int NT, const
                     int code;
                     if (FAST) code = min(max((__mulhi(val, Mv[i]) + Zv[i]) >> Sv[i], lo), 255);
                     else code = requant_code(val, Mv[i], Sv[i], z_out, lo);
-                    if (n0 + i >= N) code = 128;  // padding features are zero in the signed domain
+                    // Padding features are zero in the signed domain where that matters: the per-tensor
+                    // scheme sums whole padded rows of activations for its zero-point term.  With symmetric
+                    // weights a padding column only ever meets zero weights, so its code is left as it comes.
+                    if (ASYM && n0 + i >= N) code = 128;
                     if (TAPS) {
                         if (T.act && row_ok && n0 + i < N) T.act[row * N + n0 + i] = (uint8_t)code;
                     }
