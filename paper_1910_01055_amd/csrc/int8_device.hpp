@@ -295,6 +295,13 @@ __device__ __forceinline__ QuadConsts load_quad_consts(const CPtrs& C, int n0) {
 // FAST: every channel has 33 <= r <= 54, so (acc*M0 + 2^(r-1)) >> r + z_out collapses to
 // (mulhi(acc, M0) + rz) >> sh with rz = 2^(r-33) + (z_out << sh), sh = r - 32 (same integers).
 // HALF: the tiles were folded by fold_rows16 (two quads per tile, `hh` = this lane's half).
+// clamp(x, lo, hi) for lo <= hi as one instruction: the median of the three
+__device__ __forceinline__ int clamp_code(int x, int lo_v, int hi_s) {
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo_v), "s"(hi_s));
+    return r;
+}
+
 template <int MT, int NB, bool ASYM, bool TAPS, bool FAST, bool HALF = false>
 __device__ __forceinline__ void epi_hidden_wave(const int N, const int NT, const LayerTaps& T, const CPtrs& C,
                                                 v16i (&acc)[NB][MT], v16i (&rs)[MT], int zw_s, int grp, int g,
@@ -306,6 +313,11 @@ __device__ __forceinline__ void epi_hidden_wave(const int N, const int NT, const
     auto n0_of = [&](int q) { return (grp * NB + q / QT) * 32 + 8 * (q % QT + (HALF ? 2 * hh : 0)) + 4 * g; };
     auto valid = [&](int q) { return grp * NB + q / QT < NT; };
     QuadConsts cur = load_quad_consts<FAST>(C, valid(0) ? n0_of(0) : 0);
+    // clamp bounds as operands of the three-input median: one vector register, one scalar (the
+    // instruction takes a single scalar source)
+    int lo_v = lo;
+    asm volatile("" : "+v"(lo_v));
+    const int c255 = 255;
     static_for<0, NQ>([&](auto q_c) __attribute__((always_inline)) {
         constexpr int q = decltype(q_c)::value;
         constexpr int nb = q / QT, j = q % QT;
@@ -328,7 +340,7 @@ __device__ __forceinline__ void epi_hidden_wave(const int N, const int NT, const
                         if (T.acc && row_ok && n0 + i < N) T.acc[row * N + n0 + i] = val;
                     }
                     int code;
-                    if (FAST) code = min(max((__mulhi(val, Mv[i]) + Zv[i]) >> Sv[i], lo), 255);
+                    if (FAST) code = clamp_code((__mulhi(val, Mv[i]) + Zv[i]) >> Sv[i], lo_v, c255);
                     else code = requant_code(val, Mv[i], Sv[i], z_out, lo);
                     // Padding features are zero in the signed domain where that matters: the per-tensor
                     // scheme sums whole padded rows of activations for its zero-point term.  With symmetric
