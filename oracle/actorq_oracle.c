@@ -59,7 +59,9 @@ static int32_t rint_clamp(float v, int32_t lo, int32_t hi) {
  * default 2^n - 1 reading (error <= s/2 everywhere) or 256 for the literal
  * 2^n.  All arithmetic in fp32, IEEE division, round-half-even.
  * -------------------------------------------------------------------- */
-int orc_qparams_asym(const float* w, int64_t n, float qdenom, float* scale, int32_t* zp) {
+/* n-bit form (Sec. 3.2 states Q_n for a general n; App. on quantization-aware training sweeps n below 8):
+ * qdenom = 2^n - 1 or 2^n as above, codes and zero-point in [0, qmax] with qmax = 2^n - 1. */
+int orc_qparams_asym_n(const float* w, int64_t n, float qdenom, int32_t qmax, float* scale, int32_t* zp) {
     float lo = 0.0f, hi = 0.0f; /* min(W,0), max(W,0): zero is always inside */
     for (int64_t i = 0; i < n; ++i) {
         if (!isfinite(w[i])) return ORC_ENONFINITE;
@@ -69,14 +71,22 @@ int orc_qparams_asym(const float* w, int64_t n, float qdenom, float* scale, int3
     float s = (hi - lo) / qdenom;
     if (hi == lo) s = 1.0f;
     *scale = s;
-    *zp = rint_clamp(-lo / s, 0, 255);
+    *zp = rint_clamp(-lo / s, 0, qmax);
     return ORC_OK;
 }
 
-/* q = clamp(round(W / s) + z, 0, 255), unsigned 8-bit codes. */
-void orc_quantize_asym(const float* w, int64_t n, float scale, int32_t zp, uint8_t* q) {
+int orc_qparams_asym(const float* w, int64_t n, float qdenom, float* scale, int32_t* zp) {
+    return orc_qparams_asym_n(w, n, qdenom, 255, scale, zp);
+}
+
+/* q = clamp(round(W / s) + z, 0, qmax), unsigned codes (8-bit containers). */
+void orc_quantize_asym_n(const float* w, int64_t n, float scale, int32_t zp, int32_t qmax, uint8_t* q) {
     for (int64_t i = 0; i < n; ++i)
-        q[i] = (uint8_t)(rint_clamp(w[i] / scale, -zp, 255 - zp) + zp);
+        q[i] = (uint8_t)(rint_clamp(w[i] / scale, -zp, qmax - zp) + zp);
+}
+
+void orc_quantize_asym(const float* w, int64_t n, float scale, int32_t zp, uint8_t* q) {
+    orc_quantize_asym_n(w, n, scale, zp, 255, q);
 }
 
 /* D(W_q, delta) = delta * (W_q - z) (Sec. 3.2 dequantization with the zero-point reading). */
@@ -86,7 +96,8 @@ void orc_dequantize_asym(const uint8_t* q, int64_t n, float scale, int32_t zp, f
 
 /* Per-output-channel symmetric: each row n of W[rows][cols] gets
  * s[n] = max_k |W[n,k]| / 127 (all-zero row: s = 1), codes in [-127, 127]. */
-int orc_quantize_sym_rows(const float* w, int64_t rows, int64_t cols, float* scales, int8_t* q) {
+/* n-bit form: s[n] = max|W| / qw, codes in [-qw, qw], qw = 2^(n-1) - 1 (127 for 8 bits). */
+int orc_quantize_sym_rows_n(const float* w, int64_t rows, int64_t cols, int32_t qw, float* scales, int8_t* q) {
     for (int64_t r = 0; r < rows; ++r) {
         float m = 0.0f;
         for (int64_t c = 0; c < cols; ++c) {
@@ -95,13 +106,17 @@ int orc_quantize_sym_rows(const float* w, int64_t rows, int64_t cols, float* sca
             float a = fabsf(v);
             if (a > m) m = a;
         }
-        float s = m / 127.0f;
+        float s = m / (float)qw;
         if (m == 0.0f) s = 1.0f;
         scales[r] = s;
         for (int64_t c = 0; c < cols; ++c)
-            q[r * cols + c] = (int8_t)rint_clamp(w[r * cols + c] / s, -127, 127);
+            q[r * cols + c] = (int8_t)rint_clamp(w[r * cols + c] / s, -qw, qw);
     }
     return ORC_OK;
+}
+
+int orc_quantize_sym_rows(const float* w, int64_t rows, int64_t cols, float* scales, int8_t* q) {
+    return orc_quantize_sym_rows_n(w, rows, cols, 127, scales, q);
 }
 
 void orc_dequantize_sym_rows(const int8_t* q, int64_t rows, int64_t cols, const float* scales, float* w) {

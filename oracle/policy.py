@@ -41,18 +41,27 @@ def _chk(rc, what):
         raise ValueError(f"oracle {what} failed with status {rc}")
 
 
-def c_qparams_asym(w, qdenom=255.0):
+def c_qparams_asym(w, qdenom=255.0, qmax=255):
+    """qdenom = 2^n - 1 (default reading) or 2^n (literal); qmax = 2^n - 1 is the largest code."""
     w = np.ascontiguousarray(w, np.float32).ravel()
     s, z = _f32(), _i32()
-    _chk(lib().orc_qparams_asym(_p(w, _f32), _i64(w.size), _f32(qdenom), C.byref(s), C.byref(z)), "qparams_asym")
+    _chk(lib().orc_qparams_asym_n(_p(w, _f32), _i64(w.size), _f32(qdenom), _i32(qmax), C.byref(s), C.byref(z)),
+         "qparams_asym")
     return np.float32(s.value), int(z.value)
 
 
-def c_quantize_asym(w, scale, zp):
+def c_quantize_asym(w, scale, zp, qmax=255):
     w = np.ascontiguousarray(w, np.float32)
     q = np.empty(w.shape, np.uint8)
-    lib().orc_quantize_asym(_p(w, _f32), _i64(w.size), _f32(scale), _i32(zp), _p(q, _u8))
+    lib().orc_quantize_asym_n(_p(w, _f32), _i64(w.size), _f32(scale), _i32(zp), _i32(qmax), _p(q, _u8))
     return q
+
+
+def weight_levels(bits, qdenom=255):
+    """(denominator of delta, largest unsigned code, largest symmetric code) of n-bit weights; the
+    8-bit denominator says which reading of Sec. 3.2 is in force (255: 2^n - 1, 256: the literal 2^n)."""
+    qmax = (1 << bits) - 1
+    return float(qmax + 1 if int(qdenom) == 256 else qmax), qmax, (1 << (bits - 1)) - 1
 
 
 def c_dequantize_asym(q, scale, zp):
@@ -62,12 +71,12 @@ def c_dequantize_asym(q, scale, zp):
     return w
 
 
-def c_quantize_sym_rows(w2d):
+def c_quantize_sym_rows(w2d, qw=127):
     w2d = np.ascontiguousarray(w2d, np.float32)
     rows, cols = w2d.shape
     s = np.empty(rows, np.float32)
     q = np.empty((rows, cols), np.int8)
-    _chk(lib().orc_quantize_sym_rows(_p(w2d, _f32), _i64(rows), _i64(cols), _p(s, _f32), _p(q, _i8)),
+    _chk(lib().orc_quantize_sym_rows_n(_p(w2d, _f32), _i64(rows), _i64(cols), _i32(qw), _p(s, _f32), _p(q, _i8)),
          "quantize_sym_rows")
     return q, s
 
@@ -321,6 +330,8 @@ class OraclePolicy:
     def quantize_params(self, params, act_ranges):
         """act_ranges[i] = (lo, hi) for the input (i = 0) and each hidden output."""
         qd = float(self.net["qdenom"])
+        # weights at n bits (activations stay at 8): Sec. 3.2's Q_n with n below 8, codes in 8-bit containers
+        wd, wmax, wsym = weight_levels(int(self.net.get("wbits", 8)), self.net["qdenom"])
         nl = len(self.layers)
         assert len(act_ranges) == nl
         act_q = []
@@ -334,12 +345,12 @@ class OraclePolicy:
             w = p["w"]
             n_out = w.shape[0]
             if self.net["wscheme"] == "tensor_asym_u8":
-                s, z = c_qparams_asym(w, qd)
-                codes = c_quantize_asym(w, s, z)
+                s, z = c_qparams_asym(w, wd, wmax)
+                codes = c_quantize_asym(w, s, z, wmax)
                 s_w = np.full(n_out, s, np.float32)
                 z_w = np.full(n_out, z, np.int32)
             else:
-                c2, s_w = c_quantize_sym_rows(w.reshape(n_out, -1))
+                c2, s_w = c_quantize_sym_rows(w.reshape(n_out, -1), wsym)
                 codes = c2.reshape(w.shape)
                 z_w = np.zeros(n_out, np.int32)
             s_in, z_in = act_q[i]

@@ -625,3 +625,73 @@ def test_fp16_actor_rounds_parameters_observation_and_every_operator_output():
     # ... and the half-precision actions track the full-precision policy's
     a32, _ = O.OraclePolicy(net).forward_fp32(params, obs)
     assert 0 < np.abs(t["actions"] - a32).max() < 2e-2
+
+
+# ---------------------------------------------------------------- weights below 8 bits (Sec. 3.2: Q_n for general n)
+@pytest.mark.parametrize("bits", [2, 3, 4, 5, 6, 7, 8])
+def test_n_bit_weight_quantizer_closed_forms(bits):
+    qd, qmax, qsym = O.weight_levels(bits)
+    assert (qd, qmax, qsym) == (float(2 ** bits - 1), 2 ** bits - 1, 2 ** (bits - 1) - 1)
+    assert O.weight_levels(bits, 256)[0] == float(2 ** bits)
+    # a ramp over exactly the code range quantizes to itself: delta = 1, zero-point 0
+    ramp = np.arange(qmax + 1, dtype=np.float32)
+    s, z = O.c_qparams_asym(ramp, qd, qmax)
+    assert (s, z) == (np.float32(1.0), 0)
+    assert np.array_equal(O.c_quantize_asym(ramp, s, z, qmax), np.arange(qmax + 1))
+    # hand case from the formula: W in [-1, 3]: delta = 4 / (2^n - 1), z = round(1 / delta) = round((2^n - 1) / 4)
+    w = np.array([-1.0, 0.0, 0.5, 3.0], np.float32)
+    s, z = O.c_qparams_asym(w, qd, qmax)
+    assert s == np.float32(4.0) / np.float32(qd)
+    z_exact = Fraction(2 ** bits - 1, 4)
+    assert z in (math.floor(z_exact), math.ceil(z_exact)) and abs(z - z_exact) <= Fraction(1, 2)
+    q = O.c_quantize_asym(w, s, z, qmax)
+    assert q[0] == 0 and q[1] == z and q[3] == qmax
+    # general tensors: at most 2^n levels, every code in range, zero maps to the zero-point, error <= delta / 2
+    rng = np.random.default_rng(100 + bits)
+    w = (rng.standard_normal(5000) * 0.3 + 0.1).astype(np.float32)
+    s, z = O.c_qparams_asym(w, qd, qmax)
+    q = O.c_quantize_asym(w, s, z, qmax).astype(np.int64)
+    assert q.min() >= 0 and q.max() <= qmax and len(np.unique(q)) <= 2 ** bits
+    assert q.min() == 0 and q.max() == qmax  # min/max calibration uses the whole range
+    assert O.c_quantize_asym(np.zeros(1, np.float32), s, z, qmax)[0] == z
+    deq = np.float64(s) * (q - z)
+    assert np.abs(deq - w).max() <= 0.5 * np.float64(s) * (1 + 1e-6)
+    # monotone and idempotent on its own grid
+    order = np.argsort(w)
+    assert np.all(np.diff(q[order]) >= 0)
+    assert np.array_equal(O.c_quantize_asym(deq.astype(np.float32), s, z, qmax), q)
+    # literal denominator 2^n: delta shrinks by (2^n - 1) / 2^n and the top of the range saturates
+    s_lit, z_lit = O.c_qparams_asym(w, float(2 ** bits), qmax)
+    assert s_lit == (np.float32(w.max()) - np.float32(w.min())) / np.float32(2 ** bits) and 0 <= z_lit <= qmax
+    # per-channel symmetric: codes in [-qsym, qsym], the largest magnitude of each row reaches +-qsym
+    w2 = rng.standard_normal((6, 40)).astype(np.float32)
+    w2[3] = 0.0
+    c, sc = O.c_quantize_sym_rows(w2, qsym)
+    assert np.abs(c).max() <= qsym
+    for r in range(6):
+        if r == 3:
+            assert sc[r] == 1.0 and not c[r].any()
+        else:
+            assert sc[r] == np.abs(w2[r]).max() / np.float32(qsym)
+            assert np.abs(c[r]).max() == qsym
+            assert np.array_equal(c[r], -O.c_quantize_sym_rows(-w2[r:r + 1], qsym)[0][0])
+            assert np.abs(np.float64(sc[r]) * c[r] - w2[r]).max() <= 0.5 * np.float64(sc[r]) * (1 + 1e-6)
+    if bits == 8:  # the 8-bit entry points are the same arithmetic
+        assert np.array_equal(O.c_quantize_sym_rows(w2)[0], c)
+        assert O.c_qparams_asym(w) == (s, z)
+
+
+def test_n_bit_policy_uses_fewer_weight_levels_and_tracks_fp32():
+    net = synth.net_config("cfg2")
+    params = synth.make_params(net)
+    obs = synth.make_obs(net, 64)
+    a32, ranges = O.OraclePolicy(net).forward_fp32(params, obs)
+    errs = {}
+    for bits in (4, 6, 8):
+        n2 = dict(net, wbits=bits)
+        pol = O.OraclePolicy(n2)
+        q = pol.quantize_params(params, ranges)
+        for layer in q:
+            assert np.abs(layer["codes"].astype(np.int64)).max() <= 2 ** (bits - 1) - 1
+        errs[bits] = np.abs(pol.forward_int8(obs)["actions"] - a32).max()
+    assert errs[8] < errs[6] < errs[4] < 0.5  # coarser weights, larger action error (reported, not pinned)
