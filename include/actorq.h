@@ -79,6 +79,10 @@ typedef struct {
     int32_t in_type;        /* aq_intype */
     int32_t qdenom;         /* denominator of delta in Sec. 3.2: 255 (= 2^8 - 1, default) or 256 (= 2^8, literal) */
     float ln_eps;           /* LayerNorm epsilon (biased variance, eps inside the square root) */
+    int32_t wbits;          /* weight precision n of Sec. 3.2's Q_n: 2..8, 0 = 8.  Below 8 the weight codes use
+                               [0, 2^n - 1] (per tensor) or [-(2^(n-1) - 1), 2^(n-1) - 1] (per channel) and still
+                               travel in 8-bit containers on the int8 matrix cores; delta's denominator is 2^n - 1,
+                               or 2^n when qdenom = 256.  Activations stay at 8 bits. */
 } aq_net;
 
 #define AQ_MAX_LAYERS 8
@@ -180,6 +184,9 @@ aq_status aq_policy_step_int8(aq_policy* p, const void* d_obs, int64_t batch, vo
  * d_workspace: at least 16 KiB of device memory the call may overwrite (partial ranges of the
  * workgroups).  Word 2 of it (int32) is a sticky flag: the call sets it to 1 when it meets a
  * non-finite input and never clears it, so zero it once before the first call.
+ * qdenom selects the precision n = 2..8 and the reading of delta's denominator: 2^n - 1 (255 for 8 bits, the
+ * default reading) or 2^n (256: the literal formula); codes lie in [0, 2^n - 1] resp. [-(2^(n-1) - 1),
+ * 2^(n-1) - 1] and are stored one per byte.  Any other value: AQ_EINVAL.
  * cols must be a multiple of 4 and d_w 16-byte aligned. */
 aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int32_t wscheme, int32_t qdenom,
                              void* d_codes, float* d_scale, int32_t* d_zp, void* d_workspace, void* stream);

@@ -35,7 +35,8 @@ class AqLayer(C.Structure):
 
 class AqNet(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(AqLayer)), ("head", C.c_int32),
-                ("wscheme", C.c_int32), ("in_type", C.c_int32), ("qdenom", C.c_int32), ("ln_eps", C.c_float)]
+                ("wscheme", C.c_int32), ("in_type", C.c_int32), ("qdenom", C.c_int32), ("ln_eps", C.c_float),
+                ("wbits", C.c_int32)]
 
 
 class AqRange(C.Structure):
@@ -129,7 +130,7 @@ def make_net(net: dict):
             arr[i] = AqLayer(KIND["conv"], l["in_h"], l["in_w"], l["in_c"], l["out_c"], l["kh"], l["kw"],
                              l["stride"], ACT[l["act"]])
     cnet = AqNet(n, arr, HEAD[net["head"]], WSCHEME[net["wscheme"]], INTYPE[net["in_type"]], int(net["qdenom"]),
-                 float(net["ln_eps"]))
+                 float(net["ln_eps"]), int(net.get("wbits", 0)))
     return cnet, arr
 
 

@@ -117,6 +117,7 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     if (net->in_type != AQ_IN_F32 && net->in_type != AQ_IN_U8) return AQ_EINVAL;
     if (net->qdenom != 255 && net->qdenom != 256) return AQ_EINVAL;
     if (!(net->ln_eps > 0.0f)) return AQ_EINVAL;
+    if (net->wbits != 0 && (net->wbits < 2 || net->wbits > 8)) return AQ_EINVAL;
     int dev_count = 0;
     if (hipGetDeviceCount(&dev_count) != hipSuccess || dev_count < 1) return AQ_EHIP;
 
@@ -244,6 +245,10 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         q.asym = p->h_net.asym;
         q.in_u8 = p->h_net.in_u8;
         q.qdenom = (float)net->qdenom;
+        const int wbits = net->wbits ? net->wbits : 8;
+        q.w_qmax = (1 << wbits) - 1;
+        q.w_qw = (1 << (wbits - 1)) - 1;
+        q.w_qdenom = net->qdenom == 256 ? (float)(q.w_qmax + 1) : (float)q.w_qmax;
         int row_blk = 0, cst_blk = 0, rng_blk = 0;
         for (int l = 0; l < net->n_layers; ++l) {
             const LayerBuf& b = p->L[l];
@@ -285,6 +290,7 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         mix(net->wscheme);
         mix(net->in_type);
         mix(net->qdenom);
+        mix(net->wbits ? net->wbits : 8);
         for (const auto& b : p->L) {
             mix(b.d.kind); mix(b.d.in_h); mix(b.d.in_w); mix(b.d.in_c); mix(b.d.out_c);
             mix(b.d.kh); mix(b.d.kw); mix(b.d.stride); mix(b.d.act);
@@ -471,13 +477,18 @@ extern "C" aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t 
                                         int32_t qdenom, void* d_codes, float* d_scale, int32_t* d_zp,
                                         void* d_workspace, void* stream) {
     if (!d_w || !d_codes || !d_scale || !d_zp || !d_workspace) return AQ_EINVAL;
-    if (rows < 0 || cols < 0 || (qdenom != 255 && qdenom != 256)) return AQ_EINVAL;
+    if (rows < 0 || cols < 0) return AQ_EINVAL;
+    // qdenom = 2^n - 1 (default reading) or 2^n (literal) for n = 2..8 bits
+    int bits = 0;
+    for (int n = 2; n <= 8; ++n)
+        if (qdenom == (1 << n) - 1 || qdenom == (1 << n)) bits = n;
+    if (bits == 0) return AQ_EINVAL;
     if (wscheme != AQ_W_TENSOR_ASYM_U8 && wscheme != AQ_W_CHANNEL_SYM_S8) return AQ_EINVAL;
     if (cols % 4 != 0 || ((uintptr_t)d_w & 15) || ((uintptr_t)d_codes & 3)) return AQ_ESHAPE;
     if (rows > 0x7fffffffLL || cols / 4 > 0x7fffffffLL) return AQ_ESHAPE;
     if (rows == 0 || cols == 0) return AQ_OK;
-    return launch_quantize_tensor(d_w, rows, cols, wscheme, (float)qdenom, d_codes, d_scale, d_zp,
-                                  (uint32_t*)d_workspace, as_stream(stream));
+    return launch_quantize_tensor(d_w, rows, cols, wscheme, (float)qdenom, (1 << bits) - 1, (1 << (bits - 1)) - 1,
+                                  d_codes, d_scale, d_zp, (uint32_t*)d_workspace, as_stream(stream));
 }
 
 extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,

@@ -220,7 +220,9 @@ struct QLayerTab {
 struct QTab {
     QLayerTab L[AQ_MAX_LAYERS];
     int n_layers, asym, in_u8;
-    float qdenom;
+    float qdenom;  // activations (8 bits)
+    float w_qdenom;  // weights at n bits: denominator of delta, largest unsigned and symmetric codes
+    int w_qmax, w_qw;
     int row_blks, cst_blks, rng_blks_total;
 };
 // The caller's fp32 parameters of one quantize pass (by value: they change from call to call).

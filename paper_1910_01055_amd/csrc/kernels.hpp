@@ -6,8 +6,9 @@ namespace aq {
 
 // ---- quantizer block (quantize.hip)
 aq_status launch_fill_u32(uint32_t* p, int n, uint32_t v, hipStream_t st);
+// qdenom, qmax (largest unsigned code) and qw (largest symmetric code) describe the n-bit code range
 aq_status launch_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int wscheme, float qdenom,
-                                 void* d_codes, float* d_scale, int32_t* d_zp, uint32_t* d_ws, hipStream_t st);
+                                 int qmax, int qw, void* d_codes, float* d_scale, int32_t* d_zp, uint32_t* d_ws, hipStream_t st);
 // The whole policy: activation parameters, weight ranges (per-tensor scheme), packed 8-bit weights and
 // per-channel constants of every layer, in three or four launches.
 aq_status launch_quantize_policy(const QTab* d_tab, const QTab& h_tab, const QPtrs& ptrs, const RangesArg& r,

@@ -21,11 +21,12 @@ __global__ void k_fill_u32(uint32_t* p, int n, uint32_t v) {
 __device__ __forceinline__ bool finite_f(float v) { return fabsf(v) <= FLT_MAX; }
 
 // Sec. 3.2: delta = (|min(W,0)| + |max(W,0)|) / D ; zero-point z = round(-lo / delta).
-__device__ __forceinline__ void asym_qparams(float hi, float nlo, float qdenom, float& s, int& z) {
+// (n bits: D = 2^n - 1 or 2^n, codes and zero-point in [0, qmax = 2^n - 1])
+__device__ __forceinline__ void asym_qparams(float hi, float nlo, float qdenom, int qmax, float& s, int& z) {
     float lo = -nlo;
     s = (hi - lo) / qdenom;
     if (hi == lo) s = 1.0f;
-    z = rint_clamp(-lo / s, 0, 255);
+    z = rint_clamp(-lo / s, 0, qmax);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(256) void k_range_partials(const float4* __restrict
 // comes from the last-level cache for tensors that fit it.
 __global__ __launch_bounds__(256) void k_quant_asym_flat(const float4* __restrict__ w4, int64_t n4,
                                                          const uint32_t* __restrict__ part, int n_part, float qdenom,
-                                                         uint32_t* __restrict__ codes, float* __restrict__ scale,
+                                                         int qmax, uint32_t* __restrict__ codes, float* __restrict__ scale,
                                                          int32_t* __restrict__ zp, uint32_t* __restrict__ flag) {
     float hi = 0.0f, nlo = 0.0f;
     int bad = 0;
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(256) void k_quant_asym_flat(const float4* __restric
     nlo = fmaxf(fmaxf(s_nlo[0], s_nlo[1]), fmaxf(s_nlo[2], s_nlo[3]));
     float s;
     int z;
-    asym_qparams(hi, nlo, qdenom, s, z);
+    asym_qparams(hi, nlo, qdenom, qmax, s, z);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         scale[0] = s;
         zp[0] = z;
@@ -157,13 +158,13 @@ __global__ __launch_bounds__(256) void k_quant_asym_flat(const float4* __restric
     const QuantScale qs = make_quant_scale(s);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
-        codes[i] = quant_code4(w4[i], qs, -z, 255 - z, z);
+        codes[i] = quant_code4(w4[i], qs, -z, qmax - z, z);
 }
 
 // per-channel symmetric codes, canonical order: one wavefront per row, the row lives in
 // registers (R float4 per lane) between the |w| reduction and the rounding.
 template <int R>
-__global__ __launch_bounds__(256) void k_quant_sym_rows_flat(const float4* __restrict__ w4, int64_t rows, int cols4,
+__global__ __launch_bounds__(256) void k_quant_sym_rows_flat(const float4* __restrict__ w4, int64_t rows, int cols4, int qw,
                                                              uint32_t* __restrict__ codes, float* __restrict__ scale,
                                                              int32_t* __restrict__ zp, uint32_t* __restrict__ mm) {
     const int lane = threadIdx.x & 63;
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_flat(const float4* __res
     }
     amax = wave_max(amax);
     bad = wave_or_i32(bad);
-    float s = amax / 127.0f;
+    float s = amax / (float)qw;
     if (amax == 0.0f) s = 1.0f;
     if (lane == 0) {
         scale[row] = s;
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_flat(const float4* __res
     for (int r = 0; r < R; ++r) {
         int c = lane + 64 * r;
         if (c < cols4) {
-            dst[c] = quant_code4(v[r], qs, -127, 127, 0);
+            dst[c] = quant_code4(v[r], qs, -qw, qw, 0);
         }
     }
 }
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_flat(const float4* __res
 // reduction and the rounding (still one pass over HBM).  Many small workgroups keep the memory
 // pipeline of every CU busy while others are in their arithmetic phase.
 template <int R>
-__global__ __launch_bounds__(256) void k_quant_sym_row_wg(const float4* __restrict__ w4, int cols4,
+__global__ __launch_bounds__(256) void k_quant_sym_row_wg(const float4* __restrict__ w4, int cols4, int qw,
                                                           uint32_t* __restrict__ codes, float* __restrict__ scale,
                                                           int32_t* __restrict__ zp, uint32_t* __restrict__ mm) {
     const int64_t row = blockIdx.x;
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(256) void k_quant_sym_row_wg(const float4* __restri
     if (bad) atomicOr(&mm[2], 1u);
     __syncthreads();
     amax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
-    float s = amax / 127.0f;
+    float s = amax / (float)qw;
     if (amax == 0.0f) s = 1.0f;
     if (threadIdx.x == 0) {
         scale[row] = s;
@@ -241,13 +242,13 @@ __global__ __launch_bounds__(256) void k_quant_sym_row_wg(const float4* __restri
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int c = threadIdx.x + 256 * r;
-        if (c < cols4) dst[c] = quant_code4(v[r], qs, -127, 127, 0);
+        if (c < cols4) dst[c] = quant_code4(v[r], qs, -qw, qw, 0);
     }
 }
 
 // rows too long for the register-resident kernel: one workgroup per row, the row is read twice
 // (the second read comes from cache for any realistic channel length).
-__global__ __launch_bounds__(256) void k_quant_sym_rows_long(const float4* __restrict__ w4, int64_t rows, int cols4,
+__global__ __launch_bounds__(256) void k_quant_sym_rows_long(const float4* __restrict__ w4, int64_t rows, int cols4, int qw,
                                                              uint32_t* __restrict__ codes, float* __restrict__ scale,
                                                              int32_t* __restrict__ zp, uint32_t* __restrict__ mm) {
     const int64_t row = blockIdx.x;
@@ -271,7 +272,7 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_long(const float4* __res
     __syncthreads();
     amax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
     bad = s_bad[0] | s_bad[1] | s_bad[2] | s_bad[3];
-    float s = amax / 127.0f;
+    float s = amax / (float)qw;
     if (amax == 0.0f) s = 1.0f;
     if (threadIdx.x == 0) {
         scale[row] = s;
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_long(const float4* __res
     uint32_t* dst = codes + row * cols4;
     const QuantScale qs = make_quant_scale(s);
     for (int c = threadIdx.x; c < cols4; c += 256) {
-        dst[c] = quant_code4(src[c], qs, -127, 127, 0);
+        dst[c] = quant_code4(src[c], qs, -qw, qw, 0);
     }
 }
 
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_long(const float4* __res
 // ---------------------------------------------------------------------------------------------
 template <bool SYM>
 __device__ __forceinline__ void quant_row_packed(const float* __restrict__ w, int n, int N, int K, int KS,
-                                                 float qdenom, const uint32_t* __restrict__ mm,
+                                                 float qdenom, int qmax, int qw, const uint32_t* __restrict__ mm,
                                                  int8_t* __restrict__ wp, float* __restrict__ s_w,
                                                  int32_t* __restrict__ z_w, int32_t* __restrict__ rowsum,
                                                  int* __restrict__ status) {
@@ -314,18 +315,18 @@ __device__ __forceinline__ void quant_row_packed(const float* __restrict__ w, in
         }
         amax = wave_max(amax);
         bad = wave_or_i32(bad);
-        s = amax / 127.0f;
+        s = amax / (float)qw;
         if (amax == 0.0f) s = 1.0f;
         if (bad && lane == 0) atomicOr(status, kStatNonFinite);
     } else {
-        asym_qparams(__uint_as_float(mm[0]), __uint_as_float(mm[1]), qdenom, s, z);
+        asym_qparams(__uint_as_float(mm[0]), __uint_as_float(mm[1]), qdenom, qmax, s, z);
         if (mm[2] && lane == 0) atomicOr(status, kStatNonFinite);
     }
     int8_t* tile_row = wp + ((int64_t)(n >> 5) * KS * 64 + (n & 31)) * 16;
     int sum = 0;
     const QuantScale qs = make_quant_scale(s);
     for (int k = lane; k < K; k += 64) {
-        int q = SYM ? quant_code(src[k], qs, -127, 127) : quant_code(src[k], qs, -z, 255 - z) + z - 128;
+        int q = SYM ? quant_code(src[k], qs, -qw, qw) : quant_code(src[k], qs, -z, qmax - z) + z - 128;
         sum += q;
         tile_row[((int64_t)(k >> 5) * 64 + 32 * ((k & 31) >> 4)) * 16 + (k & 15)] = (int8_t)q;
     }
@@ -371,7 +372,7 @@ __global__ void k_qp_prep(const QTab* __restrict__ tab, RangesArg r, ActQ* __res
     float nlo = -r.lo[i] > 0.0f ? -r.lo[i] : 0.0f;
     float s;
     int z;
-    asym_qparams(hi, nlo, tab->qdenom, s, z);
+    asym_qparams(hi, nlo, tab->qdenom, 255, s, z);  // activations stay at 8 bits
     actq[i].s = s;
     actq[i].z = z;
 }
@@ -469,7 +470,7 @@ __global__ __launch_bounds__(256) void k_qp_rows(const QTab* __restrict__ tab, c
     const int l = layer_of_block(t, blockIdx.x, 0);
     const QLayerTab& L = t.L[l];
     const int n = (blockIdx.x - L.row_blk0) * 4 + (threadIdx.x >> 6);
-    quant_row_packed<SYM>(p.w[l], n, L.N, L.K, L.KS, t.qdenom, mm + 4 * l, L.wp, L.s_w, L.z_w, L.rowsum, status);
+    quant_row_packed<SYM>(p.w[l], n, L.N, L.K, L.KS, t.w_qdenom, t.w_qmax, t.w_qw, mm + 4 * l, L.wp, L.s_w, L.z_w, L.rowsum, status);
 }
 
 __global__ __launch_bounds__(256) void k_qp_consts(const QTab* __restrict__ tab, const QPtrs p,
@@ -535,7 +536,7 @@ aq_status launch_fill_u32(uint32_t* p, int n, uint32_t v, hipStream_t st) {
 }
 
 aq_status launch_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int wscheme, float qdenom,
-                                 void* d_codes, float* d_scale, int32_t* d_zp, uint32_t* d_ws, hipStream_t st) {
+                                 int qmax, int qw, void* d_codes, float* d_scale, int32_t* d_zp, uint32_t* d_ws, hipStream_t st) {
     const int64_t n = rows * cols;
     const float4* w4 = (const float4*)d_w;
     uint32_t* c4 = (uint32_t*)d_codes;
@@ -545,22 +546,22 @@ aq_status launch_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, i
         const int g1 = grid_for(n4, 256 * 4, 1024);
         hipLaunchKernelGGL(k_range_partials, dim3(g1), dim3(256), 0, st, w4, n4, d_ws + 16);
         const int g2 = grid_for(n4, 256 * 4, 2048);
-        hipLaunchKernelGGL(k_quant_asym_flat, dim3(g2), dim3(256), 0, st, w4, n4, d_ws + 16, g1, qdenom, c4, d_scale,
+        hipLaunchKernelGGL(k_quant_asym_flat, dim3(g2), dim3(256), 0, st, w4, n4, d_ws + 16, g1, qdenom, qmax, c4, d_scale,
                            d_zp, d_ws + 2);
     } else {
         const int cols4 = (int)(cols / 4);
         if (cols4 <= 64) {
             hipLaunchKernelGGL(k_quant_sym_rows_flat<1>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, w4, rows,
-                               cols4, c4, d_scale, d_zp, d_ws);
+                               cols4, qw, c4, d_scale, d_zp, d_ws);
         } else {
 #define AQ_ROW_WG(R) \
-    hipLaunchKernelGGL(k_quant_sym_row_wg<R>, dim3((unsigned)rows), dim3(256), 0, st, w4, cols4, c4, d_scale, d_zp, d_ws)
+    hipLaunchKernelGGL(k_quant_sym_row_wg<R>, dim3((unsigned)rows), dim3(256), 0, st, w4, cols4, qw, c4, d_scale, d_zp, d_ws)
             if (cols4 <= 256) AQ_ROW_WG(1);
             else if (cols4 <= 512) AQ_ROW_WG(2);
             else if (cols4 <= 1024) AQ_ROW_WG(4);
             else if (cols4 <= 2048) AQ_ROW_WG(8);
             else
-                hipLaunchKernelGGL(k_quant_sym_rows_long, dim3((unsigned)rows), dim3(256), 0, st, w4, rows, cols4, c4,
+                hipLaunchKernelGGL(k_quant_sym_rows_long, dim3((unsigned)rows), dim3(256), 0, st, w4, rows, cols4, qw, c4,
                                    d_scale, d_zp, d_ws);
 #undef AQ_ROW_WG
         }

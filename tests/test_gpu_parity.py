@@ -44,6 +44,69 @@ def test_quantize_tensor(aq, rows, cols, scheme):
     assert int(ws[2]) == 0
 
 
+@pytest.mark.parametrize("qdenom", [3, 7, 15, 16, 31, 63, 64, 127])
+@pytest.mark.parametrize("scheme", ["tensor_asym_u8", "channel_sym_s8"])
+def test_quantize_tensor_below_8_bits(aq, qdenom, scheme):
+    """Sec. 3.2's Q_n for n < 8: qdenom = 2^n - 1 or 2^n selects the precision; codes bit-exact."""
+    _say(f"quantize_tensor_below_8_bits qdenom={qdenom} {scheme}")
+    bits = int(np.ceil(np.log2(qdenom + 1))) if (qdenom & (qdenom + 1)) == 0 else int(np.log2(qdenom))
+    qmax, qsym = 2 ** bits - 1, 2 ** (bits - 1) - 1
+    for rows, cols in ((37, 132), (5, 4100), (300, 1024)):
+        w = synth.quant_tensor(rows * cols, seed=synth.QUANT_TENSOR_SEED + qdenom).reshape(rows, cols)
+        w[1] = 0.0
+        asym = scheme == "tensor_asym_u8"
+        codes = torch.zeros(rows, cols, dtype=torch.uint8 if asym else torch.int8, device=U.DEV)
+        ns = 1 if asym else rows
+        scale = torch.zeros(ns, dtype=torch.float32, device=U.DEV)
+        zp = torch.full((ns,), -1, dtype=torch.int32, device=U.DEV)
+        ws = torch.zeros(4096, dtype=torch.int32, device=U.DEV)
+        aq.quantize_tensor(U.to_dev(w), rows, cols, scheme, qdenom, codes, scale, zp, ws)
+        torch.cuda.synchronize()
+        got = codes.cpu().numpy()
+        if asym:
+            s, z = O.c_qparams_asym(w, float(qdenom), qmax)
+            ref = O.c_quantize_asym(w, s, z, qmax)
+            assert scale.cpu().numpy()[0].view(np.uint32) == np.float32(s).view(np.uint32) and int(zp[0]) == z
+            assert got.max() <= qmax
+        else:
+            ref, s = O.c_quantize_sym_rows(w, qsym)
+            assert np.array_equal(scale.cpu().numpy().view(np.uint32), s.view(np.uint32))
+            assert np.abs(got.astype(np.int32)).max() == qsym
+        assert np.array_equal(got, ref)
+    with pytest.raises(aq.AqError):
+        aq.quantize_tensor(U.to_dev(w), rows, cols, scheme, 100, codes, scale, zp, ws)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "conv_small", "literal256"])
+@pytest.mark.parametrize("wbits", [2, 4, 6])
+@pytest.mark.parametrize("path", [0, 2])
+def test_forward_with_weights_below_8_bits(aq, name, wbits, path):
+    """The whole path with n-bit weight codes (8-bit containers, 8-bit activations): every stage against
+    the oracle as at 8 bits, and the codes really use no more than 2^n levels."""
+    _say(f"forward_with_weights_below_8_bits {name} wbits={wbits} path={path}")
+    net = dict(_nets()[name], wbits=wbits)
+    params = synth.make_params(net, nonzero_bias=True)
+    batch = 150
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs)
+    for q in pol.q:
+        c = q["codes"].astype(np.int64)
+        assert c.max() - c.min() <= 2 ** wbits - 1
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    U.check_quantized_params(aq, P, pol, net)
+    P.policy_set_path(path)
+    actions, t = U.gpu_forward(P, net, obs)
+    U.compare_forward(net, pol, obs, actions, t)
+    # a blob of this policy does not load into an 8-bit handle of the same network
+    blob = torch.zeros(P.policy_blob_size(), dtype=torch.uint8, device=U.DEV)
+    P.policy_export_blob(blob)
+    Q = aq.Policy(_nets()[name])
+    Q.policy_import_blob(blob)
+    assert Q.policy_status() == aq.EINVAL
+    P.close()
+    Q.close()
+
+
 def test_quantize_tensor_literal_denominator_and_nonfinite(aq):
     w = np.array([[-1, 0, 0.5, 1]], np.float32)
     codes = torch.zeros(1, 4, dtype=torch.uint8, device=U.DEV)
