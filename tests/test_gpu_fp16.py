@@ -164,6 +164,37 @@ def test_fp16_actor_full_size(aq, name, batch):
     _check(net, params, obs[rows], actions[rows], [o.reshape(batch, -1)[rows] for o in outs])
 
 
+def _random_net(rng):
+    fc = synth.fc
+    n_layers = int(rng.integers(1, 5))
+    widths = [int(rng.choice([1, 5, 17, 31, 32, 33, 64, 67, 100, 129, 200, 256, 300, 520]))]
+    for _ in range(n_layers):
+        widths.append(int(rng.choice([1, 3, 6, 18, 21, 32, 33, 64, 65, 96, 128, 200, 256, 288, 512, 1030])))
+    layers = []
+    for i in range(n_layers):
+        last = i == n_layers - 1
+        act = "none" if last else str(rng.choice(["relu", "relu", "none", "ln_tanh"]))
+        if act == "ln_tanh" and widths[i + 1] < 32:  # (few features: one rounding step moves the statistics too far)
+            act = "relu"
+        layers.append(fc(widths[i], widths[i + 1], act))
+    return synth.small_net(layers, head=str(rng.choice(["tanh", "linear", "argmax"])),
+                           in_type=str(rng.choice(["f32", "f32", "u8"])))
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_fp16_actor_random_mlp_shapes(aq, seed):
+    rng = np.random.default_rng(9000 + seed)
+    net = _random_net(rng)
+    batch = int(rng.choice([1, 2, 31, 33, 64, 100, 257, 600]))
+    desc = "-".join(str(l["in"]) for l in net["layers"]) + f"-{net['layers'][-1]['out']}"
+    _say(f"fp16_actor_random_mlp_shapes seed={seed} {desc} acts={[l['act'] for l in net['layers']]} "
+         f"head={net['head']} {net['in_type']} batch={batch}")
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    actions, outs = _run_gpu(aq, net, params, obs)
+    _check(net, params, obs, actions, outs)
+
+
 def test_fp16_actor_conv_policy(aq):
     _say("fp16_actor_conv_policy cfg4 batch=6")
     net = synth.net_config("cfg4")

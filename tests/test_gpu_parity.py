@@ -531,6 +531,51 @@ def test_actor_step_entry_point(aq, name, path, batch):
     P.close()
 
 
+# ------------------------------------------------------------------ seeded random shapes
+def _random_net(rng):
+    fc = synth.fc
+    n_layers = int(rng.integers(1, 5))
+    widths = [int(rng.choice([1, 5, 17, 31, 32, 33, 64, 67, 100, 129, 200, 256, 300, 520]))]
+    for _ in range(n_layers):
+        widths.append(int(rng.choice([1, 3, 6, 18, 21, 32, 33, 64, 65, 96, 128, 200, 256, 288, 512, 1030])))
+    layers = []
+    for i in range(n_layers):
+        last = i == n_layers - 1
+        act = "none" if last else str(rng.choice(["relu", "relu", "none", "ln_tanh"]))
+        if act == "ln_tanh" and widths[i + 1] < 2:
+            act = "relu"
+        layers.append(fc(widths[i], widths[i + 1], act))
+    return synth.small_net(layers, head=str(rng.choice(["tanh", "linear", "argmax"])),
+                           wscheme=str(rng.choice(["channel_sym_s8", "tensor_asym_u8"])),
+                           in_type=str(rng.choice(["f32", "f32", "u8"])), qdenom=int(rng.choice([255, 255, 256])))
+
+
+@pytest.mark.parametrize("seed", list(range(40)))
+def test_random_mlp_shapes(aq, seed):
+    """Seeded random MLP policies (1-4 layers, widths on and off the tile edges, every activation, head,
+    weight scheme, input type, 4..8-bit weights) at random batch sizes, on whichever path the library
+    picks and on the per-layer path: every stage against the oracle."""
+    rng = np.random.default_rng(7000 + seed)
+    net = _random_net(rng)
+    net["wbits"] = int(rng.choice([8, 8, 6, 4]))
+    batch = int(rng.choice([1, 2, 15, 16, 17, 31, 33, 64, 100, 257, 600]))
+    path = int(rng.choice([0, 0, 2]))
+    desc = "-".join(str(l["in"]) for l in net["layers"]) + f"-{net['layers'][-1]['out']}"
+    _say(f"random_mlp_shapes seed={seed} {desc} acts={[l['act'] for l in net['layers']]} head={net['head']} "
+         f"{net['wscheme']} {net['in_type']} wbits={net['wbits']} batch={batch} path={path}")
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs)
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    U.check_quantized_params(aq, P, pol, net)
+    P.policy_set_path(path)
+    actions, t = U.gpu_forward(P, net, obs)
+    U.compare_forward(net, pol, obs, actions, t)
+    a2, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(a2, actions, equal_nan=True)
+    P.close()
+
+
 # ------------------------------------------------------------------ HIP graph capture
 @pytest.mark.parametrize("name", ["cfg2", "cfg1", "conv_small"])
 def test_graph_replays_match_eager(aq, name):
