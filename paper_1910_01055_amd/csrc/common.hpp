@@ -248,6 +248,7 @@ struct CallArgs {
     const int32_t* pack0;
     int NT0, KS0, pieces0;
     int cst_dbl;   // fused kernel: the LDS constant area is doubled (next layer's constants parked early)
+    int ln0;       // fused kernel: the first layer is followed by LayerNorm (its parked gain / offset are pre-scaled)
     int narrow0;   // fused kernel: the first layer is also the last and narrow (its weights are split over K)
     int part_off;  // fused kernel: LDS offset of the partial-sum area of a narrow last layer, or -1 when it
                    // fits the idle activation buffer

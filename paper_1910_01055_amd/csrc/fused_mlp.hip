@@ -125,6 +125,7 @@ aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     a.c.pieces0 = (a.net.n_layers == 1 ? 2 : 4) * a.net.L[0].NT * 8;
     a.c.part_off = p.part_off;
     a.c.cst_dbl = p.cst_dbl;
+    a.c.ln0 = a.net.n_layers > 1 && a.net.L[0].act == AQ_ACT_LN_TANH;
     a.c.narrow0 = a.net.n_layers == 1 && a.net.L[0].NT <= NARROW_NT;
     const bool tp = any_taps(a);
     const bool as = a.net.asym != 0;

@@ -79,9 +79,20 @@ __device__ __forceinline__ void load_consts(const LayerView& v, int tid, v4i& c0
     if (tid < v.pieces) c0 = v.pack[tid];
     if (tid + FT < v.pieces) c1 = v.pack[tid + FT];
 }
-__device__ __forceinline__ void park_consts(int pieces, int tid, int32_t* cst, const v4i& c0, const v4i& c1) {
-    if (tid < pieces) ((v4i*)cst)[tid] = c0;
-    if (tid + FT < pieces) ((v4i*)cst)[tid + FT] = c1;
+// 2 log2(e): tanh(y) = 1 - 2 / (2^(K2 y) + 1).  A LayerNorm layer's gain and offset are parked already
+// multiplied by it, so that the epilogue's fused multiply-add yields the exponent directly.
+constexpr float K2_LOG2E = 2.885390081777927f;
+__device__ __forceinline__ v4i scale_k2(const v4i& v) {
+    v4i r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = __float_as_int(__int_as_float(v[i]) * K2_LOG2E);
+    return r;
+}
+// scale_from: first 16-byte piece that holds gain / offset values (LayerNorm layers), or a large number
+__device__ __forceinline__ void park_consts(int pieces, int tid, int32_t* cst, const v4i& c0, const v4i& c1,
+                                            int scale_from = 1 << 30) {
+    if (tid < pieces) ((v4i*)cst)[tid] = tid >= scale_from ? scale_k2(c0) : c0;
+    if (tid + FT < pieces) ((v4i*)cst)[tid + FT] = tid + FT >= scale_from ? scale_k2(c1) : c1;
 }
 
 template <int NB>
@@ -343,7 +354,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
             }
         }
     }
-    if (cst_dbl) park_consts(c.pieces0, tid, cst, cv0, cv1);
+    if (cst_dbl) park_consts(c.pieces0, tid, cst, cv0, cv1, c.ln0 ? c.NT0 * 16 : 1 << 30);
     lds_barrier();
 
     const int n_layers = uni(an.n_layers);
@@ -382,7 +393,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         const CPtrs C{cstl, cstl + Np, L.rshift, cstl + 2 * Np, cstl + 3 * Np, (const float*)(cstl + Np)};
         const float* c_gamma = (const float*)(cstl + 2 * Np);
         const float* c_beta = (const float*)(cstl + 3 * Np);
-        int pieces_next = 0;
+        int pieces_next = 0, scale_next = 1 << 30;
 
         if (last) {
             ybuf = (const float*)out;
@@ -439,9 +450,10 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 const LayerView vn = layer_view(an, l + 1, n_layers);
                 load_consts(vn, tid, cv0, cv1);
                 pieces_next = vn.pieces;
+                if (vn.ln) scale_next = vn.NT * 16;  // pieces of the gain and offset arrays
             }
             if (!cst_dbl) {
-                if (cw_off >= 0) *(v4i*)(cstl + cw_off) = cw;
+                if (cw_off >= 0) *(v4i*)(cstl + cw_off) = (ln && cw_off >= 2 * Np) ? scale_k2(cw) : cw;
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_wave_barrier();
             }
@@ -497,7 +509,8 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                                 const float mv[4] = {mm.x, mm.y, mm.z, mm.w};
 #pragma unroll
                                 for (int i = 0; i < 4; ++i) {
-                                    float x = n0 + i < L.N ? (float)val[i] * mv[i] : 0.0f;
+                                    // (padding features: their scale m is stored as zero, so x = 0)
+                                    float x = (float)val[i] * mv[i];
                                     acc[nb][mt][4 * j + i] = __float_as_int(x);
                                     s += x;
                                 }
@@ -519,20 +532,21 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 #pragma unroll
                     for (int w = 0; w < FW; ++w) tot += red1[w * BROWS + m];
                     mean[mt] = tot / (float)L.N;
+                    // squared deviations over this wave's real tiles; the zeros standing in for the padding
+                    // features of the last tile each add mean^2, taken out again below, once per row
                     float ss = 0.0f;
                     static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
                         constexpr int nb = decltype(nb_c)::value;
                         const int nt = grp * NB + nb;
+                        if (active && nt < L.NT) {
 #pragma unroll
-                        for (int j = 0; j < QT; ++j)
+                            for (int j = 0; j < QT; ++j)
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                const int n = nt * 32 + 8 * (j + 2 * hh) + 4 * g + i;
-                                if (active && n < L.N) {
-                                    float d = __int_as_float(acc[nb][mt][4 * j + i]) - mean[mt];
-                                    ss += d * d;
+                                for (int i = 0; i < 4; ++i) {
+                                    const float d = __int_as_float(acc[nb][mt][4 * j + i]) - mean[mt];
+                                    ss = fmaf(d, d, ss);
                                 }
-                            }
+                        }
                     });
                     ss += __shfl_xor(ss, 32, 64);
                     if (HALF) ss += __shfl_xor(ss, 16, 64);
@@ -545,7 +559,11 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                     float tot = 0.0f;
 #pragma unroll
                     for (int w = 0; w < FW; ++w) tot += red2[w * BROWS + m];
+                    tot = fmaxf(tot - (float)(Np - L.N) * mean[mt] * mean[mt], 0.0f);  // the padding's share
                     inv[mt] = 1.0f / sqrtf(tot / (float)L.N + ln_eps);
+                    const float shift = -mean[mt] * inv[mt];
+                    // code = round(t / s + z) with t = 1 - 2 r, r = 1 / (2^e + 1): round(c0 - c1 r)
+                    const float c0 = qs_out.inv + zf_out, c1 = 2.0f * qs_out.inv;
                     const int64_t row = row0 + m;
                     const bool row_ok = row < c.batch;
                     static_for<0, NB>([&](auto nb_c) __attribute__((always_inline)) {
@@ -558,11 +576,14 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                                 const float4 ga = *(const float4*)(c_gamma + n0);
                                 const float4 be = *(const float4*)(c_beta + n0);
                                 const float gv[4] = {ga.x, ga.y, ga.z, ga.w}, bv[4] = {be.x, be.y, be.z, be.w};
-                                float tv[4];
+                                // gv, bv: gain and offset times 2 log2(e); r = 1 / (e^{2y} + 1) on the exp2 and
+                                // reciprocal units for either sign (exp2 saturates to 0 and +inf, rcp(inf) = 0)
+                                float rv[4];
 #pragma unroll
                                 for (int i = 0; i < 4; ++i) {
                                     const float x = __int_as_float(acc[nb][mt][4 * j + i]);
-                                    tv[i] = tanh_exp2(fmaf((x - mean[mt]) * inv[mt], gv[i], bv[i]));
+                                    const float e = __builtin_amdgcn_exp2f(fmaf(fmaf(x, inv[mt], shift), gv[i], bv[i]));
+                                    rv[i] = __builtin_amdgcn_rcpf(e + 1.0f);
                                 }
                                 uint32_t pack;
                                 if (qs_out.rcp_ok) {
@@ -573,12 +594,12 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 #pragma unroll
                                     for (int i = 0; i < 4; ++i) {
                                         // saturating float -> byte conversion: clamp to [0, 255] and pack
-                                        pack = __builtin_amdgcn_cvt_pk_u8_f32(rintf(fmaf(tv[i], qs_out.inv, zf_out)), i,
-                                                                              pack);
+                                        pack = __builtin_amdgcn_cvt_pk_u8_f32(rintf(fmaf(rv[i], -c1, c0)), i, pack);
                                     }
                                 } else {
-                                    pack = quant_code4(float4{tv[0], tv[1], tv[2], tv[3]}, qs_out, -z_out, 255 - z_out,
-                                                       z_out);
+                                    pack = quant_code4(float4{fmaf(rv[0], -2.0f, 1.0f), fmaf(rv[1], -2.0f, 1.0f),
+                                                              fmaf(rv[2], -2.0f, 1.0f), fmaf(rv[3], -2.0f, 1.0f)},
+                                                       qs_out, -z_out, 255 - z_out, z_out);
                                 }
                                 if (n0 + 4 > L.N) {
                                     // padding features are zero in the signed domain
@@ -591,7 +612,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                                     for (int i = 0; i < 4; ++i) {
                                         const int n = n0 + i;
                                         if (row_ok && n < L.N) {
-                                            if (T.ln) T.ln[row * L.N + n] = tv[i];
+                                            if (T.ln) T.ln[row * L.N + n] = fmaf(rv[i], -2.0f, 1.0f);
                                             if (T.act) T.act[row * L.N + n] = (uint8_t)(pack >> (8 * i));
                                         }
                                     }
@@ -603,7 +624,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                 });
             }
         }
-        if (cst_dbl) park_consts(pieces_next, tid, cst + ((l + 1) & 1) * cst_half, cv0, cv1);
+        if (cst_dbl) park_consts(pieces_next, tid, cst + ((l + 1) & 1) * cst_half, cv0, cv1, scale_next);
         lds_barrier();
         int8_t* sw = buf_in;
         buf_in = buf_out;
