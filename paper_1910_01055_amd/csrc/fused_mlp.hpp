@@ -3,8 +3,7 @@
 //   - activations never leave LDS (two ping-pong row-major int8 buffers, signed domain)
 //   - weights stream from L2 straight into MFMA operand registers (pre-packed at quantize time);
 //     the first k-steps of the NEXT pass or layer are requested before the current epilogue starts,
-//     and the next layer's descriptor is fetched one layer ahead, so no layer begins with a chain
-//     of dependent memory round trips
+//     so no layer begins by waiting for its first operands; layer descriptors come by scalar loads
 //   - each wave owns NB feature tiles per pass; per-channel constants of the layer are fetched
 //     while the MFMAs run and handed to the epilogue through LDS
 //   - epilogues: requantize(+ReLU) / LayerNorm+tanh+requantize in registers, last layer dequantize,
@@ -19,16 +18,16 @@ constexpr int FW = 8;            // wavefronts per workgroup
 constexpr int FT = FW * 64;      // threads per workgroup
 constexpr int CST_MAXN = 1024;   // widest layer whose constants fit the LDS staging area
 
-constexpr int NET_WORDS = (sizeof(NetDev) + 15) / 16 * 4;
 
-// LDS layout (bytes): [buf_in ROWS*ld][buf_out ROWS*ld][red 2*FW*ROWS floats][cst 4*cst_n words][net]
+// LDS layout (bytes): [buf_in ROWS*ld][buf_out ROWS*ld][red 2*FW*ROWS floats][cst 4*cst_n words]
 __host__ __device__ inline size_t fused_lds_bytes(int rows, int ld, int cst_n, bool cst_dbl = false) {
-    return (size_t)2 * rows * ld + (size_t)2 * FW * rows * 4 + (size_t)4 * cst_n * 4 * (cst_dbl ? 2 : 1) +
-           (size_t)NET_WORDS * 4;
+    return (size_t)2 * rows * ld + (size_t)2 * FW * rows * 4 + (size_t)4 * cst_n * 4 * (cst_dbl ? 2 : 1);
 }
 
-// Values read from the LDS copy of the network description arrive in vector registers;
-// readfirstlane moves them to scalar registers so that loop bounds and branches stay scalar.
+// The network description is read through the kernel's pointer argument with uniform indices, i.e. by
+// scalar loads into scalar registers (measured faster than a copy in LDS read back through vector
+// registers: 2 % on the headline workload).  readfirstlane keeps a value scalar wherever the compiler
+// cannot prove it uniform, so that loop bounds and branches stay scalar.
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 __device__ __forceinline__ float unif(float v) { return __int_as_float(uni(__float_as_int(v))); }
 template <class T>
@@ -222,12 +221,6 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
     // 128-row workgroups never fit one)
     const int cst_dbl = (NB == 2 || MT == 4) ? 0 : c.cst_dbl;
     const int cst_half = cst_dbl ? 4 * cst_n : 0;  // words between the two halves
-    int32_t* net_lds = cst + 4 * cst_n + cst_half;
-    const NetDev& an = *(const NetDev*)net_lds;  // valid after the first barrier
-
-    // the network description: one coalesced read into LDS, so that no layer starts by chasing
-    // pointers through global memory (every dependent global access costs about a microsecond)
-    if (tid < NET_WORDS) net_lds[tid] = tid < (int)(sizeof(NetDev) / 4) ? ((const int32_t*)netp)[tid] : 0;
 
     // first layer's first weights: requested before the observations are touched
     v4i wreg[PF][NB];
@@ -357,16 +350,16 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
     if (cst_dbl) park_consts(c.pieces0, tid, cst, cv0, cv1, c.ln0 ? c.NT0 * 16 : 1 << 30);
     lds_barrier();
 
-    const int n_layers = uni(an.n_layers);
-    const float ln_eps = unif(an.ln_eps);
+    const int n_layers = uni(a.n_layers);
+    const float ln_eps = unif(a.ln_eps);
     int N_last = 0;
     const float* ybuf = nullptr;  // dequantized last-layer rows in LDS and their stride, set by the last layer
     int ldy_h = 0;
     // a narrow last layer is handled after the loop, by all waves together
-    const bool narrow = uni(an.L[n_layers - 1].NT) <= NARROW_NT;
+    const bool narrow = uni(a.L[n_layers - 1].NT) <= NARROW_NT;
     const int n_loop = narrow ? n_layers - 1 : n_layers;
     for (int l = 0; l < n_loop; ++l) {
-        const LayerView L = layer_view(an, l, n_layers);
+        const LayerView L = layer_view(a, l, n_layers);
         const bool last = L.last, ln = L.ln;
         N_last = L.N;
         LayerTaps T{nullptr, nullptr, nullptr};
@@ -434,8 +427,8 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
             if (XPF) {
                 const bool more = g0 + FW < ngroups;
                 const int ln_i = (more || last) ? l : l + 1;
-                const int8_t* wp_n = uni_ptr(an.L[ln_i].wp);
-                const int NT_n = uni(an.L[ln_i].NT), KS_n = uni(an.L[ln_i].KS);
+                const int8_t* wp_n = uni_ptr(a.L[ln_i].wp);
+                const int NT_n = uni(a.L[ln_i].NT), KS_n = uni(a.L[ln_i].KS);
                 const int grp_n = more ? grp + FW : wave;
                 // (a narrow last layer fetches its own weights: its waves split K instead of the tiles)
                 const bool narrow_next = !more && l + 2 == n_layers && NT_n <= NARROW_NT;
@@ -447,7 +440,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
             }
             // ... and, on the last pass, the next layer's constants
             if (cst_dbl && !last && g0 + FW >= ngroups) {
-                const LayerView vn = layer_view(an, l + 1, n_layers);
+                const LayerView vn = layer_view(a, l + 1, n_layers);
                 load_consts(vn, tid, cv0, cv1);
                 pieces_next = vn.pieces;
                 if (vn.ln) scale_next = vn.NT * 16;  // pieces of the gain and offset arrays
@@ -633,7 +626,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 
     if (narrow) {
         const int l = n_layers - 1;
-        const LayerView L = layer_view(an, l, n_layers);
+        const LayerView L = layer_view(a, l, n_layers);
         N_last = L.N;
         LayerTaps T{nullptr, nullptr, nullptr};
         if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
@@ -673,7 +666,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
         float* yrow = (float*)buf_in;
         ybuf = yrow;
         ldy_h = Np + 1;
-        const int head_n = uni(an.head);
+        const int head_n = uni(a.head);
         float* direct = head_n != AQ_HEAD_ARGMAX ? (float*)c.actions : nullptr;
         float* tap_y = TAPS ? t.y : nullptr;
         if (L.NT == 1)
@@ -688,7 +681,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 
     // action head on the dequantized last-layer rows y (fp32, in LDS): tanh / identity / argmax
     {
-        const int head = uni(an.head);
+        const int head = uni(a.head);
         const int ldy = ldy_h;
         const int N = N_last;
         if (head == AQ_HEAD_ARGMAX) {
