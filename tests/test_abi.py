@@ -30,7 +30,7 @@ def test_struct_layouts_match_header():
     from paper_1910_01055_amd import binding as b
     assert ctypes.sizeof(b.AqLayer) == 9 * 4
     assert ctypes.sizeof(b.AqRange) == 8
-    assert ctypes.sizeof(b.AqNet) == 4 + 4 + 8 + 4 * 4 + 4 + 4  # int32, pad, pointer, 4 x int32, float, pad
+    assert ctypes.sizeof(b.AqNet) == 4 + 4 + 8 + 4 * 4 + 4 + 4  # int32, pad, pointer, 4 x int32, float, int32
     assert ctypes.sizeof(b.AqTaps) == 5 * 8
     assert b.MAX_LAYERS == int(re.search(r"#define AQ_MAX_LAYERS (\d+)", open(HEADER).read()).group(1))
 
@@ -58,3 +58,14 @@ def test_synth_configs_match_the_stated_workloads():
     a = synth.make_obs(synth.net_config("cfg2"), 4)
     b2 = synth.make_obs(synth.net_config("cfg2"), 4)
     assert (a == b2).all() and a.dtype.name == "float32"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more exits with a message instead of running."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and not r.stdout.strip()
