@@ -167,10 +167,11 @@ def quantize_workload(torch, aq, synth, U, scheme, iters=30, n_buf=40, repeat=1)
             "frac_hbm_peak": gbs / HBM_PEAK_GBS}
 
 
-def blob_workload(torch, aq, synth, U, name):
+def blob_workload(torch, aq, synth, U, name, wbits=8):
     """Learner -> actor hand-off of a quantized policy as one packed blob: export from one handle, import
-    into another (device to device, no repacking), next to the cost of quantizing the fp32 parameters."""
-    net = synth.net_config(name)
+    into another (device to device, no repacking), next to the cost of quantizing the fp32 parameters.
+    With wbits < 8 the weight codes also travel sub-byte (n-bit fields, expanded on import)."""
+    net = dict(synth.net_config(name), wbits=wbits)
     params = synth.make_params(net)
     obs = synth.make_obs(net, 512)
     P, Q = aq.Policy(net), aq.Policy(net)
@@ -192,10 +193,21 @@ def blob_workload(torch, aq, synth, U, name):
     ms_q = _graph_ms(torch, lambda: P.quantize_params(w, b, g, be, ranges), 20)
     ms_e = _graph_ms(torch, lambda: P.policy_export_blob(blob), 50)
     ms_i = _graph_ms(torch, lambda: Q.policy_import_blob(blob), 50)
+    out = {"workload": f"{name} policy blob hand-off" + (f", {wbits}-bit weights" if wbits != 8 else ""), "blob_bytes": n,
+           "us_export": ms_e * 1e3, "us_import": ms_i * 1e3, "us_quantize_params": ms_q * 1e3,
+           "GBps_import": 2.0 * n / (ms_i * 1e-3) / 1e9}
+    if wbits != 8:
+        n_p = P.policy_packed_blob_size()
+        pblob = torch.empty(n_p, dtype=torch.uint8, device=U.DEV)
+        P.policy_export_packed_blob(pblob)
+        Q.policy_import_packed_blob(pblob)
+        assert Q.policy_status() == aq.OK
+        out["packed_blob_bytes"] = n_p
+        out["us_export_packed"] = _graph_ms(torch, lambda: P.policy_export_packed_blob(pblob), 50) * 1e3
+        out["us_import_packed"] = _graph_ms(torch, lambda: Q.policy_import_packed_blob(pblob), 50) * 1e3
     P.close()
     Q.close()
-    return {"workload": f"{name} policy blob hand-off", "blob_bytes": n, "us_export": ms_e * 1e3, "us_import": ms_i * 1e3,
-            "us_quantize_params": ms_q * 1e3, "GBps_import": 2.0 * n / (ms_i * 1e-3) / 1e9}
+    return out
 
 
 def cpu_baseline(synth, U, net, params, obs, ranges, budget_s=12.0):
@@ -342,6 +354,7 @@ def main():
         extra.append(quantize_workload(torch, aq, synth, U, "channel_sym_s8", iters=6, n_buf=4, repeat=16))
         for name in ("cfg2", "cfg5"):
             extra.append(blob_workload(torch, aq, synth, U, name))
+        extra.append(blob_workload(torch, aq, synth, U, "cfg5", wbits=4))
         result["other_workloads"] = extra
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(synth, U, net, params, obs, ranges)

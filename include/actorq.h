@@ -148,6 +148,15 @@ aq_status aq_policy_blob_size(const aq_policy* p, uint64_t* bytes);
 aq_status aq_policy_export_blob(const aq_policy* p, void* d_blob, uint64_t bytes, void* stream);
 aq_status aq_policy_import_blob(aq_policy* p, const void* d_blob, uint64_t bytes, void* stream);
 
+/* The same hand-off with the weight codes stored sub-byte: a policy whose weight precision is n < 8 bits
+ * (aq_net.wbits) travels as n-bit fields, 8 codes per n bytes, and is expanded to the 8-bit operand layout
+ * on import (constants and activation parameters as in the plain blob).  With n = 8 the packed blob is the
+ * plain one byte for byte, apart from its magic number.  Size, export, import and their errors as above;
+ * a packed blob only loads into a handle of the same network description and the same wbits. */
+aq_status aq_policy_packed_blob_size(const aq_policy* p, uint64_t* bytes);
+aq_status aq_policy_export_packed_blob(const aq_policy* p, void* d_blob, uint64_t bytes, void* stream);
+aq_status aq_policy_import_packed_blob(aq_policy* p, const void* d_blob, uint64_t bytes, void* stream);
+
 /* Exploration on the actor (Sec. 4.1: a Gaussian noise layer on the policy output whose sigma
  * depends on the actor; for the discrete-control policies, epsilon-greedy), applied in place to the
  * actions of a preceding forward on the same stream.

@@ -24,7 +24,8 @@ EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_pol
            "aq_quantize_tensor", "aq_quantize_params", "aq_policy_export_layer", "aq_policy_export_act_qparams",
            "aq_policy_forward_int8", "aq_policy_forward_fp32", "aq_status_string",
            "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore", "aq_policy_step_int8",
-           "aq_convert_params_fp16", "aq_policy_forward_fp16"]
+           "aq_convert_params_fp16", "aq_policy_forward_fp16",
+           "aq_policy_packed_blob_size", "aq_policy_export_packed_blob", "aq_policy_import_packed_blob"]
 
 
 class AqLayer(C.Structure):
@@ -192,6 +193,19 @@ class Policy:
     def policy_import_blob(self, blob):
         _check(load().aq_policy_import_blob(self._h, _ptr(blob), blob.numel() * blob.element_size(), _stream()),
                "aq_policy_import_blob")
+
+    def policy_packed_blob_size(self):
+        n = C.c_uint64(0)
+        _check(load().aq_policy_packed_blob_size(self._h, C.byref(n)), "aq_policy_packed_blob_size")
+        return int(n.value)
+
+    def policy_export_packed_blob(self, blob):
+        _check(load().aq_policy_export_packed_blob(self._h, _ptr(blob), blob.numel() * blob.element_size(), _stream()),
+               "aq_policy_export_packed_blob")
+
+    def policy_import_packed_blob(self, blob):
+        _check(load().aq_policy_import_packed_blob(self._h, _ptr(blob), blob.numel() * blob.element_size(), _stream()),
+               "aq_policy_import_packed_blob")
 
     def quantize_params(self, w, b, gamma, beta, ranges):
         """w, b, gamma, beta: per-layer lists of device tensors (entries or lists may be None);

@@ -454,6 +454,106 @@ extern "C" aq_status aq_policy_import_blob(aq_policy* p, const void* d_blob, uin
     return AQ_OK;
 }
 
+// ---- packed policy blob: the same header (other magic) and tail, then per layer the weight codes as
+// n-bit fields (n = the policy's weight precision) followed by the layer's constants verbatim.
+namespace {
+constexpr uint32_t kPackedMagic = 0x50515141u;  // "AQQP"
+struct PackedLayout {
+    std::vector<size_t> w_off, w_bytes, c_off, c_src, c_bytes;  // blob offsets / slab offsets per layer
+    size_t total = 0;
+};
+int policy_wbits(const aq_policy* p) { return p->net.wbits ? p->net.wbits : 8; }
+PackedLayout packed_layout(const aq_policy* p) {
+    PackedLayout L;
+    const int bits = policy_wbits(p);
+    size_t at = kBlobHeader + kBlobTail;
+    const char* base = (const char*)p->slab;
+    for (size_t l = 0; l < p->L.size(); ++l) {
+        const LayerBuf& b = p->L[l];
+        const size_t wb = (size_t)b.NT * b.KS * 1024;
+        const size_t begin = (size_t)((const char*)b.wp - base);
+        const size_t end = l + 1 < p->L.size() ? (size_t)((const char*)p->L[l + 1].wp - base) : p->layer_bytes;
+        L.w_off.push_back(at);
+        L.w_bytes.push_back(wb / 8 * bits);
+        at += (wb / 8 * bits + 255) / 256 * 256;
+        L.c_off.push_back(at);
+        L.c_src.push_back(begin + wb);
+        L.c_bytes.push_back(end - begin - wb);
+        at += end - begin - wb;
+    }
+    L.total = at;
+    return L;
+}
+void packed_words(const aq_policy* p, const PackedLayout& L, uint32_t (&w)[6]) {
+    blob_words(p, w);
+    w[0] = kPackedMagic;
+    w[4] = (uint32_t)(L.total - kBlobHeader);
+    w[5] = (uint32_t)((uint64_t)(L.total - kBlobHeader) >> 32);
+}
+}  // namespace
+
+extern "C" aq_status aq_policy_packed_blob_size(const aq_policy* p, uint64_t* bytes) {
+    if (!p || !bytes) return AQ_EINVAL;
+    *bytes = packed_layout(p).total;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_export_packed_blob(const aq_policy* p, void* d_blob, uint64_t bytes, void* stream) {
+    if (!p || !d_blob || ((uintptr_t)d_blob & 15)) return AQ_EINVAL;
+    const PackedLayout L = packed_layout(p);
+    if (bytes < L.total) return AQ_EINVAL;
+    if (!p->quantized) return AQ_ENOTQUANT;
+    hipStream_t st = as_stream(stream);
+    uint32_t w[6];
+    packed_words(p, L, w);
+    char* dst = (char*)d_blob;
+    aq_status s = launch_blob_header_write((uint32_t*)dst, w, st);
+    if (s != AQ_OK) return s;
+    AQ_HIP_CHECK(hipMemcpyAsync(dst + kBlobHeader, p->d_net->actq, kTailBytes, hipMemcpyDeviceToDevice, st));
+    const int bits = policy_wbits(p);
+    const int off = p->h_net.asym ? 128 : (1 << (bits - 1)) - 1;
+    for (size_t l = 0; l < p->L.size(); ++l) {
+        const LayerBuf& b = p->L[l];
+        s = launch_pack_bits(b.wp, (uint8_t*)dst + L.w_off[l], (int64_t)b.NT * b.KS * 1024, bits, off, st);
+        if (s != AQ_OK) return s;
+        const size_t gap = L.c_off[l] - (L.w_off[l] + L.w_bytes[l]);  // alignment padding: a multiple of 4, kept zero
+        if (gap) {
+            s = launch_fill_u32((uint32_t*)(dst + L.w_off[l] + L.w_bytes[l]), (int)(gap / 4), 0u, st);
+            if (s != AQ_OK) return s;
+        }
+        AQ_HIP_CHECK(hipMemcpyAsync(dst + L.c_off[l], (const char*)p->slab + L.c_src[l], L.c_bytes[l],
+                                    hipMemcpyDeviceToDevice, st));
+    }
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_import_packed_blob(aq_policy* p, const void* d_blob, uint64_t bytes, void* stream) {
+    if (!p || !d_blob || ((uintptr_t)d_blob & 15)) return AQ_EINVAL;
+    const PackedLayout L = packed_layout(p);
+    if (bytes < L.total) return AQ_EINVAL;
+    hipStream_t st = as_stream(stream);
+    uint32_t w[6];
+    packed_words(p, L, w);
+    const char* src = (const char*)d_blob;
+    aq_status s = launch_fill_u32((uint32_t*)p->status, 1, 0u, st);
+    if (s != AQ_OK) return s;
+    s = launch_blob_header_check((const uint32_t*)src, w, p->status, st);
+    if (s != AQ_OK) return s;
+    AQ_HIP_CHECK(hipMemcpyAsync(p->d_net->actq, src + kBlobHeader, kTailBytes, hipMemcpyDeviceToDevice, st));
+    const int bits = policy_wbits(p);
+    const int off = p->h_net.asym ? 128 : (1 << (bits - 1)) - 1;
+    for (size_t l = 0; l < p->L.size(); ++l) {
+        const LayerBuf& b = p->L[l];
+        s = launch_unpack_bits((const uint8_t*)src + L.w_off[l], b.wp, (int64_t)b.NT * b.KS * 1024, bits, off, b.N, b.K,
+                               b.KS, st);
+        if (s != AQ_OK) return s;
+        AQ_HIP_CHECK(hipMemcpyAsync((char*)p->slab + L.c_src[l], src + L.c_off[l], L.c_bytes[l],
+                                    hipMemcpyDeviceToDevice, st));
+    }
+    p->quantized = true;
+    return AQ_OK;
+}
+
 static aq_status explore_args_ok(const aq_policy* p, const aq_explore* ex, int64_t batch) {
     if (batch > 0xffffffffLL) return AQ_EINVAL;
     const bool discrete = p->net.head == AQ_HEAD_ARGMAX;

@@ -19,6 +19,11 @@ aq_status launch_unpack_weights(const int8_t* wp, int N, int K, int KS, int asym
 aq_status launch_blob_header_write(uint32_t* d_hdr, const uint32_t* h_words, hipStream_t st);
 aq_status launch_blob_header_check(const uint32_t* d_hdr, const uint32_t* h_words, int* status, hipStream_t st);
 
+// n-bit weight codes of one layer (operand order, signed domain) <-> sub-byte fields, 8 codes per n bytes
+aq_status launch_pack_bits(const int8_t* wp, uint8_t* out, int64_t n_codes, int bits, int off, hipStream_t st);
+aq_status launch_unpack_bits(const uint8_t* in, int8_t* wp, int64_t n_codes, int bits, int off, int N, int K, int KS,
+                             hipStream_t st);
+
 // ---- exploration on the produced actions (explore.hip)
 aq_status launch_explore(void* d_actions, int64_t rows, int A, int head, const float* d_sigma, float epsilon,
                          uint64_t seed, uint64_t step, hipStream_t st);

@@ -508,8 +508,71 @@ __global__ void k_blob_header_check(const uint32_t* __restrict__ hdr, const Blob
 }
 
 // ---------------------------------------------------------------------------------------------
+// n-bit weight codes stored sub-byte (the packed policy blob): eight consecutive codes of the operand
+// order -> n bytes and back.  Codes are kept in the signed domain in the library (symmetric: the code
+// itself, in [-qw, qw]; per tensor: unsigned code - 128), the stored field is the code plus `off`
+// (qw resp. 128), an n-bit unsigned number.  Padding entries (feature >= N or k >= K) are zero in the
+// signed domain, which the per-tensor scheme cannot store in n < 8 bits: they are written as field 0
+// and restored from their position when unpacking.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_pack_bits(const int8_t* __restrict__ wp, uint8_t* __restrict__ out,
+                                                   int64_t groups, int bits, int off) {
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= groups) return;
+    const uint64_t v = *(const uint64_t*)(wp + 8 * g);
+    const int fmax = (1 << bits) - 1;
+    uint64_t acc = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        int u = (int)(int8_t)(v >> (8 * j)) + off;
+        u = u < 0 ? 0 : (u > fmax ? 0 : u);
+        acc |= (uint64_t)u << (j * bits);
+    }
+    uint8_t* dst = out + g * bits;
+    for (int b = 0; b < bits; ++b) dst[b] = (uint8_t)(acc >> (8 * b));
+}
+
+__global__ __launch_bounds__(256) void k_unpack_bits(const uint8_t* __restrict__ in, int8_t* __restrict__ wp,
+                                                     int64_t groups, int bits, int off, int N, int K, int KS) {
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (g >= groups) return;
+    const uint8_t* src = in + g * bits;
+    uint64_t acc = 0;
+    for (int b = 0; b < bits; ++b) acc |= (uint64_t)src[b] << (8 * b);
+    // position of the group's first element in the operand order: tile (n / 32, k / 32) = 1 KiB,
+    // lane = n % 32 + 32 * ((k % 32) / 16), byte = k % 16
+    const int64_t e = 8 * g;
+    const int64_t tile = e >> 10;
+    const int nt = (int)(tile / KS), ks = (int)(tile - (int64_t)nt * KS);
+    const int lane = (int)((e & 1023) >> 4), byte0 = (int)(e & 15);
+    const int n = nt * 32 + (lane & 31), k0 = ks * 32 + 16 * (lane >> 5) + byte0;
+    const uint64_t fmask = ((uint64_t)1 << bits) - 1;
+    uint64_t v = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        int sgn = (int)((acc >> (j * bits)) & fmask) - off;
+        if (n >= N || k0 + j >= K) sgn = 0;
+        v |= (uint64_t)(uint8_t)(int8_t)sgn << (8 * j);
+    }
+    *(uint64_t*)(wp + 8 * g) = v;
+}
+
+// ---------------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------------
+aq_status launch_pack_bits(const int8_t* wp, uint8_t* out, int64_t n_codes, int bits, int off, hipStream_t st) {
+    const int64_t groups = n_codes / 8;
+    hipLaunchKernelGGL(k_pack_bits, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, wp, out, groups, bits, off);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+aq_status launch_unpack_bits(const uint8_t* in, int8_t* wp, int64_t n_codes, int bits, int off, int N, int K, int KS,
+                             hipStream_t st) {
+    const int64_t groups = n_codes / 8;
+    hipLaunchKernelGGL(k_unpack_bits, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, st, in, wp, groups, bits, off,
+                       N, K, KS);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
+}
+
 aq_status launch_blob_header_write(uint32_t* d_hdr, const uint32_t* h_words, hipStream_t st) {
     BlobWords b;
     for (int i = 0; i < 6; ++i) b.w[i] = h_words[i];

@@ -419,6 +419,57 @@ def test_policy_blob_round_trip(aq, name):
     Q.close()
 
 
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "conv_small", "odd_asym"])
+@pytest.mark.parametrize("wbits", [2, 4, 5, 6, 8])
+def test_packed_policy_blob_round_trip(aq, name, wbits):
+    """n-bit weight codes travel sub-byte: the packed blob is about n/8 of the weights' size, and a fresh
+    handle that imports it exposes the oracle's codes and constants and computes the same bits."""
+    _say(f"packed_policy_blob_round_trip {name} wbits={wbits}")
+    net = dict(_nets()[name], wbits=wbits)
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, 130)
+    pol, ranges = U.make_oracle(net, params, obs)
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    n_plain, n_packed = P.policy_blob_size(), P.policy_packed_blob_size()
+    w_bytes = sum(int(np.prod(synth.layer_weight_shape(l))) for l in net["layers"])
+    assert n_packed <= n_plain
+    if wbits < 8:
+        assert n_plain - n_packed >= w_bytes * (8 - wbits) // 8  # at least the real weights shrink by n/8
+    blob = torch.full((n_packed + 64,), 0xA5, dtype=torch.uint8, device=U.DEV)
+    P.policy_export_packed_blob(blob[:n_packed])
+    torch.cuda.synchronize()
+    assert bool((blob[n_packed:] == 0xA5).all())  # nothing written past the stated size
+    Q = aq.Policy(net)
+    Q.policy_import_packed_blob(blob[:n_packed])
+    assert Q.policy_status() == aq.OK
+    U.check_quantized_params(aq, Q, pol, net)
+    for path in (0, 2):
+        Q.policy_set_path(path)
+        actions, t = U.gpu_forward(Q, net, obs)
+        U.compare_forward(net, pol, obs, actions, t)
+    # exporting from the importer gives the same bytes; a plain blob of it equals the original's
+    blob2 = torch.zeros(n_packed, dtype=torch.uint8, device=U.DEV)
+    Q.policy_export_packed_blob(blob2)
+    assert torch.equal(blob2, blob[:n_packed])
+    b1 = torch.zeros(n_plain, dtype=torch.uint8, device=U.DEV)
+    b2 = torch.zeros(n_plain, dtype=torch.uint8, device=U.DEV)
+    P.policy_export_blob(b1)
+    Q.policy_export_blob(b2)
+    assert torch.equal(b1, b2)
+    # a handle with another weight precision, or the plain importer, refuses it
+    R = aq.Policy(dict(net, wbits=8 if wbits != 8 else 4))
+    if R.policy_packed_blob_size() <= n_packed:
+        R.policy_import_packed_blob(blob[:n_packed])
+        assert R.policy_status() == aq.EINVAL
+    if n_plain <= n_packed:
+        Q2 = aq.Policy(net)
+        Q2.policy_import_blob(blob[:n_packed])
+        assert Q2.policy_status() == aq.EINVAL
+        Q2.close()
+    for h in (P, Q, R):
+        h.close()
+
+
 # ------------------------------------------------------------------ exploration (Sec. 4.1)
 @pytest.mark.parametrize("rows,A", [(1, 1), (77, 21), (4096, 6), (1000, 64)])
 def test_explore_gaussian_matches_oracle(aq, rows, A):
