@@ -109,7 +109,9 @@ typedef struct {
     float* y;
 } aq_taps;
 
-/* Creates a policy handle for `net` on the current HIP device.  Validates that the layers chain.
+/* Creates a policy handle for `net` on the current HIP device.  Validates that the layers chain
+ * (AQ_ESHAPE otherwise) and that every layer is within the size limits of the int32 accumulation:
+ * K = kh * kw * in_c <= 65536, out_c <= 2^20, in_h and in_w <= 16384 (AQ_ESHAPE beyond them).
  * Allocates the per-layer device buffers (packed 8-bit weights, per-channel constants). */
 aq_status aq_policy_create(const aq_net* net, aq_policy** out);
 aq_status aq_policy_destroy(aq_policy* p);

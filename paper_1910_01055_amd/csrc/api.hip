@@ -95,6 +95,8 @@ static void fill_layer_dev(const aq_policy* p, int l, LayerDev& d) {
 
 static hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
+constexpr int kMaxK = 1 << 16, kMaxN = 1 << 20, kMaxSide = 1 << 14;
+
 extern "C" const char* aq_status_string(aq_status s) {
     switch (s) {
         case AQ_OK: return "ok";
@@ -142,6 +144,14 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         if (d.act < 0 || d.act > AQ_ACT_LN_TANH || d.out_c < 1 || d.in_c < 1) {
             delete p;
             return AQ_EINVAL;
+        }
+        // Size limits: K products of two signed 8-bit values (each at most 2^14 in magnitude) must stay
+        // inside the int32 accumulator, and tile counts and per-sample element counts inside int32.
+        if (d.in_c > kMaxK || d.out_c > kMaxN ||
+            (d.kind == AQ_CONV2D && (d.in_h > kMaxSide || d.in_w > kMaxSide ||
+                                     (int64_t)d.kh * d.kw * d.in_c > kMaxK))) {
+            delete p;
+            return AQ_ESHAPE;
         }
         if (d.kind == AQ_FC) {
             b.fc = true;

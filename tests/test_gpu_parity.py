@@ -737,3 +737,8 @@ def test_edges(aq):
     with pytest.raises(aq.AqError) as e:
         aq.Policy(broken)
     assert e.value.status == aq.ESHAPE
+    # layers beyond the int32 accumulation bound (K <= 65536) or the width limit are refused
+    for too_big in (synth.small_net([synth.fc(65537, 8, "none")]), synth.small_net([synth.fc(8, (1 << 20) + 1, "none")])):
+        with pytest.raises(aq.AqError) as e:
+            aq.Policy(too_big)
+        assert e.value.status == aq.ESHAPE
