@@ -22,7 +22,9 @@ _LIB = None
 def lib():
     global _LIB
     if _LIB is None:
-        path = _build.build(force=False)
+        # ACTORQ_ORACLE_LIB: a build of an altered copy of the C source, set only by the test that checks
+        # that the pins notice planted mistakes
+        path = os.environ.get("ACTORQ_ORACLE_LIB") or _build.build(force=False)
         _LIB = C.CDLL(path)
         _LIB.orc_num_threads.restype = C.c_int
     return _LIB

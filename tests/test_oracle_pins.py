@@ -214,6 +214,14 @@ def test_conv_acc_matches_im2col_and_fc():
     xw = torch.from_numpy(w.astype(np.float64)).permute(0, 3, 1, 2)
     t = torch.nn.functional.conv2d(xa, xw, torch.from_numpy(bias_q.astype(np.float64)), stride=st)
     assert np.array_equal(t.permute(0, 2, 3, 1).numpy(), acc.astype(np.float64))
+    # unsigned weight codes with a non-zero weight zero-point (the per-tensor scheme): same two checks
+    wu = rng.integers(0, 256, (Co, kh, kw, Cc)).astype(np.int16)
+    z_wu = rng.integers(1, 255, Co).astype(np.int32)
+    acc_u = O.c_conv_acc(a, z_a, wu, st, z_wu, bias_q)
+    assert acc_u.reshape(-1, Co).tolist() == _brute_fc(cols, z_a, wu.reshape(Co, -1), z_wu, bias_q)
+    xwu = torch.from_numpy(wu.astype(np.float64) - z_wu[:, None, None, None]).permute(0, 3, 1, 2)
+    tu = torch.nn.functional.conv2d(xa, xwu, torch.from_numpy(bias_q.astype(np.float64)), stride=st)
+    assert np.array_equal(tu.permute(0, 2, 3, 1).numpy(), acc_u.astype(np.float64))
     # a 1x1 convolution over a 1x1 image is a fully connected layer
     a1 = rng.integers(0, 256, (3, 1, 1, 20), dtype=np.uint8)
     w1 = rng.integers(-127, 128, (7, 1, 1, 20)).astype(np.int16)
@@ -509,12 +517,20 @@ def test_epsilon_greedy_exploration():
     out = O.c_explore_eps_greedy(greedy, A, eps, seed, step)
     changed_or_same = out != greedy
     # a replaced action equals the old one with probability 1/A: count replacements through the definition instead
-    repl = 0
-    for b in (0, 1, 17, 19999):
+    explored = []
+    for b in list(range(200)) + [19999]:
         r = _py_philox([b, 0xFFFFFFFF, step, 0], [seed, 0])
         u = np.float32(r[0] >> 8) * np.float32(2.0 ** -24)
         want = (r[1] * A) >> 32 if u < np.float32(eps) else int(greedy[b])
         assert int(out[b]) == want
+        explored.append(bool(u < np.float32(eps)))
+    assert 5 <= sum(explored) <= 45           # both branches were checked (about 20 of 201 rows explore)
+    # the random action is independent of the decision to explore: over the rows that changed, every action
+    # that differs from the greedy one is equally likely (a generator word used twice would pile them up at
+    # the low indices)
+    ch = np.flatnonzero(changed_or_same)
+    cnt = np.bincount(out[ch], minlength=A)
+    assert np.abs(cnt - ch.size / A).max() < 5 * math.sqrt(ch.size / A)
     frac = np.mean(out == allrand)          # rows where the random action was taken (or coincides)
     expect = eps + (1 - eps) / A
     assert abs(frac - expect) < 5 * math.sqrt(expect * (1 - expect) / rows)
