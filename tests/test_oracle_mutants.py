@@ -85,11 +85,63 @@ MUTANTS = [
 ]
 
 
-def _run_pins(lib):
-    env = dict(os.environ, ACTORQ_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
-    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
-                        "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
-    return r.returncode, r.stdout[-1500:]
+# The same for the layer-by-layer chain in oracle/policy.py (which operator follows which, which scale and
+# zero-point go where, what is rounded to binary16): (name, text occurring exactly once, replacement)
+CHAIN_MUTANTS = [
+    ("chain_unaltered", None, None),
+    ("fp32_relu_skipped", "                x = c_relu_f64(x)\n", "                pass\n"),
+    ("fp32_tanh_after_layernorm_skipped",
+     'x = c_tanh_f64(c_layernorm_f64(x, p["gamma"], p["beta"], self.net["ln_eps"]))',
+     'x = c_layernorm_f64(x, p["gamma"], p["beta"], self.net["ln_eps"])'),
+    ("fp32_tanh_head_skipped", "out = c_tanh_f64(y).astype(np.float32)", "out = y.astype(np.float32)"),
+    ("fp16_weights_not_rounded", 'w16, b16 = r16(p["w"]), r16(p["b"])', 'w16, b16 = p["w"], r16(p["b"])'),
+    ("fp16_bias_not_rounded", 'w16, b16 = r16(p["w"]), r16(p["b"])', 'w16, b16 = r16(p["w"]), p["b"]'),
+    ("fp16_layer_output_not_rounded", "            y = r16(pre)\n", "            y = pre\n"),
+    ("fp16_layernorm_output_not_rounded",
+     'y = r16(c_layernorm_f64(y, r16(p["gamma"]), r16(p["beta"]), self.net["ln_eps"]))',
+     'y = c_layernorm_f64(y, r16(p["gamma"]), r16(p["beta"]), self.net["ln_eps"])'),
+    ("fp16_observation_not_rounded", "x = r16(obs) if start_x is None else", "x = np.asarray(obs, np.float32) if start_x is None else"),
+    ("fp16_head_not_rounded", 'taps["actions"] = r16(c_tanh_f64(y))', 'taps["actions"] = c_tanh_f64(y)'),
+    ("requant_uses_input_scale", "s_out = act_q[i + 1][0] if requant else np.float32(0.0)",
+     "s_out = act_q[i][0] if requant else np.float32(0.0)"),
+    ("requant_uses_input_zero_point", '"z_out": act_q[i + 1][1] if i < nl - 1 else None',
+     '"z_out": act_q[i][1] if i < nl - 1 else None'),
+    ("weights_quantized_at_8_bits_whatever_n", "codes = c_quantize_asym(w, s, z, wmax)", "codes = c_quantize_asym(w, s, z, 255)"),
+    ("int8_fc_ignores_input_zero_point",
+     'acc = c_fc_acc(a.reshape(a.shape[0], -1), q["z_in"], q["codes"], q["z_w"], q["bias_q"])',
+     'acc = c_fc_acc(a.reshape(a.shape[0], -1), 0, q["codes"], q["z_w"], q["bias_q"])'),
+    ("int8_relu_flag_dropped", 'c_requant(acc, q["M0"], q["rshift"], q["z_out"], l["act"] == "relu")',
+     'c_requant(acc, q["M0"], q["rshift"], q["z_out"], False)'),
+    ("int8_tanh_head_skipped", '                    taps["actions"] = c_tanh_f32(y)\n', '                    taps["actions"] = y\n'),
+    ("int8_layernorm_uses_next_layers_gain", 'c_ln_tanh(acc, q["m"], q["gamma"], q["beta"], self.net["ln_eps"], q["s_out"], q["z_out"])',
+     'c_ln_tanh(acc, q["m"], q["beta"], q["gamma"], self.net["ln_eps"], q["s_out"], q["z_out"])'),
+]
+
+# loaded by the child pytest with -p: installs the altered copy as oracle.policy before the pins import it
+PLUGIN = '''
+import importlib.util, os, sys
+def pytest_configure(config):
+    import oracle
+    spec = importlib.util.spec_from_file_location("oracle.policy", os.environ["ACTORQ_ORACLE_POLICY_COPY"])
+    m = importlib.util.module_from_spec(spec)
+    sys.modules["oracle.policy"] = m
+    spec.loader.exec_module(m)
+    oracle.policy = m
+'''
+
+
+def _run_pins(lib, policy_copy=None, plugin_dir=None):
+    env = dict(os.environ, OMP_NUM_THREADS="2")
+    cmd = [sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q", "-p",
+           "no:cacheprovider"]
+    if lib:
+        env["ACTORQ_ORACLE_LIB"] = lib
+    if policy_copy:
+        env["ACTORQ_ORACLE_POLICY_COPY"] = policy_copy
+        env["PYTHONPATH"] = plugin_dir + os.pathsep + env.get("PYTHONPATH", "")
+        cmd += ["-p", "actorq_policy_copy_plugin"]
+    r = subprocess.run(cmd, cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+    return r.returncode, (r.stdout + r.stderr)[-1500:]
 
 
 @pytest.fixture(scope="module")
@@ -118,3 +170,30 @@ def test_pins_notice(verdicts, name):
         assert rc == 0, tail
     else:
         assert rc != 0, f"no pin fails when the oracle has the mistake '{name}'"
+
+
+@pytest.fixture(scope="module")
+def chain_verdicts(tmp_path_factory):
+    work = tmp_path_factory.mktemp("chain_mutants")
+    open(work / "actorq_policy_copy_plugin.py", "w").write(PLUGIN)
+    src = open(os.path.join(ROOT, "oracle", "policy.py")).read()
+    copies = {}
+    for name, old, new in CHAIN_MUTANTS:
+        text = src
+        if old is not None:
+            assert src.count(old) == 1, f"{name}: the text to alter occurs {src.count(old)} times"
+            text = src.replace(old, new)
+        copies[name] = str(work / f"{name}.py")
+        open(copies[name], "w").write(text)
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        out = dict(zip(copies, pool.map(lambda c: _run_pins(None, c, str(work)), copies.values())))
+    return out
+
+
+@pytest.mark.parametrize("name", [m[0] for m in CHAIN_MUTANTS])
+def test_pins_notice_chain_mistakes(chain_verdicts, name):
+    rc, tail = chain_verdicts[name]
+    if name == "chain_unaltered":
+        assert rc == 0, tail
+    else:
+        assert rc != 0, f"no pin fails when the oracle's chain has the mistake '{name}'"

@@ -615,6 +615,10 @@ def test_fp16_actor_rounds_parameters_observation_and_every_operator_output():
     p1 = [{"w": np.ones((2, 4), np.float32), "b": np.zeros(2, np.float32)}]
     t = pol.forward_fp16(p1, ones * np.float32(1 + 3 * h))
     assert np.array_equal(t["pre"][0], [[4.0 * (1 + 4 * h)] * 2])
+    # the bias is rounded before use: 2049 -> 2048 (tie to even), 2051 -> 2052; the sums stay exact (no second rounding)
+    pb = [{"w": np.zeros((2, 4), np.float32), "b": np.array([2049.0, 2051.0], np.float32)}]
+    t = pol.forward_fp16(pb, ones)
+    assert np.array_equal(t["pre"][0], [[2048.0, 2052.0]])
     # the affine result is rounded once: 2049 is not a binary16 value (spacing 2 above 2048, tie to even)
     p2 = [{"w": np.ones((2, 4), np.float32), "b": np.array([2045.0, 2047.0], np.float32)}]
     t = pol.forward_fp16(p2, ones)
@@ -711,3 +715,36 @@ def test_n_bit_policy_uses_fewer_weight_levels_and_tracks_fp32():
             assert np.abs(layer["codes"].astype(np.int64)).max() <= 2 ** (bits - 1) - 1
         errs[bits] = np.abs(pol.forward_int8(obs)["actions"] - a32).max()
     assert errs[8] < errs[6] < errs[4] < 0.5  # coarser weights, larger action error (reported, not pinned)
+
+
+def test_n_bit_policy_codes_stay_inside_n_bits_at_the_top_of_the_range():
+    """Both ends of W = {-1.5, 1.5} at n = 2 sit on a tie: delta = 1, z = round(1.5) = 2 and round(1.5) + 2 = 4
+    is one past the largest 2-bit code, so the clamp of Sec. 3.2's quantizer to [0, 2^n - 1] decides it."""
+    net = synth.small_net([synth.fc(4, 2, "none")], head="linear", wscheme="tensor_asym_u8")
+    net["wbits"] = 2
+    w = np.array([[-1.5, 0.0, 1.0, 1.5], [0.5, -0.5, -1.0, 1.5]], np.float32)
+    pol = O.OraclePolicy(net)
+    q = pol.quantize_params([{"w": w, "b": np.zeros(2, np.float32)}], [(np.float32(-1), np.float32(1))])
+    assert q[0]["s_w"][0] == np.float32(1.0) and q[0]["z_w"][0] == 2
+    assert q[0]["codes"].tolist() == [[0, 2, 3, 3], [2, 2, 1, 3]]   # 0.5 -> 0 and -0.5 -> -0 (ties to even), then + 2
+
+
+def test_relu_in_the_code_domain_is_a_floor_at_the_zero_point():
+    """With a calibrated range that reaches below zero the zero-point of a ReLU layer's output is positive:
+    the layer's codes are then the codes of the same layer without ReLU, floored at the zero-point (ReLU
+    maps every negative value to 0, whose code is z), and the dequantized activations are non-negative."""
+    layers = [synth.fc(12, 16, "relu"), synth.fc(16, 3, "none")]
+    net = synth.small_net(layers)
+    plain = synth.small_net([synth.fc(12, 16, "none"), synth.fc(16, 3, "none")])
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, 40)
+    ranges = [(np.float32(-3), np.float32(3)), (np.float32(-1.0), np.float32(2.0))]
+    pol, pol0 = O.OraclePolicy(net), O.OraclePolicy(plain)
+    pol.quantize_params(params, ranges)
+    pol0.quantize_params(params, ranges)
+    z = pol.act_q[1][1]
+    assert z == 85                                            # round(1 / (3 / 255))
+    with_relu, without = pol.forward_int8(obs)["act"][0], pol0.forward_int8(obs)["act"][0]
+    assert (without < z).any() and (without > z).any()
+    assert np.array_equal(with_relu, np.maximum(without, z))
+    assert (O.c_dequantize_asym(with_relu, pol.act_q[1][0], z) >= 0).all()
