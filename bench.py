@@ -238,8 +238,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--eager", action="store_true", help="launch from the host instead of replaying HIP graphs "
                     "(for profiler runs)")
-    ap.add_argument("--only", metavar="CFG:BATCH", help="time one secondary forward workload only, e.g. cfg5:16384 "
-                    "(for profiler runs)")
+    ap.add_argument("--only", metavar="CFG:BATCH", help="time one secondary workload only: a forward pass, e.g. cfg5:16384, "
+                    "or quantize4m for the 4 M-parameter quantize pass under both schemes (for profiler runs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain 64 MiB device-to-device copies (reference for scaling HBM byte counters)")
     args = ap.parse_args()
@@ -265,6 +265,9 @@ def main():
     global _USE_GRAPHS
     _USE_GRAPHS = not args.eager
 
+    if args.only == "quantize4m":
+        print(json.dumps([quantize_workload(torch, aq, synth, U, sch) for sch in ("channel_sym_s8", "tensor_asym_u8")]))
+        return
     if args.only:
         name, bsz = args.only.split(":")
         o, c = forward_workload(torch, aq, synth, U, name, int(bsz), 100)
