@@ -122,9 +122,17 @@ aq_status aq_policy_destroy(aq_policy* p);
 aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch);
 
 /* Chooses the 8-bit forward's launch plan: 0 = automatic (whole-network fused kernel when the
- * network is an MLP that fits it, else one launch per layer), 1 = fused only (AQ_ESHAPE from the
- * forward if it does not fit), 2 = one launch per layer.  Both plans compute identical integers. */
+ * network is an MLP that fits it, else one launch per layer, with the leading convolutions of a
+ * frame policy in a single launch where their shapes allow it), 1 = fused only (AQ_ESHAPE from the
+ * forward if it does not fit), 2 = one launch per layer (convolutions as in 0), 3 = one launch per
+ * layer for every layer.  All plans compute identical integers. */
 aq_status aq_policy_set_path(aq_policy* p, int32_t path);
+
+/* *n_layers = how many leading convolution layers the 8-bit forward of this handle runs as a single
+ * launch under the current launch plan (0: none; it takes 8-bit frames, per-channel symmetric weights,
+ * kh * kw * in_c a multiple of 32, and kw * in_c, stride * in_c, in_w * in_c multiples of 16), given a
+ * 16-byte aligned observation buffer.  No GPU work. */
+aq_status aq_policy_conv_stack_layers(const aq_policy* p, int32_t* n_layers);
 
 /* Synchronizes `stream` and returns the sticky device-side error of the last
  * aq_quantize_params or aq_policy_import_blob (AQ_OK, AQ_ENONFINITE, AQ_ERANGE, or AQ_EINVAL for a

@@ -49,7 +49,8 @@ struct aq_policy {
     bool quantized = false;
     size_t layer_bytes = 0;    // the slab's leading part: every layer's packed weights and constants
     uint64_t net_hash = 0;     // of the network description (blob header)
-    int path = 0;  // 0 auto, 1 fused only, 2 one launch per layer
+    int path = 0;  // 0 auto, 1 fused only, 2 one launch per layer, 3 one launch per layer also for the convolutions
+    bool conv_stack = true;
     // activation scratch of the per-layer path and of the fp32 actor (grown on demand)
     int64_t cap_i8 = 0, cap_f32 = 0;
     int8_t* act_i8[2] = {nullptr, nullptr};
@@ -388,8 +389,18 @@ extern "C" aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch) {
 }
 
 extern "C" aq_status aq_policy_set_path(aq_policy* p, int32_t path) {
-    if (!p || path < 0 || path > 2) return AQ_EINVAL;
-    p->path = path;
+    if (!p || path < 0 || path > 3) return AQ_EINVAL;
+    p->conv_stack = path != 3;
+    p->path = path == 3 ? 2 : path;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_conv_stack_layers(const aq_policy* p, int32_t* n_layers) {
+    if (!p || !n_layers) return AQ_EINVAL;
+    FwdArgs a{};
+    a.net = p->h_net;
+    a.c.batch = 1;
+    *n_layers = p->conv_stack ? conv_stack_layers(a) : 0;
     return AQ_OK;
 }
 
@@ -732,7 +743,13 @@ static aq_status forward_int8_impl(aq_policy* p, const void* d_obs, int64_t batc
     }
     // the dequantized last-layer rows are only materialised for the y tap or for an argmax head
     float* ybuf = a.t.y ? a.t.y : (p->net.head == AQ_HEAD_ARGMAX ? p->act_f32[1] : nullptr);
-    for (int l = 0; l < nl; ++l) {
+    // a frame policy's convolutions run as one launch where their shapes allow it
+    const int nc = p->conv_stack ? conv_stack_layers(a) : 0;
+    if (nc) {
+        s = launch_conv_stack(a, p->act_i8[(nc - 1) & 1], st);
+        if (s != AQ_OK) return s;
+    }
+    for (int l = nc; l < nl; ++l) {
         const LayerBuf& b = p->L[l];
         const int64_t rows_l = batch * b.oh * b.ow;
         LayerIO io;

@@ -53,6 +53,10 @@ aq_status launch_layer_int8(const FwdArgs& a, int layer, const LayerIO& io, hipS
 bool skinny_layer_supported(const LayerDev& L, int64_t rows);
 bool skinny_layer_does_argmax(const FwdArgs& a, int l);
 // whether launch_layer_int8 hands layer l at this batch to the K-split kernel
+// the leading convolution layers in one launch (0 layers = shapes it does not take); writes the last
+// convolution's signed codes to `out` ([batch * oh * ow][N])
+int conv_stack_layers(const FwdArgs& a);
+aq_status launch_conv_stack(const FwdArgs& a, int8_t* out, hipStream_t st);
 bool layer_uses_skinny(const FwdArgs& a, int l);
 aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStream_t st);
 aq_status launch_ln_tanh_rows(const FwdArgs& a, int layer, const float* x, int8_t* out, int64_t rows, hipStream_t st);

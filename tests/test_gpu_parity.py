@@ -150,6 +150,15 @@ def _nets():
         "conv_small": synth.small_net([conv(12, 12, 4, 16, 4, 4, 2, "relu"), conv(5, 5, 16, 32, 3, 3, 1, "relu"),
                                        fc(288, 48, "relu"), fc(48, 5, "none")], head="argmax", in_type="u8",
                                       init="he_normal"),
+        # convolution stacks whose shapes the single-launch kernel takes: a ragged single tile, 48 and 40
+        # features (second feature tile half empty), 49 output positions (ragged second row tile), a layer
+        # without ReLU
+        "conv_stack_a": synth.small_net([conv(20, 20, 4, 16, 8, 8, 4, "relu"), conv(4, 4, 16, 8, 2, 2, 1, "none"),
+                                         fc(72, 24, "relu"), fc(24, 5, "none")], head="argmax", in_type="u8",
+                                        init="he_normal"),
+        "conv_stack_b": synth.small_net([conv(28, 28, 4, 48, 4, 4, 4, "relu"), conv(7, 7, 48, 32, 2, 2, 2, "relu"),
+                                         conv(3, 3, 32, 16, 2, 2, 1, "relu"), fc(64, 20, "relu"), fc(20, 6, "none")],
+                                        head="tanh", in_type="u8", init="he_normal"),
         "conv_odd": synth.small_net([conv(9, 10, 3, 5, 3, 2, 2, "relu"), fc(100, 24, "none"), fc(24, 7, "none")],
                                     head="tanh", in_type="u8", init="he_normal"),
     }
@@ -173,6 +182,35 @@ def test_forward_every_stage(aq, name, path, batch):
     # without taps the actions are the same
     a2, _ = U.gpu_forward(P, net, obs, taps=False)
     assert np.array_equal(a2, actions, equal_nan=True)
+    P.close()
+
+
+@pytest.mark.parametrize("name,nc", [("conv_stack_a", 2), ("conv_stack_b", 3), ("cfg4", 3), ("conv_small", 0)])
+@pytest.mark.parametrize("batch", [1, 3, 70])
+def test_convolutions_in_one_launch(aq, name, nc, batch):
+    """The leading convolutions as one launch (frame and feature maps in LDS) against the oracle, stage by
+    stage, and against one launch per layer; without taps the actions must not change."""
+    _say(f"convolutions_in_one_launch {name} batch={batch}")
+    net = _nets()[name] if name in _nets() else synth.net_config(name)
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs)
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    assert P.policy_conv_stack_layers() == nc
+    got = {}
+    for path in (0, 3):
+        P.policy_set_path(path)
+        assert P.policy_conv_stack_layers() == (nc if path == 0 else 0)
+        actions, t = U.gpu_forward(P, net, obs)
+        U.compare_forward(net, pol, obs, actions, t)
+        plain, _ = U.gpu_forward(P, net, obs, taps=False)
+        assert np.array_equal(plain, actions)
+        got[path] = actions
+    assert np.array_equal(got[0], got[3])
+    # observations at an address that is not 16-byte aligned take the per-layer launches: same result
+    P.policy_set_path(0)
+    shifted, _ = U.gpu_forward(P, net, obs, taps=False, misalign=3)
+    assert np.array_equal(shifted, got[0])
     P.close()
 
 
