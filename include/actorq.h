@@ -130,7 +130,7 @@ aq_status aq_policy_set_path(aq_policy* p, int32_t path);
 
 /* *n_layers = how many leading convolution layers the 8-bit forward of this handle runs as a single
  * launch under the current launch plan (0: none; it takes 8-bit frames, per-channel symmetric weights,
- * kh * kw * in_c a multiple of 32, and kw * in_c, stride * in_c, in_w * in_c multiples of 16), given a
+ * kh * kw * in_c and kw * in_c multiples of 32, stride * in_c and in_w * in_c multiples of 16), given a
  * 16-byte aligned observation buffer.  No GPU work. */
 aq_status aq_policy_conv_stack_layers(const aq_policy* p, int32_t* n_layers);
 

@@ -1,28 +1,37 @@
 // The leading convolution layers of a frame policy (Sec. 4.1: the Atari-style policies take stacked
 // 8-bit frames through three convolutions before the fully connected layers) in one launch: one
-// workgroup per image keeps the frame and every intermediate feature map in LDS, so the maps never
-// travel through global memory and the three launches of the per-layer path become one.
+// workgroup per image keeps the frame, every intermediate feature map and the layers' epilogue
+// constants in LDS.  Frame and constants are requested in one burst at its start (one round trip);
+// the maps never travel through global memory, and the three launches of the per-layer path become one.
+// Weights stream from L2 in operand order (staging them in LDS as well was measured slower: the burst
+// grows to 100 KB per workgroup and only one workgroup fits a CU).
 //
 // No im2col: with NHWC maps a 32-byte k-step of the implicit GEMM is 32 contiguous bytes of the input
 // map (part of one kernel row), so an MFMA's activation operand is one 16-byte LDS read per lane at an
 // address computed from the output position.  A wave owns a (32 output positions) x (32 features)
-// tile at a time; weights stream from L2 in operand order, a few k-steps ahead.
+// tile at a time.
 //
 // Shapes it takes (the host checks them, anything else goes one launch per layer): 8-bit frames,
 // per-channel symmetric weights, K = kh*kw*in_c a multiple of 32, kw*in_c, stride*in_c and in_w*in_c
-// multiples of 16 (operand reads stay aligned and inside one kernel row), N a multiple of 4.
+// multiples of 16 and kw*in_c a multiple of 32 (operand reads stay aligned and a k-step stays inside one
+// kernel row), N a multiple of 4, and a frame and constants within the burst's register budget (32 KB,
+// 2048 words).
 #include "int8_device.hpp"
 
 namespace aq {
 
 namespace {
-constexpr int CS_W = 8;    // waves per workgroup
-constexpr int CS_PF = 8;   // weight k-steps in flight per wave
-constexpr size_t CS_MAX_LDS = 96 * 1024;
+constexpr int CS_W = 8;          // waves per workgroup
+constexpr int CS_T = CS_W * 64;  // threads
+constexpr int CS_FU = 4;         // 16-byte pieces of the frame per thread
+constexpr int CS_CU = 4;         // words of epilogue constants per thread
+constexpr int CS_CONSTS = 5;     // arrays per layer: bias_fold | M0 | rz | sh (one contiguous pack), rshift
+constexpr size_t CS_MAX_LDS = 160 * 1024;
 
 struct StackPlan {
     int nc;          // leading convolution layers taken
-    int off_b;       // LDS offset of the second map buffer
+    int off_b;       // LDS offsets: second map buffer, constants
+    int off_c;
     size_t lds;
 };
 
@@ -37,48 +46,98 @@ bool plan_stack(const FwdArgs& a, StackPlan* p) {
         ++nc;
     }
     if (nc < 2 || nc >= net.n_layers) return false;  // a fully connected layer must follow
-    size_t sz[2] = {0, 0};
+    size_t sz[2] = {0, 0}, c_words = 0;
     for (int l = 0; l < nc; ++l) {
         const LayerDev& L = net.L[l];
         const int run = L.kw * L.in_c;
         if (L.act == AQ_ACT_LN_TANH) return false;
-        if (L.K != L.KS * 32 || run % 16 || (L.stride * L.in_c) % 16 || (L.in_w * L.in_c) % 16 || (L.N & 3)) return false;
+        if (L.K != L.KS * 32 || run % 32 || (L.stride * L.in_c) % 16 || (L.in_w * L.in_c) % 16 || (L.N & 3)) return false;
         if (a.t.ln[l]) return false;
         const size_t in_bytes = (size_t)L.in_h * L.in_w * L.in_c;
         if (in_bytes % 16) return false;
         if (in_bytes > sz[l & 1]) sz[l & 1] = in_bytes;
+        c_words += (size_t)CS_CONSTS * L.NT * 32;
     }
+    const size_t frame = (size_t)net.L[0].in_h * net.L[0].in_w * net.L[0].in_c;
+    if (frame > (size_t)CS_FU * CS_T * 16 || c_words > (size_t)CS_CU * CS_T) return false;
     if (((uintptr_t)a.c.obs & 15) || a.c.batch > 0x7fffffffLL) return false;
     p->nc = nc;
     p->off_b = (int)sz[0];
-    p->lds = sz[0] + sz[1];
+    p->off_c = (int)(sz[0] + sz[1]);
+    p->lds = sz[0] + sz[1] + c_words * 4;
     return p->lds <= CS_MAX_LDS;
 }
 }  // namespace
 
 template <bool TAPS>
-__global__ __launch_bounds__(CS_W * 64) void k_conv_stack(const NetDev* __restrict__ netp, const TapArgs t, const int nc,
-                                                         const uint8_t* __restrict__ frames, int8_t* __restrict__ out,
-                                                         const int off_b) {
+__global__ __launch_bounds__(CS_T) void k_conv_stack(const NetDev* __restrict__ netp, const TapArgs t, const int nc,
+                                                     const uint8_t* __restrict__ frames, int8_t* __restrict__ out,
+                                                     const int off_b, const int off_c) {
     extern __shared__ __align__(16) int8_t smem[];
     const NetDev& a = *netp;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, n = lane & 31;
     const int64_t img = blockIdx.x;
-    {   // the frame -> LDS, into the signed domain (code - 128)
+    {   // the burst: frame pieces and the constant words of all layers, then their LDS stores
         const LayerDev& L0 = a.L[0];
-        const int pieces = (L0.in_h * L0.in_w * L0.in_c) >> 4;
-        const v4i* src = (const v4i*)frames + img * pieces;
-        v4i* dst = (v4i*)smem;
-        for (int i = tid; i < pieces; i += CS_W * 64) {
-            v4i v = src[i];
-            v[0] ^= 0x80808080;
-            v[1] ^= 0x80808080;
-            v[2] ^= 0x80808080;
-            v[3] ^= 0x80808080;
-            dst[i] = v;
+        const int f_pieces = (L0.in_h * L0.in_w * L0.in_c) >> 4;
+        int c_words = 0;
+        for (int l = 0; l < nc; ++l) c_words += CS_CONSTS * a.L[l].NT * 32;
+        const v4i* fsrc = (const v4i*)frames + img * f_pieces;
+        v4i fr[CS_FU];
+        int cr[CS_CU];
+#pragma unroll
+        for (int u = 0; u < CS_FU; ++u) {
+            const int i = tid + u * CS_T;
+            fr[u] = fsrc[i < f_pieces ? i : f_pieces - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < CS_CU; ++u) {
+            int i = tid + u * CS_T;
+            i = i < c_words ? i : c_words - 1;
+            // which layer word i belongs to: per-lane selects over per-layer scalars (the layer index stays
+            // uniform, so the description is read by scalar loads and nothing waits on a gather)
+            const int32_t* pack = a.L[0].bias_fold;
+            const int32_t* rsh = a.L[0].rshift;
+            int np4 = 4 * a.L[0].NT * 32;
+            bool found = false;
+#pragma unroll
+            for (int j = 0; j < AQ_MAX_LAYERS - 1; ++j) {
+                if (j + 1 < nc) {
+                    const int cnt = CS_CONSTS * a.L[j].NT * 32;
+                    if (!found && i >= cnt) {
+                        i -= cnt;
+                        pack = a.L[j + 1].bias_fold;
+                        rsh = a.L[j + 1].rshift;
+                        np4 = 4 * a.L[j + 1].NT * 32;
+                    } else {
+                        found = true;
+                    }
+                }
+            }
+            cr[u] = i < np4 ? pack[i] : rsh[i - np4];
+        }
+        v4i* fdst = (v4i*)smem;
+        int* cdst = (int*)(smem + off_c);
+#pragma unroll
+        for (int u = 0; u < CS_FU; ++u) {
+            const int i = tid + u * CS_T;
+            if (i < f_pieces) {   // into the signed domain (code - 128)
+                v4i x = fr[u];
+                x[0] ^= 0x80808080;
+                x[1] ^= 0x80808080;
+                x[2] ^= 0x80808080;
+                x[3] ^= 0x80808080;
+                fdst[i] = x;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < CS_CU; ++u) {
+            const int i = tid + u * CS_T;
+            if (i < c_words) cdst[i] = cr[u];
         }
     }
     __syncthreads();
+    int c_at = off_c;  // this layer's constants in LDS
     for (int l = 0; l < nc; ++l) {
         const LayerDev& L = a.L[l];
         const int8_t* in = smem + ((l & 1) ? off_b : 0);
@@ -91,41 +150,50 @@ __global__ __launch_bounds__(CS_W * 64) void k_conv_stack(const NetDev* __restri
         const bool fast = a.fast[l] != 0;
         LayerTaps T{nullptr, nullptr, nullptr};
         if (TAPS) T = LayerTaps{t.acc[l], t.act[l], nullptr};
-        const CPtrs C = global_consts(L);
+        const int np = NT * 32;
+        const int32_t* cst = (const int32_t*)(smem + c_at);
+        const CPtrs C{cst, cst + np, cst + 4 * np, cst + 2 * np, cst + 3 * np, nullptr};
         for (int tile = wave; tile < RT * NT; tile += CS_W) {
             const int nt = tile % NT, rt = tile / NT;
             const int r = rt * 32 + n;           // this lane's output position (operand column)
             const int rc = r < R ? r : R - 1;    // a ragged last tile re-reads the last position; never stored
             const int oy = rc / L.ow, ox = rc - oy * L.ow;
             const int8_t* base = in + (oy * L.stride * L.in_w + ox * L.stride) * L.in_c;
-            gv4i_ptr wptr = (gv4i_ptr)L.wp + (int64_t)nt * KS * 64 + lane;
-            v4i w[CS_PF];
-#pragma unroll
-            for (int p = 0; p < CS_PF; ++p) w[p] = wptr[(int64_t)(p < KS ? p : KS - 1) * 64];
+            gv4i_ptr wg = (gv4i_ptr)L.wp + (int64_t)nt * KS * 64 + lane;
             v16i acc[1][1];
             acc[0][0] = zero16();
-            // (ky, kr): kernel row and byte offset inside it of this lane's half of the current k-step
-            int ky = 0, kr = g * 16;
-            while (kr >= run) {
-                kr -= run;
-                ++ky;
-            }
-            for (int ks0 = 0; ks0 < KS; ks0 += CS_PF) {
+            // Operands of four k-steps at a time, two sets in flight: the reads of one set run under the
+            // MFMAs of the other.  px walks this lane's half of the k-steps through the input map: 32 bytes
+            // on, and at the end of a kernel row (kr == run) down to the next map row.
+            const int8_t* px = base + g * 16;
+            int kr = 0;
+            auto load4 = [&](int k0, v4i (&A)[4], v4i (&X)[4]) __attribute__((always_inline)) {
 #pragma unroll
-                for (int p = 0; p < CS_PF; ++p) {
-                    const int k = ks0 + p;
-                    if (k < KS) {
-                        const v4i x = *(const v4i*)(base + ky * row_bytes + kr);
-                        acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(w[p], x, acc[0][0], 0, 0, 0);
+                for (int j = 0; j < 4; ++j) {
+                    const int k = k0 + j;
+                    const int kc = k < KS ? k : KS - 1;
+                    A[j] = wg[(int64_t)kc * 64];
+                    X[j] = *(const v4i*)px;
+                    if (k < KS - 1) {   // (uniform) never steps past the last k-step's bytes
                         kr += 32;
-                        while (kr >= run) {
-                            kr -= run;
-                            ++ky;
-                        }
-                        const int kn = k + CS_PF;
-                        w[p] = wptr[(int64_t)(kn < KS ? kn : KS - 1) * 64];
+                        const bool wrap = kr == run;
+                        px += wrap ? 32 + row_bytes - run : 32;
+                        kr = wrap ? 0 : kr;
                     }
                 }
+            };
+            auto mma4 = [&](int k0, v4i (&A)[4], v4i (&X)[4]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (k0 + j < KS) acc[0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[j], X[j], acc[0][0], 0, 0, 0);
+            };
+            v4i A0[4], X0[4], A1[4], X1[4];
+            load4(0, A0, X0);
+            for (int k0 = 0; k0 < KS; k0 += 8) {
+                load4(k0 + 4, A1, X1);
+                mma4(k0, A0, X0);
+                load4(k0 + 8, A0, X0);
+                mma4(k0 + 4, A1, X1);
             }
             v16i rs[1];
             rs[0] = zero16();
@@ -138,6 +206,7 @@ __global__ __launch_bounds__(CS_W * 64) void k_conv_stack(const NetDev* __restri
                 epi_hidden_wave<1, 1, false, TAPS, false>(N, NT, T, C, acc, rs, 0, nt, g, row_g, img * R + R, true, z_out, lo,
                                                          out0, 0, true, N);
         }
+        c_at += CS_CONSTS * np * 4;
         __syncthreads();
     }
 }
@@ -161,8 +230,8 @@ aq_status launch_conv_stack(const FwdArgs& a, int8_t* out, hipStream_t st) {
                 return AQ_EHIP;                                                                                      \
             attr_set = true;                                                                                         \
         }                                                                                                            \
-        hipLaunchKernelGGL((k_conv_stack<TP>), grid, dim3(CS_W * 64), p.lds, st, a.d_net, a.t, p.nc,                 \
-                           (const uint8_t*)a.c.obs, out, p.off_b);                                                   \
+        hipLaunchKernelGGL((k_conv_stack<TP>), grid, dim3(CS_T), p.lds, st, a.d_net, a.t, p.nc,                      \
+                           (const uint8_t*)a.c.obs, out, p.off_b, p.off_c);                                          \
     } while (0)
     if (taps) AQ_STACK(true);
     else AQ_STACK(false);

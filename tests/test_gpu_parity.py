@@ -156,7 +156,7 @@ def _nets():
         "conv_stack_a": synth.small_net([conv(20, 20, 4, 16, 8, 8, 4, "relu"), conv(4, 4, 16, 8, 2, 2, 1, "none"),
                                          fc(72, 24, "relu"), fc(24, 5, "none")], head="argmax", in_type="u8",
                                         init="he_normal"),
-        "conv_stack_b": synth.small_net([conv(28, 28, 4, 48, 4, 4, 4, "relu"), conv(7, 7, 48, 32, 2, 2, 2, "relu"),
+        "conv_stack_b": synth.small_net([conv(28, 28, 8, 48, 4, 4, 4, "relu"), conv(7, 7, 48, 32, 2, 2, 2, "relu"),
                                          conv(3, 3, 32, 16, 2, 2, 1, "relu"), fc(64, 20, "relu"), fc(20, 6, "none")],
                                         head="tanh", in_type="u8", init="he_normal"),
         "conv_odd": synth.small_net([conv(9, 10, 3, 5, 3, 2, 2, "relu"), fc(100, 24, "none"), fc(24, 7, "none")],
