@@ -21,8 +21,8 @@
 namespace aq {
 
 namespace {
-constexpr int CS_W = 8;          // waves per workgroup
-constexpr int CS_T = CS_W * 64;  // threads
+constexpr int CS_W = 8;          // waves per workgroup (16 when every image gets a CU to itself)
+constexpr int CS_T = CS_W * 64;  // threads of the smaller workgroup: sizes the burst's limits
 constexpr int CS_FU = 4;         // 16-byte pieces of the frame per thread
 constexpr int CS_CU = 4;         // words of epilogue constants per thread
 constexpr int CS_CONSTS = 5;     // arrays per layer: bias_fold | M0 | rz | sh (one contiguous pack), rshift
@@ -69,14 +69,15 @@ bool plan_stack(const FwdArgs& a, StackPlan* p) {
 }
 }  // namespace
 
-template <bool TAPS>
-__global__ __launch_bounds__(CS_T) void k_conv_stack(const NetDev* __restrict__ netp, const TapArgs t, const int nc,
+template <bool TAPS, int W>
+__global__ __launch_bounds__(W * 64) void k_conv_stack(const NetDev* __restrict__ netp, const TapArgs t, const int nc,
                                                      const uint8_t* __restrict__ frames, int8_t* __restrict__ out,
                                                      const int off_b, const int off_c) {
     extern __shared__ __align__(16) int8_t smem[];
     const NetDev& a = *netp;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, n = lane & 31;
     const int64_t img = blockIdx.x;
+    constexpr int NTHR = W * 64;
     {   // the burst: frame pieces and the constant words of all layers, then their LDS stores
         const LayerDev& L0 = a.L[0];
         const int f_pieces = (L0.in_h * L0.in_w * L0.in_c) >> 4;
@@ -87,12 +88,12 @@ __global__ __launch_bounds__(CS_T) void k_conv_stack(const NetDev* __restrict__ 
         int cr[CS_CU];
 #pragma unroll
         for (int u = 0; u < CS_FU; ++u) {
-            const int i = tid + u * CS_T;
+            const int i = tid + u * NTHR;
             fr[u] = fsrc[i < f_pieces ? i : f_pieces - 1];
         }
 #pragma unroll
         for (int u = 0; u < CS_CU; ++u) {
-            int i = tid + u * CS_T;
+            int i = tid + u * NTHR;
             i = i < c_words ? i : c_words - 1;
             // which layer word i belongs to: per-lane selects over per-layer scalars (the layer index stays
             // uniform, so the description is read by scalar loads and nothing waits on a gather)
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(CS_T) void k_conv_stack(const NetDev* __restrict__ 
         int* cdst = (int*)(smem + off_c);
 #pragma unroll
         for (int u = 0; u < CS_FU; ++u) {
-            const int i = tid + u * CS_T;
+            const int i = tid + u * NTHR;
             if (i < f_pieces) {   // into the signed domain (code - 128)
                 v4i x = fr[u];
                 x[0] ^= 0x80808080;
@@ -132,7 +133,7 @@ __global__ __launch_bounds__(CS_T) void k_conv_stack(const NetDev* __restrict__ 
         }
 #pragma unroll
         for (int u = 0; u < CS_CU; ++u) {
-            const int i = tid + u * CS_T;
+            const int i = tid + u * NTHR;
             if (i < c_words) cdst[i] = cr[u];
         }
     }
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(CS_T) void k_conv_stack(const NetDev* __restrict__ 
         const int np = NT * 32;
         const int32_t* cst = (const int32_t*)(smem + c_at);
         const CPtrs C{cst, cst + np, cst + 4 * np, cst + 2 * np, cst + 3 * np, nullptr};
-        for (int tile = wave; tile < RT * NT; tile += CS_W) {
+        for (int tile = wave; tile < RT * NT; tile += W) {
             const int nt = tile % NT, rt = tile / NT;
             const int r = rt * 32 + n;           // this lane's output position (operand column)
             const int rc = r < R ? r : R - 1;    // a ragged last tile re-reads the last position; never stored
@@ -221,20 +222,27 @@ aq_status launch_conv_stack(const FwdArgs& a, int8_t* out, hipStream_t st) {
     if (!plan_stack(a, &p)) return AQ_ESHAPE;
     const bool taps = any_taps(a);
     dim3 grid((unsigned)a.c.batch);
-#define AQ_STACK(TP)                                                                                                 \
+#define AQ_STACK(TP, WV)                                                                                             \
     do {                                                                                                             \
         static bool attr_set = false;                                                                                \
         if (!attr_set) {                                                                                             \
-            if (hipFuncSetAttribute((const void*)k_conv_stack<TP>, hipFuncAttributeMaxDynamicSharedMemorySize,       \
+            if (hipFuncSetAttribute((const void*)k_conv_stack<TP, WV>, hipFuncAttributeMaxDynamicSharedMemorySize,   \
                                     (int)CS_MAX_LDS) != hipSuccess)                                                  \
                 return AQ_EHIP;                                                                                      \
             attr_set = true;                                                                                         \
         }                                                                                                            \
-        hipLaunchKernelGGL((k_conv_stack<TP>), grid, dim3(CS_T), p.lds, st, a.d_net, a.t, p.nc,                      \
+        hipLaunchKernelGGL((k_conv_stack<TP, WV>), grid, dim3(WV * 64), p.lds, st, a.d_net, a.t, p.nc,               \
                            (const uint8_t*)a.c.obs, out, p.off_b, p.off_c);                                          \
     } while (0)
-    if (taps) AQ_STACK(true);
-    else AQ_STACK(false);
+    // up to one image per CU: sixteen waves (the first layer's tiles then run in one round); beyond that
+    // eight, so that two workgroups share a CU
+    if (a.c.batch <= 256) {
+        if (taps) AQ_STACK(true, 16);
+        else AQ_STACK(false, 16);
+    } else {
+        if (taps) AQ_STACK(true, 8);
+        else AQ_STACK(false, 8);
+    }
 #undef AQ_STACK
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }

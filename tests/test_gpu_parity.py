@@ -666,7 +666,7 @@ def test_random_mlp_shapes(aq, seed):
 
 
 # ------------------------------------------------------------------ HIP graph capture
-@pytest.mark.parametrize("name", ["cfg2", "cfg1", "conv_small"])
+@pytest.mark.parametrize("name", ["cfg2", "cfg1", "conv_small", "conv_stack_b"])
 def test_graph_replays_match_eager(aq, name):
     """The benchmark replays the library's launches from a HIP graph: quantize, forward, actor step and the
     blob hand-off are captured once and replayed several times, with eager work and synchronizations in
