@@ -345,7 +345,7 @@ def main():
         extra.append({"workload": "cfg2 batch 4096 forward + exploration noise", "us_per_step": ms_step * 1e3,
                       "inferences_per_s": batch / (ms_step * 1e-3)})
         for name, bsz, it in (("cfg5", 16384, 100), ("cfg3", 65536, 100), ("cfg3", 256, 500), ("cfg3", 1, 500),
-                              ("cfg1", 256, 500), ("cfg4", 256, 100), ("paper_fc2048", 1, 200),
+                              ("cfg1", 256, 500), ("cfg4", 256, 100), ("cfg4", 1, 200), ("paper_fc2048", 1, 200),
                               ("paper_fc2048", 16, 200)):
             o, c = forward_workload(torch, aq, synth, U, name, bsz, it)
             c[0].close()
