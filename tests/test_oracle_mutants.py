@@ -145,7 +145,7 @@ def _run_pins(lib, policy_copy=None, plugin_dir=None):
 
 
 @pytest.fixture(scope="module")
-def verdicts(tmp_path_factory):
+def outcomes(tmp_path_factory):
     """Builds every altered copy and runs the pins on each, a few at a time."""
     work = tmp_path_factory.mktemp("mutants")
     src = open(orc_build.SRC).read()
@@ -164,8 +164,8 @@ def verdicts(tmp_path_factory):
 
 
 @pytest.mark.parametrize("name", [m[0] for m in MUTANTS])
-def test_pins_notice(verdicts, name):
-    rc, tail = verdicts[name]
+def test_pins_notice(outcomes, name):
+    rc, tail = outcomes[name]
     if name == "unaltered":
         assert rc == 0, tail
     else:
@@ -173,7 +173,7 @@ def test_pins_notice(verdicts, name):
 
 
 @pytest.fixture(scope="module")
-def chain_verdicts(tmp_path_factory):
+def chain_outcomes(tmp_path_factory):
     work = tmp_path_factory.mktemp("chain_mutants")
     open(work / "actorq_policy_copy_plugin.py", "w").write(PLUGIN)
     src = open(os.path.join(ROOT, "oracle", "policy.py")).read()
@@ -191,8 +191,8 @@ def chain_verdicts(tmp_path_factory):
 
 
 @pytest.mark.parametrize("name", [m[0] for m in CHAIN_MUTANTS])
-def test_pins_notice_chain_mistakes(chain_verdicts, name):
-    rc, tail = chain_verdicts[name]
+def test_pins_notice_chain_mistakes(chain_outcomes, name):
+    rc, tail = chain_outcomes[name]
     if name == "chain_unaltered":
         assert rc == 0, tail
     else:
