@@ -133,6 +133,9 @@ aq_status aq_policy_set_path(aq_policy* p, int32_t path);
  * kh * kw * in_c and kw * in_c multiples of 32, stride * in_c and in_w * in_c multiples of 16), given a
  * 16-byte aligned observation buffer.  No GPU work. */
 aq_status aq_policy_conv_stack_layers(const aq_policy* p, int32_t* n_layers);
+/* The same for the half-precision forward (its rules: 8-bit frames, kw * in_c a multiple of 16,
+ * stride * in_c and in_w * in_c multiples of 8, out_c a multiple of 4, two to four convolutions). */
+aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers);
 
 /* Synchronizes `stream` and returns the sticky device-side error of the last
  * aq_quantize_params or aq_policy_import_blob (AQ_OK, AQ_ENONFINITE, AQ_ERANGE, or AQ_EINVAL for a

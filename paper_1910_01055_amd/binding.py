@@ -26,7 +26,7 @@ EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_pol
            "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore", "aq_policy_step_int8",
            "aq_convert_params_fp16", "aq_policy_forward_fp16",
            "aq_policy_packed_blob_size", "aq_policy_export_packed_blob", "aq_policy_import_packed_blob",
-           "aq_policy_conv_stack_layers"]
+           "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers"]
 
 
 class AqLayer(C.Structure):
@@ -82,6 +82,7 @@ def load():
     lib.aq_policy_set_path.argtypes = [vp, i32]
     lib.aq_policy_status.argtypes = [vp, vp]
     lib.aq_policy_conv_stack_layers.argtypes = [vp, C.POINTER(C.c_int32)]
+    lib.aq_policy_fp16_conv_stack_layers.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.aq_quantize_tensor.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.aq_quantize_params.argtypes = [vp, pp, pp, pp, pp, C.POINTER(AqRange), vp]
     lib.aq_policy_export_layer.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -169,6 +170,11 @@ class Policy:
     def policy_conv_stack_layers(self):
         n = C.c_int32(0)
         _check(load().aq_policy_conv_stack_layers(self._h, C.byref(n)), "aq_policy_conv_stack_layers")
+        return int(n.value)
+
+    def policy_fp16_conv_stack_layers(self):
+        n = C.c_int32(0)
+        _check(load().aq_policy_fp16_conv_stack_layers(self._h, C.byref(n)), "aq_policy_fp16_conv_stack_layers")
         return int(n.value)
 
     def policy_status(self):

@@ -900,23 +900,14 @@ extern "C" aq_status aq_convert_params_fp16(aq_policy* p, const float* const* h_
     return AQ_OK;
 }
 
-extern "C" aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
-                                            void* const* taps_out, void* stream) {
-    if (!p || batch < 0) return AQ_EINVAL;
-    if (!p->h16_ready) return AQ_ENOTQUANT;
-    if (batch == 0) return AQ_OK;
-    if (!d_obs || !d_actions) return AQ_EINVAL;
-    hipStream_t st = as_stream(stream);
-    aq_status s = ensure_f16(p, batch);
-    if (s != AQ_OK) return s;
+static void fp16_layers(const aq_policy* p, Fp16Layer* Ls) {
     const int nl = p->net.n_layers;
-    const int in_mode0 = p->net.in_type == AQ_IN_U8 ? 2 : 1;
     for (int l = 0; l < nl; ++l) {
         const LayerBuf& b = p->L[l];
         const bool last = l == nl - 1;
         Fp16Layer L{};
-        L.wp = p->h16_wp[l];
-        L.bias = p->h16_bias[l];
+        L.wp = p->h16_ready ? p->h16_wp[l] : nullptr;
+        L.bias = p->h16_ready ? p->h16_bias[l] : nullptr;
         L.K = b.K;
         L.N = b.N;
         L.KS16 = round_up(b.K, 64) / 16;
@@ -931,6 +922,51 @@ extern "C" aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int
         L.stride = b.d.stride;
         L.oh = b.oh;
         L.ow = b.ow;
+        Ls[l] = L;
+    }
+}
+
+extern "C" aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers) {
+    if (!p || !n_layers) return AQ_EINVAL;
+    Fp16Layer Ls[AQ_MAX_LAYERS];
+    fp16_layers(p, Ls);
+    *n_layers = p->conv_stack ? fp16_conv_stack_layers(Ls, p->net.n_layers, nullptr,
+                                                       p->net.in_type == AQ_IN_U8 ? 2 : 1, 1)
+                              : 0;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                            void* const* taps_out, void* stream) {
+    if (!p || batch < 0) return AQ_EINVAL;
+    if (!p->h16_ready) return AQ_ENOTQUANT;
+    if (batch == 0) return AQ_OK;
+    if (!d_obs || !d_actions) return AQ_EINVAL;
+    hipStream_t st = as_stream(stream);
+    aq_status s = ensure_f16(p, batch);
+    if (s != AQ_OK) return s;
+    const int nl = p->net.n_layers;
+    const int in_mode0 = p->net.in_type == AQ_IN_U8 ? 2 : 1;
+    Fp16Layer Ls[AQ_MAX_LAYERS];
+    fp16_layers(p, Ls);
+    // a frame policy's convolutions run as one launch where their shapes allow it (their maps then stay in
+    // LDS, so a tap on any but the last of them takes the per-layer launches)
+    int nc = p->conv_stack ? fp16_conv_stack_layers(Ls, nl, d_obs, in_mode0, batch) : 0;
+    for (int l = 0; l + 1 < nc; ++l)
+        if (taps_out && taps_out[l]) nc = 0;
+    if (nc) {
+        const LayerBuf& b = p->L[nc - 1];
+        void* out = p->act_f16[(nc - 1) & 1];
+        s = launch_fp16_conv_stack(Ls, nl, d_obs, in_mode0, batch, out, st);
+        if (s != AQ_OK) return s;
+        if (taps_out && taps_out[nc - 1])
+            AQ_HIP_CHECK(hipMemcpyAsync(taps_out[nc - 1], out, (size_t)batch * b.oh * b.ow * b.N * 2,
+                                        hipMemcpyDeviceToDevice, st));
+    }
+    for (int l = nc; l < nl; ++l) {
+        const LayerBuf& b = p->L[l];
+        const bool last = l == nl - 1;
+        Fp16Layer L = Ls[l];
         const int64_t rows_l = batch * b.oh * b.ow;
         const void* in = l == 0 ? d_obs : (const void*)p->act_f16[(l - 1) & 1];
         void* out = p->act_f16[l & 1];

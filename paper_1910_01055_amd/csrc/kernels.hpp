@@ -100,5 +100,10 @@ aq_status launch_layer_fp16(const Fp16Layer& L, const void* in, int in_mode, voi
 aq_status launch_fp16_ln_tanh(void* x, int64_t rows, int N, const float* gamma, const float* beta, float eps,
                               hipStream_t st);
 aq_status launch_fp16_head(const void* y, int64_t rows, int N, int head, void* actions, hipStream_t st);
+// the leading convolutions of a frame policy in one launch (fp16_conv_stack.hip): how many layers it takes
+// (0 = none of these shapes), and the launch, which writes the last convolution's map to `out`
+int fp16_conv_stack_layers(const Fp16Layer* L, int n_layers, const void* obs, int in_mode0, int64_t batch);
+aq_status launch_fp16_conv_stack(const Fp16Layer* L, int n_layers, const void* obs, int in_mode0, int64_t batch,
+                                 void* out, hipStream_t st);
 
 }  // namespace aq

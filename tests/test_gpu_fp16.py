@@ -204,6 +204,60 @@ def test_fp16_actor_conv_policy(aq):
     _check(net, params, obs, actions, outs)
 
 
+def _stack_nets():
+    fc, conv = synth.fc, synth.conv
+    return {
+        "cfg4": (synth.net_config("cfg4"), 3),
+        "conv_small": (_nets()["conv_small"], 2),
+        "three_convs_tanh": (synth.small_net([conv(28, 28, 8, 48, 4, 4, 4, "relu"), conv(7, 7, 48, 32, 2, 2, 2, "none"),
+                                              conv(3, 3, 32, 16, 2, 2, 1, "relu"), fc(64, 20, "relu"), fc(20, 6, "none")],
+                                             head="tanh", in_type="u8", init="he_normal"), 3),
+        "conv_odd": (_nets()["conv_odd"], 0),
+    }
+
+
+@pytest.mark.parametrize("name", list(_stack_nets().keys()))
+@pytest.mark.parametrize("batch", [1, 5, 70])
+def test_fp16_actor_convolutions_in_one_launch(aq, name, batch):
+    """The leading convolutions as one launch (maps in LDS): the last convolution's map, every later layer
+    and the actions must equal the per-layer launches bit for bit (same arithmetic in the same order), and
+    pass the oracle's checks."""
+    _say(f"fp16_actor_convolutions_in_one_launch {name} batch={batch}")
+    net, nc = _stack_nets()[name]
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    P = aq.Policy(net)
+    w, b, g, be = U.upload_params(params)
+    P.convert_params_fp16(w, b, g, be)
+    assert P.policy_fp16_conv_stack_layers() == nc
+    rf = U.layer_rows_feats(net, batch)
+    A = synth.action_dim(net)
+
+    def run(first_tap):
+        taps = [torch.zeros(r * n, dtype=torch.float16, device=U.DEV) if i >= first_tap else None
+                for i, (r, n) in enumerate(rf)]
+        if net["head"] == "argmax":
+            actions = torch.full((batch,), -1, dtype=torch.int32, device=U.DEV)
+        else:
+            actions = torch.full((batch, A), float("nan"), dtype=torch.float32, device=U.DEV)
+        P.policy_forward_fp16(U.to_dev(obs), actions, taps)
+        torch.cuda.synchronize()
+        return actions, taps
+
+    a_layers, t_layers = run(0)                      # a tap on the first map: one launch per layer
+    a_stack, t_stack = run(max(nc - 1, 0))           # taps from the last convolution on: the single launch
+    assert torch.equal(a_stack, a_layers)
+    for i in range(max(nc - 1, 0), len(rf)):
+        assert torch.equal(t_stack[i], t_layers[i]), f"layer {i}"
+    P.policy_set_path(3)
+    assert P.policy_fp16_conv_stack_layers() == 0
+    a3, _ = run(max(nc - 1, 0))
+    assert torch.equal(a3, a_layers)
+    P.close()
+    outs = [(t_stack[i] if i >= max(nc - 1, 0) else t_layers[i]).cpu().numpy().astype(np.float32) for i in range(len(rf))]
+    _check(net, params, obs, a_stack.cpu().numpy(), outs)
+
+
 @pytest.mark.parametrize("name", ["cfg5", "cfg2", "u8_mlp"])
 def test_fp16_actor_unaligned_buffers(aq, name):
     """Observation and action buffers that start off a 16-byte boundary take the element-wise input path
