@@ -166,3 +166,29 @@ def compare_forward(net, pol, obs, g_actions, t, rows=None):
     else:
         assert close(ga, ref["actions"]).all(), "actions"
     return flips_total
+
+
+def random_conv_stack(rng):
+    """A random frame policy whose convolutions fit the single-launch kernel's shape rules (kernel rows of a
+    multiple of 32 bytes, 16-byte aligned positions), found by rejection."""
+    while True:
+        nc = int(rng.integers(2, 4))
+        c = int(rng.choice([4, 8, 16]))
+        h, w = int(rng.integers(10, 41)), int(rng.integers(10, 41))
+        layers, ok, tiles = [], True, 0
+        for l in range(nc):
+            kw, kh, st = int(rng.integers(1, 9)), int(rng.integers(1, 9)), int(rng.integers(1, 5))
+            n = int(rng.choice([8, 16, 24, 32, 40, 48, 64, 72]))
+            if (kw * c) % 32 or (st * c) % 16 or (w * c) % 16 or kh > h or kw > w:
+                ok = False
+                break
+            layers.append(synth.conv(h, w, c, n, kh, kw, st, str(rng.choice(["relu", "relu", "none"]))))
+            h, w, c = (h - kh) // st + 1, (w - kw) // st + 1, n
+            tiles += (n + 31) // 32
+        first = layers[0] if layers else None
+        if not ok or tiles > 12 or h * w * c > 4000 or first["in_h"] * first["in_w"] * first["in_c"] > 32768 \
+                or (first["in_h"] * first["in_w"] * first["in_c"]) % 16:
+            continue
+        hidden = int(rng.choice([20, 48]))
+        layers += [synth.fc(h * w * c, hidden, "relu"), synth.fc(hidden, int(rng.integers(2, 19)), "none")]
+        return synth.small_net(layers, head=str(rng.choice(["argmax", "tanh"])), in_type="u8", init="he_normal"), nc

@@ -90,7 +90,7 @@ def _run_gpu(aq, net, params, obs):
     return actions.cpu().numpy(), [t.cpu().numpy().astype(np.float32) for t in taps]
 
 
-def _check(net, params, obs, actions, outs):
+def _check(net, params, obs, actions, outs, end_to_end=True):
     pol = O.OraclePolicy(net)
     nl = len(net["layers"])
     r16 = O.c_round_fp16
@@ -129,7 +129,10 @@ def _check(net, params, obs, actions, outs):
     else:
         assert np.abs(_ordered(actions) - _ordered(head)).max() <= 1
         assert np.mean(actions == head) >= 0.98
-    # end to end against the oracle alone
+    if not end_to_end:
+        return
+    # end to end against the oracle alone (a criterion for the named configurations: layer-by-layer
+    # rounding differences compound, and networks with saturating activations amplify them)
     full = pol.forward_fp16(params, obs)["actions"]
     if net["head"] == "argmax":
         assert np.mean(actions == full) >= 0.97
@@ -256,6 +259,46 @@ def test_fp16_actor_convolutions_in_one_launch(aq, name, batch):
     P.close()
     outs = [(t_stack[i] if i >= max(nc - 1, 0) else t_layers[i]).cpu().numpy().astype(np.float32) for i in range(len(rf))]
     _check(net, params, obs, a_stack.cpu().numpy(), outs)
+
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_fp16_actor_random_convolution_stacks(aq, seed):
+    """Random frame policies (kernel rows of 32 to 384 values, strides 1-4, ragged tiles): the single launch
+    against the per-layer launches, bit for bit, and against the oracle's checks."""
+    rng = np.random.default_rng(7100 + seed)
+    net, nc = U.random_conv_stack(rng)
+    if nc > 4:
+        pytest.skip("more convolutions than the half-precision stack takes")
+    batch = int(rng.choice([1, 4, 33]))
+    _say(f"fp16_actor_random_convolution_stacks seed={seed} batch={batch}")
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    P = aq.Policy(net)
+    w, b, g, be = U.upload_params(params)
+    P.convert_params_fp16(w, b, g, be)
+    assert P.policy_fp16_conv_stack_layers() == nc
+    rf = U.layer_rows_feats(net, batch)
+    A = synth.action_dim(net)
+
+    def run(first_tap):
+        taps = [torch.zeros(r * n, dtype=torch.float16, device=U.DEV) if i >= first_tap else None
+                for i, (r, n) in enumerate(rf)]
+        if net["head"] == "argmax":
+            actions = torch.full((batch,), -1, dtype=torch.int32, device=U.DEV)
+        else:
+            actions = torch.full((batch, A), float("nan"), dtype=torch.float32, device=U.DEV)
+        P.policy_forward_fp16(U.to_dev(obs), actions, taps)
+        torch.cuda.synchronize()
+        return actions, taps
+
+    a_layers, t_layers = run(0)
+    a_stack, t_stack = run(nc - 1)
+    P.close()
+    assert torch.equal(a_stack, a_layers)
+    for i in range(nc - 1, len(rf)):
+        assert torch.equal(t_stack[i], t_layers[i]), f"layer {i}"
+    outs = [(t_stack[i] if i >= nc - 1 else t_layers[i]).cpu().numpy().astype(np.float32) for i in range(len(rf))]
+    _check(net, params, obs, a_stack.cpu().numpy(), outs, end_to_end=False)  # every layer from the previous one
 
 
 @pytest.mark.parametrize("name", ["cfg5", "cfg2", "u8_mlp"])

@@ -214,36 +214,10 @@ def test_convolutions_in_one_launch(aq, name, nc, batch):
     P.close()
 
 
-def _random_conv_stack(rng):
-    """A random frame policy whose convolutions fit the single-launch kernel's shape rules (kernel rows of a
-    multiple of 32 bytes, 16-byte aligned positions), found by rejection."""
-    while True:
-        nc = int(rng.integers(2, 4))
-        c = int(rng.choice([4, 8, 16]))
-        h, w = int(rng.integers(10, 41)), int(rng.integers(10, 41))
-        layers, ok, tiles = [], True, 0
-        for l in range(nc):
-            kw, kh, st = int(rng.integers(1, 9)), int(rng.integers(1, 9)), int(rng.integers(1, 5))
-            n = int(rng.choice([8, 16, 24, 32, 40, 48, 64, 72]))
-            if (kw * c) % 32 or (st * c) % 16 or (w * c) % 16 or kh > h or kw > w:
-                ok = False
-                break
-            layers.append(synth.conv(h, w, c, n, kh, kw, st, str(rng.choice(["relu", "relu", "none"]))))
-            h, w, c = (h - kh) // st + 1, (w - kw) // st + 1, n
-            tiles += (n + 31) // 32
-        first = layers[0] if layers else None
-        if not ok or tiles > 12 or h * w * c > 4000 or first["in_h"] * first["in_w"] * first["in_c"] > 32768 \
-                or (first["in_h"] * first["in_w"] * first["in_c"]) % 16:
-            continue
-        hidden = int(rng.choice([20, 48]))
-        layers += [synth.fc(h * w * c, hidden, "relu"), synth.fc(hidden, int(rng.integers(2, 19)), "none")]
-        return synth.small_net(layers, head=str(rng.choice(["argmax", "tanh"])), in_type="u8", init="he_normal"), nc
-
-
 @pytest.mark.parametrize("seed", list(range(16)))
 def test_random_convolution_stacks(aq, seed):
     rng = np.random.default_rng(7000 + seed)
-    net, nc = _random_conv_stack(rng)
+    net, nc = U.random_conv_stack(rng)
     batch = int(rng.choice([1, 5, 37, 300]))
     _say(f"random_convolution_stacks seed={seed} batch={batch} layers={[(l['in_h'], l['in_w'], l['in_c'], l['out_c'], l['kh'], l['kw'], l['stride']) for l in net['layers'][:nc]]}")
     params = synth.make_params(net, nonzero_bias=True)
