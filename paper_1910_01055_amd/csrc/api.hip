@@ -976,6 +976,10 @@ extern "C" aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int
             L.head_actions = (float*)d_actions;
             L.head_tanh = p->net.head == AQ_HEAD_TANH;
         }
+        // an argmax policy whose logits fit one tile of the few-row kernel: the action index leaves the same launch
+        const bool fused_argmax = last && p->net.head == AQ_HEAD_ARGMAX && L.NT == 1 &&
+                                  fp16_layer_is_skinny(L, in, l == 0 ? in_mode0 : 0, rows_l);
+        if (fused_argmax) L.head_argmax = (int32_t*)d_actions;
         s = launch_layer_fp16(L, in, l == 0 ? in_mode0 : 0, out, rows_l, st);
         if (s != AQ_OK) return s;
         if (!last && b.d.act == AQ_ACT_LN_TANH) {
@@ -984,7 +988,7 @@ extern "C" aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int
         }
         if (taps_out && taps_out[l])
             AQ_HIP_CHECK(hipMemcpyAsync(taps_out[l], out, (size_t)rows_l * b.N * 2, hipMemcpyDeviceToDevice, st));
-        if (last && !fused_head) {
+        if (last && !fused_head && !fused_argmax) {
             s = launch_fp16_head(out, rows_l, b.N, p->net.head, d_actions, st);
             if (s != AQ_OK) return s;
         }

@@ -406,12 +406,30 @@ __global__ __launch_bounds__(SKH_W * 64) void k_layer_fp16_skinny(const Fp16Laye
         for (int kp = 0; kp < SKH_W; ++kp) v += part[kp * 16 * SKH_LD + reg * SKH_LD + lsrc];
         const int n = nt * 32 + nl;
         const int64_t row = row0 + m;
-        if (row >= rows || n >= L.N) continue;
-        _Float16 o = (_Float16)(v + L.bias[n]);
+        const bool ok = row < rows && n < L.N;
+        _Float16 o = (_Float16)(v + L.bias[n]);  // (bias is padded to the tile)
         if (L.relu) o = o > (_Float16)0.0f ? o : (_Float16)0.0f;
-        out[row * L.N + n] = o;
-        if (L.head_actions)
-            L.head_actions[row * L.N + n] = L.head_tanh ? (float)(_Float16)tanh_rel((float)o) : (float)o;
+        if (ok) {
+            out[row * L.N + n] = o;
+            if (L.head_actions)
+                L.head_actions[row * L.N + n] = L.head_tanh ? (float)(_Float16)tanh_rel((float)o) : (float)o;
+        }
+        if (L.head_argmax) {
+            // the whole output row sits in this tile, one feature per lane of a 32-lane group: the action
+            // index (lowest index among equal values) is a shuffle reduction away
+            float y = ok ? (float)o : -INFINITY;
+            int best = n;
+#pragma unroll
+            for (int d = 16; d > 0; d >>= 1) {
+                const float yo = __shfl_xor(y, d, 32);
+                const int bo = __shfl_xor(best, d, 32);
+                if (yo > y || (yo == y && bo < best)) {
+                    y = yo;
+                    best = bo;
+                }
+            }
+            if (nl == 0 && row < rows) L.head_argmax[row] = best;
+        }
     }
 }
 
@@ -591,6 +609,12 @@ void launch_layer_cfg(const Fp16Layer& L, const void* in, int in_mode, bool piec
 }
 }  // namespace
 
+bool fp16_layer_is_skinny(const Fp16Layer& L, const void* in, int in_mode, int64_t rows) {
+    const int64_t tiled_wgs = ((rows + 31) / 32) * (int64_t)((L.NT + HW - 1) / HW);
+    return in_mode == 0 && L.fc && L.K % 8 == 0 && ((uintptr_t)in & 15) == 0 && L.K >= 128 && tiled_wgs < 128 &&
+           (rows + 31) / 32 <= 65535;
+}
+
 aq_status launch_layer_fp16(const Fp16Layer& L, const void* in, int in_mode, void* out, int64_t rows,
                             hipStream_t st) {
     if (rows < 1) return AQ_OK;
@@ -610,8 +634,7 @@ aq_status launch_layer_fp16(const Fp16Layer& L, const void* in, int in_mode, voi
     };
     // few rows: one workgroup per output tile with K split over its waves, whenever the tiled kernel would
     // leave most CUs without a workgroup (binary16 rows of whole, aligned 16-byte pieces)
-    if (in_mode == 0 && L.fc && L.K % 8 == 0 && ((uintptr_t)in & 15) == 0 && L.K >= 128 && wgs(1, 1) < 128 &&
-        (rows + 31) / 32 <= 65535) {
+    if (fp16_layer_is_skinny(L, in, in_mode, rows)) {
         const dim3 grid((unsigned)L.NT, (unsigned)((rows + 31) / 32));
         hipLaunchKernelGGL(k_layer_fp16_skinny, grid, dim3(SKH_W * 64), 0, st, L, (const _Float16*)in, o, rows);
         return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;

@@ -89,6 +89,8 @@ struct Fp16Layer {
     int in_h, in_w, in_c, kh, kw, stride, oh, ow;
     float* head_actions;  // last layer with an elementwise head: fp32 actions [rows][N], else NULL
     int head_tanh;
+    int32_t* head_argmax;  // last layer of an argmax policy run by the few-row kernel with one feature tile:
+                           // action indices [rows], else NULL
 };
 aq_status launch_fp16_pack_weights(const float* w, int N, int K, int KS16, int NT, void* wp, int* status,
                                    hipStream_t st);
@@ -97,6 +99,8 @@ aq_status launch_fp16_round_vec(const float* src, int n, int n_pad, float fill, 
 // in_mode: 0 = binary16 activations, 1 = fp32 observations, 2 = uint8 observations
 aq_status launch_layer_fp16(const Fp16Layer& L, const void* in, int in_mode, void* out, int64_t rows,
                             hipStream_t st);
+// whether launch_layer_fp16 takes the few-row (K-split) kernel for this layer
+bool fp16_layer_is_skinny(const Fp16Layer& L, const void* in, int in_mode, int64_t rows);
 aq_status launch_fp16_ln_tanh(void* x, int64_t rows, int N, const float* gamma, const float* beta, float eps,
                               hipStream_t st);
 aq_status launch_fp16_head(const void* y, int64_t rows, int N, int head, void* actions, hipStream_t st);
