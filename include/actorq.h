@@ -266,7 +266,10 @@ aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_d_w, const 
  * holding binary16 values, or int32 [batch] for AQ_HEAD_ARGMAX; ties go to the lowest index).
  * taps_out (may be NULL): n_layers device pointers (each may be NULL) that receive layer l's binary16
  * output after its activation, [batch * oh * ow][out_c].  AQ_ENOTQUANT before the first
- * aq_convert_params_fp16.  Grows internal activation buffers on demand like aq_policy_forward_int8. */
+ * aq_convert_params_fp16.  Grows internal activation buffers on demand like aq_policy_forward_int8.
+ * A frame policy's leading convolutions run as one launch where their shapes allow it (see
+ * aq_policy_fp16_conv_stack_layers; launch plan 3 and a tap on any but the last of them select one launch
+ * per layer); both forms compute identical values. */
 aq_status aq_convert_params_fp16(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
                                  const float* const* h_d_gamma, const float* const* h_d_beta, void* stream);
 aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
