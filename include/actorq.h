@@ -50,7 +50,9 @@ typedef enum {
     AQ_ENOTQUANT = 4,  /* aq_policy_forward_int8 before aq_quantize_params */
     AQ_EHIP = 5,       /* a HIP runtime call or kernel launch failed */
     AQ_ENOMEM = 6,
-    AQ_ERANGE = 7      /* a requantization multiplier needs a shift outside [1, 62] */
+    AQ_ERANGE = 7,     /* a requantization multiplier needs a shift outside [1, 62] */
+    AQ_ETOOBIG = 8     /* the call would need more scratch memory than it may use without allocating: an internal
+                          buffer that would have to grow while `stream` is being captured into a graph */
 } aq_status;
 
 typedef enum { AQ_FC = 0, AQ_CONV2D = 1 } aq_kind;
@@ -117,8 +119,9 @@ aq_status aq_policy_create(const aq_net* net, aq_policy** out);
 aq_status aq_policy_destroy(aq_policy* p);
 
 /* Pre-allocates the internal activation buffers for batches up to max_batch, so that later
- * forwards with batch <= max_batch allocate nothing.  Forwards call it themselves when needed
- * (that first call then synchronizes the device). */
+ * forwards with batch <= max_batch allocate nothing.  Forwards grow the buffers themselves when needed
+ * (such a call waits for the device, frees and allocates; while `stream` is being captured into a graph
+ * it returns AQ_ETOOBIG instead, so reserve before capturing). */
 aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch);
 
 /* Chooses the 8-bit forward's launch plan: 0 = automatic (whole-network fused kernel when the
@@ -136,6 +139,14 @@ aq_status aq_policy_conv_stack_layers(const aq_policy* p, int32_t* n_layers);
 /* The same for the half-precision forward (its rules: 8-bit frames, kw * in_c a multiple of 16,
  * stride * in_c and in_w * in_c multiples of 8, out_c a multiple of 4, two to four convolutions). */
 aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers);
+
+/* Which compiled variant of the whole-network kernel a forward of `batch` >= 1 rows launches under the
+ * current launch plan: *rows = batch rows per workgroup (16, 32, 64 or 128), *tiles = 32-feature tiles per
+ * wavefront and pass (1 or 2); both 0 when the forward runs one launch per layer instead (a network the
+ * kernel does not take, or launch plan 2 / 3).  With the weight scheme and whether intermediate outputs are
+ * requested this names the variant, so that a test can show that every one it times is also checked.
+ * No GPU work. */
+aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles);
 
 /* Synchronizes `stream` and returns the sticky device-side error of the last
  * aq_quantize_params or aq_policy_import_blob (AQ_OK, AQ_ENONFINITE, AQ_ERANGE, or AQ_EINVAL for a

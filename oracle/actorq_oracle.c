@@ -260,11 +260,6 @@ void orc_ln_tanh(const int32_t* acc, int64_t rows, int64_t N, const float* m, co
     }
 }
 
-/* Activation (observation) quantizer: a = clamp(round(x / s) + z, 0, 255). */
-void orc_quantize_act(const float* x, int64_t n, float scale, int32_t zp, uint8_t* q) {
-    orc_quantize_asym(x, n, scale, zp, q);
-}
-
 /* tanh of fp32 values evaluated in fp64 and rounded to fp32. */
 void orc_tanh_f32(const float* y, int64_t n, float* t) {
     for (int64_t i = 0; i < n; ++i) t[i] = (float)tanh((double)y[i]);

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libactorq.so")
 MAX_LAYERS = 8
 
-OK, EINVAL, ESHAPE, ENONFINITE, ENOTQUANT, EHIP, ENOMEM, ERANGE = range(8)
+OK, EINVAL, ESHAPE, ENONFINITE, ENOTQUANT, EHIP, ENOMEM, ERANGE, ETOOBIG = range(9)
 KIND = {"fc": 0, "conv": 1}
 ACT = {"none": 0, "relu": 1, "ln_tanh": 2}
 HEAD = {"tanh": 0, "argmax": 1, "linear": 2}
@@ -26,7 +26,7 @@ EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_pol
            "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore", "aq_policy_step_int8",
            "aq_convert_params_fp16", "aq_policy_forward_fp16",
            "aq_policy_packed_blob_size", "aq_policy_export_packed_blob", "aq_policy_import_packed_blob",
-           "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers"]
+           "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers", "aq_policy_fused_plan"]
 
 
 class AqLayer(C.Structure):
@@ -83,6 +83,7 @@ def load():
     lib.aq_policy_status.argtypes = [vp, vp]
     lib.aq_policy_conv_stack_layers.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.aq_policy_fp16_conv_stack_layers.argtypes = [vp, C.POINTER(C.c_int32)]
+    lib.aq_policy_fused_plan.argtypes = [vp, i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.aq_quantize_tensor.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.aq_quantize_params.argtypes = [vp, pp, pp, pp, pp, C.POINTER(AqRange), vp]
     lib.aq_policy_export_layer.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -176,6 +177,12 @@ class Policy:
         n = C.c_int32(0)
         _check(load().aq_policy_fp16_conv_stack_layers(self._h, C.byref(n)), "aq_policy_fp16_conv_stack_layers")
         return int(n.value)
+
+    def policy_fused_plan(self, batch):
+        """(rows per workgroup, feature tiles per wavefront) of the fused kernel at this batch; (0, 0) = per layer."""
+        r, t = C.c_int32(0), C.c_int32(0)
+        _check(load().aq_policy_fused_plan(self._h, int(batch), C.byref(r), C.byref(t)), "aq_policy_fused_plan")
+        return int(r.value), int(t.value)
 
     def policy_status(self):
         return load().aq_policy_status(self._h, _stream())

@@ -6,6 +6,7 @@
 
 using namespace aq;
 
+
 namespace {
 
 struct LayerBuf {
@@ -51,10 +52,15 @@ struct aq_policy {
     uint64_t net_hash = 0;     // of the network description (blob header)
     int path = 0;  // 0 auto, 1 fused only, 2 one launch per layer, 3 one launch per layer also for the convolutions
     bool conv_stack = true;
-    // activation scratch of the per-layer path and of the fp32 actor (grown on demand)
+    // activation scratch of the per-layer path (8-bit maps, the fp32 rows a LayerNorm layer hands to its row
+    // kernel, the logits of an argmax head) and of the fp32 actor, grown on demand
     int64_t cap_i8 = 0, cap_f32 = 0;
     int8_t* act_i8[2] = {nullptr, nullptr};
+    float* ln_x = nullptr;
+    float* y_rows = nullptr;
     float* act_f32[2] = {nullptr, nullptr};
+    int64_t ln_elems = 0;  // per sample: widest LayerNorm layer output
+    int64_t y_elems = 0;   // per sample: logits kept for an argmax head
     // half-precision actor: binary16 weights in operand order and rounded bias / gain / offset per layer
     // (one allocation, made by the first aq_convert_params_fp16), and its activation scratch
     void* h16_slab = nullptr;
@@ -108,6 +114,7 @@ extern "C" const char* aq_status_string(aq_status s) {
         case AQ_EHIP: return "HIP runtime error";
         case AQ_ENOMEM: return "out of device memory";
         case AQ_ERANGE: return "requantization multiplier out of range";
+        case AQ_ETOOBIG: return "needs more scratch memory than is available without allocating";
     }
     return "unknown";
 }
@@ -196,6 +203,8 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         prev_elems = (int64_t)b.oh * b.ow * b.N;
         if (l < net->n_layers - 1 && prev_elems > p->max_hidden_elems) p->max_hidden_elems = prev_elems;
         if (prev_elems > p->max_out_elems) p->max_out_elems = prev_elems;
+        if (l < net->n_layers - 1 && d.act == AQ_ACT_LN_TANH && prev_elems > p->ln_elems) p->ln_elems = prev_elems;
+        if (l == net->n_layers - 1 && net->head == AQ_HEAD_ARGMAX) p->y_elems = prev_elems;
         offs.push_back(take((size_t)b.NT * b.KS * 1024));
         for (int i = 0; i < 7; ++i) offs.push_back(take((size_t)b.N_pad * 4));
         offs.push_back(take((size_t)b.N_pad * 4 * 4));  // the epilogue constant pack, see LayerBuf
@@ -327,28 +336,49 @@ extern "C" aq_status aq_policy_destroy(aq_policy* p) {
         if (p->act_f32[i]) (void)hipFree(p->act_f32[i]);
         if (p->act_f16[i]) (void)hipFree(p->act_f16[i]);
     }
+    if (p->ln_x) (void)hipFree(p->ln_x);
+    if (p->y_rows) (void)hipFree(p->y_rows);
     if (p->h16_slab) (void)hipFree(p->h16_slab);
     delete p;
     return AQ_OK;
 }
 
-static aq_status ensure_i8(aq_policy* p, int64_t batch) {
+// Growing a buffer frees and allocates device memory and waits for the device: not possible while the
+// caller's stream is being captured into a graph, which the forward then reports instead of breaking the capture.
+static bool capturing(hipStream_t st) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    return hipStreamIsCapturing(st, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone;
+}
+
+// bytes of one 8-bit activation map of the per-layer plan (a little slack behind the last row)
+static size_t i8_map_bytes(const aq_policy* p, int64_t batch) {
+    return (size_t)batch * (size_t)(p->max_hidden_elems > 0 ? p->max_hidden_elems : 1) + 64;
+}
+
+static aq_status ensure_i8(aq_policy* p, int64_t batch, hipStream_t st) {
     if (batch <= p->cap_i8) return AQ_OK;
+    if (capturing(st)) return AQ_ETOOBIG;
     (void)hipDeviceSynchronize();
     for (int i = 0; i < 2; ++i) {
         if (p->act_i8[i]) (void)hipFree(p->act_i8[i]);
         p->act_i8[i] = nullptr;
     }
+    if (p->ln_x) (void)hipFree(p->ln_x);
+    if (p->y_rows) (void)hipFree(p->y_rows);
+    p->ln_x = p->y_rows = nullptr;
     p->cap_i8 = 0;
-    size_t n = (size_t)batch * (size_t)(p->max_hidden_elems > 0 ? p->max_hidden_elems : 1) + 64;
     for (int i = 0; i < 2; ++i)
-        if (hipMalloc((void**)&p->act_i8[i], n) != hipSuccess) return AQ_ENOMEM;
+        if (hipMalloc((void**)&p->act_i8[i], i8_map_bytes(p, batch)) != hipSuccess) return AQ_ENOMEM;
+    // fp32 rows exist only where the 8-bit path needs them: LayerNorm inputs, argmax logits
+    if (p->ln_elems && hipMalloc((void**)&p->ln_x, (size_t)batch * p->ln_elems * 4 + 256) != hipSuccess) return AQ_ENOMEM;
+    if (p->y_elems && hipMalloc((void**)&p->y_rows, (size_t)batch * p->y_elems * 4 + 256) != hipSuccess) return AQ_ENOMEM;
     p->cap_i8 = batch;
     return AQ_OK;
 }
 
-static aq_status ensure_f32(aq_policy* p, int64_t batch) {
+static aq_status ensure_f32(aq_policy* p, int64_t batch, hipStream_t st) {
     if (batch <= p->cap_f32) return AQ_OK;
+    if (capturing(st)) return AQ_ETOOBIG;
     (void)hipDeviceSynchronize();
     for (int i = 0; i < 2; ++i) {
         if (p->act_f32[i]) (void)hipFree(p->act_f32[i]);
@@ -362,8 +392,9 @@ static aq_status ensure_f32(aq_policy* p, int64_t batch) {
     return AQ_OK;
 }
 
-static aq_status ensure_f16(aq_policy* p, int64_t batch) {
+static aq_status ensure_f16(aq_policy* p, int64_t batch, hipStream_t st) {
     if (batch <= p->cap_f16) return AQ_OK;
+    if (capturing(st)) return AQ_ETOOBIG;
     (void)hipDeviceSynchronize();
     for (int i = 0; i < 2; ++i) {
         if (p->act_f16[i]) (void)hipFree(p->act_f16[i]);
@@ -379,13 +410,13 @@ static aq_status ensure_f16(aq_policy* p, int64_t batch) {
 
 extern "C" aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch) {
     if (!p || max_batch < 0) return AQ_EINVAL;
-    aq_status s = ensure_i8(p, max_batch);
+    aq_status s = ensure_i8(p, max_batch, nullptr);
     if (s != AQ_OK) return s;
     if (p->h16_ready) {
-        s = ensure_f16(p, max_batch);
+        s = ensure_f16(p, max_batch, nullptr);
         if (s != AQ_OK) return s;
     }
-    return ensure_f32(p, max_batch);
+    return ensure_f32(p, max_batch, nullptr);
 }
 
 extern "C" aq_status aq_policy_set_path(aq_policy* p, int32_t path) {
@@ -401,6 +432,19 @@ extern "C" aq_status aq_policy_conv_stack_layers(const aq_policy* p, int32_t* n_
     a.net = p->h_net;
     a.c.batch = 1;
     *n_layers = p->conv_stack ? conv_stack_layers(a) : 0;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles) {
+    if (!p || !rows || !tiles || batch < 1) return AQ_EINVAL;
+    FwdArgs a{};
+    a.net = p->h_net;
+    a.c.batch = batch;
+    int r = 0, t = 0;
+    size_t lds = 0;
+    if (p->path == 2 || !fused_mlp_supported(a, &r, &lds, &t)) r = t = 0;
+    *rows = r;
+    *tiles = t;
     return AQ_OK;
 }
 
@@ -675,8 +719,18 @@ extern "C" aq_status aq_policy_export_act_qparams(const aq_policy* p, float* d_s
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
+// where the one-launch-per-layer plan keeps its intermediate tensors
+struct FwdScratch {
+    int8_t* i8[2];  // 8-bit activation maps, ping-pong
+    float* ln_x;    // fp32 rows into a LayerNorm row kernel
+    float* y;       // logits of an argmax head
+};
+
+// `fixed`: scratch the caller of this function provides (the allocation-free entry point); NULL = the handle's
+// own buffers, grown on demand
 static aq_status forward_int8_impl(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
-                                   const aq_taps* taps, const aq_explore* ex, void* stream) {
+                                   const aq_taps* taps, const aq_explore* ex, void* stream,
+                                   const FwdScratch* fixed = nullptr) {
     if (!p || batch < 0) return AQ_EINVAL;
     if (ex) {
         const aq_status es = explore_args_ok(p, ex, batch);
@@ -731,10 +785,15 @@ static aq_status forward_int8_impl(aq_policy* p, const void* d_obs, int64_t batc
     }
 
     // one launch per layer
-    aq_status s = ensure_i8(p, batch);
-    if (s != AQ_OK) return s;
-    s = ensure_f32(p, batch);
-    if (s != AQ_OK) return s;
+    aq_status s = AQ_OK;
+    FwdScratch sc;
+    if (fixed) {
+        sc = *fixed;
+    } else {
+        s = ensure_i8(p, batch, st);
+        if (s != AQ_OK) return s;
+        sc = FwdScratch{{p->act_i8[0], p->act_i8[1]}, p->ln_x, p->y_rows};
+    }
     if (a.net.in_u8 && a.t.a0) {
         const LayerBuf& b0 = p->L[0];
         const size_t n = (size_t)batch * b0.d.in_h * b0.d.in_w * b0.d.in_c;
@@ -742,20 +801,20 @@ static aq_status forward_int8_impl(aq_policy* p, const void* d_obs, int64_t batc
         a.t.a0 = nullptr;
     }
     // the dequantized last-layer rows are only materialised for the y tap or for an argmax head
-    float* ybuf = a.t.y ? a.t.y : (p->net.head == AQ_HEAD_ARGMAX ? p->act_f32[1] : nullptr);
+    float* ybuf = a.t.y ? a.t.y : (p->net.head == AQ_HEAD_ARGMAX ? sc.y : nullptr);
     // a frame policy's convolutions run as one launch where their shapes allow it
     const int nc = p->conv_stack ? conv_stack_layers(a) : 0;
     if (nc) {
-        s = launch_conv_stack(a, p->act_i8[(nc - 1) & 1], st);
+        s = launch_conv_stack(a, sc.i8[(nc - 1) & 1], st);
         if (s != AQ_OK) return s;
     }
     for (int l = nc; l < nl; ++l) {
         const LayerBuf& b = p->L[l];
         const int64_t rows_l = batch * b.oh * b.ow;
         LayerIO io;
-        io.in = l == 0 ? d_obs : (const void*)p->act_i8[(l - 1) & 1];
-        io.out = p->act_i8[l & 1];
-        io.ln_x = p->act_f32[0];
+        io.in = l == 0 ? d_obs : (const void*)sc.i8[(l - 1) & 1];
+        io.out = sc.i8[l & 1];
+        io.ln_x = sc.ln_x;
         io.y = ybuf;
         s = launch_layer_int8(a, l, io, st);
         if (s != AQ_OK) return s;
@@ -793,7 +852,7 @@ extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_
     for (int l = 0; l < nl; ++l)
         if (!h_d_w[l]) return AQ_EINVAL;
     hipStream_t st = as_stream(stream);
-    aq_status s = ensure_f32(p, batch);
+    aq_status s = ensure_f32(p, batch, st);
     if (s != AQ_OK) return s;
     const int in_u8 = p->net.in_type == AQ_IN_U8;
     if (d_ranges_out) {
@@ -943,7 +1002,7 @@ extern "C" aq_status aq_policy_forward_fp16(aq_policy* p, const void* d_obs, int
     if (batch == 0) return AQ_OK;
     if (!d_obs || !d_actions) return AQ_EINVAL;
     hipStream_t st = as_stream(stream);
-    aq_status s = ensure_f16(p, batch);
+    aq_status s = ensure_f16(p, batch, st);
     if (s != AQ_OK) return s;
     const int nl = p->net.n_layers;
     const int in_mode0 = p->net.in_type == AQ_IN_U8 ? 2 : 1;

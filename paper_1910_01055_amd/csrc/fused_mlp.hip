@@ -104,11 +104,12 @@ bool any_taps(const FwdArgs& a) {
     return false;
 }
 
-bool fused_mlp_supported(const FwdArgs& a, int* rows_out, size_t* lds_out) {
+bool fused_mlp_supported(const FwdArgs& a, int* rows_out, size_t* lds_out, int* tiles_out) {
     Plan p;
     if (!make_plan(a, &p)) return false;
     *rows_out = p.half ? 16 : 32 * p.mt;
     *lds_out = p.lds;
+    if (tiles_out) *tiles_out = p.nb;
     return true;
 }
 

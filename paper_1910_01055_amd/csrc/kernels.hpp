@@ -38,7 +38,7 @@ struct FwdArgs {
 
 // whole-network fused MLP kernel; returns AQ_ESHAPE when the network does not fit it
 bool any_taps(const FwdArgs& a);
-bool fused_mlp_supported(const FwdArgs& a, int* rows_per_wg_out, size_t* lds_bytes_out);
+bool fused_mlp_supported(const FwdArgs& a, int* rows_per_wg_out, size_t* lds_bytes_out, int* tiles_per_wave_out = nullptr);
 aq_status launch_fused_mlp(const FwdArgs& a, hipStream_t st);
 
 // one launch per layer (FC and implicit-GEMM convolution), activations in global memory

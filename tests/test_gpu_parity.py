@@ -176,7 +176,7 @@ def test_forward_every_stage(aq, name, path, batch):
     P, _ = U.gpu_quantize(aq, net, params, ranges)
     U.check_quantized_params(aq, P, pol, net)
     P.policy_set_path(path)
-    for rep in range(2):  # twice: a racy LDS stage would show as a changing accumulator
+    for rep in range(3):  # three times: a racy LDS stage would show as a changing accumulator
         actions, t = U.gpu_forward(P, net, obs)
         U.compare_forward(net, pol, obs, actions, t)
     # without taps the actions are the same
@@ -301,12 +301,82 @@ def test_forward_full_size(aq, name, batch, sample):
         rows = np.unique(np.concatenate([[0, batch - 1], rng.integers(0, batch, sample)]))
     flips = U.compare_forward(net, pol, obs, actions, t, rows)
     _say(f"  LayerNorm code flips at rounding ties: {flips}")
+    # the launch the benchmark times has no intermediate outputs (another compiled variant): same actions
+    plain, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(plain, actions, equal_nan=True)
     # properties that hold at any size
     if net["head"] == "tanh":
         assert np.isfinite(actions).all() and np.abs(actions).max() <= 1.0
     else:
         assert actions.min() >= 0 and actions.max() < synth.action_dim(net)
     P.close()
+
+
+# Every compiled variant of the whole-network kernel, named by (batch rows per workgroup, feature tiles per
+# wavefront, per-tensor weight scheme): the network and batch that make the launch plan pick it.  Each is run
+# with intermediate outputs (checked stage by stage against the oracle) and without (the variant a
+# benchmark times; its actions must be the same bits).
+_ODD_WIDE = [synth.fc(100, 1000, "relu"), synth.fc(1000, 1024, "relu"), synth.fc(1024, 40, "none")]
+FUSED_VARIANTS = {
+    (16, 1, False): [("cfg2", 4096)],
+    (16, 1, True): [("cfg1", 256)],
+    (32, 1, False): [("cfg2", 8192)],
+    (64, 1, False): [("cfg2", 16379)],
+    (128, 1, False): [("cfg2", 32763)],
+    (32, 2, False): [("cfg5", 8192), ("odd_wide", 8185)],
+    (64, 2, False): [("cfg5", 16384), ("odd_wide", 16379)],
+    (32, 1, True): [("cfg1", 8192)],
+    (64, 1, True): [("cfg1", 16379)],
+}
+
+
+def _variant_net(name):
+    if name == "odd_wide":  # a ragged last feature tile (1000 = 31 * 32 + 8) with two tiles per wavefront
+        return synth.small_net(_ODD_WIDE, head="tanh")
+    return synth.net_config(name)
+
+
+def test_fused_variant_table_covers_every_compiled_variant():
+    """The table above names every instantiation the library compiles (with and without intermediate outputs)."""
+    import os
+    import re
+    src = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_1910_01055_amd", "csrc",
+                       "fused_mlp.hip")
+    decl = re.findall(r"AQ_FUSED_DECL\((\d), (\d), (true|false), (true|false), (true|false)\);", open(src).read())
+    assert len(decl) >= 18
+    seen = {}
+    for mt, nb, asym, taps, half in decl:
+        key = (16 if half == "true" else 32 * int(mt), int(nb), asym == "true")
+        seen.setdefault(key, set()).add(taps)
+    assert set(seen) == set(FUSED_VARIANTS), (sorted(seen), sorted(FUSED_VARIANTS))
+    assert all(v == {"true", "false"} for v in seen.values())
+
+
+@pytest.mark.parametrize("key", sorted(FUSED_VARIANTS))
+def test_every_fused_variant_against_the_oracle(aq, key):
+    for name, batch in FUSED_VARIANTS[key]:
+        _say(f"fused_variant rows={key[0]} tiles={key[1]} per_tensor={key[2]} {name} batch={batch}")
+        net = _variant_net(name)
+        assert (net["wscheme"] == "tensor_asym_u8") == key[2]
+        params = synth.make_params(net, nonzero_bias=True)
+        obs = synth.make_obs(net, batch)
+        pol, ranges = U.make_oracle(net, params, obs[:256])
+        P, _ = U.gpu_quantize(aq, net, params, ranges)
+        assert P.policy_fused_plan(batch) == key[:2]
+        rng = np.random.default_rng(21)
+        rows = np.unique(np.concatenate([[0, 15, 16, 31, 32, 63, 64, batch - 65, batch - 33, batch - 1],
+                                         rng.integers(0, batch, 250)]))
+        first = None
+        for rep in range(3):
+            actions, t = U.gpu_forward(P, net, obs)
+            U.compare_forward(net, pol, obs, actions, t, rows)
+            del t
+            plain, _ = U.gpu_forward(P, net, obs, taps=False)
+            assert np.array_equal(plain, actions, equal_nan=True)
+            assert first is None or np.array_equal(first, plain, equal_nan=True)
+            first = plain
+        assert np.isfinite(plain).all() and np.abs(plain).max() <= 1.0
+        P.close()
 
 
 @pytest.mark.parametrize("name", ["odd_asym", "two_tile_last_asym", "wide_last", "single_narrow", "long_k_narrow",

@@ -26,6 +26,8 @@ MUTANTS = [
      "w[i] = scale * (float)((int32_t)q[i] + zp);"),
     ("channel_scale_128", "float s = m / (float)qw;", "float s = m / (float)(qw + 1);"),
     ("channel_abs_dropped", "float a = fabsf(v);", "float a = v;"),
+    ("channel_dequant_scale_of_the_column", "w[r * cols + c] = scales[r] * (float)q[r * cols + c];",
+     "w[r * cols + c] = scales[c % rows] * (float)q[r * cols + c];"),
     # layer constants
     ("multiplier_inverted", "double M = sw / (double)s_out;", "double M = sw * (double)s_out;"),
     ("shift_off_by_one", "int32_t r = 31 - e;", "int32_t r = 30 - e;"),

@@ -112,6 +112,17 @@ def test_sym_rows(seed):
     hw = np.array([[127 / 64, 0.5 / 64, 1.5 / 64, -2.5 / 64, -1.0]], np.float32)
     hq, hs = O.c_quantize_sym_rows(hw)
     assert hs[0] == np.float32(1 / 64) and list(hq[0]) == [127, 0, 2, -2, -64]
+    # Sec. 3.2's D(W_q, delta) = delta * W_q per channel: exact on the hand case (power-of-two delta), each
+    # row scaled by its own delta (rows of equal codes and different scales must differ), a code of zero
+    # gives 0.0, the round trip stays within delta / 2, and quantizing the result again returns the codes
+    assert list(O.c_dequantize_sym_rows(hq, hs)[0]) == [127 / 64, 0.0, 2 / 64, -2 / 64, -1.0]
+    two = O.c_dequantize_sym_rows(np.array([[1, -3, 0], [1, -3, 0]], np.int8), np.array([0.5, 0.25], np.float32))
+    assert two.tolist() == [[0.5, -1.5, 0.0], [0.25, -0.75, 0.0]]
+    wd = O.c_dequantize_sym_rows(q, s)
+    assert wd.dtype == np.float32 and not wd[5].any()
+    assert (np.abs(w.astype(np.float64) - wd) <= s[:, None].astype(np.float64) / 2 * (1 + 4 * 2.0 ** -23)).all()
+    q4, s4 = O.c_quantize_sym_rows(wd)
+    assert np.array_equal(q4, q)
 
 
 # ---------------------------------------------------------------- O2: layer constants
