@@ -51,8 +51,9 @@ typedef enum {
     AQ_EHIP = 5,       /* a HIP runtime call or kernel launch failed */
     AQ_ENOMEM = 6,
     AQ_ERANGE = 7,     /* a requantization multiplier needs a shift outside [1, 62] */
-    AQ_ETOOBIG = 8     /* the call would need more scratch memory than it may use without allocating: an internal
-                          buffer that would have to grow while `stream` is being captured into a graph */
+    AQ_ETOOBIG = 8     /* the call would need more scratch memory than it may use without allocating: a batch
+                          beyond the static buffer of aq_policy_forward_int8_static, or an internal buffer that
+                          would have to grow while `stream` is being captured into a graph */
 } aq_status;
 
 typedef enum { AQ_FC = 0, AQ_CONV2D = 1 } aq_kind;
@@ -251,6 +252,24 @@ aq_status aq_policy_export_act_qparams(const aq_policy* p, float* d_scale, int32
  * taps may be NULL.  Asynchronous once the internal buffers cover `batch`. */
 aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
                                  const aq_taps* taps, void* stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid it): aq_policy_forward_int8 without intermediate outputs, guaranteed to call no
+ * hipMalloc / hipFree or any other allocating routine and never to wait for the device.  The scratch of the
+ * one-launch-per-layer plan (two 8-bit activation maps, the fp32 rows in front of a LayerNorm row kernel,
+ * the logits of an argmax head) lives in a buffer of AQ_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image: every GPU the library runs on holds it until the process ends.  A batch that needs more
+ * than that -- 2 * (batch * widest hidden map + 64 bytes) + 4 * batch * (LayerNorm width + argmax logits),
+ * each piece rounded up to 256 bytes; e.g. batch <= 650 for an 84 x 84 x 4 frame policy whose first
+ * convolution yields 20 x 20 x 32 -- is refused with AQ_ETOOBIG and nothing is launched.  Networks that run
+ * as the single whole-network kernel (see aq_policy_fused_plan) keep everything on chip, use none of the
+ * buffer and take any batch.  Same arguments, results and other errors as aq_policy_forward_int8.
+ * All calls on one GPU share that GPU's buffer, whatever the handle or stream: calls that overlap in time on
+ * one GPU race; serialize them (one stream, or events).  Nothing in the buffer has to start at zero and the
+ * call reads no byte of it that it has not written itself. */
+#define AQ_STATIC_SCRATCH_BYTES (16u << 20)
+aq_status aq_policy_forward_int8_static(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                        void* stream);
 
 /* The full-precision actor (the paper's fp32 baseline) on the same network, computed in fp32
  * from the learner's parameters.  d_ranges_out (may be NULL): 2 * n_layers floats that receive

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libactorq.so")
 MAX_LAYERS = 8
 
 OK, EINVAL, ESHAPE, ENONFINITE, ENOTQUANT, EHIP, ENOMEM, ERANGE, ETOOBIG = range(9)
+STATIC_SCRATCH_BYTES = 16 << 20
 KIND = {"fc": 0, "conv": 1}
 ACT = {"none": 0, "relu": 1, "ln_tanh": 2}
 HEAD = {"tanh": 0, "argmax": 1, "linear": 2}
@@ -26,7 +27,7 @@ EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_pol
            "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore", "aq_policy_step_int8",
            "aq_convert_params_fp16", "aq_policy_forward_fp16",
            "aq_policy_packed_blob_size", "aq_policy_export_packed_blob", "aq_policy_import_packed_blob",
-           "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers", "aq_policy_fused_plan"]
+           "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers", "aq_policy_fused_plan", "aq_policy_forward_int8_static"]
 
 
 class AqLayer(C.Structure):
@@ -89,6 +90,7 @@ def load():
     lib.aq_policy_export_layer.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.aq_policy_export_act_qparams.argtypes = [vp, vp, vp, vp]
     lib.aq_policy_forward_int8.argtypes = [vp, vp, i64, vp, C.POINTER(AqTaps), vp]
+    lib.aq_policy_forward_int8_static.argtypes = [vp, vp, i64, vp, vp]
     lib.aq_policy_forward_fp32.argtypes = [vp, pp, pp, pp, pp, vp, i64, vp, vp, vp]
     lib.aq_policy_blob_size.argtypes = [vp, C.POINTER(C.c_uint64)]
     lib.aq_policy_export_blob.argtypes = [vp, vp, C.c_uint64, vp]
@@ -259,6 +261,11 @@ class Policy:
         _check(load().aq_policy_forward_int8(self._h, _ptr(obs), batch, _ptr(actions),
                                              C.byref(ctaps) if ctaps is not None else None, _stream()),
                "aq_policy_forward_int8")
+
+    def policy_forward_int8_static(self, obs, actions):
+        """The 8-bit forward that allocates nothing (scratch in the library's static device buffer)."""
+        _check(load().aq_policy_forward_int8_static(self._h, _ptr(obs), int(obs.shape[0]), _ptr(actions), _stream()),
+               "aq_policy_forward_int8_static")
 
     def policy_forward_fp32(self, w, b, gamma, beta, obs, actions, ranges_out=None):
         n = self.n_layers

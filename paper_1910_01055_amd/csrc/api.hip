@@ -1,4 +1,5 @@
 // C ABI of the library: the policy handle, argument checks and the launch sequences.
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -6,6 +7,31 @@
 
 using namespace aq;
 
+// Scratch of aq_policy_forward_int8_static: the intermediate activations of the one-launch-per-layer plan for
+// callers that cannot allocate.  The array is part of the library's device image, so every GPU the library
+// runs on holds its own copy at its own address until the process ends; host code never uses the array's
+// name as an address (it is only a host-side stand-in), but the per-device pointer looked up below.
+static __device__ __align__(256) unsigned char scratch[AQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];  // per device, filled on first use with that device current
+
+// device address of `scratch` on the current device (AQ_EHIP when the lookup fails)
+aq_status static_scratch(unsigned char** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return AQ_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return AQ_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = (unsigned char*)g_scratch_ptr[dev];
+    return AQ_OK;
+}
+}  // namespace
 
 namespace {
 
@@ -322,6 +348,14 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         (void)hipFree(p->slab);
         delete p;
         return AQ_EHIP;
+    }
+    {   // set-up of the allocation-free forward: this device's address of the static scratch
+        unsigned char* sc = nullptr;
+        if (static_scratch(&sc) != AQ_OK) {
+            (void)hipFree(p->slab);
+            delete p;
+            return AQ_EHIP;
+        }
     }
     *out = p;
     return AQ_OK;
@@ -839,6 +873,36 @@ extern "C" aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int
 extern "C" aq_status aq_policy_step_int8(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
                                          const aq_explore* ex, const aq_taps* taps, void* stream) {
     return forward_int8_impl(p, d_obs, batch, d_actions, taps, ex, stream);
+}
+
+extern "C" aq_status aq_policy_forward_int8_static(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                                   void* stream) {
+    if (!p || batch < 0) return AQ_EINVAL;
+    unsigned char* base = nullptr;
+    const aq_status ss = static_scratch(&base);
+    if (ss != AQ_OK) return ss;
+    // carve the static array: two 8-bit maps, LayerNorm rows, argmax logits (each piece 256-byte aligned)
+    auto up = [](size_t n) { return (n + 255) / 256 * 256; };
+    const size_t map = up(i8_map_bytes(p, batch));
+    const size_t ln = up((size_t)batch * (size_t)p->ln_elems * 4);
+    const size_t y = up((size_t)batch * (size_t)p->y_elems * 4);
+    FwdArgs probe{};
+    probe.net = p->h_net;
+    probe.c.batch = batch > 0 ? batch : 1;
+    int rows = 0;
+    size_t lds = 0;
+    const bool fused = p->path != 2 && fused_mlp_supported(probe, &rows, &lds);
+    FwdScratch sc{{nullptr, nullptr}, nullptr, nullptr};
+    if (!fused) {  // (the whole-network kernel keeps everything in LDS and needs none of it)
+        if ((double)batch * (double)(p->max_hidden_elems + 4 * (p->ln_elems + p->y_elems)) > 1e12 ||
+            2 * map + ln + y > (size_t)AQ_STATIC_SCRATCH_BYTES)
+            return AQ_ETOOBIG;
+        sc.i8[0] = (int8_t*)base;
+        sc.i8[1] = (int8_t*)(base + map);
+        sc.ln_x = (float*)(base + 2 * map);
+        sc.y = (float*)(base + 2 * map + ln);
+    }
+    return forward_int8_impl(p, d_obs, batch, d_actions, nullptr, nullptr, stream, &sc);
 }
 
 extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
