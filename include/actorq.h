@@ -231,7 +231,9 @@ aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int32
  * and shifts.  h_d_w[l], h_d_b[l]: device pointers to layer l's weights and bias (bias may be
  * NULL = zeros).  h_d_gamma[l], h_d_beta[l]: LayerNorm gain/offset for AQ_ACT_LN_TANH layers
  * (NULL entries = 1 and 0; the arrays themselves may be NULL).  h_ranges: n_layers activation
- * ranges (entry 0 is ignored for AQ_IN_U8).  Asynchronous; LayerNorm parameters are copied. */
+ * ranges (entry 0 is ignored for AQ_IN_U8).  h_d_w = NULL (then h_d_b, h_d_gamma, h_d_beta must be NULL as
+ * well) quantizes the parameters kept by aq_policy_set_params_fp32 (AQ_ENOTQUANT if there are none).
+ * Asynchronous; LayerNorm parameters are copied. */
 aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
                              const float* const* h_d_gamma, const float* const* h_d_beta,
                              const aq_range* h_ranges, void* stream);
@@ -271,14 +273,36 @@ aq_status aq_policy_forward_int8(aq_policy* p, const void* d_obs, int64_t batch,
 aq_status aq_policy_forward_int8_static(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
                                         void* stream);
 
-/* The full-precision actor (the paper's fp32 baseline) on the same network, computed in fp32
- * from the learner's parameters.  d_ranges_out (may be NULL): 2 * n_layers floats that receive
- * (min, max) of the network input and of every hidden layer's output over this batch -- the
- * min/max calibration of the activation ranges. */
-aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
-                                 const float* const* h_d_gamma, const float* const* h_d_beta,
-                                 const void* d_obs, int64_t batch, void* d_actions, float* d_ranges_out,
-                                 void* stream);
+/* ---- The full-precision actor (the paper's fp32 baseline, q = 32) and the min/max calibration of the
+ * activation ranges (Sec. 3.1: the learner owns the fp32 policy, the quantizer block hands the actors an
+ * 8-bit one; Sec. 3.2: activations are quantized like weights, which needs their ranges).
+ *
+ * aq_policy_set_params_fp32: copies the learner's fp32 parameters (same arrays and layouts as
+ *   aq_quantize_params; NULL biases, gains, offsets = 0, 1, 0) into buffers of the handle, device to device on
+ *   `stream`.  The first call allocates them (hipMalloc; AQ_ETOOBIG while `stream` is being captured).
+ *   Afterwards the calls below need no parameter arrays, and aq_quantize_params accepts h_d_w = NULL (with
+ *   h_d_b, h_d_gamma, h_d_beta NULL too) to quantize this copy.
+ *   Why the copy is a call of its own and not part of aq_quantize_params: calibration has to run before the
+ *   quantizer (the ranges are its input), and a model pull that only wants the 8-bit policy would otherwise
+ *   pay a second 4 bytes per parameter of HBM writes on every pull.
+ * aq_policy_forward_fp32: the fp32 actor on the kept parameters, d_obs -> d_actions (fp32 [batch][A], or
+ *   int32 [batch] for AQ_HEAD_ARGMAX).  AQ_ENOTQUANT before aq_policy_set_params_fp32.  Asynchronous once the
+ *   internal buffers cover `batch` (see aq_policy_reserve).
+ * aq_calibrate_fp32: runs the fp32 actor on a calibration batch (batch >= 1) and writes to the HOST array
+ *   h_ranges_out[n_layers] the (min, max) of the network input and of every hidden layer's output after its
+ *   activation -- the ranges aq_quantize_params takes.  Waits for `stream` (AQ_EINVAL while it is being
+ *   captured).  AQ_ENOTQUANT before aq_policy_set_params_fp32.
+ * aq_policy_forward_fp32_params: the same actor on parameter arrays passed with the call (nothing kept),
+ *   with the calibration as an optional device-side output and no wait: d_ranges_out (may be NULL) receives
+ *   2 * n_layers floats, (min, max) per activation tensor as above. */
+aq_status aq_policy_set_params_fp32(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                    const float* const* h_d_gamma, const float* const* h_d_beta, void* stream);
+aq_status aq_policy_forward_fp32(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions, void* stream);
+aq_status aq_calibrate_fp32(aq_policy* p, const void* d_obs, int64_t batch, aq_range* h_ranges_out, void* stream);
+aq_status aq_policy_forward_fp32_params(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                        const float* const* h_d_gamma, const float* const* h_d_beta,
+                                        const void* d_obs, int64_t batch, void* d_actions, float* d_ranges_out,
+                                        void* stream);
 
 /* ---- Half-precision actor (Sec. 3.2: trained policies are also quantized "to fp16"; the run-time
  * breakdown of Sec. 5 runs actors at q = 16 next to q = 8 and q = 32).  Every tensor of this policy is an

@@ -43,6 +43,18 @@ int orc_num_threads(void) {
 #endif
 }
 
+/* Number of threads the batch-row loops may use from now on (a benchmark reports the oracle on one core
+ * next to the oracle on all of them); returns the count in effect. */
+int orc_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+    return omp_get_max_threads();
+#else
+    (void)n;
+    return 1;
+#endif
+}
+
 /* round-half-to-even of v (default FP environment), then clamp to [lo, hi] in
  * float before the conversion so that huge or NaN inputs are defined: values
  * not >= lo (NaN included) give lo. */

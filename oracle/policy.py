@@ -27,6 +27,8 @@ def lib():
         path = os.environ.get("ACTORQ_ORACLE_LIB") or _build.build(force=False)
         _LIB = C.CDLL(path)
         _LIB.orc_num_threads.restype = C.c_int
+        _LIB.orc_set_num_threads.restype = C.c_int
+        _LIB.orc_set_num_threads.argtypes = [C.c_int]
     return _LIB
 
 

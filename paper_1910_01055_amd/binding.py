@@ -27,7 +27,8 @@ EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_pol
            "aq_policy_blob_size", "aq_policy_export_blob", "aq_policy_import_blob", "aq_policy_explore", "aq_policy_step_int8",
            "aq_convert_params_fp16", "aq_policy_forward_fp16",
            "aq_policy_packed_blob_size", "aq_policy_export_packed_blob", "aq_policy_import_packed_blob",
-           "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers", "aq_policy_fused_plan", "aq_policy_forward_int8_static"]
+           "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers", "aq_policy_fused_plan", "aq_policy_forward_int8_static",
+           "aq_policy_set_params_fp32", "aq_calibrate_fp32", "aq_policy_forward_fp32_params"]
 
 
 class AqLayer(C.Structure):
@@ -91,7 +92,10 @@ def load():
     lib.aq_policy_export_act_qparams.argtypes = [vp, vp, vp, vp]
     lib.aq_policy_forward_int8.argtypes = [vp, vp, i64, vp, C.POINTER(AqTaps), vp]
     lib.aq_policy_forward_int8_static.argtypes = [vp, vp, i64, vp, vp]
-    lib.aq_policy_forward_fp32.argtypes = [vp, pp, pp, pp, pp, vp, i64, vp, vp, vp]
+    lib.aq_policy_forward_fp32_params.argtypes = [vp, pp, pp, pp, pp, vp, i64, vp, vp, vp]
+    lib.aq_policy_set_params_fp32.argtypes = [vp, pp, pp, pp, pp, vp]
+    lib.aq_policy_forward_fp32.argtypes = [vp, vp, i64, vp, vp]
+    lib.aq_calibrate_fp32.argtypes = [vp, vp, i64, C.POINTER(AqRange), vp]
     lib.aq_policy_blob_size.argtypes = [vp, C.POINTER(C.c_uint64)]
     lib.aq_policy_export_blob.argtypes = [vp, vp, C.c_uint64, vp]
     lib.aq_policy_import_blob.argtypes = [vp, vp, C.c_uint64, vp]
@@ -267,11 +271,34 @@ class Policy:
         _check(load().aq_policy_forward_int8_static(self._h, _ptr(obs), int(obs.shape[0]), _ptr(actions), _stream()),
                "aq_policy_forward_int8_static")
 
-    def policy_forward_fp32(self, w, b, gamma, beta, obs, actions, ranges_out=None):
+    def policy_forward_fp32_params(self, w, b, gamma, beta, obs, actions, ranges_out=None):
         n = self.n_layers
-        _check(load().aq_policy_forward_fp32(self._h, _ptr_array(w, n), _ptr_array(b, n), _ptr_array(gamma, n),
-                                             _ptr_array(beta, n), _ptr(obs), int(obs.shape[0]), _ptr(actions),
-                                             _ptr(ranges_out), _stream()), "aq_policy_forward_fp32")
+        _check(load().aq_policy_forward_fp32_params(self._h, _ptr_array(w, n), _ptr_array(b, n), _ptr_array(gamma, n),
+                                                    _ptr_array(beta, n), _ptr(obs), int(obs.shape[0]), _ptr(actions),
+                                                    _ptr(ranges_out), _stream()), "aq_policy_forward_fp32_params")
+
+    def policy_set_params_fp32(self, w, b, gamma, beta):
+        n = self.n_layers
+        _check(load().aq_policy_set_params_fp32(self._h, _ptr_array(w, n), _ptr_array(b, n), _ptr_array(gamma, n),
+                                                _ptr_array(beta, n), _stream()), "aq_policy_set_params_fp32")
+
+    def policy_forward_fp32(self, obs, actions):
+        _check(load().aq_policy_forward_fp32(self._h, _ptr(obs), int(obs.shape[0]), _ptr(actions), _stream()),
+               "aq_policy_forward_fp32")
+
+    def calibrate_fp32(self, obs):
+        """(min, max) per activation tensor over this batch, as a list of n_layers pairs (waits for the stream)."""
+        r = (AqRange * self.n_layers)()
+        _check(load().aq_calibrate_fp32(self._h, _ptr(obs), int(obs.shape[0]), r, _stream()), "aq_calibrate_fp32")
+        return [(float(x.lo), float(x.hi)) for x in r]
+
+    def quantize_kept_params(self, ranges):
+        """aq_quantize_params on the parameters kept by policy_set_params_fp32 (NULL parameter arrays)."""
+        n = self.n_layers
+        r = (AqRange * n)()
+        for i, (lo, hi) in enumerate(ranges):
+            r[i] = AqRange(float(lo), float(hi))
+        _check(load().aq_quantize_params(self._h, None, None, None, None, r, _stream()), "aq_quantize_params")
 
     def convert_params_fp16(self, w, b, gamma, beta):
         n = self.n_layers
@@ -282,6 +309,19 @@ class Policy:
         taps = _ptr_array(taps_out, self.n_layers) if taps_out is not None else None
         _check(load().aq_policy_forward_fp16(self._h, _ptr(obs), int(obs.shape[0]), _ptr(actions), taps, _stream()),
                "aq_policy_forward_fp16")
+
+
+def to_dev(a, device="cuda:0"):
+    """numpy array (or None) -> contiguous device tensor (or None): device memory plumbing only."""
+    import numpy as np
+    import torch
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+def upload_params(params, device="cuda:0"):
+    """Per-layer fp32 parameters (dicts with w, b, optional gamma, beta) -> four lists of device tensors."""
+    return ([to_dev(p["w"], device) for p in params], [to_dev(p["b"], device) for p in params],
+            [to_dev(p.get("gamma"), device) for p in params], [to_dev(p.get("beta"), device) for p in params])
 
 
 def quantize_tensor(w, rows, cols, wscheme, qdenom, codes, scale, zp, workspace):

@@ -95,6 +95,11 @@ struct aq_policy {
     bool h16_ready = false;
     int64_t cap_f16 = 0;
     void* act_f16[2] = {nullptr, nullptr};
+    // the learner's fp32 parameters, copied by aq_policy_set_params_fp32 (one allocation at its first call)
+    void* f32_slab = nullptr;
+    std::vector<float*> f32_w, f32_b, f32_gamma, f32_beta;
+    bool f32_ready = false;
+    float* calib = nullptr;        // 2 * AQ_MAX_LAYERS floats: (min, max) per activation tensor, for aq_calibrate_fp32
     int64_t max_hidden_elems = 0;  // per sample, over hidden layer outputs
     int64_t max_out_elems = 0;     // per sample, over all layer outputs
 };
@@ -242,6 +247,7 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     size_t off_keys = take(sizeof(uint32_t) * 2 * (AQ_MAX_LAYERS + 1));
     size_t off_net = take(sizeof(NetDev));
     size_t off_qtab = take(sizeof(QTab));
+    size_t off_calib = take(sizeof(float) * 2 * AQ_MAX_LAYERS);
     if (hipMalloc(&p->slab, bytes) != hipSuccess) {
         delete p;
         return AQ_ENOMEM;
@@ -276,6 +282,7 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
     p->keys = (uint32_t*)(base + off_keys);
     p->d_net = (NetDev*)(base + off_net);
     p->d_qtab = (QTab*)(base + off_qtab);
+    p->calib = (float*)(base + off_calib);
     p->actq = p->d_net->actq;  // device address arithmetic only
     for (int l = 0; l < net->n_layers; ++l) {
         fill_layer_dev(p, l, p->h_net.L[l]);
@@ -373,6 +380,7 @@ extern "C" aq_status aq_policy_destroy(aq_policy* p) {
     if (p->ln_x) (void)hipFree(p->ln_x);
     if (p->y_rows) (void)hipFree(p->y_rows);
     if (p->h16_slab) (void)hipFree(p->h16_slab);
+    if (p->f32_slab) (void)hipFree(p->f32_slab);
     delete p;
     return AQ_OK;
 }
@@ -693,8 +701,16 @@ extern "C" aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t 
 extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
                                         const float* const* h_d_gamma, const float* const* h_d_beta,
                                         const aq_range* h_ranges, void* stream) {
-    if (!p || !h_d_w || !h_ranges) return AQ_EINVAL;
+    if (!p || !h_ranges) return AQ_EINVAL;
     const int nl = p->net.n_layers;
+    if (!h_d_w) {  // the parameters kept by aq_policy_set_params_fp32
+        if (h_d_b || h_d_gamma || h_d_beta) return AQ_EINVAL;
+        if (!p->f32_ready) return AQ_ENOTQUANT;
+        h_d_w = p->f32_w.data();
+        h_d_b = p->f32_b.data();
+        h_d_gamma = p->f32_gamma.data();
+        h_d_beta = p->f32_beta.data();
+    }
     for (int l = 0; l < nl; ++l)
         if (!h_d_w[l]) return AQ_EINVAL;
     hipStream_t st = as_stream(stream);
@@ -905,17 +921,11 @@ extern "C" aq_status aq_policy_forward_int8_static(aq_policy* p, const void* d_o
     return forward_int8_impl(p, d_obs, batch, d_actions, nullptr, nullptr, stream, &sc);
 }
 
-extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
-                                            const float* const* h_d_gamma, const float* const* h_d_beta,
-                                            const void* d_obs, int64_t batch, void* d_actions, float* d_ranges_out,
-                                            void* stream) {
-    if (!p || !h_d_w || batch < 0) return AQ_EINVAL;
-    if (batch == 0) return AQ_OK;
-    if (!d_obs || !d_actions) return AQ_EINVAL;
+// The fp32 actor on explicit parameter arrays.  d_actions may be NULL (calibration only: the head is skipped).
+static aq_status forward_fp32_impl(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                   const float* const* h_d_gamma, const float* const* h_d_beta, const void* d_obs,
+                                   int64_t batch, void* d_actions, float* d_ranges_out, hipStream_t st) {
     const int nl = p->net.n_layers;
-    for (int l = 0; l < nl; ++l)
-        if (!h_d_w[l]) return AQ_EINVAL;
-    hipStream_t st = as_stream(stream);
     aq_status s = ensure_f32(p, batch, st);
     if (s != AQ_OK) return s;
     const int in_u8 = p->net.in_type == AQ_IN_U8;
@@ -928,6 +938,8 @@ extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_
     }
     for (int l = 0; l < nl; ++l) {
         const LayerBuf& b = p->L[l];
+        const bool last = l == nl - 1;
+        if (last && !d_actions) break;
         Fp32Layer L{};
         L.w = h_d_w[l];
         L.b = h_d_b ? h_d_b[l] : nullptr;
@@ -945,7 +957,6 @@ extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_
         L.oh = b.oh;
         L.ow = b.ow;
         const int64_t rows_l = batch * b.oh * b.ow;
-        const bool last = l == nl - 1;
         const void* in = l == 0 ? d_obs : (const void*)p->act_f32[(l - 1) & 1];
         float* out = p->act_f32[l & 1];
         s = launch_fp32_layer(L, in, l == 0 ? in_u8 : 0, out, rows_l, !last && b.d.act == AQ_ACT_RELU, st);
@@ -966,6 +977,96 @@ extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const float* const* h_
     if (d_ranges_out) {
         s = launch_keys_to_ranges(p->keys, 2 * nl, d_ranges_out, st);
         if (s != AQ_OK) return s;
+    }
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_forward_fp32_params(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                                   const float* const* h_d_gamma, const float* const* h_d_beta,
+                                                   const void* d_obs, int64_t batch, void* d_actions,
+                                                   float* d_ranges_out, void* stream) {
+    if (!p || !h_d_w || batch < 0) return AQ_EINVAL;
+    if (batch == 0) return AQ_OK;
+    if (!d_obs || !d_actions) return AQ_EINVAL;
+    for (int l = 0; l < p->net.n_layers; ++l)
+        if (!h_d_w[l]) return AQ_EINVAL;
+    return forward_fp32_impl(p, h_d_w, h_d_b, h_d_gamma, h_d_beta, d_obs, batch, d_actions, d_ranges_out,
+                             as_stream(stream));
+}
+
+extern "C" aq_status aq_policy_set_params_fp32(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
+                                               const float* const* h_d_gamma, const float* const* h_d_beta,
+                                               void* stream) {
+    if (!p || !h_d_w) return AQ_EINVAL;
+    const int nl = p->net.n_layers;
+    for (int l = 0; l < nl; ++l)
+        if (!h_d_w[l]) return AQ_EINVAL;
+    hipStream_t st = as_stream(stream);
+    if (!p->f32_slab) {
+        if (capturing(st)) return AQ_ETOOBIG;
+        size_t bytes = 0;
+        std::vector<size_t> offs;
+        auto take = [&](size_t n) {
+            size_t off = bytes;
+            bytes += (n + 255) / 256 * 256;
+            return off;
+        };
+        for (const LayerBuf& b : p->L) {
+            offs.push_back(take((size_t)b.N * b.K * 4));
+            for (int i = 0; i < 3; ++i) offs.push_back(take((size_t)b.N * 4));
+        }
+        if (hipMalloc(&p->f32_slab, bytes) != hipSuccess) return AQ_ENOMEM;
+        char* base = (char*)p->f32_slab;
+        size_t oi = 0;
+        for (int l = 0; l < nl; ++l) {
+            p->f32_w.push_back((float*)(base + offs[oi++]));
+            p->f32_b.push_back((float*)(base + offs[oi++]));
+            p->f32_gamma.push_back((float*)(base + offs[oi++]));
+            p->f32_beta.push_back((float*)(base + offs[oi++]));
+        }
+    }
+    for (int l = 0; l < nl; ++l) {
+        const LayerBuf& b = p->L[l];
+        const size_t nb = (size_t)b.N * 4;
+        AQ_HIP_CHECK(hipMemcpyAsync(p->f32_w[l], h_d_w[l], (size_t)b.N * b.K * 4, hipMemcpyDeviceToDevice, st));
+        // absent biases, gains and offsets take their defaults (0, 1, 0), written by a fill launch
+        if (h_d_b && h_d_b[l]) AQ_HIP_CHECK(hipMemcpyAsync(p->f32_b[l], h_d_b[l], nb, hipMemcpyDeviceToDevice, st));
+        else if (launch_fill_u32((uint32_t*)p->f32_b[l], b.N, 0u, st) != AQ_OK) return AQ_EHIP;
+        if (h_d_gamma && h_d_gamma[l]) AQ_HIP_CHECK(hipMemcpyAsync(p->f32_gamma[l], h_d_gamma[l], nb, hipMemcpyDeviceToDevice, st));
+        else if (launch_fill_u32((uint32_t*)p->f32_gamma[l], b.N, 0x3f800000u, st) != AQ_OK) return AQ_EHIP;
+        if (h_d_beta && h_d_beta[l]) AQ_HIP_CHECK(hipMemcpyAsync(p->f32_beta[l], h_d_beta[l], nb, hipMemcpyDeviceToDevice, st));
+        else if (launch_fill_u32((uint32_t*)p->f32_beta[l], b.N, 0u, st) != AQ_OK) return AQ_EHIP;
+    }
+    p->f32_ready = true;
+    return AQ_OK;
+}
+
+extern "C" aq_status aq_policy_forward_fp32(aq_policy* p, const void* d_obs, int64_t batch, void* d_actions,
+                                            void* stream) {
+    if (!p || batch < 0) return AQ_EINVAL;
+    if (!p->f32_ready) return AQ_ENOTQUANT;
+    if (batch == 0) return AQ_OK;
+    if (!d_obs || !d_actions) return AQ_EINVAL;
+    return forward_fp32_impl(p, p->f32_w.data(), p->f32_b.data(), p->f32_gamma.data(), p->f32_beta.data(), d_obs, batch,
+                             d_actions, nullptr, as_stream(stream));
+}
+
+extern "C" aq_status aq_calibrate_fp32(aq_policy* p, const void* d_obs, int64_t batch, aq_range* h_ranges_out,
+                                       void* stream) {
+    if (!p || !d_obs || !h_ranges_out || batch < 1) return AQ_EINVAL;
+    if (!p->f32_ready) return AQ_ENOTQUANT;
+    hipStream_t st = as_stream(stream);
+    if (capturing(st)) return AQ_EINVAL;  // the call has to wait for its result
+    const aq_status s = forward_fp32_impl(p, p->f32_w.data(), p->f32_b.data(), p->f32_gamma.data(), p->f32_beta.data(),
+                                          d_obs, batch, nullptr, p->calib, st);
+    if (s != AQ_OK) return s;
+    float h[2 * AQ_MAX_LAYERS];
+    const int nl = p->net.n_layers;
+    AQ_HIP_CHECK(hipMemcpyAsync(h, p->calib, sizeof(float) * 2 * nl, hipMemcpyDeviceToHost, st));
+    AQ_HIP_CHECK(hipStreamSynchronize(st));
+    for (int l = 0; l < nl; ++l) {
+        h_ranges_out[l].lo = h[2 * l];
+        h_ranges_out[l].hi = h[2 * l + 1];
     }
     return AQ_OK;
 }

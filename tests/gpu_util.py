@@ -25,15 +25,23 @@ def close(g, o):
 
 
 def to_dev(a):
-    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    from paper_1910_01055_amd import binding
+    return binding.to_dev(a, DEV)
 
 
 def upload_params(params):
-    w = [to_dev(p["w"]) for p in params]
-    b = [to_dev(p["b"]) for p in params]
-    g = [to_dev(p.get("gamma")) for p in params]
-    be = [to_dev(p.get("beta")) for p in params]
-    return w, b, g, be
+    from paper_1910_01055_amd import binding
+    return binding.upload_params(params, DEV)
+
+
+def action_error_figures(a_q, a_f):
+    """How far the 8-bit policy's actions are from the fp32 policy's on the same observations: largest and
+    mean absolute difference, and the signal-to-quantization-noise ratio in dB."""
+    a_q = np.asarray(a_q, np.float64)
+    a_f = np.asarray(a_f, np.float64)
+    d = a_q - a_f
+    return {"max_abs": float(np.abs(d).max()), "mean_abs": float(np.abs(d).mean()),
+            "sqnr_db": float(10.0 * np.log10((a_f ** 2).sum() / max((d ** 2).sum(), 1e-300)))}
 
 
 def layer_rows_feats(net, batch):

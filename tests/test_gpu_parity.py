@@ -481,9 +481,41 @@ def test_forward_fp32(aq, name, batch):
     else:
         actions = torch.zeros(batch, A, dtype=torch.float32, device=U.DEV)
     r = torch.zeros(2 * nl, dtype=torch.float32, device=U.DEV)
-    P.policy_forward_fp32(w, b, g, be, U.to_dev(obs), actions, r)
+    d_obs = U.to_dev(obs)
+    P.policy_forward_fp32_params(w, b, g, be, d_obs, actions, r)
     torch.cuda.synchronize()
     got = actions.cpu().numpy()
+    # the same actor on parameters kept in the handle, and the calibration call
+    a2 = torch.zeros_like(actions)
+    with pytest.raises(aq.AqError) as e:
+        P.policy_forward_fp32(d_obs, a2)
+    assert e.value.status == aq.ENOTQUANT
+    with pytest.raises(aq.AqError) as e:
+        P.calibrate_fp32(d_obs)
+    assert e.value.status == aq.ENOTQUANT
+    with pytest.raises(aq.AqError) as e:
+        P.quantize_kept_params(ranges)
+    assert e.value.status == aq.ENOTQUANT
+    P.policy_set_params_fp32(w, b, g, be)
+    P.policy_forward_fp32(d_obs, a2)
+    torch.cuda.synchronize()
+    assert torch.equal(a2, actions)
+    kept = P.calibrate_fp32(d_obs)
+    assert np.array_equal(np.array(kept, np.float32).reshape(-1), r.cpu().numpy())
+    # quantizing the kept copy gives the policy that quantizing the caller's arrays gives
+    P.quantize_kept_params(ranges)
+    assert P.policy_status() == aq.OK
+    pol.quantize_params(params, ranges)
+    U.check_quantized_params(aq, P, pol, net)
+    if name == "cfg2":  # absent biases, gains and offsets take their defaults in the kept copy as well
+        Q = aq.Policy(net)
+        Q.policy_set_params_fp32(w, None, None, None)
+        a3, a4 = torch.zeros_like(actions), torch.zeros_like(actions)
+        Q.policy_forward_fp32(d_obs, a3)
+        Q.policy_forward_fp32_params(w, None, None, None, d_obs, a4)
+        torch.cuda.synchronize()
+        assert torch.equal(a3, a4) and not torch.equal(a3, actions)
+        Q.close()
     if net["head"] == "argmax":
         # an fp32 sum may reorder two nearly equal logits; require agreement wherever the oracle's margin is clear
         assert (got == ref).mean() >= 0.99
@@ -492,6 +524,37 @@ def test_forward_fp32(aq, name, batch):
     rr = r.cpu().numpy().reshape(nl, 2)
     for i, (lo, hi) in enumerate(ranges):
         assert abs(rr[i, 0] - lo) <= 1e-4 * abs(lo) + 1e-6 and abs(rr[i, 1] - hi) <= 1e-4 * abs(hi) + 1e-6
+    P.close()
+
+
+def test_quantization_error_report_matches_oracle(aq):
+    """The wide MLP's report of how far the 8-bit actions are from the fp32 actions on the same observations
+    (largest and mean absolute difference, SQNR): the figures from the GPU's two forwards equal the figures
+    from the oracle's two forwards.  The value itself is not pinned by the paper (it only calls the change of
+    the action distribution very small, App. C), so it is held to a sanity bound only."""
+    net = synth.net_config("cfg5")
+    batch = 512
+    _say(f"quantization_error_report cfg5 batch={batch}")
+    params = synth.make_params(net)
+    obs = synth.make_obs(net, batch)
+    pol = O.OraclePolicy(net)
+    o32, ranges = pol.forward_fp32(params, obs)
+    pol.quantize_params(params, ranges)
+    o8 = pol.forward_int8(obs)["actions"]
+    P, d = U.gpu_quantize(aq, net, params, ranges)
+    d_obs = U.to_dev(obs)
+    g8 = torch.zeros(batch, synth.action_dim(net), dtype=torch.float32, device=U.DEV)
+    g32 = torch.zeros_like(g8)
+    P.policy_forward_int8(d_obs, g8)
+    P.policy_set_params_fp32(*d)
+    P.policy_forward_fp32(d_obs, g32)
+    torch.cuda.synchronize()
+    fg = U.action_error_figures(g8.cpu().numpy(), g32.cpu().numpy())
+    fo = U.action_error_figures(o8, o32)
+    _say(f"  GPU {fg}\n  oracle {fo}")
+    assert abs(fg["max_abs"] - fo["max_abs"]) <= 1e-4 and abs(fg["mean_abs"] - fo["mean_abs"]) <= 1e-4
+    assert abs(fg["sqnr_db"] - fo["sqnr_db"]) <= 0.05
+    assert 0.0 < fo["mean_abs"] <= 0.05 and fo["max_abs"] <= 0.5 and fo["sqnr_db"] >= 15.0
     P.close()
 
 
