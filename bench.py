@@ -147,14 +147,14 @@ def forward_workload(torch, aq, synth, name, batch, iters, warm=20, report_error
     # algorithmic HBM bytes: observations in, actions out, 8-bit weights once
     n_w = sum(int(p["w"].size) for p in params)
     hbm = float(obs.nbytes + act.numel() * act.element_size() + n_w)
-    rows, tiles = P.policy_fused_plan(batch)
+    rows, tiles, piped = P.policy_fused_plan(batch)
     out = {"workload": f"{name} batch {batch}", "us_per_launch": ms * 1e3, "inferences_per_s": batch / (ms * 1e-3),
            "tops": ops / (ms * 1e-3) / 1e12, "frac_int8_mfma_peak": ops / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
            "GBps_algorithmic": hbm / (ms * 1e-3) / 1e9, "frac_hbm_peak": hbm / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
            "us_per_launch_eager": ms_eager * 1e3, "fp32_actor_us_per_launch": ms32 * 1e3,
            "fp16_actor_us_per_launch": ms16 * 1e3, "fp16_actor_tflops": ops / (ms16 * 1e-3) / 1e12,
            "fp16_actor_frac_fp16_mfma_peak": ops / (ms16 * 1e-3) / 1e12 / FP16_PEAK_TFLOPS,
-           "launch_plan": f"fused kernel, {rows} rows per workgroup, {tiles} feature tile(s) per wavefront" if rows
+           "launch_plan": f"fused kernel{', pipelined' if piped else ''}, {rows} rows per workgroup, {tiles} feature tile(s) per wavefront" if rows
            else "one launch per layer"}
     if report_error:
         # quantization error of the actions: the 8-bit and the half-precision actor against the fp32 actor on

@@ -144,10 +144,13 @@ aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers
 /* Which compiled variant of the whole-network kernel a forward of `batch` >= 1 rows launches under the
  * current launch plan: *rows = batch rows per workgroup (16, 32, 64 or 128), *tiles = 32-feature tiles per
  * wavefront and pass (1 or 2); both 0 when the forward runs one launch per layer instead (a network the
- * kernel does not take, or launch plan 2 / 3).  With the weight scheme and whether intermediate outputs are
- * requested this names the variant, so that a test can show that every one it times is also checked.
- * No GPU work. */
-aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles);
+ * kernel does not take, or launch plan 2 / 3).  *pipelined = 1 when the 64-row, two-tile launch is the
+ * software-pipelined kernel for wide layers (per-channel weights, fp32 observations at a 16-byte aligned
+ * address, hidden widths multiples of 64 without LayerNorm, every K a multiple of 128, at most 64 outputs;
+ * an unaligned observation buffer takes the general kernel even then).  With the weight scheme and whether
+ * intermediate outputs are requested this names the variant, so that a test can show that every one it
+ * times is also checked.  No GPU work. */
+aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles, int32_t* pipelined);
 
 /* Synchronizes `stream` and returns the sticky device-side error of the last
  * aq_quantize_params or aq_policy_import_blob (AQ_OK, AQ_ENONFINITE, AQ_ERANGE, or AQ_EINVAL for a

@@ -85,7 +85,7 @@ def load():
     lib.aq_policy_status.argtypes = [vp, vp]
     lib.aq_policy_conv_stack_layers.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.aq_policy_fp16_conv_stack_layers.argtypes = [vp, C.POINTER(C.c_int32)]
-    lib.aq_policy_fused_plan.argtypes = [vp, i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.aq_policy_fused_plan.argtypes = [vp, i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.aq_quantize_tensor.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.aq_quantize_params.argtypes = [vp, pp, pp, pp, pp, C.POINTER(AqRange), vp]
     lib.aq_policy_export_layer.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -185,10 +185,11 @@ class Policy:
         return int(n.value)
 
     def policy_fused_plan(self, batch):
-        """(rows per workgroup, feature tiles per wavefront) of the fused kernel at this batch; (0, 0) = per layer."""
-        r, t = C.c_int32(0), C.c_int32(0)
-        _check(load().aq_policy_fused_plan(self._h, int(batch), C.byref(r), C.byref(t)), "aq_policy_fused_plan")
-        return int(r.value), int(t.value)
+        """(rows per workgroup, feature tiles per wavefront, pipelined kernel?) of the fused kernel at this batch;
+        (0, 0, False) = one launch per layer."""
+        r, t, w = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        _check(load().aq_policy_fused_plan(self._h, int(batch), C.byref(r), C.byref(t), C.byref(w)), "aq_policy_fused_plan")
+        return int(r.value), int(t.value), bool(w.value)
 
     def policy_status(self):
         return load().aq_policy_status(self._h, _stream())

@@ -113,9 +113,17 @@ bool fused_mlp_supported(const FwdArgs& a, int* rows_out, size_t* lds_out, int* 
     return true;
 }
 
+bool fused_mlp_is_pipelined(const FwdArgs& a) {
+    Plan p;
+    int ld;
+    return make_plan(a, &p) && p.nb == 2 && p.mt == 2 && !p.half && wide_mlp_supported(a, &ld);
+}
+
 aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     Plan p;
     if (!make_plan(a_in, &p)) return AQ_ESHAPE;
+    // 64-row workgroups on wide layers: the pipelined kernel where the shapes and the address allow it
+    if (fused_mlp_is_pipelined(a_in) && ((uintptr_t)a_in.c.obs & 15) == 0) return launch_wide_mlp(a_in, st);
     FwdArgs a = a_in;
     a.c.ld = p.ld;
     a.c.cst_n = p.cst_n;

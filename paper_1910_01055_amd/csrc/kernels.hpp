@@ -40,6 +40,11 @@ struct FwdArgs {
 bool any_taps(const FwdArgs& a);
 bool fused_mlp_supported(const FwdArgs& a, int* rows_per_wg_out, size_t* lds_bytes_out, int* tiles_per_wave_out = nullptr);
 aq_status launch_fused_mlp(const FwdArgs& a, hipStream_t st);
+// software-pipelined whole-network kernel for wide layers (wide_mlp.hip); launch_fused_mlp hands it the shapes it takes
+bool wide_mlp_supported(const FwdArgs& a, int* ld_out);
+aq_status launch_wide_mlp(const FwdArgs& a, hipStream_t st);
+// whether launch_fused_mlp runs the pipelined kernel for this network and batch (observations 16-byte aligned)
+bool fused_mlp_is_pipelined(const FwdArgs& a);
 
 // one launch per layer (FC and implicit-GEMM convolution), activations in global memory
 struct LayerIO {

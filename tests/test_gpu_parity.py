@@ -362,7 +362,8 @@ def test_every_fused_variant_against_the_oracle(aq, key):
         obs = synth.make_obs(net, batch)
         pol, ranges = U.make_oracle(net, params, obs[:256])
         P, _ = U.gpu_quantize(aq, net, params, ranges)
-        assert P.policy_fused_plan(batch) == key[:2]
+        assert P.policy_fused_plan(batch)[:2] == key[:2]
+        assert P.policy_fused_plan(batch)[2] == (name == "cfg5" and batch == 16384)
         rng = np.random.default_rng(21)
         rows = np.unique(np.concatenate([[0, 15, 16, 31, 32, 63, 64, batch - 65, batch - 33, batch - 1],
                                          rng.integers(0, batch, 250)]))
@@ -377,6 +378,91 @@ def test_every_fused_variant_against_the_oracle(aq, key):
             first = plain
         assert np.isfinite(plain).all() and np.abs(plain).max() <= 1.0
         P.close()
+
+
+# The software-pipelined kernel for wide layers (64 rows per workgroup): the benchmark's wide MLP, layers of
+# one and two passes mixed (a 512-wide layer's epilogue cannot hide under its own layer), a width that leaves
+# wavefronts idle in the last pass (640 = 10 groups of 64 features) with an argmax head, and a single wide layer.
+def _wide_nets():
+    fc = synth.fc
+    return {
+        "cfg5": synth.net_config("cfg5"),
+        "wide_mixed": synth.small_net([fc(128, 512, "relu"), fc(512, 1024, "none"), fc(1024, 512, "relu"),
+                                       fc(512, 30, "none")], head="linear"),
+        "wide_idle_waves": synth.small_net([fc(256, 640, "relu"), fc(640, 1024, "relu"), fc(1024, 64, "none")],
+                                           head="argmax"),
+        "wide_single": synth.small_net([fc(384, 1024, "relu"), fc(1024, 5, "none")], head="tanh"),
+    }
+
+
+@pytest.mark.parametrize("name,batch", [("cfg5", 16384), ("cfg5", 16321), ("wide_mixed", 16379), ("wide_idle_waves", 16000),
+                                        ("wide_single", 12345), ("cfg5", 70000)])
+def test_pipelined_wide_kernel_against_the_oracle(aq, name, batch):
+    _say(f"pipelined_wide_kernel {name} batch={batch}")
+    net = _wide_nets()[name]
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs[:256])
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    assert P.policy_fused_plan(batch) == (64, 2, True)
+    rng = np.random.default_rng(22)
+    rows = np.unique(np.concatenate([[0, 31, 32, 63, 64, batch - 65, batch - 64, batch - 33, batch - 1],
+                                     rng.integers(0, batch, 200)]))
+    first = None
+    for rep in range(3):
+        actions, t = U.gpu_forward(P, net, obs)
+        U.compare_forward(net, pol, obs, actions, t, rows)
+        del t
+        plain, _ = U.gpu_forward(P, net, obs, taps=False)
+        assert np.array_equal(plain, actions, equal_nan=True)
+        assert first is None or np.array_equal(first, plain, equal_nan=True)
+        first = plain
+    # an observation buffer that is not 16-byte aligned takes the general kernel: same bits
+    shifted, _ = U.gpu_forward(P, net, obs, taps=False, misalign=1)
+    assert np.array_equal(shifted, plain, equal_nan=True)
+    # so does the one-launch-per-layer plan
+    P.policy_set_path(2)
+    per_layer, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(per_layer, plain, equal_nan=True)
+    P.policy_set_path(0)
+    if net["head"] != "argmax":
+        # the actor step adds the exploration noise inside the kernel: same bits as forward, then explore
+        d_obs = U.to_dev(obs)
+        sg = U.to_dev(np.random.default_rng(23).uniform(0, 0.2, batch).astype(np.float32))
+        a1 = torch.zeros(batch, synth.action_dim(net), dtype=torch.float32, device=U.DEV)
+        a2 = torch.zeros_like(a1)
+        P.policy_step_int8(d_obs, a1, 99, 5, sigma=sg)
+        P.policy_forward_int8(d_obs, a2)
+        P.policy_explore(a2, 99, 5, sigma=sg)
+        torch.cuda.synchronize()
+        assert torch.equal(a1, a2) and not np.array_equal(a1.cpu().numpy(), plain)
+    P.close()
+
+
+@pytest.mark.parametrize("hi1,hi2", [(0.02, 3.0), (3.0, 3e5), (1e-3, 1e-3)])
+def test_pipelined_wide_kernel_general_requant_form(aq, hi1, hi2):
+    """Activation ranges that push a layer's requantization shifts out of the short form's window: the
+    pipelined kernel then runs that layer's epilogue in the general 64-bit form (not hidden under MFMAs)."""
+    _say(f"pipelined_wide_requant hi=({hi1},{hi2})")
+    net = synth.small_net([synth.fc(256, 1024, "relu"), synth.fc(1024, 1024, "none"), synth.fc(1024, 9, "none")],
+                          head="linear")
+    params = synth.make_params(net, nonzero_bias=True)
+    batch = 16200
+    obs = synth.make_obs(net, batch)
+    pol = O.OraclePolicy(net)
+    _, ranges = pol.forward_fp32(params, obs[:128])
+    ranges = [ranges[0], (np.float32(0.0), np.float32(hi1)), (np.float32(-hi2), np.float32(hi2))]
+    pol.quantize_params(params, ranges)
+    r = np.concatenate([pol.q[0]["rshift"], pol.q[1]["rshift"]])
+    _say(f"  shifts span {r.min()}..{r.max()}")
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    assert P.policy_fused_plan(batch) == (64, 2, True)
+    rows = np.unique(np.concatenate([[0, 63, 64, batch - 1], np.random.default_rng(24).integers(0, batch, 120)]))
+    actions, t = U.gpu_forward(P, net, obs)
+    U.compare_forward(net, pol, obs, actions, t, rows)
+    plain, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(plain, actions, equal_nan=True)
+    P.close()
 
 
 @pytest.mark.parametrize("name", ["odd_asym", "two_tile_last_asym", "wide_last", "single_narrow", "long_k_narrow",
