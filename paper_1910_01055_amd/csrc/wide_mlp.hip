@@ -224,106 +224,134 @@ __global__ __launch_bounds__(FT) void k_mlp_wide(const NetDev* __restrict__ netp
         xf[1][0] = *(const v4i*)(xrow + k1 * 32);
         xf[1][1] = *(const v4i*)(xrow + 32 * ld + k1 * 32);
     };
+    // Everything uniform a pass needs.  It is read from the network description one pass ahead of its use, so
+    // that the scalar loads' round trips run under the previous pass's k-steps.
+    struct Pass {
+        bool valid, active;
+        int l, p, grp, npass, N, Np, KS, act, z_out, fast;
+        gbytes b0, b1;
+        gv4i_ptr pack;
+        const int32_t* rshift;
+    };
+    auto pass_of = [&](int l, int p) {
+        Pass q{};
+        q.valid = l < nh;
+        q.l = l;
+        q.p = p;
+        if (q.valid) {
+            const LayerDev& L = a.L[l];
+            const int NT = uni(L.NT), ngroups = NT >> 1;
+            q.npass = (ngroups + FW - 1) / FW;
+            q.grp = p * FW + wave;
+            q.active = q.grp < ngroups;
+            q.N = uni(L.N);
+            q.Np = NT * 32;
+            q.KS = uni(L.KS);
+            q.act = uni(L.act);
+            q.z_out = uni(a.actq[l + 1].z);
+            q.fast = uni(a.fast[l]);
+            gbytes wp = (gbytes)uni_ptr(L.wp);
+            const int grp = q.active ? q.grp : 0;
+            q.b0 = wp + (int64_t)(2 * grp) * q.KS * 1024;
+            q.b1 = wp + (int64_t)(2 * grp + 1) * q.KS * 1024;
+            q.pack = (gv4i_ptr)uni_ptr(L.bias_fold);
+            q.rshift = uni_ptr(L.rshift);
+        }
+        return q;
+    };
     int npass_prev_layer = 0;
     int pass_no = 0;
     bool w_ready = 2 * wave < c.NT0;  // this wavefront's next pass finds its first weights requested already
-    for (int l = 0; l < nh; ++l) {
-        const int NT = uni(a.L[l].NT), N = uni(a.L[l].N), ngroups = NT >> 1, npass = (ngroups + FW - 1) / FW;
-        const int act = uni(a.L[l].act);
-        const int z_out = uni(a.actq[l + 1].z);
-        const int Np = NT * 32;
-        gv4i_ptr pack_l = (gv4i_ptr)uni_ptr(a.L[l].bias_fold);
-        for (int p = 0; p < npass; ++p, ++pass_no) {
-            const int grp = p * FW + wave;
-            const bool active = grp < ngroups;
-            sc = stream_of(l, active ? grp : 0);
-            // the pass after this one, for the weight stream (nothing to request: this pass's last tile again)
-            {
-                int ln = l, pn = p + 1;
-                if (pn == npass) {
-                    ln = l + 1;
-                    pn = 0;
-                }
-                bool next_ok = false;
-                if (ln < nh) {
-                    const int ngn = uni(a.L[ln].NT) >> 1;
-                    const int grpn = pn * FW + wave;
-                    if (grpn < ngn) {
-                        sn = stream_of(ln, grpn);
-                        next_ok = true;
-                    }
-                }
-                if (!next_ok) sn = Stream{sc.b0 + (int64_t)(sc.KS - 1) * 1024, sc.b1 + (int64_t)(sc.KS - 1) * 1024, 1};
-            }
-            // this pass's per-channel constants: one 16-byte piece per lane (four arrays x 64 features),
-            // parked in the wave's slot after the first k-steps
-            v4i cw = {0, 0, 0, 0};
-            const int cw_word = (lane >> 4) * Np + 64 * grp + 4 * (lane & 15);
-            if (active) cw = pack_l[cw_word >> 2];
-            xrow = buf(l) + mrow * ld + g * 16;
-            if (active && !w_ready) {  // (the pass before this one was not this wavefront's, or requested nothing)
+    Pass P = pass_of(0, 0);
+    while (P.valid) {
+        const bool more = P.p + 1 < P.npass;
+        const Pass Nx = pass_of(more ? P.l : P.l + 1, more ? P.p + 1 : 0);
+        const int l = P.l;
+        const bool active = P.active;
+        sc = Stream{P.b0, P.b1, P.KS};
+        // the pass after this one, for the weight stream (nothing to request: this pass's last tile again)
+        if (Nx.valid && Nx.active) sn = Stream{Nx.b0, Nx.b1, Nx.KS};
+        else sn = Stream{sc.b0 + (int64_t)(sc.KS - 1) * 1024, sc.b1 + (int64_t)(sc.KS - 1) * 1024, 1};
+        // this pass's per-channel constants: one 16-byte piece per lane (four arrays x 64 features), parked in
+        // the wave's slot at the end of the pass
+        v4i cw = {0, 0, 0, 0};
+        const int cw_word = (lane >> 4) * P.Np + 64 * P.grp + 4 * (lane & 15);
+        if (active) cw = P.pack[cw_word >> 2];
+        xrow = buf(l) + mrow * ld + g * 16;
+        if (active && !w_ready) {  // (the pass before this one was not this wavefront's, or requested nothing)
 #pragma unroll
-                for (int q = 0; q < WPF; ++q) {
-                    wreg[q][0] = wload(sc.b0, q);
-                    wreg[q][1] = wload(sc.b1, q);
-                }
+            for (int q = 0; q < WPF; ++q) {
+                wreg[q][0] = wload(sc.b0, q);
+                wreg[q][1] = wload(sc.b1, q);
             }
-            // k-steps that may run before the previous pass's outputs are visible to every wavefront: all of them
-            // within a layer; in a layer's first pass those that read what the previous layer's earlier passes wrote
-            const int n_over = p > 0 ? sc.KS : WGROUP * (npass_prev_layer - 1);
-            int k0 = 0;
-            if (have_prev) {
-                if (prev_active) {
-                    if (active && prev_fast && n_over >= WGROUP && sc.KS >= WGROUP) {
-                        start_ring(0);
-                        epi_begin();
-                        static_for<0, WGROUP>([&](auto q_c) __attribute__((always_inline)) {
-                            constexpr int q = decltype(q_c)::value;
-                            kstep(q, std::integral_constant<int, q % WPF>{}, q_c);
-                        });
-                        k0 = WGROUP;
-                    } else if (prev_fast) {
-                        epi_standalone(std::true_type{});
-                    } else {
-                        epi_standalone(std::false_type{});
-                    }
-                }
-                // the previous pass's features are in LDS for every wavefront (the k-steps below, or a later
-                // pass of any wavefront, read them)
-                lds_barrier();
-            }
-            if (active) {
-                if (k0 < sc.KS) start_ring(k0);  // (after the barrier: the ring reads two k-steps ahead)
-                for (int k = k0; k < sc.KS; k += WPF) group(k);
-                // park the constants: [bias_fold | M0 | rz | sh] x 64 features
-                *(v4i*)(my_cst + (pass_no & 1) * WSLOT + (lane >> 4) * 64 + 4 * (lane & 15)) = cw;
-            }
-            w_ready = active && sn.KS > 1;  // (KS is at least 4: a one-step stream is the placeholder)
-            // hand the accumulators to the next pass's epilogue
-            have_prev = true;
-            prev_active = active;
-            prev_grp = grp;
-            prev_N = N;
-            prev_zout = z_out;
-            prev_lo = act == AQ_ACT_RELU ? z_out : 0;
-            prev_fast = uni(a.fast[l]);
-            prev_slot = pass_no & 1;
-            prev_rshift = uni_ptr(a.L[l].rshift);
-            prev_out = buf(l + 1);
-            if (TAPS) {
-                prev_tacc = t.acc[l];
-                prev_tact = t.act[l];
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    prev[i][j] = cur[i][j];
-                    cur[i][j] = zero16();
-                }
         }
-        npass_prev_layer = npass;
+        // k-steps that may run before the previous pass's outputs are visible to every wavefront: all of them
+        // within a layer; in a layer's first pass those that read what the previous layer's earlier passes wrote
+        const int n_over = P.p > 0 ? sc.KS : WGROUP * (npass_prev_layer - 1);
+        int k0 = 0;
+        if (have_prev) {
+            if (prev_active) {
+                if (active && prev_fast && n_over >= WGROUP && sc.KS >= WGROUP) {
+                    start_ring(0);
+                    epi_begin();
+                    static_for<0, WGROUP>([&](auto q_c) __attribute__((always_inline)) {
+                        constexpr int q = decltype(q_c)::value;
+                        kstep(q, std::integral_constant<int, q % WPF>{}, q_c);
+                    });
+                    k0 = WGROUP;
+                } else if (prev_fast) {
+                    epi_standalone(std::true_type{});
+                } else {
+                    epi_standalone(std::false_type{});
+                }
+            }
+            // the previous pass's features are in LDS for every wavefront (the k-steps below, or a later pass of
+            // any wavefront, read them)
+            lds_barrier();
+        }
+        if (active) {
+            if (k0 < sc.KS) start_ring(k0);  // (after the barrier: the ring reads two k-steps ahead)
+            for (int k = k0; k < sc.KS; k += WPF) group(k);
+            // park the constants: [bias_fold | M0 | rz | sh] x 64 features
+            *(v4i*)(my_cst + (pass_no & 1) * WSLOT + (lane >> 4) * 64 + 4 * (lane & 15)) = cw;
+        }
+        w_ready = active && sn.KS > 1;  // (KS is at least 4: a one-step stream is the placeholder)
+        // hand the accumulators to the next pass's epilogue
+        have_prev = true;
+        prev_active = active;
+        prev_grp = P.grp;
+        prev_N = P.N;
+        prev_zout = P.z_out;
+        prev_lo = P.act == AQ_ACT_RELU ? P.z_out : 0;
+        prev_fast = P.fast;
+        prev_slot = pass_no & 1;
+        prev_rshift = P.rshift;
+        prev_out = buf(l + 1);
+        if (TAPS) {
+            prev_tacc = t.acc[l];
+            prev_tact = t.act[l];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                prev[i][j] = cur[i][j];
+                cur[i][j] = zero16();
+            }
+        if (!more) npass_prev_layer = P.npass;
+        P = Nx;
+        ++pass_no;
     }
+    // The narrow last layer's constants and this wavefront's first weights of it do not depend on the hidden
+    // layers: requested before the last epilogue.
+    const LayerView LL = layer_view(a, nh, n_layers);
+    const NarrowMap nm = narrow_map<2>(LL.NT, LL.KS, wave);
+    v4i cv0 = {0, 0, 0, 0}, cv1 = cv0;
+    load_consts(LL, tid, cv0, cv1);
+    gv4i_ptr nwptr[1];
+    nwptr[0] = (gv4i_ptr)LL.wp + (int64_t)nm.nt * LL.KS * 64 + lane;
+    v4i nw[4][1];
+    if (nm.k0 < nm.k1) mma_prefetch<1, 4>(nwptr, nm.k0, nm.k1, nw);
     // the last hidden pass has nothing to hide under
     if (have_prev && prev_active) {
         if (prev_fast) epi_standalone(std::true_type{});
@@ -333,26 +361,18 @@ __global__ __launch_bounds__(FT) void k_mlp_wide(const NetDev* __restrict__ netp
     // ---- narrow last layer (at most two feature tiles): spread over all eight wavefronts by splitting K
     {
         const int l = nh;
-        const LayerView L = layer_view(a, l, n_layers);
+        const LayerView& L = LL;
         LayerTaps T{nullptr, nullptr, nullptr};
         if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
         const int Np = L.NT * 32;
-        v4i cv0 = {0, 0, 0, 0}, cv1 = cv0;
-        load_consts(L, tid, cv0, cv1);
         lds_barrier();  // every hidden feature is in LDS
         const int8_t* in = buf(l);
         const CPtrs C{cst_last, cst_last + Np, L.rshift, cst_last + 2 * Np, cst_last + 3 * Np, (const float*)(cst_last + Np)};
-        const NarrowMap nm = narrow_map<2>(L.NT, L.KS, wave);
         v16i pacc[1][1], prs[1];
         pacc[0][0] = zero16();
         prs[0] = zero16();
-        if (nm.k0 < nm.k1) {
-            gv4i_ptr wptr[1];
-            wptr[0] = (gv4i_ptr)L.wp + (int64_t)nm.nt * L.KS * 64 + lane;
-            v4i w1[4][1];
-            mma_prefetch<1, 4>(wptr, nm.k0, nm.k1, w1);
-            mma_run<1, 1, false, 4>(wptr, w1, in + nm.mt * 32 * ld, ld, nm.k0, nm.k1, 0, pacc, prs, lane);
-        }
+        if (nm.k0 < nm.k1)
+            mma_run<1, 1, false, 4>(nwptr, nw, in + nm.mt * 32 * ld, ld, nm.k0, nm.k1, 0, pacc, prs, lane);
         int32_t* part = (int32_t*)buf(l + 1);  // the idle activation buffer (64 * ld >= PART_BYTES, checked by the launcher)
         {
             int32_t* mine = part + wave * PART_WORDS + lane;
