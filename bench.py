@@ -173,7 +173,7 @@ def forward_workload(torch, aq, synth, name, batch, iters, warm=20, report_error
     return out, (P, w, b, g, be, ranges, d_obs, act, net, params, obs)
 
 
-def quantize_workload(torch, aq, synth, scheme, iters=30, n_buf=40, repeat=1):
+def quantize_workload(torch, aq, synth, scheme, iters=30, n_buf=40, repeat=1, reference=False):
     """Learner->actor weight quantize pass over 4M fp32 params (times `repeat`: the same values tiled
     into a larger tensor, for the asymptotic rate), rotating over distinct buffers so that the
     source comes from HBM, not from the 256 MB last-level cache."""
@@ -192,7 +192,10 @@ def quantize_workload(torch, aq, synth, scheme, iters=30, n_buf=40, repeat=1):
     def one():
         k = i[0] % n_buf
         i[0] += 1
-        aq.quantize_tensor(srcs[k], rows, cols, scheme, 255, dsts[k], scale, zp, ws)
+        if reference:  # the same bytes moved with no arithmetic: the ceiling at this size
+            aq.stream_reference(srcs[k], n, dsts[k])
+        else:
+            aq.quantize_tensor(srcs[k], rows, cols, scheme, 255, dsts[k], scale, zp, ws)
     for _ in range(n_buf):
         one()
     torch.cuda.synchronize()
@@ -200,7 +203,8 @@ def quantize_workload(torch, aq, synth, scheme, iters=30, n_buf=40, repeat=1):
     i[0] = 0
     ms = _graph_ms(torch, one, n_buf)   # one pass over all the distinct buffers per replay
     gbs = 5.0 * n / (ms * 1e-3) / 1e9
-    return {"workload": f"quantize {4 * repeat}M fp32 params, {scheme}, {n_buf} rotating buffers (HBM-resident source)",
+    what = "plain streaming of the same bytes (no arithmetic)" if reference else scheme
+    return {"workload": f"quantize {4 * repeat}M fp32 params, {what}, {n_buf} rotating buffers (HBM-resident source)",
             "us_per_call": ms * 1e3, "us_per_call_eager": ms_eager * 1e3, "GBps_algorithmic": gbs,
             "frac_hbm_peak": gbs / HBM_PEAK_GBS}
 
@@ -317,7 +321,8 @@ def main():
     _USE_GRAPHS = not args.eager
 
     if args.only == "quantize4m":
-        print(json.dumps([quantize_workload(torch, aq, synth, sch) for sch in ("channel_sym_s8", "tensor_asym_u8")]))
+        print(json.dumps([quantize_workload(torch, aq, synth, sch) for sch in ("channel_sym_s8", "tensor_asym_u8")] +
+                         [quantize_workload(torch, aq, synth, "channel_sym_s8", reference=True)]))
         return
     if args.only:
         name, bsz = args.only.split(":")
@@ -423,8 +428,13 @@ def main():
             extra.append(o)
         for scheme in ("channel_sym_s8", "tensor_asym_u8"):
             extra.append(quantize_workload(torch, aq, synth, scheme))
-        # informational: a 64 M-parameter tensor (256 MB in, 64 MB out per call) shows the asymptotic rate
-        extra.append(quantize_workload(torch, aq, synth, "channel_sym_s8", iters=6, n_buf=4, repeat=16))
+        # the ceiling at that size: the same 16 MiB in / 4 MiB out per launch with no arithmetic at all
+        extra.append(quantize_workload(torch, aq, synth, "channel_sym_s8", reference=True))
+        # larger tensors: where the per-channel pass crosses 60 % of the HBM peak (launch and ramp amortised),
+        # up to 64 M parameters (256 MB in, 64 MB out per call); the rotation always covers > 512 MB
+        for rep_, nb_ in ((2, 20), (4, 10), (8, 6), (16, 4)):
+            extra.append(quantize_workload(torch, aq, synth, "channel_sym_s8", iters=6, n_buf=nb_, repeat=rep_))
+        extra.append(quantize_workload(torch, aq, synth, "channel_sym_s8", iters=6, n_buf=4, repeat=16, reference=True))
         for name in ("cfg2", "cfg5"):
             extra.append(blob_workload(torch, aq, synth, name))
         extra.append(blob_workload(torch, aq, synth, "cfg5", wbits=4))

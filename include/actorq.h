@@ -228,6 +228,12 @@ aq_status aq_policy_step_int8(aq_policy* p, const void* d_obs, int64_t batch, vo
 aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int32_t wscheme, int32_t qdenom,
                              void* d_codes, float* d_scale, int32_t* d_zp, void* d_workspace, void* stream);
 
+/* Measurement aid for aq_quantize_tensor: moves the same bytes (n fp32 values read, n bytes written: the
+ * top byte of each value) with no arithmetic and no reduction, so that a benchmark can report what plain
+ * streaming reaches at the size it quantizes -- the ceiling of the quantize pass at that size.  n a multiple
+ * of 4, d_in 16-byte aligned (AQ_ESHAPE otherwise).  Enqueues on `stream`. */
+aq_status aq_stream_reference(const float* d_in, int64_t n, void* d_out, void* stream);
+
 /* The quantizer block (Sec. 3.1 / 3.2): turns the learner's fp32 parameters into the 8-bit
  * policy held by `p`: weight codes in the kernels' packed layout, per-channel scales, the
  * activation (scale, zero-point) of every range, integer biases, requantization multipliers

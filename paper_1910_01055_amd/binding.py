@@ -28,7 +28,7 @@ EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_pol
            "aq_convert_params_fp16", "aq_policy_forward_fp16",
            "aq_policy_packed_blob_size", "aq_policy_export_packed_blob", "aq_policy_import_packed_blob",
            "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers", "aq_policy_fused_plan", "aq_policy_forward_int8_static",
-           "aq_policy_set_params_fp32", "aq_calibrate_fp32", "aq_policy_forward_fp32_params"]
+           "aq_policy_set_params_fp32", "aq_calibrate_fp32", "aq_policy_forward_fp32_params", "aq_stream_reference"]
 
 
 class AqLayer(C.Structure):
@@ -87,6 +87,7 @@ def load():
     lib.aq_policy_fp16_conv_stack_layers.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.aq_policy_fused_plan.argtypes = [vp, i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.aq_quantize_tensor.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+    lib.aq_stream_reference.argtypes = [vp, i64, vp, vp]
     lib.aq_quantize_params.argtypes = [vp, pp, pp, pp, pp, C.POINTER(AqRange), vp]
     lib.aq_policy_export_layer.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.aq_policy_export_act_qparams.argtypes = [vp, vp, vp, vp]
@@ -323,6 +324,10 @@ def upload_params(params, device="cuda:0"):
     """Per-layer fp32 parameters (dicts with w, b, optional gamma, beta) -> four lists of device tensors."""
     return ([to_dev(p["w"], device) for p in params], [to_dev(p["b"], device) for p in params],
             [to_dev(p.get("gamma"), device) for p in params], [to_dev(p.get("beta"), device) for p in params])
+
+
+def stream_reference(src, n, dst):
+    _check(load().aq_stream_reference(_ptr(src), int(n), _ptr(dst), _stream()), "aq_stream_reference")
 
 
 def quantize_tensor(w, rows, cols, wscheme, qdenom, codes, scale, zp, workspace):

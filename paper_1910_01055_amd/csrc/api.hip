@@ -700,6 +700,13 @@ extern "C" aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t 
                                   d_codes, d_scale, d_zp, (uint32_t*)d_workspace, as_stream(stream));
 }
 
+extern "C" aq_status aq_stream_reference(const float* d_in, int64_t n, void* d_out, void* stream) {
+    if (!d_in || !d_out || n < 0) return AQ_EINVAL;
+    if (n % 4 != 0 || ((uintptr_t)d_in & 15) || ((uintptr_t)d_out & 3)) return AQ_ESHAPE;
+    if (n == 0) return AQ_OK;
+    return launch_stream_reference(d_in, n, d_out, as_stream(stream));
+}
+
 extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
                                         const float* const* h_d_gamma, const float* const* h_d_beta,
                                         const aq_range* h_ranges, void* stream) {

@@ -224,7 +224,7 @@ aq_status launch_conv_stack(const FwdArgs& a, int8_t* out, hipStream_t st) {
     dim3 grid((unsigned)a.c.batch);
 #define AQ_STACK(TP, WV)                                                                                             \
     do {                                                                                                             \
-        static bool attr_set = false;                                                                                \
+        static std::atomic<bool> attr_set{false};                                                                           \
         if (!attr_set) {                                                                                             \
             if (hipFuncSetAttribute((const void*)k_conv_stack<TP, WV>, hipFuncAttributeMaxDynamicSharedMemorySize,   \
                                     (int)CS_MAX_LDS) != hipSuccess)                                                  \

@@ -200,7 +200,7 @@ aq_status launch_fp16_conv_stack(const Fp16Layer* L, int n_layers, const void* o
     S.nc = p.nc;
     S.off_b = p.off_b;
     S.off_bias = p.off_bias;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)k_fp16_conv_stack, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)FS_MAX_LDS) != hipSuccess)

@@ -715,7 +715,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
 
 template <int MT, int NB, bool ASYM, bool TAPS, bool HALF>
 aq_status launch_fused_t(const FwdArgs& a, size_t lds, hipStream_t st) {
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};
     if (!attr_set) {
         if (hipFuncSetAttribute((const void*)k_mlp_fused<MT, NB, ASYM, TAPS, HALF>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)

@@ -13,6 +13,8 @@ aq_status launch_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, i
 // per-channel constants of every layer, in three or four launches.
 aq_status launch_quantize_policy(const QTab* d_tab, const QTab& h_tab, const QPtrs& ptrs, const RangesArg& r,
                                  ActQ* actq, int* fast, int* status, uint32_t* mm, hipStream_t st);
+// the quantize pass's traffic without its arithmetic (n a multiple of 4)
+aq_status launch_stream_reference(const float* d_in, int64_t n, void* d_out, hipStream_t st);
 aq_status launch_unpack_weights(const int8_t* wp, int N, int K, int KS, int asym, uint8_t* codes, hipStream_t st);
 
 // ---- policy blob (quantize.hip): header words [0..15] = magic, version, hash lo/hi, payload bytes lo/hi, 0...

@@ -392,7 +392,7 @@ static aq_status launch_layer_t(const FwdArgs& a, int l, const LayerIO& io, int6
     const bool asym = a.net.asym != 0;
 #define AQ_LAYER(AS, TP)                                                                                            \
     do {                                                                                                            \
-        static bool attr_set = false;                                                                               \
+        static std::atomic<bool> attr_set{false};                                                                          \
         if (!attr_set) {                                                                                            \
             if (hipFuncSetAttribute((const void*)k_layer_int8<W, MT, NB, AS, TP, DEEP>,                                   \
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)          \

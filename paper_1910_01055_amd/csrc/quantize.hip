@@ -19,6 +19,7 @@ __global__ void k_fill_u32(uint32_t* p, int n, uint32_t v) {
 }
 
 __device__ __forceinline__ bool finite_f(float v) { return fabsf(v) <= FLT_MAX; }
+typedef float f4v __attribute__((ext_vector_type(4)));
 
 // Sec. 3.2: delta = (|min(W,0)| + |max(W,0)|) / D ; zero-point z = round(-lo / delta).
 // (n bits: D = 2^n - 1 or 2^n, codes and zero-point in [0, qmax = 2^n - 1])
@@ -157,8 +158,10 @@ __global__ __launch_bounds__(256) void k_quant_asym_flat(const float4* __restric
     }
     const QuantScale qs = make_quant_scale(s);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
-        codes[i] = quant_code4(w4[i], qs, -z, qmax - z, z);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        const f4v q = __builtin_nontemporal_load((const f4v*)w4 + i);  // (last use of the tensor)
+        __builtin_nontemporal_store(quant_code4(make_float4(q[0], q[1], q[2], q[3]), qs, -z, qmax - z, z), codes + i);
+    }
 }
 
 // per-channel symmetric codes, canonical order: one wavefront per row, the row lives in
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(256) void k_quant_sym_rows_flat(const float4* __res
     for (int r = 0; r < R; ++r) {
         int c = lane + 64 * r;
         if (c < cols4) {
-            dst[c] = quant_code4(v[r], qs, -qw, qw, 0);
+            __builtin_nontemporal_store(quant_code4(v[r], qs, -qw, qw, 0), dst + c);
         }
     }
 }
@@ -214,10 +217,16 @@ __global__ __launch_bounds__(256) void k_quant_sym_row_wg(const float4* __restri
     float4 v[R];
     float amax = 0.0f;
     int bad = 0;
+    // (the tensor is read once and the codes are written once: both bypass the cache hierarchy's retention)
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int c = threadIdx.x + 256 * r;
-        v[r] = c < cols4 ? src[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c < cols4) {
+            const f4v q = __builtin_nontemporal_load((const f4v*)src + c);
+            v[r] = make_float4(q[0], q[1], q[2], q[3]);
+        } else {
+            v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -242,7 +251,7 @@ __global__ __launch_bounds__(256) void k_quant_sym_row_wg(const float4* __restri
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int c = threadIdx.x + 256 * r;
-        if (c < cols4) dst[c] = quant_code4(v[r], qs, -qw, qw, 0);
+        if (c < cols4) __builtin_nontemporal_store(quant_code4(v[r], qs, -qw, qw, 0), dst + c);
     }
 }
 
@@ -442,7 +451,11 @@ __device__ __forceinline__ void layer_consts_channel(const ActQ* __restrict__ ac
     }
     const int za_s = z_a - 128;
     const int zw_s = asym ? z_w[n] - 128 : 0;
-    bias_fold[n] = bqi - za_s * rowsum[n] + K * za_s * zw_s;
+    // (a saturated integer bias can push the folded value out of the accumulator's range: reported, like a
+    // multiplier outside the shift range, instead of wrapping silently)
+    const long long bf = (long long)bqi - (long long)za_s * rowsum[n] + (long long)K * za_s * zw_s;
+    if (bf > 2147483647LL || bf < -2147483648LL) atomicOr(status, kStatRange);
+    bias_fold[n] = (int32_t)bf;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -555,6 +568,38 @@ __global__ __launch_bounds__(256) void k_unpack_bits(const uint8_t* __restrict__
         v |= (uint64_t)(uint8_t)(int8_t)sgn << (8 * j);
     }
     *(uint64_t*)(wp + 8 * g) = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Measurement aid: the memory traffic of the flat quantize pass without its arithmetic (4 bytes read and
+// 1 byte written per element, no reduction, no dependence between the loads and the stores of a thread
+// other than the data itself).  What this kernel reaches at a given size is the ceiling for the quantizer
+// at that size.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_stream_reference(const float4* __restrict__ in4, int64_t n4,
+                                                          uint32_t* __restrict__ out) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += 2 * stride) {
+        const f4v a = __builtin_nontemporal_load((const f4v*)in4 + i);
+        const bool two = i + stride < n4;
+        f4v b = a;
+        if (two) b = __builtin_nontemporal_load((const f4v*)in4 + i + stride);
+        __builtin_nontemporal_store((__float_as_uint(a[0]) >> 24) | ((__float_as_uint(a[1]) >> 24) << 8) |
+                                        ((__float_as_uint(a[2]) >> 24) << 16) | ((__float_as_uint(a[3]) >> 24) << 24),
+                                    out + i);
+        if (two)
+            __builtin_nontemporal_store((__float_as_uint(b[0]) >> 24) | ((__float_as_uint(b[1]) >> 24) << 8) |
+                                            ((__float_as_uint(b[2]) >> 24) << 16) | ((__float_as_uint(b[3]) >> 24) << 24),
+                                        out + i + stride);
+    }
+}
+
+aq_status launch_stream_reference(const float* d_in, int64_t n, void* d_out, hipStream_t st) {
+    const int64_t n4 = n / 4;
+    int64_t g = (n4 + 511) / 512;  // two 16-byte pieces per thread, like the per-channel kernel on 2048-wide rows
+    if (g > 65536) g = 65536;
+    hipLaunchKernelGGL(k_stream_reference, dim3((unsigned)g), dim3(256), 0, st, (const float4*)d_in, n4, (uint32_t*)d_out);
+    return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
 
 // ---------------------------------------------------------------------------------------------

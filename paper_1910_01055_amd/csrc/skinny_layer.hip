@@ -232,7 +232,7 @@ aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStr
     const bool asym = a.net.asym != 0;
 #define AQ_SKINNY(AS, TP)                                                                                           \
     do {                                                                                                            \
-        static bool attr_set = false;                                                                               \
+        static std::atomic<bool> attr_set{false};                                                                          \
         if (!attr_set) {                                                                                            \
             if (hipFuncSetAttribute((const void*)k_layer_skinny<AS, TP>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                     160 * 1024) != hipSuccess)                                                      \

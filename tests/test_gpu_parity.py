@@ -998,6 +998,16 @@ def test_edges(aq):
     P.quantize_params(d[0], d[1], d[2], d[3], huge)
     assert P.policy_status() == aq.ERANGE
     P.close()
+    # a bias so large that its integer form saturates: folding the zero-point terms into it would leave the
+    # int32 range for the channels whose weight codes sum to a positive number; reported, not wrapped
+    small = synth.small_net([synth.fc(16, 64, "relu"), synth.fc(64, 4, "none")])
+    sp = synth.make_params(small)
+    sp[0]["b"][:] = 1e30
+    S = aq.Policy(small)
+    ds = U.upload_params(sp)
+    S.quantize_params(ds[0], ds[1], ds[2], ds[3], [(np.float32(0.0), np.float32(4.0)), (np.float32(0.0), np.float32(1.0))])
+    assert S.policy_status() == aq.ERANGE
+    S.close()
     # all-zero weights: scale 1, codes 0, actions tanh(0) = 0
     zero = [{"w": np.zeros_like(p["w"]), "b": np.zeros_like(p["b"])} for p in params]
     pol0, r0 = U.make_oracle(net, zero, obs)
