@@ -147,7 +147,7 @@ aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers
  * kernel does not take, or launch plan 2 / 3).  *pipelined = 1 when the 64-row, two-tile launch is the
  * software-pipelined kernel for wide layers (per-channel weights, fp32 observations at a 16-byte aligned
  * address, hidden widths multiples of 64 without LayerNorm, every K a multiple of 128, at most 64 outputs;
- * an unaligned observation buffer takes the general kernel even then).  With the weight scheme and whether
+ * an unaligned observation buffer takes the general kernel even then), 0 otherwise.  With the weight scheme and whether
  * intermediate outputs are requested this names the variant, so that a test can show that every one it
  * times is also checked.  No GPU work. */
 aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles, int32_t* pipelined);

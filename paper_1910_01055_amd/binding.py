@@ -186,11 +186,11 @@ class Policy:
         return int(n.value)
 
     def policy_fused_plan(self, batch):
-        """(rows per workgroup, feature tiles per wavefront, pipelined kernel?) of the fused kernel at this batch;
-        (0, 0, False) = one launch per layer."""
+        """(rows per workgroup, feature tiles per wavefront, kernel: 0 general / 1 pipelined for wide layers) of
+        the fused launch at this batch; (0, 0, 0) = one launch per layer."""
         r, t, w = C.c_int32(0), C.c_int32(0), C.c_int32(0)
         _check(load().aq_policy_fused_plan(self._h, int(batch), C.byref(r), C.byref(t), C.byref(w)), "aq_policy_fused_plan")
-        return int(r.value), int(t.value), bool(w.value)
+        return int(r.value), int(t.value), int(w.value)
 
     def policy_status(self):
         return load().aq_policy_status(self._h, _stream())

@@ -488,7 +488,7 @@ extern "C" aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int
     if (p->path == 2 || !fused_mlp_supported(a, &r, &lds, &t)) r = t = 0;
     *rows = r;
     *tiles = t;
-    *pipelined = r != 0 && fused_mlp_is_pipelined(a);
+    *pipelined = r != 0 ? fused_mlp_kernel_kind(a) : 0;
     return AQ_OK;
 }
 

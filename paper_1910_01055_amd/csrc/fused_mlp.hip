@@ -113,17 +113,19 @@ bool fused_mlp_supported(const FwdArgs& a, int* rows_out, size_t* lds_out, int* 
     return true;
 }
 
-bool fused_mlp_is_pipelined(const FwdArgs& a) {
+int fused_mlp_kernel_kind(const FwdArgs& a) {
     Plan p;
     int ld;
-    return make_plan(a, &p) && p.nb == 2 && p.mt == 2 && !p.half && wide_mlp_supported(a, &ld);
+    if (!make_plan(a, &p) || p.half) return 0;
+    if (p.nb == 2 && p.mt == 2 && wide_mlp_supported(a, &ld)) return 1;
+    return 0;
 }
 
 aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     Plan p;
     if (!make_plan(a_in, &p)) return AQ_ESHAPE;
     // 64-row workgroups on wide layers: the pipelined kernel where the shapes and the address allow it
-    if (fused_mlp_is_pipelined(a_in) && ((uintptr_t)a_in.c.obs & 15) == 0) return launch_wide_mlp(a_in, st);
+    if (fused_mlp_kernel_kind(a_in) == 1 && ((uintptr_t)a_in.c.obs & 15) == 0) return launch_wide_mlp(a_in, st);
     FwdArgs a = a_in;
     a.c.ld = p.ld;
     a.c.cst_n = p.cst_n;

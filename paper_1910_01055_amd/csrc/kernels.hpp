@@ -45,8 +45,9 @@ aq_status launch_fused_mlp(const FwdArgs& a, hipStream_t st);
 // software-pipelined whole-network kernel for wide layers (wide_mlp.hip); launch_fused_mlp hands it the shapes it takes
 bool wide_mlp_supported(const FwdArgs& a, int* ld_out);
 aq_status launch_wide_mlp(const FwdArgs& a, hipStream_t st);
-// whether launch_fused_mlp runs the pipelined kernel for this network and batch (observations 16-byte aligned)
-bool fused_mlp_is_pipelined(const FwdArgs& a);
+// which kernel launch_fused_mlp runs for this network and batch (observations 16-byte aligned): 0 = the general
+// fused kernel, 1 = the pipelined kernel for wide layers
+int fused_mlp_kernel_kind(const FwdArgs& a);
 
 // one launch per layer (FC and implicit-GEMM convolution), activations in global memory
 struct LayerIO {
