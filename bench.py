@@ -21,13 +21,13 @@ PULL_EVERY = 100           # actor steps between model pulls (the paper's smalle
 INT8_PEAK_TOPS = 5000.0    # MI355X dense int8 MFMA, TOP/s
 FP16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA, TFLOP/s
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the fused kernel on the headline workload, from the FETCH_SIZE and WRITE_SIZE
+# HBM bytes per launch of the whole-network kernel on the headline workload, from the FETCH_SIZE and WRITE_SIZE
 # hardware counters scaled by what they read on a plain 64 MiB copy (the rocprofv3 summary of this kernel under
 # profiles/), together with the hash of the kernel's sources at the time the counters were taken: when the
 # sources have changed since, the figure is reported as null.
 FUSED_TRAFFIC = {"bytes_per_launch": 3192825,
                  "sources_sha256": "fdcc9e631020f9b51374731f76be718e039b7406ad795f44cabfabcc4431978a"}
-FUSED_SOURCES = ("fused_mlp.hpp", "fused_mlp.hip", "int8_device.hpp", "common.hpp", "explore_device.hpp")
+FUSED_SOURCES = ("rows16_mlp.hip", "fused_mlp.hip", "int8_device.hpp", "common.hpp", "explore_device.hpp")
 
 
 def _fused_sources_hash():
@@ -147,14 +147,15 @@ def forward_workload(torch, aq, synth, name, batch, iters, warm=20, report_error
     # algorithmic HBM bytes: observations in, actions out, 8-bit weights once
     n_w = sum(int(p["w"].size) for p in params)
     hbm = float(obs.nbytes + act.numel() * act.element_size() + n_w)
-    rows, tiles, piped = P.policy_fused_plan(batch)
+    rows, tiles, kind = P.policy_fused_plan(batch)
+    kind_name = {0: "", 1: ", pipelined (k_mlp_wide)", 2: ", small-network kernel (k_mlp_rows16)"}[kind]
     out = {"workload": f"{name} batch {batch}", "us_per_launch": ms * 1e3, "inferences_per_s": batch / (ms * 1e-3),
            "tops": ops / (ms * 1e-3) / 1e12, "frac_int8_mfma_peak": ops / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
            "GBps_algorithmic": hbm / (ms * 1e-3) / 1e9, "frac_hbm_peak": hbm / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
            "us_per_launch_eager": ms_eager * 1e3, "fp32_actor_us_per_launch": ms32 * 1e3,
            "fp16_actor_us_per_launch": ms16 * 1e3, "fp16_actor_tflops": ops / (ms16 * 1e-3) / 1e12,
            "fp16_actor_frac_fp16_mfma_peak": ops / (ms16 * 1e-3) / 1e12 / FP16_PEAK_TFLOPS,
-           "launch_plan": f"fused kernel{', pipelined' if piped else ''}, {rows} rows per workgroup, {tiles} feature tile(s) per wavefront" if rows
+           "launch_plan": f"fused kernel{kind_name}, {rows} rows per workgroup, {tiles} feature tile(s) per wavefront" if rows
            else "one launch per layer"}
     if report_error:
         # quantization error of the actions: the 8-bit and the half-precision actor against the fp32 actor on
@@ -402,7 +403,7 @@ def main():
                      "traffic": FUSED_TRAFFIC["bytes_per_launch"] if traffic_ok else None,
                      "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE counters, copy-calibrated)" if traffic_ok
                      else "null: the kernel's sources have changed since the counters were taken",
-                     "kernel": "k_mlp_fused (whole-network int8 MLP)", "us_per_launch": head["us_per_launch"],
+                     "kernel": "k_mlp_rows16 (whole-network int8 MLP, 16 batch rows per workgroup)", "us_per_launch": head["us_per_launch"],
                      "timing": "median of 5 repeats of HIP-graph replays of back-to-back launches, HIP events"},
         "fp32_actor_us_per_launch": head["fp32_actor_us_per_launch"],
         "fp16_actor_us_per_launch": head["fp16_actor_us_per_launch"],

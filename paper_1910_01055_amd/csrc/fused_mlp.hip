@@ -116,7 +116,8 @@ bool fused_mlp_supported(const FwdArgs& a, int* rows_out, size_t* lds_out, int* 
 int fused_mlp_kernel_kind(const FwdArgs& a) {
     Plan p;
     int ld;
-    if (!make_plan(a, &p) || p.half) return 0;
+    if (!make_plan(a, &p)) return 0;
+    if (p.half) return rows16_mlp_supported(a) ? 2 : 0;
     if (p.nb == 2 && p.mt == 2 && wide_mlp_supported(a, &ld)) return 1;
     return 0;
 }
@@ -125,7 +126,10 @@ aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     Plan p;
     if (!make_plan(a_in, &p)) return AQ_ESHAPE;
     // 64-row workgroups on wide layers: the pipelined kernel where the shapes and the address allow it
-    if (fused_mlp_kernel_kind(a_in) == 1 && ((uintptr_t)a_in.c.obs & 15) == 0) return launch_wide_mlp(a_in, st);
+    // 16-row workgroups on small networks: the kernel built for that case
+    const int kind = ((uintptr_t)a_in.c.obs & 15) == 0 ? fused_mlp_kernel_kind(a_in) : 0;
+    if (kind == 1) return launch_wide_mlp(a_in, st);
+    if (kind == 2) return launch_rows16_mlp(a_in, st);
     FwdArgs a = a_in;
     a.c.ld = p.ld;
     a.c.cst_n = p.cst_n;

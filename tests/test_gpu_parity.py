@@ -252,9 +252,14 @@ def test_forward_unaligned_observations_and_tile_edges(aq, name, path, batch):
     U.compare_forward(net, pol, obs, a_ref, t, rows)
     a_mis, t = U.gpu_forward(P, net, obs, misalign=1)
     U.compare_forward(net, pol, obs, a_mis, t, rows)
-    assert np.array_equal(a_mis, a_ref, equal_nan=True)
     a_mis2, _ = U.gpu_forward(P, net, obs, taps=False, misalign=3)
-    assert np.array_equal(a_mis2, a_ref, equal_nan=True)
+    assert np.array_equal(a_mis2, a_mis, equal_nan=True)
+    # An unaligned buffer takes the general kernel.  Where the aligned one ran the 16-row kernel, a LayerNorm
+    # layer's fp32 statistics were summed in another order, and a code next to a rounding tie may differ: both
+    # runs are held to the oracle above, bit equality between them is required of integer-only networks.
+    ln = any(l["act"] == "ln_tanh" for l in net["layers"])
+    if not (ln and path == 0 and P.policy_fused_plan(batch)[2] == 2):
+        assert np.array_equal(a_mis, a_ref, equal_nan=True)
     P.close()
 
 
@@ -312,27 +317,35 @@ def test_forward_full_size(aq, name, batch, sample):
     P.close()
 
 
-# Every compiled variant of the whole-network kernel, named by (batch rows per workgroup, feature tiles per
-# wavefront, per-tensor weight scheme): the network and batch that make the launch plan pick it.  Each is run
-# with intermediate outputs (checked stage by stage against the oracle) and without (the variant a
-# benchmark times; its actions must be the same bits).
+# Every compiled variant of the whole-network kernels, named by (batch rows per workgroup, feature tiles per
+# wavefront, per-tensor weight scheme, kernel kind: 0 general, 1 pipelined for wide layers, 2 the 16-row kernel
+# for small networks): the network and batch that make the launch plan pick it.  Each is run with intermediate
+# outputs (checked stage by stage against the oracle) and without (the variant a benchmark times; its actions
+# must be the same bits).
 _ODD_WIDE = [synth.fc(100, 1000, "relu"), synth.fc(1000, 1024, "relu"), synth.fc(1024, 40, "none")]
 FUSED_VARIANTS = {
-    (16, 1, False): [("cfg2", 4096)],
-    (16, 1, True): [("cfg1", 256)],
-    (32, 1, False): [("cfg2", 8192)],
-    (64, 1, False): [("cfg2", 16379)],
-    (128, 1, False): [("cfg2", 32763), ("mid_wide", 32763)],
-    (32, 2, False): [("cfg5", 8192), ("odd_wide", 8185)],
-    (64, 2, False): [("cfg5", 16384), ("odd_wide", 16379)],
-    (32, 1, True): [("cfg1", 8192)],
-    (64, 1, True): [("cfg1", 16379)],
+    (16, 1, False, 2): [("cfg2", 4096), ("cfg2", 4081), ("odd_small", 3000), ("argmax_small", 333)],
+    (16, 1, False, 0): [("mid_wide", 4096)],
+    (16, 1, True, 0): [("cfg1", 256)],
+    (32, 1, False, 0): [("cfg2", 8192)],
+    (64, 1, False, 0): [("cfg2", 16379)],
+    (128, 1, False, 0): [("cfg2", 32763), ("mid_wide", 32763)],
+    (32, 2, False, 0): [("cfg5", 8192), ("odd_wide", 8185)],
+    (64, 2, False, 0): [("odd_wide", 16379)],
+    (64, 2, False, 1): [("cfg5", 16384)],
+    (32, 1, True, 0): [("cfg1", 8192)],
+    (64, 1, True, 0): [("cfg1", 16379)],
 }
 
 
 def _variant_net(name):
     if name == "odd_wide":  # a ragged last feature tile (1000 = 31 * 32 + 8) with two tiles per wavefront
         return synth.small_net(_ODD_WIDE, head="tanh")
+    if name == "odd_small":  # the 16-row kernel on ragged shapes: odd K, odd tile counts, LayerNorm on a ragged width
+        return synth.small_net([synth.fc(37, 200, "relu"), synth.fc(200, 72, "ln_tanh"), synth.fc(72, 250, "none"),
+                                synth.fc(250, 40, "none")], head="linear")
+    if name == "argmax_small":  # ... and with an argmax head over two feature tiles
+        return synth.small_net([synth.fc(130, 96, "relu"), synth.fc(96, 50, "none")], head="argmax")
     if name == "mid_wide":  # 128-row workgroups with a 512-wide layer (two passes of the eight wavefronts)
         return synth.small_net([synth.fc(67, 512, "relu"), synth.fc(512, 256, "relu"), synth.fc(256, 21, "none")],
                                head="tanh")
@@ -351,8 +364,11 @@ def test_fused_variant_table_covers_every_compiled_variant():
     for mt, nb, asym, taps, half in decl:
         key = (16 if half == "true" else 32 * int(mt), int(nb), asym == "true")
         seen.setdefault(key, set()).add(taps)
-    assert set(seen) == set(FUSED_VARIANTS), (sorted(seen), sorted(FUSED_VARIANTS))
+    # the general kernel's instantiations, plus the pipelined and the 16-row kernel (each compiled with and
+    # without intermediate outputs in its own file)
+    assert set(seen) == {k[:3] for k in FUSED_VARIANTS if k[3] == 0}, (sorted(seen), sorted(FUSED_VARIANTS))
     assert all(v == {"true", "false"} for v in seen.values())
+    assert {k[3] for k in FUSED_VARIANTS} == {0, 1, 2}
 
 
 @pytest.mark.parametrize("key", sorted(FUSED_VARIANTS))
@@ -365,8 +381,7 @@ def test_every_fused_variant_against_the_oracle(aq, key):
         obs = synth.make_obs(net, batch)
         pol, ranges = U.make_oracle(net, params, obs[:256])
         P, _ = U.gpu_quantize(aq, net, params, ranges)
-        assert P.policy_fused_plan(batch)[:2] == key[:2]
-        assert P.policy_fused_plan(batch)[2] == (1 if (name == "cfg5" and batch == 16384) else 0)
+        assert P.policy_fused_plan(batch) == (key[0], key[1], key[3])
         rng = np.random.default_rng(21)
         rows = np.unique(np.concatenate([[0, 15, 16, 31, 32, 63, 64, batch - 65, batch - 33, batch - 1],
                                          rng.integers(0, batch, 250)]))
@@ -379,7 +394,8 @@ def test_every_fused_variant_against_the_oracle(aq, key):
             assert np.array_equal(plain, actions, equal_nan=True)
             assert first is None or np.array_equal(first, plain, equal_nan=True)
             first = plain
-        assert np.isfinite(plain).all() and np.abs(plain).max() <= 1.0
+        if net["head"] == "tanh":
+            assert np.isfinite(plain).all() and np.abs(plain).max() <= 1.0
         P.close()
 
 
