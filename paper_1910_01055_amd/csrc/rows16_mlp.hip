@@ -13,7 +13,7 @@
 //     flags - comes from the device-resident description by one burst of scalar loads at the start: no
 //     layer waits for a descriptor;
 //   - weights and per-channel constants go from global memory straight to registers, one layer ahead: all
-//     of a layer's operands (at most 8 KiB per wavefront) are requested before the previous layer's epilogue,
+//     of a layer's operands (at most 8 KiB per wavefront) are requested at the start of the previous layer,
 //     the constants of its epilogue too.  A lane's four features of a tile are shared by the 16 lanes of its
 //     row, so each lane fetches one 16-byte piece (array x tile) and the epilogue takes its operands from the
 //     row's lanes by DPP row broadcasts: one load instruction per wavefront and layer instead of eight (the
@@ -177,15 +177,19 @@ __global__ __launch_bounds__(RT) void k_mlp_rows16(const NetDev* __restrict__ ne
     // hidden layer operands of this wavefront's 32 features: [k-step][16-feature tile]; loads are unconditional
     // from clamped addresses (an idle wavefront re-reads the last tile, a k-group past K the last k-tile: those
     // registers are not used, or meet zero activations)
-    auto load_w = [&](const R16Layer& L, v4i (&w)[RSTEPS][2]) __attribute__((always_inline)) {
+    // (`first`: the first layer's requests are the kernel's first, with nothing older in flight whose wait they
+    // could blur, so the k-steps past its K - most of them for a narrow observation - are skipped)
+    auto load_w = [&](const R16Layer& L, v4i (&w)[RSTEPS][2], bool first) __attribute__((always_inline)) {
         const int nt = wave < L.NT ? wave : L.NT - 1;
         gv4i_ptr base = (gv4i_ptr)L.wp + (int64_t)nt * L.KS * 64 + (b + 32 * (g4 & 1));
 #pragma unroll
         for (int s = 0; s < RSTEPS; ++s) {
             int ks = 2 * s + (g4 >> 1);
             ks = ks < L.KS ? ks : L.KS - 1;
+            if (!first || 2 * s < L.KS) {
 #pragma unroll
-            for (int tl = 0; tl < 2; ++tl) w[s][tl] = base[ks * 64 + 16 * tl];
+                for (int tl = 0; tl < 2; ++tl) w[s][tl] = base[ks * 64 + 16 * tl];
+            }
         }
     };
     // ... and the constants of its epilogue.  The lanes of a 16-lane row all need the same eight 16-byte
@@ -226,12 +230,12 @@ __global__ __launch_bounds__(RT) void k_mlp_rows16(const NetDev* __restrict__ ne
         }
     };
 
-    v4i w[RSTEPS][2];     // operands of the layer being multiplied, then of the next one
+    v4i w[2][RSTEPS][2];  // operands of the layer being multiplied, and of the next one
     v4i cst[2];           // this lane's piece of the constants of the layer whose epilogue runs, and of the next one
     v4i wl[2];            // operands of the last layer
     auto is_ln = [&](int l) { return a.L[l].act == AQ_ACT_LN_TANH; };
     if constexpr (nh > 0) {
-        load_w(a.L[0], w);
+        load_w(a.L[0], w[0], true);
         cst[0] = load_c(a.L[0], is_ln(0) || fastf[0]);
     } else {
         load_wl(LL, wl);
@@ -287,6 +291,15 @@ __global__ __launch_bounds__(RT) void k_mlp_rows16(const NetDev* __restrict__ ne
             LayerTaps T{nullptr, nullptr, nullptr};
             if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
 
+            // The next layer's operands and constants are requested first: their eight loads per wavefront queue
+            // at the CU's single vector memory path (64 KiB per 256 x 256 layer at 64 B / clock), and a
+            // wavefront stuck there cannot start its epilogue; here it would be waiting for LDS anyway.
+            if constexpr (l + 1 < nh) {
+                load_w(a.L[l + 1], w[(l + 1) & 1], false);
+                cst[(l + 1) & 1] = load_c(a.L[l + 1], is_ln(l + 1) || fastf[l + 1]);
+            } else {
+                load_wl(LL, wl);
+            }
             v4i acc[2];
             acc[0] = acc[1] = v4i{0, 0, 0, 0};
             {
@@ -298,18 +311,11 @@ __global__ __launch_bounds__(RT) void k_mlp_rows16(const NetDev* __restrict__ ne
 #pragma unroll
                     for (int s = 0; s < RSTEPS; ++s) {
                         if (s < ks64) {
-                            acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w[s][0], bx[s], acc[0], 0, 0, 0);
-                            acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w[s][1], bx[s], acc[1], 0, 0, 0);
+                            acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w[l & 1][s][0], bx[s], acc[0], 0, 0, 0);
+                            acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(w[l & 1][s][1], bx[s], acc[1], 0, 0, 0);
                         }
                     }
                 }
-            }
-            // the next layer's operands and constants: requested before this layer's epilogue
-            if constexpr (l + 1 < nh) {
-                load_w(a.L[l + 1], w);
-                cst[(l + 1) & 1] = load_c(a.L[l + 1], is_ln(l + 1) || fastf[l + 1]);
-            } else {
-                load_wl(LL, wl);
             }
             const v4i cm = cst[l & 1];
             const float s_out = s_q[l + 1];
@@ -329,30 +335,35 @@ __global__ __launch_bounds__(RT) void k_mlp_rows16(const NetDev* __restrict__ ne
                     const int lo = L.act == AQ_ACT_RELU ? z_out : 0;
                     int lo_v = lo;
                     asm volatile("" : "+v"(lo_v));
-                    const int fast = fastf[l];
-                    static_for<0, 2>([&](auto tl_c) __attribute__((always_inline)) {
-                        constexpr int tl = decltype(tl_c)::value;
-                        const int n0 = nbase + 16 * tl;
-                        uint32_t pack = 0;
+                    // (the form of the requantization is a fact of the layer: one branch around the whole tile pair)
+                    auto tiles = [&](auto fast_c) __attribute__((always_inline)) {
+                        constexpr bool fast = decltype(fast_c)::value;
+                        static_for<0, 2>([&](auto tl_c) __attribute__((always_inline)) {
+                            constexpr int tl = decltype(tl_c)::value;
+                            const int n0 = nbase + 16 * tl;
+                            uint32_t pack = 0;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int val = acc[tl][i] + AQ_R16_C(cm, 0, tl, i);
-                            if (TAPS) {
-                                if (T.acc && row_ok && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val;
+                            for (int i = 0; i < 4; ++i) {
+                                const int val = acc[tl][i] + AQ_R16_C(cm, 0, tl, i);
+                                if (TAPS) {
+                                    if (T.acc && row_ok && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val;
+                                }
+                                int code;
+                                if (fast)
+                                    code = clamp_code((__mulhi(val, AQ_R16_C(cm, 1, tl, i)) + AQ_R16_C(cm, 2, tl, i)) >>
+                                                          AQ_R16_CSH(cm, 3, tl, i), lo_v, 255);
+                                else
+                                    code = requant_code(val, AQ_R16_C(cm, 1, tl, i), AQ_R16_CSH(cm, 3, tl, i), z_out, lo);
+                                if (TAPS) {
+                                    if (T.act && row_ok && n0 + i < L.N) T.act[row * L.N + n0 + i] = (uint8_t)code;
+                                }
+                                pack |= (uint32_t)code << (8 * i);
                             }
-                            int code;
-                            if (fast)
-                                code = clamp_code((__mulhi(val, AQ_R16_C(cm, 1, tl, i)) + AQ_R16_C(cm, 2, tl, i)) >>
-                                                      AQ_R16_CSH(cm, 3, tl, i), lo_v, 255);
-                            else
-                                code = requant_code(val, AQ_R16_C(cm, 1, tl, i), AQ_R16_CSH(cm, 3, tl, i), z_out, lo);
-                            if (TAPS) {
-                                if (T.act && row_ok && n0 + i < L.N) T.act[row * L.N + n0 + i] = (uint8_t)code;
-                            }
-                            pack |= (uint32_t)code << (8 * i);
-                        }
-                        *(uint32_t*)(out + b * RLD + n0) = pack ^ 0x80808080u;
-                    });
+                            *(uint32_t*)(out + b * RLD + n0) = pack ^ 0x80808080u;
+                        });
+                    };
+                    if (fastf[l]) tiles(std::true_type{});
+                    else tiles(std::false_type{});
                 }
             } else {
                 // LayerNorm over the layer's N features, tanh, re-quantize.  x = acc * (s_in s_w) in fp32; this
