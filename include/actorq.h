@@ -141,18 +141,17 @@ aq_status aq_policy_conv_stack_layers(const aq_policy* p, int32_t* n_layers);
  * stride * in_c and in_w * in_c multiples of 8, out_c a multiple of 4, two to four convolutions). */
 aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers);
 
-/* Which compiled variant of the whole-network kernel a forward of `batch` >= 1 rows launches under the
+/* Which compiled variant of the whole-network kernels a forward of `batch` >= 1 rows launches under the
  * current launch plan: *rows = batch rows per workgroup (16, 32, 64 or 128), *tiles = 32-feature tiles per
  * wavefront and pass (1 or 2); both 0 when the forward runs one launch per layer instead (a network the
- * kernel does not take, or launch plan 2 / 3).  *pipelined (the kernel kind) = 1 when the 64-row, two-tile launch is the
- * software-pipelined kernel for wide layers (per-channel weights, fp32 observations at a 16-byte aligned
- * address, hidden widths multiples of 64 without LayerNorm, every K a multiple of 128, at most 64 outputs;
- * an unaligned observation buffer takes the general kernel even then); 2 when the 16-row launch is the kernel
- * for small networks (per-channel weights, fp32 observations at a 16-byte aligned address, at most four fully
- * connected layers, first-layer inputs and hidden widths up to 256, at most 64 outputs; an unaligned buffer
- * takes the general kernel here too); 0 otherwise.  With the weight scheme and whether
- * intermediate outputs are requested this names the variant, so that a test can show that every one it
- * times is also checked.  No GPU work. */
+ * kernels do not take, or launch plan 2 / 3).  *pipelined is the kernel kind: 0 = the general kernel; 1 = the
+ * software-pipelined kernel for wide layers (64 rows, two tiles; per-channel weights, fp32 observations, hidden
+ * widths multiples of 64 without LayerNorm, every K a multiple of 128, at most 64 outputs); 2 = the kernel for
+ * small networks (16, 32 or 64 rows by batch size; per-channel weights, fp32 observations, at most four fully
+ * connected layers, first-layer inputs and hidden widths up to 256, at most 64 outputs).  Kinds 1 and 2 need a
+ * 16-byte aligned observation buffer; an unaligned one takes the general kernel with the rows and tiles its own
+ * plan gives (not reported here).  With the weight scheme and whether intermediate outputs are requested this
+ * names the variant, so that a test can show that every one it times is also checked.  No GPU work. */
 aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles, int32_t* pipelined);
 
 /* Synchronizes `stream` and returns the sticky device-side error of the last

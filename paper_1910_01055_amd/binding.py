@@ -187,7 +187,7 @@ class Policy:
 
     def policy_fused_plan(self, batch):
         """(rows per workgroup, feature tiles per wavefront, kernel: 0 general / 1 pipelined for wide layers /
-        2 the 16-row kernel for small networks) of the fused launch at this batch; (0, 0, 0) = one launch per layer."""
+        2 the kernel for small networks) of the fused launch at this batch; (0, 0, 0) = one launch per layer."""
         r, t, w = C.c_int32(0), C.c_int32(0), C.c_int32(0)
         _check(load().aq_policy_fused_plan(self._h, int(batch), C.byref(r), C.byref(t), C.byref(w)), "aq_policy_fused_plan")
         return int(r.value), int(t.value), int(w.value)

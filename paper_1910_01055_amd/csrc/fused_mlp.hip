@@ -110,6 +110,10 @@ bool fused_mlp_supported(const FwdArgs& a, int* rows_out, size_t* lds_out, int* 
     *rows_out = p.half ? 16 : 32 * p.mt;
     *lds_out = p.lds;
     if (tiles_out) *tiles_out = p.nb;
+    if (fused_mlp_kernel_kind(a) == 2) {  // (given a 16-byte aligned observation buffer)
+        *rows_out = 16 * rows16_mlp_row_tiles(a.c.batch);
+        if (tiles_out) *tiles_out = 1;
+    }
     return true;
 }
 
@@ -117,7 +121,8 @@ int fused_mlp_kernel_kind(const FwdArgs& a) {
     Plan p;
     int ld;
     if (!make_plan(a, &p)) return 0;
-    if (p.half) return rows16_mlp_supported(a) ? 2 : 0;
+    if (rows16_mlp_supported(a)) return 2;
+    if (p.half) return 0;
     if (p.nb == 2 && p.mt == 2 && wide_mlp_supported(a, &ld)) return 1;
     return 0;
 }

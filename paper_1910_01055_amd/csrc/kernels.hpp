@@ -45,9 +45,10 @@ aq_status launch_fused_mlp(const FwdArgs& a, hipStream_t st);
 // software-pipelined whole-network kernel for wide layers (wide_mlp.hip); launch_fused_mlp hands it the shapes it takes
 bool wide_mlp_supported(const FwdArgs& a, int* ld_out);
 aq_status launch_wide_mlp(const FwdArgs& a, hipStream_t st);
-// whole-network kernel for small networks at 16 rows per workgroup (rows16_mlp.hip); launch_fused_mlp hands it
-// the shapes it takes whenever the plan is 16 rows per workgroup
+// whole-network kernel for small networks, 16, 32 or 64 rows per workgroup (rows16_mlp.hpp / .hip);
+// launch_fused_mlp hands it the shapes it takes
 bool rows16_mlp_supported(const FwdArgs& a);
+int rows16_mlp_row_tiles(int64_t batch);  // 16-row tiles per workgroup at this batch: 1, 2 or 4
 aq_status launch_rows16_mlp(const FwdArgs& a, hipStream_t st);
 // which kernel launch_fused_mlp runs for this network and batch (observations 16-byte aligned): 0 = the general
 // fused kernel, 1 = the pipelined kernel for wide layers, 2 = the 16-row kernel for small networks

@@ -324,12 +324,18 @@ def test_forward_full_size(aq, name, batch, sample):
 # must be the same bits).
 _ODD_WIDE = [synth.fc(100, 1000, "relu"), synth.fc(1000, 1024, "relu"), synth.fc(1024, 40, "none")]
 FUSED_VARIANTS = {
-    (16, 1, False, 2): [("cfg2", 4096), ("cfg2", 4081), ("odd_small", 3000), ("argmax_small", 333)],
+    # the kernel for small networks: one, two and four 16-row tiles per workgroup (batch up to 4096, up to 16384,
+    # beyond), each with ragged shapes, LayerNorm on a ragged width, argmax over two feature tiles, one layer
+    (16, 1, False, 2): [("cfg2", 4096), ("cfg2", 4081), ("odd_small", 3000), ("argmax_small", 333), ("single_narrow", 100)],
+    (32, 1, False, 2): [("cfg2", 8192), ("odd_small", 8185), ("argmax_small", 5000), ("single_narrow", 4100)],
+    (64, 1, False, 2): [("cfg2", 16400), ("cfg2", 32763), ("odd_small", 20011), ("argmax_small", 17000),
+                        ("single_narrow", 16390), ("odd_sym_ln", 16385)],
+    # the general kernel
     (16, 1, False, 0): [("mid_wide", 4096)],
     (16, 1, True, 0): [("cfg1", 256)],
-    (32, 1, False, 0): [("cfg2", 8192)],
-    (64, 1, False, 0): [("cfg2", 16379)],
-    (128, 1, False, 0): [("cfg2", 32763), ("mid_wide", 32763)],
+    (32, 1, False, 0): [("mid_wide", 8192)],
+    (64, 1, False, 0): [("mid_wide", 16379)],
+    (128, 1, False, 0): [("mid_wide", 32763), ("mid_wide_ln", 32700)],
     (32, 2, False, 0): [("cfg5", 8192), ("odd_wide", 8185)],
     (64, 2, False, 0): [("odd_wide", 16379)],
     (64, 2, False, 1): [("cfg5", 16384)],
@@ -346,6 +352,11 @@ def _variant_net(name):
                                 synth.fc(250, 40, "none")], head="linear")
     if name == "argmax_small":  # ... and with an argmax head over two feature tiles
         return synth.small_net([synth.fc(130, 96, "relu"), synth.fc(96, 50, "none")], head="argmax")
+    if name == "mid_wide_ln":  # ... with LayerNorm over a 256-wide layer behind it
+        return synth.small_net([synth.fc(67, 512, "relu"), synth.fc(512, 256, "ln_tanh"), synth.fc(256, 21, "none")],
+                               head="tanh")
+    if name in ("single_narrow", "odd_sym_ln"):
+        return _nets()[name]
     if name == "mid_wide":  # 128-row workgroups with a 512-wide layer (two passes of the eight wavefronts)
         return synth.small_net([synth.fc(67, 512, "relu"), synth.fc(512, 256, "relu"), synth.fc(256, 21, "none")],
                                head="tanh")
@@ -383,7 +394,7 @@ def test_every_fused_variant_against_the_oracle(aq, key):
         P, _ = U.gpu_quantize(aq, net, params, ranges)
         assert P.policy_fused_plan(batch) == (key[0], key[1], key[3])
         rng = np.random.default_rng(21)
-        rows = np.unique(np.concatenate([[0, 15, 16, 31, 32, 63, 64, batch - 65, batch - 33, batch - 1],
+        rows = np.unique(np.concatenate([[0, 15, 16, 31, 32, 63, 64, batch - 65, batch - 33, batch - 17, batch - 1],
                                          rng.integers(0, batch, 250)]))
         first = None
         for rep in range(3):
