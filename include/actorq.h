@@ -147,8 +147,8 @@ aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers
  * kernels do not take, or launch plan 2 / 3).  *pipelined is the kernel kind: 0 = the general kernel; 1 = the
  * software-pipelined kernel for wide layers (64 rows, two tiles; per-channel weights, fp32 observations, hidden
  * widths multiples of 64 without LayerNorm, every K a multiple of 128, at most 64 outputs); 2 = the kernel for
- * small networks (16, 32 or 64 rows by batch size; per-channel weights, fp32 observations, at most four fully
- * connected layers, first-layer inputs and hidden widths up to 256, at most 64 outputs).  Kinds 1 and 2 need a
+ * small networks (16, 32 or 64 rows by batch size; either weight scheme, fp32 or 8-bit observations, at most four
+ * fully connected layers, first-layer inputs and hidden widths up to 256, at most 64 outputs).  Kinds 1 and 2 need a
  * 16-byte aligned observation buffer; an unaligned one takes the general kernel with the rows and tiles its own
  * plan gives (not reported here).  With the weight scheme and whether intermediate outputs are requested this
  * names the variant, so that a test can show that every one it times is also checked.  No GPU work. */

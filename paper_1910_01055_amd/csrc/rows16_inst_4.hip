@@ -1,9 +1,9 @@
 // Explicit instantiation of the small-policy whole-network kernel with 4 row tiles (64 batch rows) per
-// workgroup, with and without intermediate taps.
+// workgroup (per-channel symmetric weights), with and without intermediate taps.
 #include "rows16_mlp.hpp"
 
 namespace aq {
 namespace r16 {
-AQ_ROWS16_INST(4);
+AQ_ROWS16_INST(4, false);
 }  // namespace r16
 }  // namespace aq

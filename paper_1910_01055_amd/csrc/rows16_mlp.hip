@@ -4,15 +4,18 @@
 
 namespace aq {
 namespace r16 {
-AQ_ROWS16_INST(1);
-AQ_ROWS16_DECL(2);
-AQ_ROWS16_DECL(4);
+AQ_ROWS16_INST(1, false);
+AQ_ROWS16_DECL(2, false);
+AQ_ROWS16_DECL(4, false);
+AQ_ROWS16_DECL(1, true);
+AQ_ROWS16_DECL(2, true);
+AQ_ROWS16_DECL(4, true);
 }  // namespace r16
 
 // Shapes the kernel takes (see the head of rows16_mlp.hpp).
 bool rows16_mlp_supported(const FwdArgs& a) {
     const NetDev& n = a.net;
-    if (n.asym || n.in_u8 || n.n_layers < 1 || n.n_layers > r16::RMAXL) return false;
+    if (n.n_layers < 1 || n.n_layers > r16::RMAXL) return false;
     for (int l = 0; l < n.n_layers; ++l) {
         const LayerDev& L = n.L[l];
         if (L.kh != 1 || L.kw != 1 || L.in_h != 1 || L.in_w != 1) return false;
@@ -42,18 +45,24 @@ aq_status launch_rows16_mlp(const FwdArgs& a, hipStream_t st) {
     ra.actions = a.c.actions;
     ra.batch = a.c.batch;
     ra.K0 = a.net.L[0].K;
-    ra.n_layers = a.net.n_layers;
+    ra.shape = a.net.n_layers | (a.net.in_u8 ? 1 << 8 : 0);
     ra.ex_sigma = a.c.ex_sigma;
     ra.ex_k0 = a.c.ex_k0;
     ra.ex_k1 = a.c.ex_k1;
     ra.ex_s0 = a.c.ex_s0;
     ra.ex_s1 = a.c.ex_s1;
     const bool tp = any_taps(a);
+#define AQ_GO(MT)                                                                                         \
+    return a.net.asym ? (tp ? r16::launch_rows16_t<MT, true, true>(a.d_net, ra, a.t, st)                  \
+                            : r16::launch_rows16_t<MT, true, false>(a.d_net, ra, a.t, st))                \
+                      : (tp ? r16::launch_rows16_t<MT, false, true>(a.d_net, ra, a.t, st)                 \
+                            : r16::launch_rows16_t<MT, false, false>(a.d_net, ra, a.t, st))
     switch (rows16_mlp_row_tiles(a.c.batch)) {
-        case 1: return tp ? r16::launch_rows16_t<1, true>(a.d_net, ra, a.t, st) : r16::launch_rows16_t<1, false>(a.d_net, ra, a.t, st);
-        case 2: return tp ? r16::launch_rows16_t<2, true>(a.d_net, ra, a.t, st) : r16::launch_rows16_t<2, false>(a.d_net, ra, a.t, st);
-        default: return tp ? r16::launch_rows16_t<4, true>(a.d_net, ra, a.t, st) : r16::launch_rows16_t<4, false>(a.d_net, ra, a.t, st);
+        case 1: AQ_GO(1);
+        case 2: AQ_GO(2);
+        default: AQ_GO(4);
     }
+#undef AQ_GO
 }
 
 }  // namespace aq

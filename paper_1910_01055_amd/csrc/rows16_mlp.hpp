@@ -33,8 +33,13 @@
 // memory path per row shrink by MT, and the kernel is kept within 128 registers so that two workgroups share
 // a CU: while one sits in a barrier or waits for LDS, the other's epilogue has the vector ALU.
 //
-// Shapes: per-channel symmetric weights, fp32 observations at a 16-byte aligned address, one to four fully
-// connected layers, first-layer K and hidden widths at most 256, last layer at most 64 outputs.
+// ASYM (per-tensor asymmetric weights, the scheme Sec. 3.2 writes out): the accumulator needs - z_w' sum_k a_s per
+// batch row on top of the folded bias; the row sums come from one extra MFMA per k-step against an all-ones
+// operand (the matrix cores are idle most of the time here), which leaves them in the lanes that hold the row's
+// accumulators.  Padding features are then written as zero codes, because the next layer sums whole padded rows.
+//
+// Shapes: fp32 or 8-bit observations at a 16-byte aligned address, one to four fully connected layers, first-layer
+// K and hidden widths at most 256, last layer at most 64 outputs.
 #pragma once
 #include "explore_device.hpp"
 #include "int8_device.hpp"
@@ -75,7 +80,8 @@ struct R16Args {
     int64_t batch;
     const float* ex_sigma;  // Gaussian exploration noise added where the actions are written, or NULL
     uint32_t ex_k0, ex_k1, ex_s0, ex_s1;
-    int K0, n_layers;
+    int K0;
+    int shape;  // number of layers | observations are 8-bit codes << 8
 };
 static_assert(sizeof(R16Args) == 56, "the kernel arguments must stay within one 64-byte line");
 
@@ -109,7 +115,7 @@ __device__ __forceinline__ float sum_rows4(float s) {
 // a compile-time fact, so that every global load sits in straight-line code and the compiler can count exactly
 // which ones an instruction has to wait for (with the layer count a run-time value, epilogues waited for the
 // loads of the next layer requested just before them).
-template <int MT, int NH, bool TAPS>
+template <int MT, int NH, bool ASYM, bool TAPS>
 __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev* __restrict__ netp, const R16Args c,
                                                                      const TapArgs t) {
     constexpr int ROWS = 16 * MT;
@@ -117,7 +123,8 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
     __shared__ __align__(16) int8_t s_buf[2][ROWS * RLD];
     __shared__ __align__(16) float s_red[ROWS * RW * 2];
     constexpr int NITEMS = MT == 4 ? 16 : 8;
-    __shared__ __align__(16) int32_t s_part[NITEMS * 4 * 64];  // accumulators of the last layer's items
+    constexpr int PR = ASYM ? 5 : 4;  // words per lane and item: four accumulators (and the row sum of the activations)
+    __shared__ __align__(16) int32_t s_part[NITEMS * PR * 64];  // accumulators of the last layer's items
     const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
     const int b = lane & 15, g4 = lane >> 4;  // this lane's batch row and k-group (operands) / feature quad (results)
     const int64_t row0 = (int64_t)blockIdx.x * ROWS;
@@ -133,6 +140,7 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
     const float inv_q4 = 1.0f / (float)q4;
     const float* src1 = c.obs + row0 * K0;
     const bool k_al = (K0 & 3) == 0;
+    const bool in_u8 = (c.shape >> 8) != 0;  // 8-bit observations are codes already (scale 1, zero-point 0)
     const int nquads = ROWS * q4;
     float4 ov[NQ];
     int om[NQ], ok4[NQ];
@@ -144,14 +152,29 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
         ok4[u] = 4 * (q - om[u] * q4);
         ov[u] = float4{0.0f, 0.0f, 0.0f, 0.0f};
         if (u * RT < nquads && om[u] < vrows) {
-            const float* src = src1 + om[u] * K0 + ok4[u];
-            if (k_al) {
-                ov[u] = *(const float4*)src;
+            if (in_u8) {
+                // four codes: one word where the rows are 4-byte aligned, single bytes otherwise (kept in .x)
+                const uint8_t* src = (const uint8_t*)c.obs + (row0 + om[u]) * K0 + ok4[u];
+                uint32_t q4w;
+                if (k_al) {
+                    q4w = *(const uint32_t*)src;
+                } else {
+                    q4w = src[0];
+                    if (ok4[u] + 1 < K0) q4w |= (uint32_t)src[1] << 8;
+                    if (ok4[u] + 2 < K0) q4w |= (uint32_t)src[2] << 16;
+                    if (ok4[u] + 3 < K0) q4w |= (uint32_t)src[3] << 24;
+                }
+                ov[u].x = __uint_as_float(q4w);
             } else {
-                ov[u].x = src[0];
-                if (ok4[u] + 1 < K0) ov[u].y = src[1];
-                if (ok4[u] + 2 < K0) ov[u].z = src[2];
-                if (ok4[u] + 3 < K0) ov[u].w = src[3];
+                const float* src = src1 + om[u] * K0 + ok4[u];
+                if (k_al) {
+                    ov[u] = *(const float4*)src;
+                } else {
+                    ov[u].x = src[0];
+                    if (ok4[u] + 1 < K0) ov[u].y = src[1];
+                    if (ok4[u] + 2 < K0) ov[u].z = src[2];
+                    if (ok4[u] + 3 < K0) ov[u].w = src[3];
+                }
             }
         }
     }
@@ -182,6 +205,15 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
     }
 #pragma unroll
     for (int i = 0; i < RMAXL; ++i) fastf[i] = uni(netp->fast[i]);
+    // per-tensor weights: the tensor's zero-point in the signed domain (written by the quantizer)
+    int zw_s[RMAXL];
+#pragma unroll
+    for (int i = 0; i < RMAXL; ++i) {
+        zw_s[i] = 0;
+        if (ASYM && i <= NH) zw_s[i] = uni(*(gint_ptr)uni_ptr(netp->L[i].z_w)) - 128;
+    }
+    v4i ones;
+    ones[0] = ones[1] = ones[2] = ones[3] = 0x01010101;
 
     // hidden layer operands of this wavefront's 32 features: [k-step][16-feature tile]; loads are unconditional
     // from clamped addresses (an idle wavefront re-reads the last tile, a k-group past K the last k-tile: those
@@ -267,7 +299,7 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
 #pragma unroll
         for (int u = 0; u < NQ; ++u) {
             if (u * RT < nquads && om[u] < ROWS) {
-                uint32_t pack = quant_u8x4(ov[u], qs0, zf0);
+                uint32_t pack = in_u8 ? __float_as_uint(ov[u].x) : quant_u8x4(ov[u], qs0, zf0);
                 const int left_k = K0 - ok4[u];  // real values in this quad: 1..4 (or more)
                 if (TAPS) {
                     if (t.a0 && om[u] < vrows) {
@@ -322,9 +354,9 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
         };
         if constexpr (WDBL) request_next();
         const v4i(&wcur)[RSTEPS][2] = w[WDBL ? l & 1 : 0];
-        v4i acc[MT][2];
+        v4i acc[MT][2], rsa[MT];  // (rsa: every register of it ends up holding sum_k a_s of this lane's batch row)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[mt][0] = acc[mt][1] = v4i{0, 0, 0, 0};
+        for (int mt = 0; mt < MT; ++mt) acc[mt][0] = acc[mt][1] = rsa[mt] = v4i{0, 0, 0, 0};
         {
             const int8_t* xrow = in + b * RLD + 16 * g4;
             if constexpr (MT == 1) {
@@ -337,6 +369,7 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                         if (s < ks64) {
                             acc[0][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wcur[s][0], bx[s], acc[0][0], 0, 0, 0);
                             acc[0][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wcur[s][1], bx[s], acc[0][1], 0, 0, 0);
+                            if (ASYM) rsa[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, bx[s], rsa[0], 0, 0, 0);
                         }
                     }
                 }
@@ -356,6 +389,7 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                         for (int mt = 0; mt < MT; ++mt) {
                             acc[mt][0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wcur[s][0], bx[s & 1][mt], acc[mt][0], 0, 0, 0);
                             acc[mt][1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wcur[s][1], bx[s & 1][mt], acc[mt][1], 0, 0, 0);
+                            if (ASYM) rsa[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, bx[s & 1][mt], rsa[mt], 0, 0, 0);
                         }
                     }
                 }
@@ -366,6 +400,9 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
         const float s_out = s_q[l + 1];
         const int z_out = z_q[l + 1];
         const int nbase = 32 * wave + 4 * g4;
+        int rowterm[MT];  // - z_w' sum_k a_s of this lane's row of each row tile
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) rowterm[mt] = ASYM ? -zw_s[l] * rsa[mt][0] : 0;
         // a layer with an odd number of 32-feature tiles: the next layer's last 64-wide k-step reads 32
         // columns nobody computes; the first idle wavefront zeroes them
         if ((L.NT & 1) && wave == L.NT) {
@@ -402,13 +439,17 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                             uint32_t pack = 0;
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                const int val = acc[mt][tl][i] + cb[i];
+                                int val = acc[mt][tl][i] + cb[i];
+                                if (ASYM) val += rowterm[mt];
                                 if (TAPS) {
                                     if (T.acc && row_ok && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val;
                                 }
                                 int code;
                                 if (fast) code = clamp_code((__mulhi(val, cmul[i]) + cz[i]) >> csh[i], lo_v, 255);
                                 else code = requant_code(val, cmul[i], csh[i], z_out, lo);
+                                // per-tensor weights: padding features are zero in the signed domain (the next
+                                // layer sums whole padded rows); with symmetric weights they only meet zero weights
+                                if (ASYM && n0 + i >= L.N) code = 128;
                                 if (TAPS) {
                                     if (T.act && row_ok && n0 + i < L.N) T.act[row * L.N + n0 + i] = (uint8_t)code;
                                 }
@@ -440,7 +481,8 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                     const float cmul = __int_as_float(AQ_R16_C(cm, 1, tl, i));
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-                        const int val = acc[mt][tl][i] + cb;
+                        int val = acc[mt][tl][i] + cb;
+                        if (ASYM) val += rowterm[mt];
                         if (TAPS) {
                             const int64_t row = row0 + 16 * mt + b;
                             if (T.acc && active && row < c.batch && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val;
@@ -553,6 +595,11 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                                                       fmaf(rv[2], -2.0f, 1.0f), fmaf(rv[3], -2.0f, 1.0f)},
                                                qs_out, -z_out, 255 - z_out, z_out);
                         }
+                        if (ASYM && n0 + 4 > L.N) {  // padding features: zero in the signed domain
+                            const int keep = L.N - n0;  // < 4, may be <= 0
+                            const uint32_t kmask = keep <= 0 ? 0u : (1u << (8 * keep)) - 1u;
+                            pack = (pack & kmask) | (0x80808080u & ~kmask);
+                        }
                         if (TAPS) {
                             const int64_t row = row0 + 16 * mt + b;
 #pragma unroll
@@ -585,7 +632,7 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
             const int item = wave + RW * it;
             const int pair = item & (lm.pairs - 1), kp = item >> lm.lg_pairs;
             const int mt = pair >> lm.lg_t16;
-            v4i acc = v4i{0, 0, 0, 0};
+            v4i acc = v4i{0, 0, 0, 0}, rsl = v4i{0, 0, 0, 0};
             if (item < lm.pairs * lm.ksplit) {
                 v4i bx[LJ];
 #pragma unroll
@@ -595,9 +642,13 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                 }
 #pragma unroll
                 for (int j = 0; j < LJ; ++j)
-                    if (kp + j * lm.ksplit < ks64) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wl[it][j], bx[j], acc, 0, 0, 0);
+                    if (kp + j * lm.ksplit < ks64) {
+                        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wl[it][j], bx[j], acc, 0, 0, 0);
+                        if (ASYM) rsl = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, bx[j], rsl, 0, 0, 0);
+                    }
 #pragma unroll
-                for (int r = 0; r < 4; ++r) s_part[(item * 4 + r) * 64 + lane] = acc[r];
+                for (int r = 0; r < 4; ++r) s_part[(item * PR + r) * 64 + lane] = acc[r];
+                if (ASYM) s_part[(item * PR + 4) * 64 + lane] = rsl[0];
             }
         }
         // this thread's outputs of the reduction: (pair, register, lane) = (o >> 8, (o >> 6) & 3, o & 63) for
@@ -626,11 +677,15 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
             const int o = tid + it * RT;
             const int pair = o >> 8, r = (o >> 6) & 3, ln_ = o & 63;
             if (pair < lm.pairs) {
-                int v = 0;
+                int v = 0, rsum = 0;
 #pragma unroll
                 for (int kp = 0; kp < 4; ++kp)
-                    if (kp < lm.ksplit) v += s_part[((pair + lm.pairs * kp) * 4 + r) * 64 + ln_];
+                    if (kp < lm.ksplit) {
+                        v += s_part[((pair + lm.pairs * kp) * PR + r) * 64 + ln_];
+                        if (ASYM) rsum += s_part[((pair + lm.pairs * kp) * PR + 4) * 64 + ln_];
+                    }
                 v += bf[it];
+                if (ASYM) v -= zw_s[nh] * rsum;
                 const int tile = pair & (lm.t16 - 1), mt = pair >> lm.lg_t16;
                 const int n = 16 * tile + 4 * (ln_ >> 4) + r, m = 16 * mt + (ln_ & 15);
                 const int64_t orow = row0 + m;
@@ -669,25 +724,25 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
     }
 }
 
-template <int MT, bool TAPS>
+template <int MT, bool ASYM, bool TAPS>
 aq_status launch_rows16_t(const NetDev* d_net, const R16Args& ra, const TapArgs& t, hipStream_t st) {
     const unsigned grid = (unsigned)((ra.batch + 16 * MT - 1) / (16 * MT));
-    switch (ra.n_layers) {
-        case 1: hipLaunchKernelGGL((k_mlp_rows16<MT, 0, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
-        case 2: hipLaunchKernelGGL((k_mlp_rows16<MT, 1, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
-        case 3: hipLaunchKernelGGL((k_mlp_rows16<MT, 2, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
-        case 4: hipLaunchKernelGGL((k_mlp_rows16<MT, 3, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
+    switch (ra.shape & 255) {
+        case 1: hipLaunchKernelGGL((k_mlp_rows16<MT, 0, ASYM, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
+        case 2: hipLaunchKernelGGL((k_mlp_rows16<MT, 1, ASYM, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
+        case 3: hipLaunchKernelGGL((k_mlp_rows16<MT, 2, ASYM, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
+        case 4: hipLaunchKernelGGL((k_mlp_rows16<MT, 3, ASYM, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
         default: return AQ_ESHAPE;
     }
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
-// one translation unit per MT, so that the variants compile in parallel
-#define AQ_ROWS16_DECL(MT) \
-    extern template aq_status launch_rows16_t<MT, false>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t); \
-    extern template aq_status launch_rows16_t<MT, true>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t)
-#define AQ_ROWS16_INST(MT) \
-    template aq_status launch_rows16_t<MT, false>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t); \
-    template aq_status launch_rows16_t<MT, true>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t)
+// one translation unit per (MT, ASYM), so that the variants compile in parallel
+#define AQ_ROWS16_DECL(MT, AS) \
+    extern template aq_status launch_rows16_t<MT, AS, false>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t); \
+    extern template aq_status launch_rows16_t<MT, AS, true>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t)
+#define AQ_ROWS16_INST(MT, AS) \
+    template aq_status launch_rows16_t<MT, AS, false>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t); \
+    template aq_status launch_rows16_t<MT, AS, true>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t)
 
 }  // namespace r16
 }  // namespace aq

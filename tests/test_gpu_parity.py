@@ -325,22 +325,29 @@ def test_forward_full_size(aq, name, batch, sample):
 _ODD_WIDE = [synth.fc(100, 1000, "relu"), synth.fc(1000, 1024, "relu"), synth.fc(1024, 40, "none")]
 FUSED_VARIANTS = {
     # the kernel for small networks: one, two and four 16-row tiles per workgroup (batch up to 4096, up to 16384,
-    # beyond), each with ragged shapes, LayerNorm on a ragged width, argmax over two feature tiles, one layer
-    (16, 1, False, 2): [("cfg2", 4096), ("cfg2", 4081), ("odd_small", 3000), ("argmax_small", 333), ("single_narrow", 100)],
+    # beyond), each with ragged shapes, LayerNorm on a ragged width, argmax over two feature tiles, one layer,
+    # 8-bit observations (rows of 48 and of 37 bytes), for both weight schemes
+    (16, 1, False, 2): [("cfg2", 4096), ("cfg2", 4081), ("odd_small", 3000), ("argmax_small", 333), ("single_narrow", 100),
+                        ("u8_mlp", 300)],
     (32, 1, False, 2): [("cfg2", 8192), ("odd_small", 8185), ("argmax_small", 5000), ("single_narrow", 4100)],
     (64, 1, False, 2): [("cfg2", 16400), ("cfg2", 32763), ("odd_small", 20011), ("argmax_small", 17000),
-                        ("single_narrow", 16390), ("odd_sym_ln", 16385)],
+                        ("single_narrow", 16390), ("odd_sym_ln", 16385), ("u8_mlp", 16500)],
+    (16, 1, True, 2): [("cfg1", 256), ("odd_asym", 100), ("two_tile_last_asym", 333), ("literal256", 77),
+                       ("u8_odd_asym", 500), ("asym_ln", 1000)],
+    (32, 1, True, 2): [("cfg1", 8192), ("cfg1", 16379), ("odd_asym", 8185), ("asym_ln", 5000)],
+    (64, 1, True, 2): [("cfg1", 16400), ("odd_asym", 20011), ("two_tile_last_asym", 17000), ("u8_odd_asym", 16390),
+                       ("asym_ln", 16500)],
     # the general kernel
     (16, 1, False, 0): [("mid_wide", 4096)],
-    (16, 1, True, 0): [("cfg1", 256)],
+    (16, 1, True, 0): [("mid_wide_asym", 4096)],
     (32, 1, False, 0): [("mid_wide", 8192)],
     (64, 1, False, 0): [("mid_wide", 16379)],
     (128, 1, False, 0): [("mid_wide", 32763), ("mid_wide_ln", 32700)],
     (32, 2, False, 0): [("cfg5", 8192), ("odd_wide", 8185)],
     (64, 2, False, 0): [("odd_wide", 16379)],
     (64, 2, False, 1): [("cfg5", 16384)],
-    (32, 1, True, 0): [("cfg1", 8192)],
-    (64, 1, True, 0): [("cfg1", 16379)],
+    (32, 1, True, 0): [("mid_wide_asym", 8192)],
+    (64, 1, True, 0): [("mid_wide_asym", 16379)],
 }
 
 
@@ -355,7 +362,16 @@ def _variant_net(name):
     if name == "mid_wide_ln":  # ... with LayerNorm over a 256-wide layer behind it
         return synth.small_net([synth.fc(67, 512, "relu"), synth.fc(512, 256, "ln_tanh"), synth.fc(256, 21, "none")],
                                head="tanh")
-    if name in ("single_narrow", "odd_sym_ln"):
+    if name == "mid_wide_asym":  # per-tensor weights with a layer too wide for the small-network kernel
+        return synth.small_net([synth.fc(67, 512, "relu"), synth.fc(512, 256, "relu"), synth.fc(256, 21, "none")],
+                               head="tanh", wscheme="tensor_asym_u8")
+    if name == "u8_odd_asym":  # 8-bit observations in rows that are not 4-byte aligned, per-tensor weights
+        return synth.small_net([synth.fc(37, 100, "relu"), synth.fc(100, 30, "none"), synth.fc(30, 11, "none")],
+                               head="tanh", wscheme="tensor_asym_u8", in_type="u8")
+    if name == "asym_ln":  # LayerNorm on a ragged width with per-tensor weights
+        return synth.small_net([synth.fc(20, 150, "ln_tanh"), synth.fc(150, 90, "relu"), synth.fc(90, 33, "none")],
+                               head="linear", wscheme="tensor_asym_u8")
+    if name in _nets():
         return _nets()[name]
     if name == "mid_wide":  # 128-row workgroups with a 512-wide layer (two passes of the eight wavefronts)
         return synth.small_net([synth.fc(67, 512, "relu"), synth.fc(512, 256, "relu"), synth.fc(256, 21, "none")],
