@@ -137,7 +137,7 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
     // a thread takes up to NQ (row, four consecutive k) quads: one 16-byte load where the rows are 16-byte
     // aligned (K0 a multiple of 4), four 4-byte loads otherwise
     const int q4 = (K0 + 3) >> 2;  // quads per row, <= 64
-    const float inv_q4 = 1.0f / (float)q4;
+    const float inv_q4 = __builtin_amdgcn_rcpf((float)q4);  // (1 ulp: far inside the margin below)
     const float* src1 = c.obs + row0 * K0;
     const bool k_al = (K0 & 3) == 0;
     const bool in_u8 = (c.shape >> 8) != 0;  // 8-bit observations are codes already (scale 1, zero-point 0)
@@ -159,10 +159,12 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                 if (k_al) {
                     q4w = *(const uint32_t*)src;
                 } else {
-                    q4w = src[0];
-                    if (ok4[u] + 1 < K0) q4w |= (uint32_t)src[1] << 8;
-                    if (ok4[u] + 2 < K0) q4w |= (uint32_t)src[2] << 16;
-                    if (ok4[u] + 3 < K0) q4w |= (uint32_t)src[3] << 24;
+                    // (all four requested at once: bytes past the row's end re-read its last one and are masked
+                    // out after the xor below)
+                    const int last = K0 - 1 - ok4[u];  // >= 0
+                    const uint32_t b0 = src[0], b1 = src[last < 1 ? last : 1], b2 = src[last < 2 ? last : 2],
+                                   b3 = src[last < 3 ? last : 3];
+                    q4w = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
                 }
                 ov[u].x = __uint_as_float(q4w);
             } else {
@@ -318,7 +320,7 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
         // ... and up to the end of the last 64-wide k-step
         const int kz4 = ((K0 + 63) & ~63) >> 2, extra = kz4 - q4;  // words per row
         if (extra > 0) {
-            const float inv_e = 1.0f / (float)extra;
+            const float inv_e = __builtin_amdgcn_rcpf((float)extra);
             for (int i = tid; i < ROWS * extra; i += RT) {
                 const int m = (int)(((float)i + 0.5f) * inv_e), kq = q4 + i - m * extra;
                 *(uint32_t*)(buf + m * RLD + 4 * kq) = 0u;
