@@ -29,12 +29,14 @@ bool rows16_mlp_supported(const FwdArgs& a) {
     return true;
 }
 
-// Row tiles per workgroup: one while every workgroup gets a CU of its own (the time is then a workgroup's
-// latency chain); beyond that, two workgroups share a CU, and more rows per workgroup mean fewer weight bytes
-// through the CU's vector memory path per row.
+// Row tiles per workgroup, from a sweep of cfg2's network over batch sizes (us per launch at 1 / 2 / 4 tiles:
+// batch 4096: 6.8 / 9.3 / 13.5; 8192: 9.4 / 9.6 / 13.5; 16384: 16.4 / 13.0 / 13.7; 24576: 23.1 / 19.2 / 20.1;
+// 32768: 29.8 / 23.7 / 20.2; 65536: 57.0 / 43.9 / 37.2): one tile while at most two workgroups share a CU, two
+// tiles up to three workgroups per CU, four beyond (more rows per workgroup mean fewer weight bytes through the
+// CU's vector memory path per row, and two resident workgroups overlap each other's barriers).
 int rows16_mlp_row_tiles(int64_t batch) {
-    if (batch <= 16 * 256) return 1;
-    if (batch <= 32 * 512) return 2;
+    if (batch <= 16 * 512) return 1;
+    if (batch <= 32 * 768) return 2;
     return 4;
 }
 

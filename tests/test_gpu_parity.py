@@ -324,19 +324,20 @@ def test_forward_full_size(aq, name, batch, sample):
 # must be the same bits).
 _ODD_WIDE = [synth.fc(100, 1000, "relu"), synth.fc(1000, 1024, "relu"), synth.fc(1024, 40, "none")]
 FUSED_VARIANTS = {
-    # the kernel for small networks: one, two and four 16-row tiles per workgroup (batch up to 4096, up to 16384,
+    # the kernel for small networks: one, two and four 16-row tiles per workgroup (batch up to 8192, up to 24576,
     # beyond), each with ragged shapes, LayerNorm on a ragged width, argmax over two feature tiles, one layer,
     # 8-bit observations (rows of 48 and of 37 bytes), for both weight schemes
-    (16, 1, False, 2): [("cfg2", 4096), ("cfg2", 4081), ("odd_small", 3000), ("argmax_small", 333), ("single_narrow", 100),
+    (16, 1, False, 2): [("cfg2", 4096), ("cfg2", 8185), ("odd_small", 3000), ("argmax_small", 333), ("single_narrow", 100),
                         ("u8_mlp", 300)],
-    (32, 1, False, 2): [("cfg2", 8192), ("odd_small", 8185), ("argmax_small", 5000), ("single_narrow", 4100)],
-    (64, 1, False, 2): [("cfg2", 16400), ("cfg2", 32763), ("odd_small", 20011), ("argmax_small", 17000),
-                        ("single_narrow", 16390), ("odd_sym_ln", 16385), ("u8_mlp", 16500)],
+    (32, 1, False, 2): [("cfg2", 16384), ("odd_small", 8200), ("argmax_small", 12001), ("single_narrow", 8193),
+                        ("u8_mlp", 10000)],
+    (64, 1, False, 2): [("cfg2", 24580), ("cfg2", 32763), ("odd_small", 30011), ("argmax_small", 25000),
+                        ("single_narrow", 24590), ("odd_sym_ln", 24577), ("u8_mlp", 26500)],
     (16, 1, True, 2): [("cfg1", 256), ("odd_asym", 100), ("two_tile_last_asym", 333), ("literal256", 77),
-                       ("u8_odd_asym", 500), ("asym_ln", 1000)],
-    (32, 1, True, 2): [("cfg1", 8192), ("cfg1", 16379), ("odd_asym", 8185), ("asym_ln", 5000)],
-    (64, 1, True, 2): [("cfg1", 16400), ("odd_asym", 20011), ("two_tile_last_asym", 17000), ("u8_odd_asym", 16390),
-                       ("asym_ln", 16500)],
+                       ("u8_odd_asym", 500), ("asym_ln", 1000), ("cfg1", 8192)],
+    (32, 1, True, 2): [("cfg1", 16379), ("odd_asym", 8200), ("asym_ln", 9000), ("two_tile_last_asym", 8500)],
+    (64, 1, True, 2): [("cfg1", 24600), ("odd_asym", 30011), ("two_tile_last_asym", 27000), ("u8_odd_asym", 24590),
+                       ("asym_ln", 26500)],
     # the general kernel
     (16, 1, False, 0): [("mid_wide", 4096)],
     (16, 1, True, 0): [("mid_wide_asym", 4096)],
