@@ -949,6 +949,55 @@ def test_random_mlp_shapes(aq, seed):
     P.close()
 
 
+def _random_small_net(rng):
+    """A random network of the small-network kernel's shape class without LayerNorm (integers only)."""
+    fc = synth.fc
+    n_layers = int(rng.integers(1, 5))
+    widths = [int(rng.choice([1, 3, 4, 17, 63, 64, 65, 67, 128, 130, 255, 256]))]
+    for i in range(n_layers):
+        last = i == n_layers - 1
+        widths.append(int(rng.choice([1, 2, 6, 16, 17, 21, 32, 33, 64] if last else
+                                     [1, 5, 16, 31, 32, 33, 64, 96, 100, 160, 224, 255, 256])))
+    layers = [fc(widths[i], widths[i + 1], "none" if i == n_layers - 1 else str(rng.choice(["relu", "none"])))
+              for i in range(n_layers)]
+    return synth.small_net(layers, head=str(rng.choice(["tanh", "linear", "argmax"])),
+                           wscheme=str(rng.choice(["channel_sym_s8", "tensor_asym_u8"])),
+                           in_type=str(rng.choice(["f32", "f32", "u8"])))
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_small_network_kernel_equals_the_other_plans(aq, seed):
+    """Integer-only random networks of the small-network kernel's shape class, at batch sizes that take one, two
+    and four row tiles per workgroup: the actions equal, bit for bit, those of the general whole-network kernel
+    (selected by an unaligned observation buffer) and of the one-launch-per-layer plan; sampled rows also go
+    against the oracle stage by stage."""
+    rng = np.random.default_rng(9100 + seed)
+    net = _random_small_net(rng)
+    batch = int(rng.choice([1, 15, 16, 17, 100, 4097, 8191, 8200, 20000, 24577, 30001]))
+    desc = "-".join(str(l["in"]) for l in net["layers"]) + f"-{net['layers'][-1]['out']}"
+    _say(f"small_network_kernel_equals seed={seed} {desc} acts={[l['act'] for l in net['layers']]} head={net['head']} "
+         f"{net['wscheme']} {net['in_type']} batch={batch}")
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, obs[:256])
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    tiles = 1 if batch <= 8192 else (2 if batch <= 24576 else 4)
+    assert P.policy_fused_plan(batch) == (16 * tiles, 1, 2)
+    rows = None if batch <= 128 else np.unique(np.concatenate([[0, 15, 16, 63, 64, batch - 17, batch - 1],
+                                                                rng.integers(0, batch, 60)]))
+    actions, t = U.gpu_forward(P, net, obs)
+    U.compare_forward(net, pol, obs, actions, t, rows)
+    del t
+    plain, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(plain, actions, equal_nan=True)
+    general, _ = U.gpu_forward(P, net, obs, taps=False, misalign=1 if net["in_type"] == "f32" else 3)
+    assert np.array_equal(general, plain, equal_nan=True)
+    P.policy_set_path(2)
+    per_layer, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(per_layer, plain, equal_nan=True)
+    P.close()
+
+
 # ------------------------------------------------------------------ HIP graph capture
 @pytest.mark.parametrize("name", ["cfg2", "cfg1", "conv_small", "conv_stack_b"])
 def test_graph_replays_match_eager(aq, name):
