@@ -1,17 +1,16 @@
 // Whole-network int8 MLP for small policies (Sec. 3.1 actor inference on the 8-bit policy of Sec. 3.2): one
 // workgroup of 8 wavefronts owns 16 * MT batch rows (MT = 1, 2 or 4 row tiles) from the observation to the action.
 //
-// At these sizes (a few hundred features per layer, at most one 16-row block per CU) a launch holds a
-// fraction of a microsecond of matrix-core work; its time is the chain of round trips inside one workgroup.
-// This kernel is laid out to keep that chain short:
+// At these sizes (a few hundred features per layer) a launch at small batch holds a fraction of a microsecond
+// of matrix-core work; its time is the chain of round trips and vector-ALU phases inside one workgroup.  This
+// kernel is laid out to keep that chain short:
 //   - v_mfma_i32_16x16x64_i8: a tile is 16 features x 16 batch rows, so a 16-row block fills it (no
 //     don't-care rows, no fold afterwards) and K = 256 is four dependent MFMAs instead of eight; a wavefront
 //     owns 32 features = two independent accumulator chains;
-//   - the kernel arguments fit one 64-byte line (they live in host-visible memory: every line of them costs
-//     a round trip over the host link on first touch, about 1800 clocks measured); everything else about the
-//     network - every layer's pointers and sizes, the activation scales and zero-points, the short-form
-//     flags - comes from the device-resident description by one burst of scalar loads at the start: no
-//     layer waits for a descriptor;
+//   - the kernel arguments fit one 64-byte line and hold what the observation addresses need; everything else
+//     about the network - every layer's pointers and sizes, the activation scales and zero-points, the
+//     short-form flags - comes from the device-resident description by one burst of scalar loads right after
+//     the observation requests: no layer waits for a descriptor;
 //   - weights and per-channel constants go from global memory straight to registers, one layer ahead: all
 //     of a layer's operands (at most 8 KiB per wavefront) are requested at the start of the previous layer,
 //     the constants of its epilogue too.  A lane's four features of a tile are shared by the 16 lanes of its
@@ -21,8 +20,8 @@
 //     LDS, no barrier to publish them;
 //   - LayerNorm statistics cross the wavefronts once: every wavefront reduces its 32 features to (sum, sum of
 //     squared deviations from its own mean), and the eight pairs combine exactly (the pairwise update of
-//     Chan, Golub, LeVeque 1979), so the layer has two barriers less than a mean pass followed by a
-//     deviation pass;
+//     Chan, Golub, LeVeque 1979), so the layer has one barrier where a mean pass followed by a deviation
+//     pass has two;
 //   - one barrier per layer; the narrow last layer is split over all wavefronts (feature tile x K).
 //
 // Weights are read from the library's 32 x 32 operand tiles unchanged: the 16-byte piece of lane
@@ -49,7 +48,7 @@ namespace r16 {
 
 constexpr int RW = 8;          // wavefronts per workgroup
 constexpr int RT = RW * 64;    // threads per workgroup
-constexpr int RLD = 272;       // LDS row stride, bytes: 256 codes + 16 (rows land on different banks)
+constexpr int RLD = 272;       // LDS row stride, bytes: 256 codes + 16 (16-byte operand reads of 8 rows hit 32 different banks)
 constexpr int RMAXL = 4;       // layers
 constexpr int RMAXK = 256;     // widest layer input / hidden layer
 constexpr int RSTEPS = 4;      // k-steps of 64 per layer at most
@@ -72,8 +71,7 @@ struct R16Layer {
     const int32_t* rshift;  // [32 NT] shifts of the general requantization form
     int N, NT, KS, act;
 };
-// the kernel arguments besides the description's address: 56 bytes, one line together with it (they live in
-// host-visible memory; every line of them is a round trip on first touch)
+// the kernel arguments besides the description's address: 56 bytes, one 64-byte line together with it
 struct R16Args {
     const float* obs;
     void* actions;
