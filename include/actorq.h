@@ -144,7 +144,7 @@ aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers
 /* Which compiled variant of the whole-network kernels a forward of `batch` >= 1 rows launches under the
  * current launch plan: *rows = batch rows per workgroup (16, 32, 64 or 128), *tiles = 32-feature tiles per
  * wavefront and pass (1 or 2); both 0 when the forward runs one launch per layer instead (a network the
- * kernels do not take, or launch plan 2 / 3).  *pipelined is the kernel kind: 0 = the general kernel; 1 = the
+ * kernels do not take, or launch plan 2 / 3).  *kind is the kernel: 0 = the general kernel; 1 = the
  * software-pipelined kernel for wide layers (64 rows, two tiles; per-channel weights, fp32 observations, hidden
  * widths multiples of 64 without LayerNorm, every K a multiple of 128, at most 64 outputs); 2 = the kernel for
  * small networks (16, 32 or 64 rows by batch size; either weight scheme, fp32 or 8-bit observations, at most four
@@ -152,7 +152,7 @@ aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers
  * 16-byte aligned observation buffer; an unaligned one takes the general kernel with the rows and tiles its own
  * plan gives (not reported here).  With the weight scheme and whether intermediate outputs are requested this
  * names the variant, so that a test can show that every one it times is also checked.  No GPU work. */
-aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles, int32_t* pipelined);
+aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles, int32_t* kind);
 
 /* Synchronizes `stream` and returns the sticky device-side error of the last
  * aq_quantize_params or aq_policy_import_blob (AQ_OK, AQ_ENONFINITE, AQ_ERANGE, or AQ_EINVAL for a

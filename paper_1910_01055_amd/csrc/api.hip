@@ -478,8 +478,8 @@ extern "C" aq_status aq_policy_conv_stack_layers(const aq_policy* p, int32_t* n_
 }
 
 extern "C" aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles,
-                                          int32_t* pipelined) {
-    if (!p || !rows || !tiles || !pipelined || batch < 1) return AQ_EINVAL;
+                                          int32_t* kind) {
+    if (!p || !rows || !tiles || !kind || batch < 1) return AQ_EINVAL;
     FwdArgs a{};
     a.net = p->h_net;
     a.c.batch = batch;
@@ -488,7 +488,7 @@ extern "C" aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int
     if (p->path == 2 || !fused_mlp_supported(a, &r, &lds, &t)) r = t = 0;
     *rows = r;
     *tiles = t;
-    *pipelined = r != 0 ? fused_mlp_kernel_kind(a) : 0;
+    *kind = r != 0 ? fused_mlp_kernel_kind(a) : 0;
     return AQ_OK;
 }
 

@@ -318,7 +318,7 @@ def test_forward_full_size(aq, name, batch, sample):
 
 
 # Every compiled variant of the whole-network kernels, named by (batch rows per workgroup, feature tiles per
-# wavefront, per-tensor weight scheme, kernel kind: 0 general, 1 pipelined for wide layers, 2 the 16-row kernel
+# wavefront, per-tensor weight scheme, kernel kind: 0 general, 1 pipelined for wide layers, 2 the kernel
 # for small networks): the network and batch that make the launch plan pick it.  Each is run with intermediate
 # outputs (checked stage by stage against the oracle) and without (the variant a benchmark times; its actions
 # must be the same bits).
@@ -392,7 +392,7 @@ def test_fused_variant_table_covers_every_compiled_variant():
     for mt, nb, asym, taps, half in decl:
         key = (16 if half == "true" else 32 * int(mt), int(nb), asym == "true")
         seen.setdefault(key, set()).add(taps)
-    # the general kernel's instantiations, plus the pipelined and the 16-row kernel (each compiled with and
+    # the general kernel's instantiations, plus the pipelined and the small-network kernel (each compiled with and
     # without intermediate outputs in its own file)
     assert set(seen) == {k[:3] for k in FUSED_VARIANTS if k[3] == 0}, (sorted(seen), sorted(FUSED_VARIANTS))
     assert all(v == {"true", "false"} for v in seen.values())
