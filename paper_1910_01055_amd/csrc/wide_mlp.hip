@@ -87,6 +87,9 @@ __global__ __launch_bounds__(FT) void k_mlp_wide(const NetDev* __restrict__ netp
         const int64_t left = c.batch - row0;
         const int vrows = left < WROWS ? (int)left : WROWS;
         const int n4 = (vrows * K0) >> 2, k4 = K0 >> 2;
+        // idx / k4 by a reciprocal: (idx + 0.5) / k4 stays at least 0.5 / k4 away from every integer, far more
+        // than the rounding error at these magnitudes (idx < 2^16)
+        const float inv_k4 = __builtin_amdgcn_rcpf((float)k4);
         const float4* src = (const float4*)((const float*)c.obs + row0 * K0);
         for (int i0 = tid; i0 < n4; i0 += 4 * FT) {
             float4 v[4];
@@ -101,7 +104,7 @@ __global__ __launch_bounds__(FT) void k_mlp_wide(const NetDev* __restrict__ netp
                     if (TAPS) {
                         if (t.a0) *(uint32_t*)(t.a0 + row0 * K0 + 4 * idx) = pack;
                     }
-                    const int m = idx / k4, kq = idx - m * k4;
+                    const int m = (int)(((float)idx + 0.5f) * inv_k4), kq = idx - m * k4;
                     *(uint32_t*)(buf_in + m * ld + 4 * kq) = pack ^ 0x80808080u;
                 }
             }
