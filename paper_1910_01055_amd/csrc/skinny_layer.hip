@@ -68,12 +68,20 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
         v4i wreg[SK_PF][1];
         mma_prefetch<1, SK_PF>(wptr, k0, k1, wreg);
 
-        // this wave's K slice of the 32 rows -> LDS (signed domain; zero beyond the batch and beyond K)
+        // this wave's K slice of the tile's rows -> LDS (signed domain; zero beyond K).  Rows past the batch are
+        // not staged at all: a batch row is a column of the MFMA's second operand, so whatever LDS holds there
+        // only reaches accumulators of rows that are never stored (at batch 1 that is 31 of the 32 rows)
         const int kb0 = k0 * 32, kb1 = k1 * 32;  // byte range of K
+        const int64_t left = rows - row0;
+        const int vrows = left < 32 ? (int)left : 32;
         if (in_mode == 1) {
             // 8-bit activations, rows of K bytes with K a multiple of 16, 16-byte aligned: whole pieces
             const int ppr = (kb1 - kb0) >> 4;  // pieces per row
-            const int total = 32 * ppr;
+            const int total = vrows * ppr;
+            // idx / ppr by a reciprocal: (idx + 0.5) / ppr stays at least 0.5 / ppr away from every integer, far
+            // more than the rounding error at these magnitudes (an integer division costs about thirty vector
+            // instructions, and this staging loop sits in front of the layer's MFMAs)
+            const float inv_ppr = __builtin_amdgcn_rcpf((float)ppr);
             constexpr int SU = 8;
             for (int base = lane; base < total; base += 64 * SU) {
                 v4i v[SU];
@@ -82,16 +90,16 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
                     const int idx = base + u * 64;
                     v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0;
                     if (idx < total) {
-                        const int m = idx / ppr, c = idx - m * ppr;
+                        const int m = (int)(((float)idx + 0.5f) * inv_ppr), c = idx - m * ppr;
                         const int k = kb0 + c * 16;
-                        if (row0 + m < rows && k < K) v[u] = *(const v4i*)((const int8_t*)io.in + (row0 + m) * K + k);
+                        if (k < K) v[u] = *(const v4i*)((const int8_t*)io.in + (row0 + m) * K + k);
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < SU; ++u) {
                     const int idx = base + u * 64;
                     if (idx < total) {
-                        const int m = idx / ppr, c = idx - m * ppr;
+                        const int m = (int)(((float)idx + 0.5f) * inv_ppr), c = idx - m * ppr;
                         *(v4i*)(xs + m * LDX + c * 16) = v[u];
                     }
                 }
@@ -105,12 +113,13 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
             }
             const QuantScale qs0 = make_quant_scale(s0);
             const int kb = kb1 - kb0;
-            for (int idx = lane; idx < 32 * kb; idx += 64) {
-                const int m = idx / kb, kk = idx - m * kb;
+            const float inv_kb = __builtin_amdgcn_rcpf((float)kb);
+            for (int idx = lane; idx < vrows * kb; idx += 64) {
+                const int m = (int)(((float)idx + 0.5f) * inv_kb), kk = idx - m * kb;
                 const int k = kb0 + kk;
                 const int64_t row = row0 + m;
                 int sv = 0;
-                if (row < rows && k < K) {
+                if (k < K) {
                     const int64_t off = row * K + k;
                     if (first) {
                         int code;
