@@ -83,10 +83,25 @@ struct R16Args {
 };
 static_assert(sizeof(R16Args) == 56, "the kernel arguments must stay within one 64-byte line");
 
-// lane N of every 16-lane row, broadcast to that row
+// lane N of every 16-lane row, broadcast to that row.  The old value is left undefined (a row broadcast writes
+// every lane): no move that clears the destination first.
 template <int N>
 __device__ __forceinline__ int row_bcast(int v) {
-    return __builtin_amdgcn_update_dpp(0, v, 0x150 + N, 0xF, 0xF, false);
+    return __builtin_amdgcn_mov_dpp(v, 0x150 + N, 0xF, 0xF, true);
+}
+// r[i] = (lane N of the row's c[i]) + v[i] for a quad: the broadcast rides on the addition (v_add_u32_dpp, the
+// form the compiler itself emits for some of these additions, but not for all), so a constant that is only
+// ever added costs no instruction of its own.  The leading two wait states are the ones a DPP read needs after a
+// vector instruction wrote its source; inside an asm block the compiler does not insert them.
+template <int N>
+__device__ __forceinline__ void add_row_bcast4(int (&r)[4], const v4i& c, const int (&v)[4]) {
+    asm("s_nop 1\n\t"
+        "v_add_u32_dpp %0, %4, %8 row_newbcast:%12 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "v_add_u32_dpp %1, %5, %9 row_newbcast:%12 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "v_add_u32_dpp %2, %6, %10 row_newbcast:%12 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "v_add_u32_dpp %3, %7, %11 row_newbcast:%12 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+        : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+        : "v"(c[0]), "v"(c[1]), "v"(c[2]), "v"(c[3]), "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "n"(N));
 }
 // The same as an operand of its own instruction.  Needed for shift amounts: the compiler folds a row broadcast
 // into the shift (v_ashrrev_i32_dpp), and that instruction came back from the hardware with the broadcast
@@ -423,37 +438,50 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                     static_for<0, 2>([&](auto tl_c) __attribute__((always_inline)) {
                         constexpr int tl = decltype(tl_c)::value;
                         const int n0 = nbase + 16 * tl;
-                        // the tile's constants once, then every row tile
-                        int cb[4], cmul[4], cz[4], csh[4];
+                        // multipliers and shift amounts once per tile (every row tile uses them); the integer
+                        // bias and the rounding term ride on their additions
+                        int cmul[4], csh[4];
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            cb[i] = AQ_R16_C(cm, 0, tl, i);
                             cmul[i] = AQ_R16_C(cm, 1, tl, i);
-                            cz[i] = AQ_R16_C(cm, 2, tl, i);
                             csh[i] = AQ_R16_CSH(cm, 3, tl, i);
                         }
 #pragma unroll
                         for (int mt = 0; mt < MT; ++mt) {
                             const int64_t row = row0 + 16 * mt + b;
                             const bool row_ok = row < c.batch;
+                            const int a4[4] = {acc[mt][tl][0], acc[mt][tl][1], acc[mt][tl][2], acc[mt][tl][3]};
+                            int val[4];
+                            add_row_bcast4<tl>(val, cm, a4);
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                if (ASYM) val[i] += rowterm[mt];
+                                if (TAPS) {
+                                    if (T.acc && row_ok && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val[i];
+                                }
+                            }
+                            int code[4];
+                            if (fast) {
+                                const int hi[4] = {__mulhi(val[0], cmul[0]), __mulhi(val[1], cmul[1]),
+                                                   __mulhi(val[2], cmul[2]), __mulhi(val[3], cmul[3])};
+                                int t[4];
+                                add_row_bcast4<4 + tl>(t, cm, hi);
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) code[i] = clamp_code(t[i] >> csh[i], lo_v, 255);
+                            } else {
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) code[i] = requant_code(val[i], cmul[i], csh[i], z_out, lo);
+                            }
                             uint32_t pack = 0;
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                int val = acc[mt][tl][i] + cb[i];
-                                if (ASYM) val += rowterm[mt];
-                                if (TAPS) {
-                                    if (T.acc && row_ok && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val;
-                                }
-                                int code;
-                                if (fast) code = clamp_code((__mulhi(val, cmul[i]) + cz[i]) >> csh[i], lo_v, 255);
-                                else code = requant_code(val, cmul[i], csh[i], z_out, lo);
                                 // per-tensor weights: padding features are zero in the signed domain (the next
                                 // layer sums whole padded rows); with symmetric weights they only meet zero weights
-                                if (ASYM && n0 + i >= L.N) code = 128;
+                                if (ASYM && n0 + i >= L.N) code[i] = 128;
                                 if (TAPS) {
-                                    if (T.act && row_ok && n0 + i < L.N) T.act[row * L.N + n0 + i] = (uint8_t)code;
+                                    if (T.act && row_ok && n0 + i < L.N) T.act[row * L.N + n0 + i] = (uint8_t)code[i];
                                 }
-                                pack |= (uint32_t)code << (8 * i);
+                                pack |= (uint32_t)code[i] << (8 * i);
                             }
                             *(uint32_t*)(out + (16 * mt + b) * RLD + n0) = pack ^ 0x80808080u;
                         }
@@ -473,21 +501,24 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
             static_for<0, 2>([&](auto tl_c) __attribute__((always_inline)) {
                 constexpr int tl = decltype(tl_c)::value;
                 const int n0 = nbase + 16 * tl;
+                // (padding features: their scale is stored as zero, so x = 0; idle wavefronts hold zero
+                // accumulators and re-read the last tile's constants: their pair is not used)
+                float cmul[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int cb = AQ_R16_C(cm, 0, tl, i);
-                    // (padding features: their scale is stored as zero, so x = 0; idle wavefronts hold zero
-                    // accumulators and re-read the last tile's constants: their pair is not used)
-                    const float cmul = __int_as_float(AQ_R16_C(cm, 1, tl, i));
+                for (int i = 0; i < 4; ++i) cmul[i] = __int_as_float(AQ_R16_C(cm, 1, tl, i));
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        int val = acc[mt][tl][i] + cb;
-                        if (ASYM) val += rowterm[mt];
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int a4[4] = {acc[mt][tl][0], acc[mt][tl][1], acc[mt][tl][2], acc[mt][tl][3]};
+                    int val[4];
+                    add_row_bcast4<tl>(val, cm, a4);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (ASYM) val[i] += rowterm[mt];
                         if (TAPS) {
                             const int64_t row = row0 + 16 * mt + b;
-                            if (T.acc && active && row < c.batch && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val;
+                            if (T.acc && active && row < c.batch && n0 + i < L.N) T.acc[row * L.N + n0 + i] = val[i];
                         }
-                        x[mt][tl][i] = (float)val * cmul;
+                        x[mt][tl][i] = (float)val[i] * cmul[i];
                     }
                 }
             });
