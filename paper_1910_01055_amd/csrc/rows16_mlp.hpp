@@ -556,38 +556,30 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
             const QuantScale qs_out = make_quant_scale(s_out);
             const float c0 = qs_out.inv + (float)z_out, c1 = 2.0f * qs_out.inv;
             const float inv_N = __builtin_amdgcn_rcpf((float)L.N);
-            const int n_full = L.N >> 5, n_tail = L.N & 31;  // wavefronts with 32 features, features of the next one
-            const float inv_tail = __builtin_amdgcn_rcpf((float)(n_tail > 0 ? n_tail : 1));
+            // The eight (sum, squared deviations) pairs of a row are combined by the four lanes that hold the row:
+            // lane group g4 takes the pairs of wavefronts 2 g4 and 2 g4 + 1 (one 16-byte read), the groups meet by
+            // two lane exchanges.  A wavefront past the layer's width counts no features, the last one with
+            // features may count fewer than 32.
+            static_assert(RW == 8, "two pairs for each of the four lane groups of a row");
+            float cnt[2], inv_cnt[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int left = L.N - 32 * (2 * g4 + j);
+                const int n_j = left < 0 ? 0 : (left > 32 ? 32 : left);
+                cnt[j] = (float)n_j;
+                inv_cnt[j] = __builtin_amdgcn_rcpf((float)(n_j > 0 ? n_j : 1));
+            }
             lds_barrier();
             float inv[MT], shift[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
-                float sw[RW], qw[RW];
-#pragma unroll
-                for (int i = 0; i < RW / 2; ++i) {
-                    const float4 v = *(const float4*)(s_red + (16 * mt + b) * RW * 2 + 4 * i);
-                    sw[2 * i] = v.x;
-                    qw[2 * i] = v.y;
-                    sw[2 * i + 1] = v.z;
-                    qw[2 * i + 1] = v.w;
-                }
-                float tot = 0.0f;
-#pragma unroll
-                for (int i = 0; i < RW; ++i)
-                    if (i < n_full || (i == n_full && n_tail > 0)) tot += sw[i];
-                const float mean = tot * inv_N;
+                const float4 v = *(const float4*)(s_red + (16 * mt + b) * RW * 2 + 4 * g4);
+                const float sw[2] = {cnt[0] > 0.0f ? v.x : 0.0f, cnt[1] > 0.0f ? v.z : 0.0f};
+                const float qw[2] = {cnt[0] > 0.0f ? v.y : 0.0f, cnt[1] > 0.0f ? v.w : 0.0f};
+                const float mean = sum_rows4(sw[0] + sw[1]) * inv_N;
                 // pairwise combination: sum of squared deviations from the common mean
-                float m2 = 0.0f;
-#pragma unroll
-                for (int i = 0; i < RW; ++i) {
-                    if (i < n_full) {
-                        const float d = sw[i] * 0.03125f - mean;
-                        m2 += fmaf(32.0f * d, d, qw[i]);
-                    } else if (i == n_full && n_tail > 0) {
-                        const float d = sw[i] * inv_tail - mean;
-                        m2 += fmaf((float)n_tail * d, d, qw[i]);
-                    }
-                }
+                const float d0 = sw[0] * inv_cnt[0] - mean, d1 = sw[1] * inv_cnt[1] - mean;
+                const float m2 = sum_rows4(fmaf(cnt[0] * d0, d0, qw[0]) + fmaf(cnt[1] * d1, d1, qw[1]));
                 // (2 log2 e rides on the row's scale and shift and on the offset: exp2 then yields e^{2y})
                 inv[mt] = __builtin_amdgcn_rsqf(fmaf(m2, inv_N, a.ln_eps)) * K2_LOG2E;
                 shift[mt] = -mean * inv[mt];
