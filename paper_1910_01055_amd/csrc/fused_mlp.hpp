@@ -586,8 +586,8 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
                                     pack = 0;
 #pragma unroll
                                     for (int i = 0; i < 4; ++i) {
-                                        // saturating float -> byte conversion: clamp to [0, 255] and pack
-                                        pack = __builtin_amdgcn_cvt_pk_u8_f32(rintf(fmaf(rv[i], -c1, c0)), i, pack);
+                                        // float -> byte conversion: rounds half to even, saturates at 0 and 255, packs
+                                        pack = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(rv[i], -c1, c0), i, pack);
                                     }
                                 } else {
                                     pack = quant_code4(float4{fmaf(rv[0], -2.0f, 1.0f), fmaf(rv[1], -2.0f, 1.0f),

@@ -608,11 +608,12 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                         uint32_t pack;
                         if (qs_out.rcp_ok) {
                             // the tanh value already carries rounding differences of its own, so the code is taken
-                            // from t * (1/s) + z directly (it can differ from round(t/s) only at a rounding tie)
+                            // from t * (1/s) + z directly (it can differ from round(t/s) only at a rounding tie);
+                            // the float -> byte conversion rounds half to even itself and saturates at 0 and 255
                             pack = 0;
 #pragma unroll
                             for (int i = 0; i < 4; ++i)
-                                pack = __builtin_amdgcn_cvt_pk_u8_f32(rintf(fmaf(rv[i], -c1, c0)), i, pack);
+                                pack = __builtin_amdgcn_cvt_pk_u8_f32(fmaf(rv[i], -c1, c0), i, pack);
                         } else {
                             pack = quant_code4(float4{fmaf(rv[0], -2.0f, 1.0f), fmaf(rv[1], -2.0f, 1.0f),
                                                       fmaf(rv[2], -2.0f, 1.0f), fmaf(rv[3], -2.0f, 1.0f)},
