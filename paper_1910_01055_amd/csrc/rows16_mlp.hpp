@@ -354,7 +354,8 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
         LayerTaps T{nullptr, nullptr, nullptr};
         if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
 
-        // The next layer's operands and constants.  One row tile: requested first - their eight loads per
+        // The next layer's operands and constants.  One row tile: requested in front of the MFMAs, right behind
+        // the reads of this layer's activations - their eight loads per
         // wavefront queue at the CU's single vector memory path (64 KiB per 256 x 256 layer at 64 B / clock), and a
         // wavefront stuck there cannot start its epilogue; here it would be waiting for LDS anyway.  More row
         // tiles: requested after the MFMAs, into the registers they free (two workgroups share the CU's
@@ -367,7 +368,6 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                 load_wl(LL, wl);
             }
         };
-        if constexpr (WDBL) request_next();
         const v4i(&wcur)[RSTEPS][2] = w[WDBL ? l & 1 : 0];
         v4i acc[MT][2], rsa[MT];  // (rsa: every register of it ends up holding sum_k a_s of this lane's batch row)
 #pragma unroll
@@ -378,6 +378,10 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                 v4i bx[RSTEPS];
 #pragma unroll
                 for (int s = 0; s < RSTEPS; ++s) bx[s] = *(const v4i*)(xrow + 64 * s);
+                // (the activation reads go first: their LDS round trip runs while the requests below queue)
+                __builtin_amdgcn_sched_barrier(0);
+                request_next();
+                __builtin_amdgcn_sched_barrier(0);
                 if (active) {
 #pragma unroll
                     for (int s = 0; s < RSTEPS; ++s) {
