@@ -148,7 +148,8 @@ def forward_workload(torch, aq, synth, name, batch, iters, warm=20, report_error
     n_w = sum(int(p["w"].size) for p in params)
     hbm = float(obs.nbytes + act.numel() * act.element_size() + n_w)
     rows, tiles, kind = P.policy_fused_plan(batch)
-    kind_name = {0: "", 1: ", pipelined (k_mlp_wide)", 2: ", small-network kernel (k_mlp_rows16)"}[kind]
+    kind_name = {0: "", 1: ", pipelined (k_mlp_wide)", 2: ", small-network kernel (k_mlp_rows16)",
+                 3: ", small-network kernel (k_mlp_rows16, a workgroup alone on its CU)"}[kind]
     out = {"workload": f"{name} batch {batch}", "us_per_launch": ms * 1e3, "inferences_per_s": batch / (ms * 1e-3),
            "tops": ops / (ms * 1e-3) / 1e12, "frac_int8_mfma_peak": ops / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS,
            "GBps_algorithmic": hbm / (ms * 1e-3) / 1e9, "frac_hbm_peak": hbm / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -148,7 +148,9 @@ aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers
  * software-pipelined kernel for wide layers (64 rows, two tiles; per-channel weights, fp32 observations, hidden
  * widths multiples of 64 without LayerNorm, every K a multiple of 128, at most 64 outputs); 2 = the kernel for
  * small networks (16, 32 or 64 rows by batch size; either weight scheme, fp32 or 8-bit observations, at most four
- * fully connected layers, first-layer inputs and hidden widths up to 256, at most 64 outputs).  Kinds 1 and 2 need a
+ * fully connected layers, first-layer inputs and hidden widths up to 256, at most 64 outputs); 3 = the same kernel
+ * in the form it takes while every workgroup has a CU to itself (batch <= 4096, 16 rows: a layer's operands are
+ * requested behind the epilogue two layers earlier).  Kinds 1 to 3 need a
  * 16-byte aligned observation buffer; an unaligned one takes the general kernel with the rows and tiles its own
  * plan gives (not reported here).  With the weight scheme and whether intermediate outputs are requested this
  * names the variant, so that a test can show that every one it times is also checked.  No GPU work. */

@@ -110,7 +110,7 @@ bool fused_mlp_supported(const FwdArgs& a, int* rows_out, size_t* lds_out, int* 
     *rows_out = p.half ? 16 : 32 * p.mt;
     *lds_out = p.lds;
     if (tiles_out) *tiles_out = p.nb;
-    if (fused_mlp_kernel_kind(a) == 2) {  // (given a 16-byte aligned observation buffer)
+    if (fused_mlp_kernel_kind(a) >= 2) {  // (given a 16-byte aligned observation buffer)
         *rows_out = 16 * rows16_mlp_row_tiles(a.c.batch);
         if (tiles_out) *tiles_out = 1;
     }
@@ -121,7 +121,7 @@ int fused_mlp_kernel_kind(const FwdArgs& a) {
     Plan p;
     int ld;
     if (!make_plan(a, &p)) return 0;
-    if (rows16_mlp_supported(a)) return 2;
+    if (rows16_mlp_supported(a)) return rows16_mlp_alone_on_cu(a.c.batch) ? 3 : 2;
     if (p.half) return 0;
     if (p.nb == 2 && p.mt == 2 && wide_mlp_supported(a, &ld)) return 1;
     return 0;
@@ -134,7 +134,7 @@ aq_status launch_fused_mlp(const FwdArgs& a_in, hipStream_t st) {
     // 16-row workgroups on small networks: the kernel built for that case
     const int kind = ((uintptr_t)a_in.c.obs & 15) == 0 ? fused_mlp_kernel_kind(a_in) : 0;
     if (kind == 1) return launch_wide_mlp(a_in, st);
-    if (kind == 2) return launch_rows16_mlp(a_in, st);
+    if (kind >= 2) return launch_rows16_mlp(a_in, st);
     FwdArgs a = a_in;
     a.c.ld = p.ld;
     a.c.cst_n = p.cst_n;

@@ -49,6 +49,7 @@ aq_status launch_wide_mlp(const FwdArgs& a, hipStream_t st);
 // launch_fused_mlp hands it the shapes it takes
 bool rows16_mlp_supported(const FwdArgs& a);
 int rows16_mlp_row_tiles(int64_t batch);  // 16-row tiles per workgroup at this batch: 1, 2 or 4
+bool rows16_mlp_alone_on_cu(int64_t batch);  // at most one 16-row workgroup per CU at this batch
 aq_status launch_rows16_mlp(const FwdArgs& a, hipStream_t st);
 // which kernel launch_fused_mlp runs for this network and batch (observations 16-byte aligned): 0 = the general
 // fused kernel, 1 = the pipelined kernel for wide layers, 2 = the 16-row kernel for small networks

@@ -10,6 +10,8 @@ AQ_ROWS16_DECL(4, false);
 AQ_ROWS16_DECL(1, true);
 AQ_ROWS16_DECL(2, true);
 AQ_ROWS16_DECL(4, true);
+AQ_ROWS16_LATE_DECL(false);
+AQ_ROWS16_LATE_DECL(true);
 }  // namespace r16
 
 // Shapes the kernel takes (see the head of rows16_mlp.hpp).
@@ -34,6 +36,10 @@ bool rows16_mlp_supported(const FwdArgs& a) {
 // 32768: 29.8 / 23.7 / 20.2; 65536: 57.0 / 43.9 / 37.2): one tile while at most two workgroups share a CU, two
 // tiles up to three workgroups per CU, four beyond (more rows per workgroup mean fewer weight bytes through the
 // CU's vector memory path per row, and two resident workgroups overlap each other's barriers).
+// Every workgroup has a CU to itself (256 CUs, 16 rows per workgroup): the variant that requests a layer's
+// operands behind the epilogue two layers earlier.
+bool rows16_mlp_alone_on_cu(int64_t batch) { return batch <= 16 * 256; }
+
 int rows16_mlp_row_tiles(int64_t batch) {
     if (batch <= 16 * 512) return 1;
     if (batch <= 32 * 768) return 2;
@@ -59,6 +65,11 @@ aq_status launch_rows16_mlp(const FwdArgs& a, hipStream_t st) {
                             : r16::launch_rows16_t<MT, true, false>(a.d_net, ra, a.t, st))                \
                       : (tp ? r16::launch_rows16_t<MT, false, true>(a.d_net, ra, a.t, st)                 \
                             : r16::launch_rows16_t<MT, false, false>(a.d_net, ra, a.t, st))
+    if (rows16_mlp_alone_on_cu(a.c.batch))
+        return a.net.asym ? (tp ? r16::launch_rows16_t<1, true, true, true>(a.d_net, ra, a.t, st)
+                                : r16::launch_rows16_t<1, true, false, true>(a.d_net, ra, a.t, st))
+                          : (tp ? r16::launch_rows16_t<1, false, true, true>(a.d_net, ra, a.t, st)
+                                : r16::launch_rows16_t<1, false, false, true>(a.d_net, ra, a.t, st));
     switch (rows16_mlp_row_tiles(a.c.batch)) {
         case 1: AQ_GO(1);
         case 2: AQ_GO(2);

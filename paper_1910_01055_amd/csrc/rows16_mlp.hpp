@@ -128,7 +128,9 @@ __device__ __forceinline__ float sum_rows4(float s) {
 // a compile-time fact, so that every global load sits in straight-line code and the compiler can count exactly
 // which ones an instruction has to wait for (with the layer count a run-time value, epilogues waited for the
 // loads of the next layer requested just before them).
-template <int MT, int NH, bool ASYM, bool TAPS>
+// LATE (one row tile, every workgroup with a CU to itself): when a layer's operands are requested, see
+// request_layer below.
+template <int MT, int NH, bool ASYM, bool TAPS, bool LATE = false>
 __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev* __restrict__ netp, const R16Args c,
                                                                      const TapArgs t) {
     constexpr int ROWS = 16 * MT;
@@ -293,6 +295,7 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
         }
     };
 
+    static_assert(!LATE || MT == 1, "two operand sets: one row tile only");
     constexpr bool WDBL = MT == 1;  // two operand sets: the next layer's are requested before this layer's MFMAs
     v4i w[WDBL ? 2 : 1][RSTEPS][2];  // operands of the layer being multiplied (and of the next one)
     v4i cst[2];           // this lane's piece of the constants of the layer whose epilogue runs, and of the next one
@@ -354,20 +357,27 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
         LayerTaps T{nullptr, nullptr, nullptr};
         if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
 
-        // The next layer's operands and constants.  One row tile: requested in front of the MFMAs, right behind
-        // the reads of this layer's activations - their eight loads per
-        // wavefront queue at the CU's single vector memory path (64 KiB per 256 x 256 layer at 64 B / clock), and a
-        // wavefront stuck there cannot start its epilogue; here it would be waiting for LDS anyway.  More row
-        // tiles: requested after the MFMAs, into the registers they free (two workgroups share the CU's
-        // register file, and the other workgroup's work hides the queueing).
-        auto request_next = [&]() __attribute__((always_inline)) {
-            if constexpr (l + 1 < nh) {
-                load_w(a.L[l + 1], w[WDBL ? (l + 1) & 1 : 0], false);
-                cst[(l + 1) & 1] = load_c(a.L[l + 1], is_ln(l + 1) || fastf[l + 1]);
-            } else {
+        // The operands and constants of a later layer j (j = nh: the last layer; beyond: nothing).  Their eight
+        // loads per wavefront queue at the CU's single vector memory path (64 KiB per 256 x 256 layer at 64 B / clock):
+        // eight wavefronts that request together leave the last one waiting a thousand clocks for its turn, and a
+        // wavefront stuck there cannot start its epilogue.  One row tile (two operand sets): layer l + 1 is
+        // requested in front of layer l's MFMAs, right behind the reads of its activations (the LDS round trip runs
+        // while the requests queue).  LATE, a workgroup alone on its CU: only layer 1 is requested there; layer
+        // l + 2 is requested at the end of layer l, behind its epilogue - the wavefronts get there one after the
+        // other, the early ones would only wait at the barrier, and the set that layer l multiplied is free
+        // (cfg2 at batch 4096 6.02 -> 5.91 us; with two workgroups on a CU it is the slower order: batch 8192
+        // 7.88 -> 8.09 us).  More row tiles: layer l + 1 after layer l's MFMAs, into the registers they free (two
+        // workgroups share the CU's register file, and the other workgroup's work hides the queueing).
+        auto request_layer = [&](auto j_c) __attribute__((always_inline)) {
+            constexpr int j = decltype(j_c)::value;
+            if constexpr (j < nh) {
+                load_w(a.L[j], w[WDBL ? j & 1 : 0], false);
+                cst[j & 1] = load_c(a.L[j], is_ln(j) || fastf[j]);
+            } else if constexpr (j == nh) {
                 load_wl(LL, wl);
             }
         };
+        auto request_next = [&]() __attribute__((always_inline)) { request_layer(std::integral_constant<int, l + 1>{}); };
         const v4i(&wcur)[RSTEPS][2] = w[WDBL ? l & 1 : 0];
         v4i acc[MT][2], rsa[MT];  // (rsa: every register of it ends up holding sum_k a_s of this lane's batch row)
 #pragma unroll
@@ -380,7 +390,7 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                 for (int s = 0; s < RSTEPS; ++s) bx[s] = *(const v4i*)(xrow + 64 * s);
                 // (the activation reads go first: their LDS round trip runs while the requests below queue)
                 __builtin_amdgcn_sched_barrier(0);
-                request_next();
+                if constexpr (!LATE || l == 0) request_next();
                 __builtin_amdgcn_sched_barrier(0);
                 if (active) {
 #pragma unroll
@@ -643,6 +653,10 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                 });
             }
         }
+        if constexpr (LATE) {
+            __builtin_amdgcn_sched_barrier(0);
+            request_layer(std::integral_constant<int, l + 2>{});
+        }
         lds_barrier();
     });
 
@@ -752,14 +766,14 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
     }
 }
 
-template <int MT, bool ASYM, bool TAPS>
+template <int MT, bool ASYM, bool TAPS, bool LATE = false>
 aq_status launch_rows16_t(const NetDev* d_net, const R16Args& ra, const TapArgs& t, hipStream_t st) {
     const unsigned grid = (unsigned)((ra.batch + 16 * MT - 1) / (16 * MT));
     switch (ra.shape & 255) {
-        case 1: hipLaunchKernelGGL((k_mlp_rows16<MT, 0, ASYM, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
-        case 2: hipLaunchKernelGGL((k_mlp_rows16<MT, 1, ASYM, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
-        case 3: hipLaunchKernelGGL((k_mlp_rows16<MT, 2, ASYM, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
-        case 4: hipLaunchKernelGGL((k_mlp_rows16<MT, 3, ASYM, TAPS>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
+        case 1: hipLaunchKernelGGL((k_mlp_rows16<MT, 0, ASYM, TAPS, LATE>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
+        case 2: hipLaunchKernelGGL((k_mlp_rows16<MT, 1, ASYM, TAPS, LATE>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
+        case 3: hipLaunchKernelGGL((k_mlp_rows16<MT, 2, ASYM, TAPS, LATE>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
+        case 4: hipLaunchKernelGGL((k_mlp_rows16<MT, 3, ASYM, TAPS, LATE>), dim3(grid), dim3(RT), 0, st, d_net, ra, t); break;
         default: return AQ_ESHAPE;
     }
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
@@ -771,6 +785,13 @@ aq_status launch_rows16_t(const NetDev* d_net, const R16Args& ra, const TapArgs&
 #define AQ_ROWS16_INST(MT, AS) \
     template aq_status launch_rows16_t<MT, AS, false>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t); \
     template aq_status launch_rows16_t<MT, AS, true>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t)
+// ... and the one-row-tile variants for a workgroup that has its CU to itself
+#define AQ_ROWS16_LATE_DECL(AS) \
+    extern template aq_status launch_rows16_t<1, AS, false, true>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t); \
+    extern template aq_status launch_rows16_t<1, AS, true, true>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t)
+#define AQ_ROWS16_LATE_INST(AS) \
+    template aq_status launch_rows16_t<1, AS, false, true>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t); \
+    template aq_status launch_rows16_t<1, AS, true, true>(const NetDev*, const R16Args&, const TapArgs&, hipStream_t)
 
 }  // namespace r16
 }  // namespace aq
