@@ -23,22 +23,34 @@ constexpr int SK_PART_WORDS = 17 * SK_PART_LD;
 __host__ __device__ inline size_t skinny_lds_bytes(int kchunk) {
     return (size_t)SK_W * 32 * (kchunk * 32 + 16) + (size_t)SK_W * SK_PART_WORDS * 4;
 }
+
+// What the host knows of the layer at launch time, by value: with the pointers among the kernel arguments the
+// weight requests go out after one scalar round trip instead of two (arguments, then the layer's entry of the
+// device-resident description); only what the quantizer kernels write (activation scales and zero-points, the
+// short-form flag, the weight zero-point) is still read from the description, off the critical path.
+struct SkinnyLayer {
+    const int8_t* wp;
+    const int32_t *bias_fold, *M0, *rz, *sh, *rshift, *z_w;
+    const float* m;
+    int K, KS, N, act;
+    int first, last, head, in_u8;
+};
 }  // namespace
 
 template <bool ASYM, bool TAPS>
-__global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __restrict__ netp, const TapArgs t, const int l,
+__global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __restrict__ netp, const SkinnyLayer L,
+                                                           const TapArgs t, const int l,
                                                            const LayerIO io, const int64_t rows, const int kchunk,
                                                            const int in_mode, const void* __restrict__ actions,
                                                            void* __restrict__ argmax_out) {
     extern __shared__ __align__(16) int8_t smem[];
     const NetDev& a = *netp;
-    const LayerDev& L = a.L[l];
     LayerTaps T{nullptr, nullptr, nullptr};
     if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nt = blockIdx.x;
     const int64_t row0 = (int64_t)blockIdx.y * 32;
-    const bool first = l == 0, last = l == a.n_layers - 1;
+    const bool first = L.first != 0, last = L.last != 0;
     const bool ln = !last && L.act == AQ_ACT_LN_TANH;
     const int K = L.K, KS = L.KS, N = L.N;
     const int k0 = wave * kchunk, k1 = k0 + kchunk < KS ? k0 + kchunk : KS;
@@ -55,7 +67,7 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
     const int lo = (!last && L.act == AQ_ACT_RELU) ? z_out : 0;
     const int zw_s = ASYM ? L.z_w[0] - 128 : 0;
     const bool fast = !last && !ln && a.fast[l] != 0;
-    const int head = a.head;
+    const int head = L.head;
     const bool argmax_here = argmax_out != nullptr;  // last layer, argmax head, a single feature tile
 
     v16i pacc[1][1], prs[1];
@@ -123,7 +135,7 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
                     const int64_t off = row * K + k;
                     if (first) {
                         int code;
-                        if (a.in_u8) code = ((const uint8_t*)io.in)[off];
+                        if (L.in_u8) code = ((const uint8_t*)io.in)[off];
                         else code = quant_code(((const float*)io.in)[off], qs0, -z0, 255 - z0) + z0;
                         if (TAPS) {
                             if (t.a0 && nt == 0) t.a0[off] = (uint8_t)code;
@@ -237,6 +249,8 @@ aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStr
     const void* actions = (last && a.net.head != AQ_HEAD_ARGMAX) ? a.c.actions : nullptr;
     void* argmax_out = skinny_layer_does_argmax(a, l) ? a.c.actions : nullptr;
     dim3 grid((unsigned)L.NT, (unsigned)((rows + 31) / 32));
+    const SkinnyLayer sl{L.wp, L.bias_fold, L.M0, L.rz, L.sh, L.rshift, L.z_w, L.m, L.K, L.KS, L.N, L.act,
+                         first, last, a.net.head, a.net.in_u8};
     const bool taps = any_taps(a);
     const bool asym = a.net.asym != 0;
 #define AQ_SKINNY(AS, TP)                                                                                           \
@@ -248,7 +262,7 @@ aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStr
                 return AQ_EHIP;                                                                                     \
             attr_set = true;                                                                                        \
         }                                                                                                           \
-        hipLaunchKernelGGL((k_layer_skinny<AS, TP>), grid, dim3(SK_W * 64), lds, st, a.d_net, a.t, l, io, rows, kchunk, \
+        hipLaunchKernelGGL((k_layer_skinny<AS, TP>), grid, dim3(SK_W * 64), lds, st, a.d_net, sl, a.t, l, io, rows, kchunk, \
                            in_mode, actions, argmax_out);                                                                       \
     } while (0)
     if (asym) {
