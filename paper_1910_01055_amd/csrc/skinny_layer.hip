@@ -74,47 +74,57 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
     pacc[0][0] = zero16();
     prs[0] = zero16();
     if (k0 < k1) {
-        // the wave's whole weight share goes out first
-        gv4i_ptr wptr[1];
-        wptr[0] = (gv4i_ptr)L.wp + (int64_t)nt * KS * 64 + lane;
-        v4i wreg[SK_PF][1];
-        mma_prefetch<1, SK_PF>(wptr, k0, k1, wreg);
-
         // this wave's K slice of the tile's rows -> LDS (signed domain; zero beyond K).  Rows past the batch are
         // not staged at all: a batch row is a column of the MFMA's second operand, so whatever LDS holds there
         // only reaches accumulators of rows that are never stored (at batch 1 that is 31 of the 32 rows)
         const int kb0 = k0 * 32, kb1 = k1 * 32;  // byte range of K
         const int64_t left = rows - row0;
         const int vrows = left < 32 ? (int)left : 32;
+        // 8-bit activations, rows of K bytes with K a multiple of 16, 16-byte aligned: whole pieces.  The first
+        // eight pieces per lane (all of them for slices up to 256 bytes) are requested ahead of the weights: they
+        // are few, the MFMAs cannot start before they have been through LDS, and behind the eight wavefronts'
+        // weight requests they would wait for 128 KiB to pass the CU's vector memory path.
+        const int ppr = (kb1 - kb0) >> 4;  // pieces per row
+        const int total = in_mode == 1 ? vrows * ppr : 0;
+        // idx / ppr by a reciprocal: (idx + 0.5) / ppr stays at least 0.5 / ppr away from every integer, far
+        // more than the rounding error at these magnitudes (an integer division costs about thirty vector
+        // instructions, and this staging loop sits in front of the layer's MFMAs)
+        const float inv_ppr = __builtin_amdgcn_rcpf((float)ppr);
+        constexpr int SU = 8;
+        auto piece_load = [&](int idx) __attribute__((always_inline)) {
+            v4i v = {0, 0, 0, 0};
+            if (idx < total) {
+                const int m = (int)(((float)idx + 0.5f) * inv_ppr), c = idx - m * ppr;
+                const int k = kb0 + c * 16;
+                if (k < K) v = *(const v4i*)((const int8_t*)io.in + (row0 + m) * K + k);
+            }
+            return v;
+        };
+        auto piece_store = [&](int idx, const v4i& v) __attribute__((always_inline)) {
+            if (idx < total) {
+                const int m = (int)(((float)idx + 0.5f) * inv_ppr), c = idx - m * ppr;
+                *(v4i*)(xs + m * LDX + c * 16) = v;
+            }
+        };
+        v4i v0[SU];
+#pragma unroll
+        for (int u = 0; u < SU; ++u) v0[u] = piece_load(lane + u * 64);
+
+        // the wave's whole weight share
+        gv4i_ptr wptr[1];
+        wptr[0] = (gv4i_ptr)L.wp + (int64_t)nt * KS * 64 + lane;
+        v4i wreg[SK_PF][1];
+        mma_prefetch<1, SK_PF>(wptr, k0, k1, wreg);
+
         if (in_mode == 1) {
-            // 8-bit activations, rows of K bytes with K a multiple of 16, 16-byte aligned: whole pieces
-            const int ppr = (kb1 - kb0) >> 4;  // pieces per row
-            const int total = vrows * ppr;
-            // idx / ppr by a reciprocal: (idx + 0.5) / ppr stays at least 0.5 / ppr away from every integer, far
-            // more than the rounding error at these magnitudes (an integer division costs about thirty vector
-            // instructions, and this staging loop sits in front of the layer's MFMAs)
-            const float inv_ppr = __builtin_amdgcn_rcpf((float)ppr);
-            constexpr int SU = 8;
-            for (int base = lane; base < total; base += 64 * SU) {
+#pragma unroll
+            for (int u = 0; u < SU; ++u) piece_store(lane + u * 64, v0[u]);
+            for (int base = lane + 64 * SU; base < total; base += 64 * SU) {
                 v4i v[SU];
 #pragma unroll
-                for (int u = 0; u < SU; ++u) {
-                    const int idx = base + u * 64;
-                    v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0;
-                    if (idx < total) {
-                        const int m = (int)(((float)idx + 0.5f) * inv_ppr), c = idx - m * ppr;
-                        const int k = kb0 + c * 16;
-                        if (k < K) v[u] = *(const v4i*)((const int8_t*)io.in + (row0 + m) * K + k);
-                    }
-                }
+                for (int u = 0; u < SU; ++u) v[u] = piece_load(base + u * 64);
 #pragma unroll
-                for (int u = 0; u < SU; ++u) {
-                    const int idx = base + u * 64;
-                    if (idx < total) {
-                        const int m = (int)(((float)idx + 0.5f) * inv_ppr), c = idx - m * ppr;
-                        *(v4i*)(xs + m * LDX + c * 16) = v[u];
-                    }
-                }
+                for (int u = 0; u < SU; ++u) piece_store(base + u * 64, v[u]);
             }
         } else {
             float s0 = 1.0f;
