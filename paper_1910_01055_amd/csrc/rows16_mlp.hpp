@@ -161,12 +161,18 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
     int om[NQ], ok4[NQ];
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
+        // (a slot past the last quad is skipped as a whole, by a scalar branch: with a narrow observation most
+        // of the NQ slots are empty, and their index arithmetic alone was a tenth of the kernel's vector
+        // instructions at four row tiles)
+        om[u] = ROWS;
+        ok4[u] = 0;
+        ov[u] = float4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (u * RT >= nquads) continue;
         const int q = tid + u * RT;
         // q / q4: (q + 0.5) / q4 stays at least 0.5 / q4 away from every integer
         om[u] = (int)(((float)q + 0.5f) * inv_q4);
         ok4[u] = 4 * (q - om[u] * q4);
-        ov[u] = float4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (u * RT < nquads && om[u] < vrows) {
+        if (om[u] < vrows) {
             if (in_u8) {
                 // four codes: one word where the rows are 4-byte aligned, single bytes otherwise (kept in .x)
                 const uint8_t* src = (const uint8_t*)c.obs + (row0 + om[u]) * K0 + ok4[u];
@@ -316,7 +322,8 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
         const float zf0 = (float)z_q[0];
 #pragma unroll
         for (int u = 0; u < NQ; ++u) {
-            if (u * RT < nquads && om[u] < ROWS) {
+            if (u * RT >= nquads) continue;  // (scalar branch: an empty slot costs nothing)
+            if (om[u] < ROWS) {
                 uint32_t pack = in_u8 ? __float_as_uint(ov[u].x) : quant_u8x4(ov[u], qs0, zf0);
                 const int left_k = K0 - ok4[u];  // real values in this quad: 1..4 (or more)
                 if (TAPS) {
