@@ -27,6 +27,26 @@ constexpr int CS_FU = 4;         // 16-byte pieces of the frame per thread
 constexpr int CS_CU = 4;         // words of epilogue constants per thread
 constexpr int CS_CONSTS = 5;     // arrays per layer: bias_fold | M0 | rz | sh (one contiguous pack), rshift
 constexpr size_t CS_MAX_LDS = 160 * 1024;
+constexpr int CS_MAXC = 4;       // convolution layers of a stack at most
+
+// What the host knows of the stack at launch time, by value: the burst's requests and every layer's tile loop
+// then need nothing but the kernel arguments (one scalar round trip at the start; read from the device-resident
+// description the burst's addresses took four thousand clocks of dependent scalar loads to work out, and every
+// layer began with a round trip for its own entry).  Only what the quantizer kernels write (activation zero-points,
+// short-form flags) still comes from the description, requested at the start.
+struct StackLayer {
+    const int8_t* wp;
+    int oh, ow, in_w, in_c, kw, stride, N, NT, KS, act;
+};
+struct StackArgs {
+    int f_pieces;            // 16-byte pieces of a frame
+    int c_words;             // constant words of all layers
+    int cnt[CS_MAXC];        // ... of each layer, and where they come from: four arrays in one pack, then rshift
+    int np4[CS_MAXC];
+    const int32_t* pack[CS_MAXC];
+    const int32_t* rsh[CS_MAXC];
+    StackLayer L[CS_MAXC];
+};
 
 struct StackPlan {
     int nc;          // leading convolution layers taken
@@ -45,7 +65,7 @@ bool plan_stack(const FwdArgs& a, StackPlan* p) {
         if (fc) break;
         ++nc;
     }
-    if (nc < 2 || nc >= net.n_layers) return false;  // a fully connected layer must follow
+    if (nc < 2 || nc > CS_MAXC || nc >= net.n_layers) return false;  // a fully connected layer must follow
     size_t sz[2] = {0, 0}, c_words = 0;
     for (int l = 0; l < nc; ++l) {
         const LayerDev& L = net.L[l];
@@ -69,8 +89,8 @@ bool plan_stack(const FwdArgs& a, StackPlan* p) {
 }
 }  // namespace
 
-template <bool TAPS, int W>
-__global__ __launch_bounds__(W * 64) void k_conv_stack(const NetDev* __restrict__ netp, const TapArgs t, const int nc,
+template <bool TAPS, int W, int NC>
+__global__ __launch_bounds__(W * 64) void k_conv_stack(const NetDev* __restrict__ netp, const TapArgs t, const StackArgs sa,
                                                      const uint8_t* __restrict__ frames, int8_t* __restrict__ out,
                                                      const int off_b, const int off_c) {
     extern __shared__ __align__(16) int8_t smem[];
@@ -78,11 +98,17 @@ __global__ __launch_bounds__(W * 64) void k_conv_stack(const NetDev* __restrict_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, n = lane & 31;
     const int64_t img = blockIdx.x;
     constexpr int NTHR = W * 64;
+    constexpr int nc = NC;
+    // (written by the quantizer kernels: requested now, used by the epilogues)
+    int z_q[NC], fastf[NC];
+#pragma unroll
+    for (int l = 0; l < NC; ++l) {
+        z_q[l] = a.actq[l + 1].z;
+        fastf[l] = a.fast[l];
+    }
     {   // the burst: frame pieces and the constant words of all layers, then their LDS stores
-        const LayerDev& L0 = a.L[0];
-        const int f_pieces = (L0.in_h * L0.in_w * L0.in_c) >> 4;
-        int c_words = 0;
-        for (int l = 0; l < nc; ++l) c_words += CS_CONSTS * a.L[l].NT * 32;
+        const int f_pieces = sa.f_pieces;
+        const int c_words = sa.c_words;
         const v4i* fsrc = (const v4i*)frames + img * f_pieces;
         v4i fr[CS_FU];
         int cr[CS_CU];
@@ -95,24 +121,21 @@ __global__ __launch_bounds__(W * 64) void k_conv_stack(const NetDev* __restrict_
         for (int u = 0; u < CS_CU; ++u) {
             int i = tid + u * NTHR;
             i = i < c_words ? i : c_words - 1;
-            // which layer word i belongs to: per-lane selects over per-layer scalars (the layer index stays
-            // uniform, so the description is read by scalar loads and nothing waits on a gather)
-            const int32_t* pack = a.L[0].bias_fold;
-            const int32_t* rsh = a.L[0].rshift;
-            int np4 = 4 * a.L[0].NT * 32;
+            // which layer word i belongs to: per-lane selects over per-layer scalars
+            const int32_t* pack = sa.pack[0];
+            const int32_t* rsh = sa.rsh[0];
+            int np4 = sa.np4[0];
             bool found = false;
 #pragma unroll
-            for (int j = 0; j < AQ_MAX_LAYERS - 1; ++j) {
-                if (j + 1 < nc) {
-                    const int cnt = CS_CONSTS * a.L[j].NT * 32;
-                    if (!found && i >= cnt) {
-                        i -= cnt;
-                        pack = a.L[j + 1].bias_fold;
-                        rsh = a.L[j + 1].rshift;
-                        np4 = 4 * a.L[j + 1].NT * 32;
-                    } else {
-                        found = true;
-                    }
+            for (int j = 0; j + 1 < NC; ++j) {
+                const int cnt = sa.cnt[j];
+                if (!found && i >= cnt) {
+                    i -= cnt;
+                    pack = sa.pack[j + 1];
+                    rsh = sa.rsh[j + 1];
+                    np4 = sa.np4[j + 1];
+                } else {
+                    found = true;
                 }
             }
             cr[u] = i < np4 ? pack[i] : rsh[i - np4];
@@ -139,16 +162,17 @@ __global__ __launch_bounds__(W * 64) void k_conv_stack(const NetDev* __restrict_
     }
     __syncthreads();
     int c_at = off_c;  // this layer's constants in LDS
-    for (int l = 0; l < nc; ++l) {
-        const LayerDev& L = a.L[l];
+    static_for<0, NC>([&](auto l_c) __attribute__((always_inline)) {
+        constexpr int l = decltype(l_c)::value;
+        const StackLayer& L = sa.L[l];
         const int8_t* in = smem + ((l & 1) ? off_b : 0);
         int8_t* map_out = smem + ((l & 1) ? 0 : off_b);
         const int R = L.oh * L.ow, RT = (R + 31) >> 5, NT = L.NT, KS = L.KS, N = L.N;
         const int run = L.kw * L.in_c, row_bytes = L.in_w * L.in_c;
-        const bool to_global = l == nc - 1;
-        const int z_out = a.actq[l + 1].z;
+        constexpr bool to_global = l == nc - 1;
+        const int z_out = z_q[l];
         const int lo = L.act == AQ_ACT_RELU ? z_out : 0;
-        const bool fast = a.fast[l] != 0;
+        const bool fast = fastf[l] != 0;
         LayerTaps T{nullptr, nullptr, nullptr};
         if (TAPS) T = LayerTaps{t.acc[l], t.act[l], nullptr};
         const int np = NT * 32;
@@ -209,7 +233,7 @@ __global__ __launch_bounds__(W * 64) void k_conv_stack(const NetDev* __restrict_
         }
         c_at += CS_CONSTS * np * 4;
         __syncthreads();
-    }
+    });
 }
 
 int conv_stack_layers(const FwdArgs& a) {
@@ -222,27 +246,48 @@ aq_status launch_conv_stack(const FwdArgs& a, int8_t* out, hipStream_t st) {
     if (!plan_stack(a, &p)) return AQ_ESHAPE;
     const bool taps = any_taps(a);
     dim3 grid((unsigned)a.c.batch);
-#define AQ_STACK(TP, WV)                                                                                             \
+    StackArgs sa{};
+    {
+        const LayerDev& L0 = a.net.L[0];
+        sa.f_pieces = (L0.in_h * L0.in_w * L0.in_c) >> 4;
+        for (int l = 0; l < p.nc; ++l) {
+            const LayerDev& L = a.net.L[l];
+            sa.cnt[l] = CS_CONSTS * L.NT * 32;
+            sa.np4[l] = 4 * L.NT * 32;
+            sa.pack[l] = L.bias_fold;
+            sa.rsh[l] = L.rshift;
+            sa.c_words += sa.cnt[l];
+            sa.L[l] = StackLayer{L.wp, L.oh, L.ow, L.in_w, L.in_c, L.kw, L.stride, L.N, L.NT, L.KS, L.act};
+        }
+    }
+#define AQ_STACK(TP, WV, NCV)                                                                                        \
     do {                                                                                                             \
-        static std::atomic<bool> attr_set{false};                                                                           \
+        static std::atomic<bool> attr_set{false};                                                                    \
         if (!attr_set) {                                                                                             \
-            if (hipFuncSetAttribute((const void*)k_conv_stack<TP, WV>, hipFuncAttributeMaxDynamicSharedMemorySize,   \
+            if (hipFuncSetAttribute((const void*)k_conv_stack<TP, WV, NCV>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                     (int)CS_MAX_LDS) != hipSuccess)                                                  \
                 return AQ_EHIP;                                                                                      \
             attr_set = true;                                                                                         \
         }                                                                                                            \
-        hipLaunchKernelGGL((k_conv_stack<TP, WV>), grid, dim3(WV * 64), p.lds, st, a.d_net, a.t, p.nc,               \
+        hipLaunchKernelGGL((k_conv_stack<TP, WV, NCV>), grid, dim3(WV * 64), p.lds, st, a.d_net, a.t, sa,            \
                            (const uint8_t*)a.c.obs, out, p.off_b, p.off_c);                                          \
     } while (0)
+#define AQ_STACK_NC(TP, WV)                 \
+    switch (p.nc) {                         \
+        case 2: AQ_STACK(TP, WV, 2); break; \
+        case 3: AQ_STACK(TP, WV, 3); break; \
+        default: AQ_STACK(TP, WV, 4); break; \
+    }
     // up to one image per CU: sixteen waves (the first layer's tiles then run in one round); beyond that
     // eight, so that two workgroups share a CU
     if (a.c.batch <= 256) {
-        if (taps) AQ_STACK(true, 16);
-        else AQ_STACK(false, 16);
+        if (taps) AQ_STACK_NC(true, 16)
+        else AQ_STACK_NC(false, 16)
     } else {
-        if (taps) AQ_STACK(true, 8);
-        else AQ_STACK(false, 8);
+        if (taps) AQ_STACK_NC(true, 8)
+        else AQ_STACK_NC(false, 8)
     }
+#undef AQ_STACK_NC
 #undef AQ_STACK
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
