@@ -37,7 +37,8 @@ struct SkinnyLayer {
 };
 }  // namespace
 
-template <bool ASYM, bool TAPS>
+// TR: batch rows per workgroup, 32 or 16 (where 32 would leave CUs without a workgroup).
+template <bool ASYM, bool TAPS, int TR>
 __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __restrict__ netp, const SkinnyLayer L,
                                                            const TapArgs t, const int l,
                                                            const LayerIO io, const int64_t rows, const int kchunk,
@@ -49,7 +50,8 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
     if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nt = blockIdx.x;
-    const int64_t row0 = (int64_t)blockIdx.y * 32;
+    constexpr int tile_rows = TR;
+    const int64_t row0 = (int64_t)blockIdx.y * tile_rows;
     const bool first = L.first != 0, last = L.last != 0;
     const bool ln = !last && L.act == AQ_ACT_LN_TANH;
     const int K = L.K, KS = L.KS, N = L.N;
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
         // only reaches accumulators of rows that are never stored (at batch 1 that is 31 of the 32 rows)
         const int kb0 = k0 * 32, kb1 = k1 * 32;  // byte range of K
         const int64_t left = rows - row0;
-        const int vrows = left < 32 ? (int)left : 32;
+        const int vrows = left < tile_rows ? (int)left : tile_rows;
         // 8-bit activations, rows of K bytes with K a multiple of 16, 16-byte aligned: whole pieces.  The first
         // eight pieces per lane (all of them for slices up to 256 bytes) are requested ahead of the weights: they
         // are few, the MFMAs cannot start before they have been through LDS, and behind the eight wavefronts'
@@ -176,6 +178,7 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
         const int m = (tid >> 5) + 16 * it, nl = tid & 31;
+        if (m >= tile_rows) break;  // (a 16-row tile: the upper half of the MFMA tile belongs to nobody)
         const int reg = 4 * (nl >> 3) + (nl & 3), lsrc = m + 32 * ((nl >> 2) & 1);
         int v = 0, rsum = 0;
 #pragma unroll
@@ -245,7 +248,7 @@ bool skinny_layer_supported(const LayerDev& L, int64_t rows) {
     if (!fc) return false;
     const int kchunk = (L.KS + SK_W - 1) / SK_W;
     if (kchunk > SK_MAX_KCHUNK) return false;
-    return (rows + 31) / 32 <= 65535;
+    return (rows + 15) / 16 <= 65535;
 }
 
 aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStream_t st) {
@@ -258,22 +261,30 @@ aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStr
     const int in_mode = (!first && (L.K & 15) == 0 && ((uintptr_t)io.in & 15) == 0) ? 1 : 0;
     const void* actions = (last && a.net.head != AQ_HEAD_ARGMAX) ? a.c.actions : nullptr;
     void* argmax_out = skinny_layer_does_argmax(a, l) ? a.c.actions : nullptr;
-    dim3 grid((unsigned)L.NT, (unsigned)((rows + 31) / 32));
+    // 16-row tiles where 32-row tiles would give fewer workgroups than CUs (half of each MFMA tile is then idle,
+    // but a workgroup stages half the activation bytes and twice as many CUs stream weights)
+    const int tile_rows = (rows > 16 && (int64_t)L.NT * ((rows + 31) / 32) < 256) ? 16 : 32;
+    dim3 grid((unsigned)L.NT, (unsigned)((rows + tile_rows - 1) / tile_rows));
     const SkinnyLayer sl{L.wp, L.bias_fold, L.M0, L.rz, L.sh, L.rshift, L.z_w, L.m, L.K, L.KS, L.N, L.act,
                          first, last, a.net.head, a.net.in_u8};
     const bool taps = any_taps(a);
     const bool asym = a.net.asym != 0;
-#define AQ_SKINNY(AS, TP)                                                                                           \
+#define AQ_SKINNY_T(AS, TP, TRV)                                                                                    \
     do {                                                                                                            \
-        static std::atomic<bool> attr_set{false};                                                                          \
+        static std::atomic<bool> attr_set{false};                                                                   \
         if (!attr_set) {                                                                                            \
-            if (hipFuncSetAttribute((const void*)k_layer_skinny<AS, TP>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+            if (hipFuncSetAttribute((const void*)k_layer_skinny<AS, TP, TRV>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                     160 * 1024) != hipSuccess)                                                      \
                 return AQ_EHIP;                                                                                     \
             attr_set = true;                                                                                        \
         }                                                                                                           \
-        hipLaunchKernelGGL((k_layer_skinny<AS, TP>), grid, dim3(SK_W * 64), lds, st, a.d_net, sl, a.t, l, io, rows, kchunk, \
-                           in_mode, actions, argmax_out);                                                                       \
+        hipLaunchKernelGGL((k_layer_skinny<AS, TP, TRV>), grid, dim3(SK_W * 64), lds, st, a.d_net, sl, a.t, l, io, rows, \
+                           kchunk, in_mode, actions, argmax_out);                                                   \
+    } while (0)
+#define AQ_SKINNY(AS, TP)                   \
+    do {                                    \
+        if (tile_rows == 16) AQ_SKINNY_T(AS, TP, 16); \
+        else AQ_SKINNY_T(AS, TP, 32);       \
     } while (0)
     if (asym) {
         if (taps) AQ_SKINNY(true, true);
@@ -282,6 +293,7 @@ aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStr
         if (taps) AQ_SKINNY(false, true);
         else AQ_SKINNY(false, false);
     }
+#undef AQ_SKINNY_T
 #undef AQ_SKINNY
     return hipGetLastError() == hipSuccess ? AQ_OK : AQ_EHIP;
 }
