@@ -211,6 +211,32 @@ def quantize_workload(torch, aq, synth, scheme, iters=30, n_buf=40, repeat=1, re
             "frac_hbm_peak": gbs / HBM_PEAK_GBS}
 
 
+def mfma_loop_workload(torch, aq, operands, stream_weights=True, ksteps=2048):
+    """What the matrix cores sustain in the wide whole-network kernel's k-step loop with nothing around it (no
+    observation load, no epilogue, no barrier): one workgroup per CU, per CU and k-step 32 MFMAs on 16 KiB of
+    streamed weights.  The clock under matrix load depends on the operand bits, so three operand sets: zeros,
+    codes distributed like cfg5's (Gaussian weight codes, post-ReLU activations), uniformly random bytes."""
+    import numpy as np
+    rng = np.random.default_rng(41)
+    if operands == "zeros":
+        w = np.zeros(1 << 20, dtype=np.int8)
+        x = np.zeros(64 * 1024, dtype=np.int8)
+    elif operands == "cfg5-like codes":
+        w = np.clip(np.rint(rng.standard_normal(1 << 20) * 38.0), -127, 127).astype(np.int8)
+        x = (np.clip(np.rint(np.maximum(rng.standard_normal(64 * 1024), 0.0) * 64.0), 0, 255) - 128).astype(np.int8)
+    else:
+        w = rng.integers(-128, 128, 1 << 20, dtype=np.int8)
+        x = rng.integers(-128, 128, 64 * 1024, dtype=np.int8)
+    d_w, d_x = aq.to_dev(w, DEV), aq.to_dev(x, DEV)
+    acc = torch.zeros(32768, dtype=torch.int32, device=DEV)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    ms = _graph_ms(torch, lambda: aq.mfma_loop_reference(d_w, d_x, ksteps, stream_weights, cus, acc), 4)
+    tops = cus * ksteps * 32 * 65536.0 / (ms * 1e-3) / 1e12
+    return {"workload": f"int8 MFMA k-step loop alone, {operands}, weights " +
+                        ("streamed (16 KiB per CU and k-step)" if stream_weights else "kept in registers"),
+            "us_per_call": ms * 1e3, "int8_TOPs": tops, "frac_int8_mfma_peak": tops / INT8_PEAK_TOPS}
+
+
 def blob_workload(torch, aq, synth, name, wbits=8):
     """Learner -> actor hand-off of a quantized policy as one packed blob: export from one handle, import
     into another (device to device, no repacking), next to the cost of quantizing the fp32 parameters.
@@ -437,6 +463,10 @@ def main():
         for rep_, nb_ in ((2, 20), (4, 10), (8, 6), (16, 4)):
             extra.append(quantize_workload(torch, aq, synth, "channel_sym_s8", iters=6, n_buf=nb_, repeat=rep_))
         extra.append(quantize_workload(torch, aq, synth, "channel_sym_s8", iters=6, n_buf=4, repeat=16, reference=True))
+        # the ceiling of cfg5's kernel: its k-step loop with nothing around it, on three operand sets
+        for operands, streamed in (("zeros", True), ("cfg5-like codes", True), ("cfg5-like codes", False),
+                                   ("random bytes", True)):
+            extra.append(mfma_loop_workload(torch, aq, operands, streamed))
         for name in ("cfg2", "cfg5"):
             extra.append(blob_workload(torch, aq, synth, name))
         extra.append(blob_workload(torch, aq, synth, "cfg5", wbits=4))

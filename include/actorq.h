@@ -238,6 +238,25 @@ aq_status aq_quantize_tensor(const float* d_w, int64_t rows, int64_t cols, int32
  * of 4, d_in 16-byte aligned (AQ_ESHAPE otherwise).  Enqueues on `stream`. */
 aq_status aq_stream_reference(const float* d_in, int64_t n, void* d_out, void* stream);
 
+/* Measurement aid for aq_policy_forward_int8 on wide layers at large batch: the inner loop of the whole-network
+ * kernel that serves them and nothing else -- per workgroup (8 wavefronts, one workgroup per CU) 64 activation
+ * rows of K = 1024 held in LDS, per wavefront and k-step four 32x32x32 int8 MFMAs on 2 x 1 KiB of weight operands
+ * read from device memory in operand order (stream_weights != 0) or kept in registers (stream_weights = 0: the first
+ * four k-steps' operands again and again), no
+ * epilogue and no barrier -- so that a benchmark can report the int8 rate the matrix cores sustain in that loop
+ * shape on given operands: the ceiling of the kernel's passes.  (The rate depends on the operand values: the
+ * clock under matrix load drops with the bits that toggle.)
+ * d_weights: 1 MiB of device memory, 16 feature tiles x 64 k-steps x 1 KiB (lane l of a tile's k-step holds 16
+ * bytes: feature l mod 32, k = 16 * (l / 32) .. + 15), walked round and round; wavefront w uses tiles 2w, 2w + 1.
+ * d_acts: 64 x 1024 int8, row-major, walked 32 k-steps round and round.  Both 16-byte aligned (AQ_ESHAPE).
+ * ksteps: k-steps per wavefront, a positive multiple of 4; workgroups: 1 .. 65536 (AQ_EINVAL otherwise).
+ * d_acc: 32768 int32 the call overwrites with workgroup 0's accumulators, index
+ * (((w * 2 + feature tile) * 2 + row tile) * 16 + r) * 64 + lane, where register r of lane l is feature
+ * 8 * (r / 4) + 4 * (l / 32) + r % 4 and row l mod 32 of the 32 x 32 tile.  Work per call: workgroups * ksteps *
+ * 32 MFMAs of 65536 op.  NULL pointers: AQ_EINVAL.  Enqueues on `stream`. */
+aq_status aq_mfma_loop_reference(const void* d_weights, const void* d_acts, int32_t ksteps, int32_t stream_weights,
+                                 int32_t workgroups, int32_t* d_acc, void* stream);
+
 /* The quantizer block (Sec. 3.1 / 3.2): turns the learner's fp32 parameters into the 8-bit
  * policy held by `p`: weight codes in the kernels' packed layout, per-channel scales, the
  * activation (scale, zero-point) of every range, integer biases, requantization multipliers

@@ -28,7 +28,8 @@ EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_pol
            "aq_convert_params_fp16", "aq_policy_forward_fp16",
            "aq_policy_packed_blob_size", "aq_policy_export_packed_blob", "aq_policy_import_packed_blob",
            "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers", "aq_policy_fused_plan", "aq_policy_forward_int8_static",
-           "aq_policy_set_params_fp32", "aq_calibrate_fp32", "aq_policy_forward_fp32_params", "aq_stream_reference"]
+           "aq_policy_set_params_fp32", "aq_calibrate_fp32", "aq_policy_forward_fp32_params", "aq_stream_reference",
+           "aq_mfma_loop_reference"]
 
 
 class AqLayer(C.Structure):
@@ -88,6 +89,7 @@ def load():
     lib.aq_policy_fused_plan.argtypes = [vp, i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.aq_quantize_tensor.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.aq_stream_reference.argtypes = [vp, i64, vp, vp]
+    lib.aq_mfma_loop_reference.argtypes = [vp, vp, i32, i32, i32, vp, vp]
     lib.aq_quantize_params.argtypes = [vp, pp, pp, pp, pp, C.POINTER(AqRange), vp]
     lib.aq_policy_export_layer.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.aq_policy_export_act_qparams.argtypes = [vp, vp, vp, vp]
@@ -328,6 +330,11 @@ def upload_params(params, device="cuda:0"):
 
 def stream_reference(src, n, dst):
     _check(load().aq_stream_reference(_ptr(src), int(n), _ptr(dst), _stream()), "aq_stream_reference")
+
+
+def mfma_loop_reference(weights, acts, ksteps, stream_weights, workgroups, acc):
+    _check(load().aq_mfma_loop_reference(_ptr(weights), _ptr(acts), int(ksteps), int(bool(stream_weights)), int(workgroups),
+                                         _ptr(acc), _stream()), "aq_mfma_loop_reference")
 
 
 def quantize_tensor(w, rows, cols, wscheme, qdenom, codes, scale, zp, workspace):

@@ -707,6 +707,14 @@ extern "C" aq_status aq_stream_reference(const float* d_in, int64_t n, void* d_o
     return launch_stream_reference(d_in, n, d_out, as_stream(stream));
 }
 
+extern "C" aq_status aq_mfma_loop_reference(const void* d_weights, const void* d_acts, int32_t ksteps, int32_t stream_weights,
+                                             int32_t workgroups, int32_t* d_acc, void* stream) {
+    if (!d_weights || !d_acts || !d_acc) return AQ_EINVAL;
+    if (ksteps < 4 || ksteps % 4 != 0 || workgroups < 1 || workgroups > 65536) return AQ_EINVAL;
+    if (((uintptr_t)d_weights & 15) || ((uintptr_t)d_acts & 15) || ((uintptr_t)d_acc & 3)) return AQ_ESHAPE;
+    return launch_mfma_reference(d_weights, d_acts, ksteps, stream_weights != 0, workgroups, d_acc, as_stream(stream));
+}
+
 extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w, const float* const* h_d_b,
                                         const float* const* h_d_gamma, const float* const* h_d_beta,
                                         const aq_range* h_ranges, void* stream) {

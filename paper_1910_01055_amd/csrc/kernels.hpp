@@ -15,6 +15,9 @@ aq_status launch_quantize_policy(const QTab* d_tab, const QTab& h_tab, const QPt
                                  ActQ* actq, int* fast, int* status, uint32_t* mm, hipStream_t st);
 // the quantize pass's traffic without its arithmetic (n a multiple of 4)
 aq_status launch_stream_reference(const float* d_in, int64_t n, void* d_out, hipStream_t st);
+// the pipelined wide kernel's k-step loop alone (mfma_reference.hip); sizes as in aq_mfma_loop_reference
+aq_status launch_mfma_reference(const void* d_weights, const void* d_acts, int ksteps, bool stream_weights, int workgroups,
+                                int32_t* d_acc, hipStream_t st);
 aq_status launch_unpack_weights(const int8_t* wp, int N, int K, int KS, int asym, uint8_t* codes, hipStream_t st);
 
 // ---- policy blob (quantize.hip): header words [0..15] = magic, version, hash lo/hi, payload bytes lo/hi, 0...

@@ -46,6 +46,7 @@ def test_status_strings_and_argument_errors_without_gpu():
     assert lib.aq_policy_export_blob(None, None, 0, None) == b.EINVAL
     assert lib.aq_policy_import_blob(None, None, 0, None) == b.EINVAL
     assert lib.aq_stream_reference(None, 4, None, None) == b.EINVAL
+    assert lib.aq_mfma_loop_reference(None, None, 4, 1, 1, None, None) == b.EINVAL
     assert lib.aq_calibrate_fp32(None, None, 1, None, None) == b.EINVAL
     assert lib.aq_policy_set_params_fp32(None, None, None, None, None, None) == b.EINVAL
     assert lib.aq_policy_forward_fp32(None, None, 1, None, None) == b.EINVAL

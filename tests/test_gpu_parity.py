@@ -1127,3 +1127,53 @@ def test_edges(aq):
         with pytest.raises(aq.AqError) as e:
             aq.Policy(too_big)
         assert e.value.status == aq.ESHAPE
+
+
+# ------------------------------------------------------------------ measurement aids
+def test_stream_reference_moves_the_top_byte_of_every_value(aq):
+    _say("stream_reference")
+    n = 4 * 70001
+    src = np.random.default_rng(31).standard_normal(n).astype(np.float32)
+    d_src = U.to_dev(src)
+    dst = torch.zeros(n, dtype=torch.uint8, device=U.DEV)
+    aq.stream_reference(d_src, n, dst)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy(), (src.view(np.uint32) >> 24).astype(np.uint8))
+
+
+@pytest.mark.parametrize("ksteps,stream", [(4, 1), (64, 1), (200, 1), (72, 0)])
+def test_mfma_loop_reference_accumulators(aq, ksteps, stream):
+    """The timing loop computes what it says: workgroup 0's accumulators equal the integer products of the
+    weight tiles and activation rows it walked (so the rate it is timed at is the rate of real MFMAs on the
+    operands given)."""
+    _say(f"mfma_loop_reference ksteps={ksteps} stream={stream}")
+    rng = np.random.default_rng(32)
+    w = rng.integers(-127, 128, (16, 64, 64, 16), dtype=np.int8)   # [tile][k-step][lane][16 bytes]
+    x = rng.integers(-128, 128, (64, 1024), dtype=np.int8)
+    d_w, d_x = U.to_dev(w), U.to_dev(x)
+    acc = torch.full((32768,), 7, dtype=torch.int32, device=U.DEV)
+    aq.mfma_loop_reference(d_w, d_x, ksteps, stream, 3, acc)
+    torch.cuda.synchronize()
+    got = acc.cpu().numpy().reshape(8, 2, 2, 16, 64)            # [wave][feature tile][row tile][register][lane]
+    # a tile's k-step as a 32 x 32 matrix [feature][k]: lane l holds feature l % 32, k = 16 * (l // 32) .. + 15
+    wt = w.reshape(16, 64, 2, 32, 16).transpose(0, 1, 3, 2, 4).reshape(16, 64, 32, 32).astype(np.int64)
+    xs = x.astype(np.int64)
+    for wave in range(8):
+        for ft in range(2):
+            for rt in range(2):
+                ref = np.zeros((32, 32), dtype=np.int64)        # [feature][row]
+                for k in range(ksteps):
+                    ks = k % 64 if stream else k % 4             # weights kept in registers: the first four k-steps
+                    kk = k % 32
+                    ref += wt[2 * wave + ft, ks] @ xs[32 * rt:32 * rt + 32, 32 * kk:32 * kk + 32].T
+                lane = np.arange(64)
+                for r in range(16):
+                    feat = 8 * (r // 4) + 4 * (lane // 32) + r % 4
+                    assert np.array_equal(got[wave, ft, rt, r], ref[feat, lane % 32].astype(np.int32)), (wave, ft, rt, r)
+    # argument errors
+    with pytest.raises(aq.AqError) as e:
+        aq.mfma_loop_reference(d_w, d_x, 6, 1, 1, acc)
+    assert e.value.status == aq.EINVAL
+    with pytest.raises(aq.AqError) as e:
+        aq.mfma_loop_reference(d_w, d_x, 8, 1, 0, acc)
+    assert e.value.status == aq.EINVAL
