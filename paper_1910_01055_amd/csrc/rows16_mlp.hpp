@@ -721,10 +721,12 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
         float* ybuf = (float*)s_buf[l & 1];  // argmax policies: dequantized rows, stride Np + 1 (the input is free now)
         const int ldy = Np + 1;
         const int head = a.head;
+        float held[OI];  // elementwise heads: this thread's actions, for the exploration pass below
 #pragma unroll
         for (int it = 0; it < OI; ++it) {
             const int o = tid + it * RT;
             const int pair = o >> 8, r = (o >> 6) & 3, ln_ = o & 63;
+            held[it] = 0.0f;
             if (pair < lm.pairs) {
                 int v = 0, rsum = 0;
 #pragma unroll
@@ -749,14 +751,31 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                     if (TAPS) {
                         if (t.y) t.y[orow * L.N + n] = y;
                     }
-                    float act = head == AQ_HEAD_TANH ? tanh_head(y) : y;
-                    if (c.ex_sigma)  // exploration noise of Sec. 4.1, sigma per actor (= per batch row)
-                        act = act + c.ex_sigma[orow] * gaussian_draw((uint32_t)orow, n, c.ex_k0, c.ex_k1, c.ex_s0, c.ex_s1);
-                    ((float*)c.actions)[orow * L.N + n] = act;
+                    const float act = head == AQ_HEAD_TANH ? tanh_head(y) : y;
+                    held[it] = act;
+                    if (!c.ex_sigma) ((float*)c.actions)[orow * L.N + n] = act;
                 }
             }
         }
-        if (head != AQ_HEAD_ARGMAX) return;
+        if (head != AQ_HEAD_ARGMAX) {
+            // Exploration noise of Sec. 4.1, sigma per actor (= per batch row).  Its code (a counter-based generator
+            // and Box-Muller per output) is long; inside the loop above a forward pass without exploration would
+            // jump over it once per output, and each jump lands on instructions that are not in the cache.
+            if (c.ex_sigma) {
+#pragma unroll
+                for (int it = 0; it < OI; ++it) {
+                    const int o = tid + it * RT;
+                    const int pair = o >> 8, r = (o >> 6) & 3, ln_ = o & 63;
+                    const int tile = pair & (lm.t16 - 1), mt = pair >> lm.lg_t16;
+                    const int n = 16 * tile + 4 * (ln_ >> 4) + r, m = 16 * mt + (ln_ & 15);
+                    const int64_t orow = row0 + m;
+                    if (pair < lm.pairs && orow < c.batch && n < L.N)
+                        ((float*)c.actions)[orow * L.N + n] =
+                            held[it] + c.ex_sigma[orow] * gaussian_draw((uint32_t)orow, n, c.ex_k0, c.ex_k1, c.ex_s0, c.ex_s1);
+                }
+            }
+            return;
+        }
         lds_barrier();
         // argmax over the dequantized rows (lowest index wins ties)
         if (tid < ROWS && row0 + tid < c.batch) {
