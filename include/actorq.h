@@ -156,6 +156,16 @@ aq_status aq_policy_fp16_conv_stack_layers(const aq_policy* p, int32_t* n_layers
  * names the variant, so that a test can show that every one it times is also checked.  No GPU work. */
 aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows, int32_t* tiles, int32_t* kind);
 
+/* How many layers of a forward pass at this batch size would read their weights sub-byte: a policy whose weight
+ * precision is n <= 4 bits (aq_net.wbits; the precision sweep of the paper's appendix on quantization-aware
+ * training) with per-channel symmetric weights keeps its fully connected layers' codes a second time as nibbles
+ * (two codes per byte), and the few-row layer kernel -- the one-launch-per-layer plan at batch sizes below 8192,
+ * i.e. the paper's own regime of actors that run one observation at a time -- streams those, half the weight
+ * bytes, and expands them in registers; the integer results are those of the 8-bit containers, bit for bit.
+ * Every other plan (the whole-network kernels, convolutions, large batches) reads the 8-bit containers.
+ * batch >= 1; NULL arguments: AQ_EINVAL. */
+aq_status aq_policy_subbyte_layers(const aq_policy* p, int64_t batch, int32_t* n_layers);
+
 /* Synchronizes `stream` and returns the sticky device-side error of the last
  * aq_quantize_params or aq_policy_import_blob (AQ_OK, AQ_ENONFINITE, AQ_ERANGE, or AQ_EINVAL for a
  * blob whose header does not match). */

@@ -29,7 +29,7 @@ EXPORTS = ["aq_policy_create", "aq_policy_destroy", "aq_policy_reserve", "aq_pol
            "aq_policy_packed_blob_size", "aq_policy_export_packed_blob", "aq_policy_import_packed_blob",
            "aq_policy_conv_stack_layers", "aq_policy_fp16_conv_stack_layers", "aq_policy_fused_plan", "aq_policy_forward_int8_static",
            "aq_policy_set_params_fp32", "aq_calibrate_fp32", "aq_policy_forward_fp32_params", "aq_stream_reference",
-           "aq_mfma_loop_reference"]
+           "aq_mfma_loop_reference", "aq_policy_subbyte_layers"]
 
 
 class AqLayer(C.Structure):
@@ -86,6 +86,7 @@ def load():
     lib.aq_policy_status.argtypes = [vp, vp]
     lib.aq_policy_conv_stack_layers.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.aq_policy_fp16_conv_stack_layers.argtypes = [vp, C.POINTER(C.c_int32)]
+    lib.aq_policy_subbyte_layers.argtypes = [vp, i64, C.POINTER(C.c_int32)]
     lib.aq_policy_fused_plan.argtypes = [vp, i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.aq_quantize_tensor.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.aq_stream_reference.argtypes = [vp, i64, vp, vp]
@@ -193,6 +194,12 @@ class Policy:
         r, t, w = C.c_int32(0), C.c_int32(0), C.c_int32(0)
         _check(load().aq_policy_fused_plan(self._h, int(batch), C.byref(r), C.byref(t), C.byref(w)), "aq_policy_fused_plan")
         return int(r.value), int(t.value), int(w.value)
+
+    def policy_subbyte_layers(self, batch):
+        """Layers of a forward pass at this batch that stream their weights as nibbles (policies of <= 4 bits)."""
+        n = C.c_int32(0)
+        _check(load().aq_policy_subbyte_layers(self._h, int(batch), C.byref(n)), "aq_policy_subbyte_layers")
+        return int(n.value)
 
     def policy_status(self):
         return load().aq_policy_status(self._h, _stream())

@@ -99,6 +99,10 @@ struct aq_policy {
     void* f32_slab = nullptr;
     std::vector<float*> f32_w, f32_b, f32_gamma, f32_beta;
     bool f32_ready = false;
+    // policies of at most 4 bits, per-channel symmetric: the fully connected layers' weights once more as nibbles,
+    // for the few-row kernel (one allocation at create; filled behind every quantize / import)
+    void* w4_slab = nullptr;
+    std::vector<uint8_t*> w4;
     float* calib = nullptr;        // 2 * AQ_MAX_LAYERS floats: (min, max) per activation tensor, for aq_calibrate_fp32
     int64_t max_hidden_elems = 0;  // per sample, over hidden layer outputs
     int64_t max_out_elems = 0;     // per sample, over all layer outputs
@@ -258,6 +262,33 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         delete p;
         return AQ_EHIP;
     }
+    p->w4.assign(p->L.size(), nullptr);
+    if ((net->wbits != 0 && net->wbits <= 4) && net->wscheme == AQ_W_CHANNEL_SYM_S8) {
+        size_t w4_bytes = 0;
+        LayerDev probe{};
+        for (size_t l = 0; l < p->L.size(); ++l) {
+            const LayerBuf& b = p->L[l];
+            probe.kh = probe.kw = probe.in_h = probe.in_w = b.fc ? 1 : 2;
+            probe.KS = b.KS;
+            if (skinny_layer_supported(probe, 1)) w4_bytes += (size_t)b.NT * b.KS * 512;
+        }
+        if (w4_bytes) {
+            if (hipMalloc(&p->w4_slab, w4_bytes) != hipSuccess) {
+                (void)hipFree(p->slab);
+                delete p;
+                return AQ_ENOMEM;
+            }
+            size_t o4 = 0;
+            for (size_t l = 0; l < p->L.size(); ++l) {
+                const LayerBuf& b = p->L[l];
+                probe.kh = probe.kw = probe.in_h = probe.in_w = b.fc ? 1 : 2;
+                probe.KS = b.KS;
+                if (!skinny_layer_supported(probe, 1)) continue;
+                p->w4[l] = (uint8_t*)p->w4_slab + o4;
+                o4 += (size_t)b.NT * b.KS * 512;
+            }
+        }
+    }
     char* base = (char*)p->slab;
     size_t oi = 0;
     for (auto& b : p->L) {
@@ -372,6 +403,7 @@ extern "C" aq_status aq_policy_destroy(aq_policy* p) {
     if (!p) return AQ_EINVAL;
     (void)hipDeviceSynchronize();
     if (p->slab) (void)hipFree(p->slab);
+    if (p->w4_slab) (void)hipFree(p->w4_slab);
     for (int i = 0; i < 2; ++i) {
         if (p->act_i8[i]) (void)hipFree(p->act_i8[i]);
         if (p->act_f32[i]) (void)hipFree(p->act_f32[i]);
@@ -492,6 +524,22 @@ extern "C" aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int
     return AQ_OK;
 }
 
+extern "C" aq_status aq_policy_subbyte_layers(const aq_policy* p, int64_t batch, int32_t* n_layers) {
+    if (!p || !n_layers || batch < 1) return AQ_EINVAL;
+    FwdArgs a{};
+    a.net = p->h_net;
+    a.c.batch = batch;
+    int r = 0;
+    size_t lds = 0;
+    int n = 0;
+    if (p->path == 2 || !fused_mlp_supported(a, &r, &lds)) {
+        const int nc = p->conv_stack ? conv_stack_layers(a) : 0;
+        for (int l = nc; l < (int)p->L.size(); ++l) n += p->w4[l] && !p->h_net.asym && layer_uses_skinny(a, l);
+    }
+    *n_layers = n;
+    return AQ_OK;
+}
+
 extern "C" aq_status aq_policy_status(aq_policy* p, void* stream) {
     if (!p) return AQ_EINVAL;
     int h2[2] = {0, 0};  // [0] the 8-bit policy's status word, [1] the half-precision policy's
@@ -524,6 +572,17 @@ void blob_words(const aq_policy* p, uint32_t (&w)[6]) {
 }
 constexpr size_t kTailBytes = sizeof(ActQ) * (AQ_MAX_LAYERS + 1) + sizeof(int) * AQ_MAX_LAYERS;
 }  // namespace
+
+// the nibble copies of the weights follow every change of the packed 8-bit operands
+static aq_status refresh_w4(aq_policy* p, hipStream_t st) {
+    for (size_t l = 0; l < p->L.size(); ++l) {
+        if (!p->w4[l]) continue;
+        const LayerBuf& b = p->L[l];
+        const aq_status s = launch_pack_nibbles(b.wp, p->w4[l], (int64_t)b.NT * b.KS * 64, st);
+        if (s != AQ_OK) return s;
+    }
+    return AQ_OK;
+}
 
 extern "C" aq_status aq_policy_blob_size(const aq_policy* p, uint64_t* bytes) {
     if (!p || !bytes) return AQ_EINVAL;
@@ -559,6 +618,8 @@ extern "C" aq_status aq_policy_import_blob(aq_policy* p, const void* d_blob, uin
     if (s != AQ_OK) return s;
     AQ_HIP_CHECK(hipMemcpyAsync(p->d_net->actq, src + kBlobHeader, kTailBytes, hipMemcpyDeviceToDevice, st));
     AQ_HIP_CHECK(hipMemcpyAsync(p->slab, src + kBlobHeader + kBlobTail, p->layer_bytes, hipMemcpyDeviceToDevice, st));
+    s = refresh_w4(p, st);
+    if (s != AQ_OK) return s;
     p->quantized = true;
     return AQ_OK;
 }
@@ -659,6 +720,8 @@ extern "C" aq_status aq_policy_import_packed_blob(aq_policy* p, const void* d_bl
         AQ_HIP_CHECK(hipMemcpyAsync((char*)p->slab + L.c_src[l], src + L.c_off[l], L.c_bytes[l],
                                     hipMemcpyDeviceToDevice, st));
     }
+    s = refresh_w4(p, st);
+    if (s != AQ_OK) return s;
     p->quantized = true;
     return AQ_OK;
 }
@@ -741,8 +804,10 @@ extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w,
         ptrs.gamma[l] = h_d_gamma ? h_d_gamma[l] : nullptr;
         ptrs.beta[l] = h_d_beta ? h_d_beta[l] : nullptr;
     }
-    const aq_status s = launch_quantize_policy(p->d_qtab, p->h_qtab, ptrs, r, p->actq, p->d_net->fast, p->status,
-                                               p->mm, st);
+    aq_status s = launch_quantize_policy(p->d_qtab, p->h_qtab, ptrs, r, p->actq, p->d_net->fast, p->status,
+                                         p->mm, st);
+    if (s != AQ_OK) return s;
+    s = refresh_w4(p, st);
     if (s != AQ_OK) return s;
     p->quantized = true;
     return AQ_OK;
@@ -818,6 +883,7 @@ static aq_status forward_int8_impl(aq_policy* p, const void* d_obs, int64_t batc
     a.c.K0 = p->L[0].K;
     a.c.Kp0 = p->L[0].K_pad;
     a.c.in_u8 = p->h_net.in_u8;
+    for (int l = 0; l < nl; ++l) a.w4[l] = p->w4[l];
     if (taps) {
         for (int l = 0; l < nl; ++l) {
             a.t.acc[l] = taps->acc ? taps->acc[l] : nullptr;

@@ -39,6 +39,8 @@ struct FwdArgs {
     const NetDev* d_net;  // the same, in device memory
     CallArgs c;
     TapArgs t;
+    // host side only: per layer, the weights as nibbles for the few-row kernel (policies of at most 4 bits), or NULL
+    const uint8_t* w4[AQ_MAX_LAYERS];
 };
 
 // whole-network fused MLP kernel; returns AQ_ESHAPE when the network does not fit it
@@ -76,6 +78,8 @@ int conv_stack_layers(const FwdArgs& a);
 aq_status launch_conv_stack(const FwdArgs& a, int8_t* out, hipStream_t st);
 bool layer_uses_skinny(const FwdArgs& a, int l);
 aq_status launch_layer_skinny(const FwdArgs& a, int l, const LayerIO& io, hipStream_t st);
+// the few-row kernel's nibble weights from a layer's packed 8-bit operands: `pieces` = NT * KS * 64 (16 bytes -> 8)
+aq_status launch_pack_nibbles(const int8_t* wp, uint8_t* w4, int64_t pieces, hipStream_t st);
 aq_status launch_ln_tanh_rows(const FwdArgs& a, int layer, const float* x, int8_t* out, int64_t rows, hipStream_t st);
 aq_status launch_head_rows(const float* y, int64_t rows, int N, int head, void* actions, hipStream_t st);
 

@@ -52,6 +52,7 @@ def test_status_strings_and_argument_errors_without_gpu():
     assert lib.aq_policy_forward_fp32(None, None, 1, None, None) == b.EINVAL
     assert lib.aq_policy_forward_int8_static(None, None, 1, None, None) == b.EINVAL
     assert lib.aq_policy_fused_plan(None, 1, None, None, None) == b.EINVAL
+    assert lib.aq_policy_subbyte_layers(None, 1, None) == b.EINVAL
     assert lib.aq_status_string(8).startswith(b"needs more scratch")
 
 

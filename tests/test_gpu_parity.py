@@ -1129,6 +1129,56 @@ def test_edges(aq):
         assert e.value.status == aq.ESHAPE
 
 
+# ------------------------------------------------------------------ weights streamed as nibbles
+@pytest.mark.parametrize("name,batch,wbits", [("paper_fc2048", 1, 4), ("paper_fc2048", 16, 4), ("paper_fc2048", 40, 3),
+                                              ("paper_fc2048", 300, 4), ("cfg5", 96, 4), ("cfg2", 33, 2)])
+def test_few_row_layers_stream_nibble_weights(aq, name, batch, wbits):
+    """Policies of at most 4 bits with per-channel symmetric weights: the few-row layer kernel reads the codes two
+    per byte and expands them in registers.  Every stage against the oracle (whose n-bit codes are the same
+    integers), with and without taps, at 16- and 32-row tiles, through a blob hand-off, and identical to the same
+    policy read from its 8-bit containers (the general per-layer kernel at a batch beyond the few-row kernel's)."""
+    _say(f"few_row_layers_stream_nibble_weights {name} batch={batch} wbits={wbits}")
+    net = dict(synth.net_config(name), wbits=wbits)
+    nl = len(net["layers"])
+    params = synth.make_params(net, nonzero_bias=True)
+    obs = synth.make_obs(net, batch)
+    pol, ranges = U.make_oracle(net, params, synth.make_obs(net, 64))
+    P, _ = U.gpu_quantize(aq, net, params, ranges)
+    U.check_quantized_params(aq, P, pol, net)
+    P.policy_set_path(2)
+    assert P.policy_subbyte_layers(batch) == nl
+    assert P.policy_subbyte_layers(8192) == 0      # beyond the few-row kernel: 8-bit containers
+    actions, t = U.gpu_forward(P, net, obs)
+    U.compare_forward(net, pol, obs, actions, t)
+    del t
+    plain, _ = U.gpu_forward(P, net, obs, taps=False)
+    assert np.array_equal(plain, actions, equal_nan=True)
+    # the hand-off of the policy as a blob (plain and packed) rebuilds the nibble copy on the other side
+    for packed in (False, True):
+        Q = aq.Policy(net)
+        if packed:
+            blob = torch.zeros(P.policy_packed_blob_size(), dtype=torch.uint8, device=U.DEV)
+            P.policy_export_packed_blob(blob)
+            Q.policy_import_packed_blob(blob)
+        else:
+            blob = torch.zeros(P.policy_blob_size(), dtype=torch.uint8, device=U.DEV)
+            P.policy_export_blob(blob)
+            Q.policy_import_blob(blob)
+        assert Q.policy_status() == aq.OK
+        Q.policy_set_path(2)
+        assert Q.policy_subbyte_layers(batch) == nl
+        again, _ = U.gpu_forward(Q, net, obs, taps=False)
+        assert np.array_equal(again, plain, equal_nan=True)
+        Q.close()
+    P.close()
+    # the same precision with per-tensor asymmetric weights, and 8-bit policies, keep to the 8-bit containers
+    for other in (dict(net, wscheme="tensor_asym_u8"), dict(net, wbits=8), dict(net, wbits=5)):
+        R = aq.Policy(other)
+        R.policy_set_path(2)
+        assert R.policy_subbyte_layers(batch) == 0
+        R.close()
+
+
 # ------------------------------------------------------------------ measurement aids
 def test_stream_reference_moves_the_top_byte_of_every_value(aq):
     _say("stream_reference")
