@@ -237,6 +237,36 @@ def mfma_loop_workload(torch, aq, operands, stream_weights=True, ksteps=2048):
             "us_per_call": ms * 1e3, "int8_TOPs": tops, "frac_int8_mfma_peak": tops / INT8_PEAK_TOPS}
 
 
+def subbyte_workload(torch, aq, synth, name, batch, iters=200):
+    """A 4-bit policy (per-channel symmetric codes in [-7, 7]) on the one-launch-per-layer plan: its weights read
+    from the 8-bit containers (plan 2) against the same weights streamed as nibbles and expanded in registers
+    (plan 4); identical integers, so the actions must be equal."""
+    net = dict(synth.net_config(name), wbits=4)
+    params = synth.make_params(net)
+    obs = synth.make_obs(net, batch)
+    P = aq.Policy(net)
+    w, b, g, be = aq.upload_params(params, DEV)
+    d_obs = aq.to_dev(obs, DEV)
+    P.policy_set_params_fp32(w, b, g, be)
+    P.quantize_params(w, b, g, be, P.calibrate_fp32(d_obs))
+    P.policy_reserve(batch)
+    acts, us = [], []
+    for plan in (2, 4):
+        P.policy_set_path(plan)
+        act = torch.zeros(batch, synth.action_dim(net), dtype=torch.float32, device=DEV)
+        fwd = lambda: P.policy_forward_int8(d_obs, act)
+        for _ in range(10):
+            fwd()
+        torch.cuda.synchronize()
+        us.append(_graph_ms(torch, fwd, iters) * 1e3)
+        acts.append(act)
+    out = {"workload": f"{name} batch {batch}, 4-bit weights, one launch per layer",
+           "us_per_launch_8bit_containers": us[0], "us_per_launch_nibbles": us[1],
+           "layers_streaming_nibbles": P.policy_subbyte_layers(batch), "actions_equal": bool(torch.equal(acts[0], acts[1]))}
+    P.close()
+    return out
+
+
 def blob_workload(torch, aq, synth, name, wbits=8):
     """Learner -> actor hand-off of a quantized policy as one packed blob: export from one handle, import
     into another (device to device, no repacking), next to the cost of quantizing the fp32 parameters.
@@ -474,6 +504,8 @@ def main():
         for o in extra:
             if o.get("workload") == "cfg5 batch 16384":
                 o["frac_of_kstep_loop_alone"] = o["tops"] / loop_tops
+        for bsz in (1, 300):
+            extra.append(subbyte_workload(torch, aq, synth, "paper_fc2048", bsz))
         for name in ("cfg2", "cfg5"):
             extra.append(blob_workload(torch, aq, synth, name))
         extra.append(blob_workload(torch, aq, synth, "cfg5", wbits=4))

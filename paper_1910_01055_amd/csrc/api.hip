@@ -78,6 +78,7 @@ struct aq_policy {
     uint64_t net_hash = 0;     // of the network description (blob header)
     int path = 0;  // 0 auto, 1 fused only, 2 one launch per layer, 3 one launch per layer also for the convolutions
     bool conv_stack = true;
+    bool subbyte = false;  // plan 4: plan 2 with the few-row layers streaming the nibble copies of their weights
     // activation scratch of the per-layer path (8-bit maps, the fp32 rows a LayerNorm layer hands to its row
     // kernel, the logits of an argmax head) and of the fp32 actor, grown on demand
     int64_t cap_i8 = 0, cap_f32 = 0;
@@ -494,9 +495,10 @@ extern "C" aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch) {
 }
 
 extern "C" aq_status aq_policy_set_path(aq_policy* p, int32_t path) {
-    if (!p || path < 0 || path > 3) return AQ_EINVAL;
+    if (!p || path < 0 || path > 4) return AQ_EINVAL;
     p->conv_stack = path != 3;
-    p->path = path == 3 ? 2 : path;
+    p->subbyte = path == 4;
+    p->path = path >= 3 ? 2 : path;
     return AQ_OK;
 }
 
@@ -534,7 +536,8 @@ extern "C" aq_status aq_policy_subbyte_layers(const aq_policy* p, int64_t batch,
     int n = 0;
     if (p->path == 2 || !fused_mlp_supported(a, &r, &lds)) {
         const int nc = p->conv_stack ? conv_stack_layers(a) : 0;
-        for (int l = nc; l < (int)p->L.size(); ++l) n += p->w4[l] && !p->h_net.asym && layer_uses_skinny(a, l);
+        for (int l = nc; l < (int)p->L.size(); ++l)
+            n += p->subbyte && p->w4[l] && !p->h_net.asym && layer_uses_skinny(a, l);
     }
     *n_layers = n;
     return AQ_OK;
@@ -883,7 +886,7 @@ static aq_status forward_int8_impl(aq_policy* p, const void* d_obs, int64_t batc
     a.c.K0 = p->L[0].K;
     a.c.Kp0 = p->L[0].K_pad;
     a.c.in_u8 = p->h_net.in_u8;
-    for (int l = 0; l < nl; ++l) a.w4[l] = p->w4[l];
+    for (int l = 0; l < nl; ++l) a.w4[l] = p->subbyte ? p->w4[l] : nullptr;
     if (taps) {
         for (int l = 0; l < nl; ++l) {
             a.t.acc[l] = taps->acc ? taps->acc[l] : nullptr;

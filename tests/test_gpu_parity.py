@@ -1136,7 +1136,7 @@ def test_few_row_layers_stream_nibble_weights(aq, name, batch, wbits):
     """Policies of at most 4 bits with per-channel symmetric weights: the few-row layer kernel reads the codes two
     per byte and expands them in registers.  Every stage against the oracle (whose n-bit codes are the same
     integers), with and without taps, at 16- and 32-row tiles, through a blob hand-off, and identical to the same
-    policy read from its 8-bit containers (the general per-layer kernel at a batch beyond the few-row kernel's)."""
+    policy read from its 8-bit containers (launch plan 2)."""
     _say(f"few_row_layers_stream_nibble_weights {name} batch={batch} wbits={wbits}")
     net = dict(synth.net_config(name), wbits=wbits)
     nl = len(net["layers"])
@@ -1146,9 +1146,13 @@ def test_few_row_layers_stream_nibble_weights(aq, name, batch, wbits):
     P, _ = U.gpu_quantize(aq, net, params, ranges)
     U.check_quantized_params(aq, P, pol, net)
     P.policy_set_path(2)
+    assert P.policy_subbyte_layers(batch) == 0     # a plan to choose, not the default
+    from_bytes, _ = U.gpu_forward(P, net, obs, taps=False)
+    P.policy_set_path(4)
     assert P.policy_subbyte_layers(batch) == nl
     assert P.policy_subbyte_layers(8192) == 0      # beyond the few-row kernel: 8-bit containers
     actions, t = U.gpu_forward(P, net, obs)
+    assert np.array_equal(from_bytes, actions, equal_nan=True)
     U.compare_forward(net, pol, obs, actions, t)
     del t
     plain, _ = U.gpu_forward(P, net, obs, taps=False)
@@ -1165,7 +1169,7 @@ def test_few_row_layers_stream_nibble_weights(aq, name, batch, wbits):
             P.policy_export_blob(blob)
             Q.policy_import_blob(blob)
         assert Q.policy_status() == aq.OK
-        Q.policy_set_path(2)
+        Q.policy_set_path(4)
         assert Q.policy_subbyte_layers(batch) == nl
         again, _ = U.gpu_forward(Q, net, obs, taps=False)
         assert np.array_equal(again, plain, equal_nan=True)
@@ -1174,7 +1178,7 @@ def test_few_row_layers_stream_nibble_weights(aq, name, batch, wbits):
     # the same precision with per-tensor asymmetric weights, and 8-bit policies, keep to the 8-bit containers
     for other in (dict(net, wscheme="tensor_asym_u8"), dict(net, wbits=8), dict(net, wbits=5)):
         R = aq.Policy(other)
-        R.policy_set_path(2)
+        R.policy_set_path(4)
         assert R.policy_subbyte_layers(batch) == 0
         R.close()
 
