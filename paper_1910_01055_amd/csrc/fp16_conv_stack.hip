@@ -157,12 +157,18 @@ __global__ __launch_bounds__(FS_T) void k_fp16_conv_stack(const Fp16Stack S, con
             };
             h8 A0[4], X0[4], A1[4], X1[4];
             load4(0, A0, X0);
-            for (int k0 = 0; k0 < KS; k0 += 8) {
+            int k0 = 0;
+            for (; k0 + 8 < KS; k0 += 8) {
                 load4(k0 + 4, A1, X1);
                 mma4(k0, A0, X0);
                 load4(k0 + 8, A0, X0);
                 mma4(k0 + 4, A1, X1);
             }
+            // the last eight k-steps or fewer, without the request for a group after them: past K a request
+            // re-reads the last k-step and still takes its slot on the vector memory path
+            if (k0 + 4 < KS) load4(k0 + 4, A1, X1);
+            mma4(k0, A0, X0);
+            mma4(k0 + 4, A1, X1);
             // + bias, one rounding to binary16, ReLU; lane = one output position, four features per quad
             _Float16* dst = to_global ? out + (img * R + r) * N : map_out + r * N;
 #pragma unroll
