@@ -129,8 +129,10 @@ aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch);
  * network is an MLP that fits it, else one launch per layer, with the leading convolutions of a
  * frame policy in a single launch where their shapes allow it), 1 = fused only (AQ_ESHAPE from the
  * forward if it does not fit), 2 = one launch per layer (convolutions as in 0), 3 = one launch per
- * layer for every layer, 4 = plan 2 with sub-byte weight streaming where the policy has it (see
- * aq_policy_subbyte_layers).  All plans compute identical integers.  Other values: AQ_EINVAL. */
+ * layer for every layer, 4 = plan 2 with sub-byte weight streaming where the policy allows it (see
+ * aq_policy_subbyte_layers; choosing it the first time allocates the nibble copies of the weights,
+ * AQ_ENOMEM if that fails, and the first forward pass after every quantize or import rewrites them with
+ * one small launch per layer).  All plans compute identical integers.  Other values: AQ_EINVAL. */
 aq_status aq_policy_set_path(aq_policy* p, int32_t path);
 
 /* *n_layers = how many leading convolution layers the 8-bit forward of this handle runs as a single
@@ -159,8 +161,8 @@ aq_status aq_policy_fused_plan(const aq_policy* p, int64_t batch, int32_t* rows,
 
 /* How many layers of a forward pass at this batch size read their weights sub-byte.  A policy whose weight
  * precision is n <= 4 bits (aq_net.wbits; the precision sweep of the paper's appendix on quantization-aware
- * training) with per-channel symmetric weights keeps its fully connected layers' codes a second time as nibbles
- * (two codes per byte); under launch plan 4 (aq_policy_set_path) the few-row layer kernel -- one launch per layer
+ * training) with per-channel symmetric weights keeps, once launch plan 4 is chosen (aq_policy_set_path), its fully
+ * connected layers' codes a second time as nibbles (two codes per byte); under that plan the few-row layer kernel -- one launch per layer
  * at batch sizes below 8192, the paper's own regime of actors that run one observation at a time -- streams
  * those, half the weight bytes, and expands them in registers; the integer results are those of the 8-bit
  * containers, bit for bit.  It is a plan to choose, not the default: at the sizes measured the layer's time is

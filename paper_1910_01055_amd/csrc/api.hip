@@ -100,10 +100,12 @@ struct aq_policy {
     void* f32_slab = nullptr;
     std::vector<float*> f32_w, f32_b, f32_gamma, f32_beta;
     bool f32_ready = false;
-    // policies of at most 4 bits, per-channel symmetric: the fully connected layers' weights once more as nibbles,
-    // for the few-row kernel (one allocation at create; filled behind every quantize / import)
+    // policies of at most 4 bits, per-channel symmetric, under launch plan 4: the fully connected layers' weights
+    // once more as nibbles, for the few-row kernel (one allocation when the plan is first chosen; rewritten by
+    // the first forward pass after every quantize / import)
     void* w4_slab = nullptr;
     std::vector<uint8_t*> w4;
+    bool w4_stale = true;
     float* calib = nullptr;        // 2 * AQ_MAX_LAYERS floats: (min, max) per activation tensor, for aq_calibrate_fp32
     int64_t max_hidden_elems = 0;  // per sample, over hidden layer outputs
     int64_t max_out_elems = 0;     // per sample, over all layer outputs
@@ -264,32 +266,6 @@ extern "C" aq_status aq_policy_create(const aq_net* net, aq_policy** out) {
         return AQ_EHIP;
     }
     p->w4.assign(p->L.size(), nullptr);
-    if ((net->wbits != 0 && net->wbits <= 4) && net->wscheme == AQ_W_CHANNEL_SYM_S8) {
-        size_t w4_bytes = 0;
-        LayerDev probe{};
-        for (size_t l = 0; l < p->L.size(); ++l) {
-            const LayerBuf& b = p->L[l];
-            probe.kh = probe.kw = probe.in_h = probe.in_w = b.fc ? 1 : 2;
-            probe.KS = b.KS;
-            if (skinny_layer_supported(probe, 1)) w4_bytes += (size_t)b.NT * b.KS * 512;
-        }
-        if (w4_bytes) {
-            if (hipMalloc(&p->w4_slab, w4_bytes) != hipSuccess) {
-                (void)hipFree(p->slab);
-                delete p;
-                return AQ_ENOMEM;
-            }
-            size_t o4 = 0;
-            for (size_t l = 0; l < p->L.size(); ++l) {
-                const LayerBuf& b = p->L[l];
-                probe.kh = probe.kw = probe.in_h = probe.in_w = b.fc ? 1 : 2;
-                probe.KS = b.KS;
-                if (!skinny_layer_supported(probe, 1)) continue;
-                p->w4[l] = (uint8_t*)p->w4_slab + o4;
-                o4 += (size_t)b.NT * b.KS * 512;
-            }
-        }
-    }
     char* base = (char*)p->slab;
     size_t oi = 0;
     for (auto& b : p->L) {
@@ -496,6 +472,28 @@ extern "C" aq_status aq_policy_reserve(aq_policy* p, int64_t max_batch) {
 
 extern "C" aq_status aq_policy_set_path(aq_policy* p, int32_t path) {
     if (!p || path < 0 || path > 4) return AQ_EINVAL;
+    if (path == 4 && !p->w4_slab && p->net.wbits != 0 && p->net.wbits <= 4 && p->net.wscheme == AQ_W_CHANNEL_SYM_S8) {
+        size_t w4_bytes = 0;
+        std::vector<size_t> need(p->L.size(), 0);
+        for (size_t l = 0; l < p->L.size(); ++l) {
+            const LayerBuf& b = p->L[l];
+            LayerDev probe{};
+            probe.kh = probe.kw = probe.in_h = probe.in_w = b.fc ? 1 : 2;
+            probe.KS = b.KS;
+            if (skinny_layer_supported(probe, 1)) need[l] = (size_t)b.NT * b.KS * 512;
+            w4_bytes += need[l];
+        }
+        if (w4_bytes) {
+            if (hipMalloc(&p->w4_slab, w4_bytes) != hipSuccess) return AQ_ENOMEM;
+            size_t o4 = 0;
+            for (size_t l = 0; l < p->L.size(); ++l) {
+                if (!need[l]) continue;
+                p->w4[l] = (uint8_t*)p->w4_slab + o4;
+                o4 += need[l];
+            }
+            p->w4_stale = true;
+        }
+    }
     p->conv_stack = path != 3;
     p->subbyte = path == 4;
     p->path = path >= 3 ? 2 : path;
@@ -576,7 +574,8 @@ void blob_words(const aq_policy* p, uint32_t (&w)[6]) {
 constexpr size_t kTailBytes = sizeof(ActQ) * (AQ_MAX_LAYERS + 1) + sizeof(int) * AQ_MAX_LAYERS;
 }  // namespace
 
-// the nibble copies of the weights follow every change of the packed 8-bit operands
+// the nibble copies of the weights follow every change of the packed 8-bit operands: written by the first forward
+// pass under launch plan 4 after such a change
 static aq_status refresh_w4(aq_policy* p, hipStream_t st) {
     for (size_t l = 0; l < p->L.size(); ++l) {
         if (!p->w4[l]) continue;
@@ -584,6 +583,7 @@ static aq_status refresh_w4(aq_policy* p, hipStream_t st) {
         const aq_status s = launch_pack_nibbles(b.wp, p->w4[l], (int64_t)b.NT * b.KS * 64, st);
         if (s != AQ_OK) return s;
     }
+    p->w4_stale = false;
     return AQ_OK;
 }
 
@@ -621,8 +621,7 @@ extern "C" aq_status aq_policy_import_blob(aq_policy* p, const void* d_blob, uin
     if (s != AQ_OK) return s;
     AQ_HIP_CHECK(hipMemcpyAsync(p->d_net->actq, src + kBlobHeader, kTailBytes, hipMemcpyDeviceToDevice, st));
     AQ_HIP_CHECK(hipMemcpyAsync(p->slab, src + kBlobHeader + kBlobTail, p->layer_bytes, hipMemcpyDeviceToDevice, st));
-    s = refresh_w4(p, st);
-    if (s != AQ_OK) return s;
+    p->w4_stale = true;
     p->quantized = true;
     return AQ_OK;
 }
@@ -723,8 +722,7 @@ extern "C" aq_status aq_policy_import_packed_blob(aq_policy* p, const void* d_bl
         AQ_HIP_CHECK(hipMemcpyAsync((char*)p->slab + L.c_src[l], src + L.c_off[l], L.c_bytes[l],
                                     hipMemcpyDeviceToDevice, st));
     }
-    s = refresh_w4(p, st);
-    if (s != AQ_OK) return s;
+    p->w4_stale = true;
     p->quantized = true;
     return AQ_OK;
 }
@@ -810,8 +808,7 @@ extern "C" aq_status aq_quantize_params(aq_policy* p, const float* const* h_d_w,
     aq_status s = launch_quantize_policy(p->d_qtab, p->h_qtab, ptrs, r, p->actq, p->d_net->fast, p->status,
                                          p->mm, st);
     if (s != AQ_OK) return s;
-    s = refresh_w4(p, st);
-    if (s != AQ_OK) return s;
+    p->w4_stale = true;
     p->quantized = true;
     return AQ_OK;
 }
@@ -886,6 +883,10 @@ static aq_status forward_int8_impl(aq_policy* p, const void* d_obs, int64_t batc
     a.c.K0 = p->L[0].K;
     a.c.Kp0 = p->L[0].K_pad;
     a.c.in_u8 = p->h_net.in_u8;
+    if (p->subbyte && p->w4_slab && p->w4_stale) {
+        const aq_status ws = refresh_w4(p, st);
+        if (ws != AQ_OK) return ws;
+    }
     for (int l = 0; l < nl; ++l) a.w4[l] = p->subbyte ? p->w4[l] : nullptr;
     if (taps) {
         for (int l = 0; l < nl; ++l) {
