@@ -149,8 +149,9 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
     const int K0 = c.K0;
     const int64_t left = c.batch - row0;
     const int vrows = left < ROWS ? (int)left : ROWS;
-    // a thread takes up to NQ (row, four consecutive k) quads: one 16-byte load where the rows are 16-byte
-    // aligned (K0 a multiple of 4), four 4-byte loads otherwise
+    // a thread takes up to NQ (row, four consecutive k) quads: one 16-byte load where the rows are 16-byte aligned
+    // (K0 a multiple of 4); otherwise four 4-byte loads (one row tile) or one 16-byte load at a 4-byte aligned
+    // address (several row tiles; only the quad that ends the batch goes word by word)
     const int q4 = (K0 + 3) >> 2;  // quads per row, <= 64
     const float inv_q4 = __builtin_amdgcn_rcpf((float)q4);  // (1 ulp: far inside the margin below)
     const float* src1 = c.obs + row0 * K0;
@@ -192,7 +193,16 @@ __global__ __launch_bounds__(RT, MT == 1 ? 2 : 4) void k_mlp_rows16(const NetDev
                 const float* src = src1 + om[u] * K0 + ok4[u];
                 if (k_al) {
                     ov[u] = *(const float4*)src;
-                } else {
+                } else if (MT > 1 && !(left <= ROWS && om[u] == vrows - 1 && ok4[u] + 3 >= K0)) {
+                    // rows at 4-byte aligned addresses, several row tiles per workgroup (where the requests
+                    // count: cfg3 @ 65536 32.6 -> 31.75 us; a single 16-row tile, bound by latency, was 1 %
+                    // slower with it): still one request, of 16 bytes at that alignment.  Past
+                    // the row's end the words are the next row's first ones (they exist: only the batch's last
+                    // row has none behind it) and are masked out once quantized
+                    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+                    const f4u v = *(const f4u*)src;
+                    ov[u] = float4{v[0], v[1], v[2], v[3]};
+                } else {  // the last words of the whole batch
                     ov[u].x = src[0];
                     if (ok4[u] + 1 < K0) ov[u].y = src[1];
                     if (ok4[u] + 2 < K0) ov[u].z = src[2];
