@@ -1177,6 +1177,9 @@ def test_few_row_layers_stream_nibble_weights(aq, name, batch, wbits):
         again, _ = U.gpu_forward(Q, net, obs, taps=False)
         assert np.array_equal(again, plain, equal_nan=True)
         Q.close()
+    with pytest.raises(aq.AqError) as e:
+        P.policy_set_path(5)
+    assert e.value.status == aq.EINVAL
     P.close()
     # the same precision with per-tensor asymmetric weights, and 8-bit policies, keep to the 8-bit containers
     for other in (dict(net, wscheme="tensor_asym_u8"), dict(net, wbits=8), dict(net, wbits=5)):
