@@ -22,8 +22,9 @@ namespace aq {
 
 namespace {
 constexpr int SK_W = 8;                    // waves per workgroup = K split
-// Weight k-steps a wave requests up front (template parameter PF): 8 for 8-bit weights (longer shares are
-// refilled as they are used), 8 or 16 = the whole share for nibble weights, whichever covers it.  Requests beyond the share re-read its last k-step (straight-line loads, so that the waits can
+// Weight k-steps a wave requests up front (template parameter PF): 4 or 8 for 8-bit weights (shares up to 4
+// k-steps / longer ones, refilled as they are used), 8 or 16 = the whole share for nibble weights, whichever
+// covers it.  Requests beyond the share re-read its last k-step (straight-line loads, so that the waits can
 // be counted), and every such re-read takes its 16 clocks of the CU's vector memory path like a useful one: with
 // 16 in flight for a share of 8, a 2048 x 2048 layer at batch 1 took 3.7 us instead of 3.2.
 constexpr int SK_MAX_KCHUNK = 15;          // k-steps per wave that fit the LDS budget below
@@ -83,7 +84,10 @@ __global__ __launch_bounds__(SK_W * 64) void k_layer_skinny(const NetDev* __rest
     const NetDev& a = *netp;
     LayerTaps T{nullptr, nullptr, nullptr};
     if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // (the wave index as a scalar: what depends on it - this wave's k-steps - then branches on the scalar unit.
+    // Left in a vector register it makes those tests lane masks, and a block that holds nothing but an MFMA may
+    // lose its skip branch: the matrix cores do not honour an empty lane mask, the k-step would be added anyway)
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nt = blockIdx.x;
     constexpr int tile_rows = TR;
     const int64_t row0 = (int64_t)blockIdx.y * tile_rows;
@@ -362,6 +366,7 @@ aq_status skinny_launch(const SkinnyCall& c) {
 }
 template <bool AS, bool TP, int TRV, bool W4V>
 aq_status skinny_pick_depth(const SkinnyCall& c) {
+    if (!W4V && c.kchunk <= 4) return skinny_launch<AS, TP, TRV, W4V, W4V ? 8 : 4>(c);
     if (c.kchunk <= 8 || !W4V) return skinny_launch<AS, TP, TRV, W4V, 8>(c);
     return skinny_launch<AS, TP, TRV, W4V, W4V ? 16 : 8>(c);
 }
