@@ -95,6 +95,8 @@ __global__ __launch_bounds__(W * 64) void k_conv_stack(const NetDev* __restrict_
                                                      const int off_b, const int off_c) {
     extern __shared__ __align__(16) int8_t smem[];
     const NetDev& a = *netp;
+    // (the wave index stays a vector value here: it only selects tiles, in a loop; the tests that guard MFMAs are on
+    // the scalar K.  An MFMA behind a lane-mask test could run under an empty mask, which the matrix cores ignore)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, n = lane & 31;
     const int64_t img = blockIdx.x;
     constexpr int NTHR = W * 64;

@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256, 2) void k_layer_fp16(const Fp16Layer L, const 
     constexpr int XBUF = ROWS * HLD;
     constexpr int XS = 2 * XBUF > HW * 32 * SW ? 2 * XBUF : HW * 32 * SW;
     __shared__ __align__(16) _Float16 xs[XS];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row0 = (int64_t)blockIdx.x * ROWS;
     const int nt0 = (blockIdx.y * HW + wave) * NB;  // this wave's first feature tile
     const bool wave_on = nt0 < L.NT;
@@ -362,7 +362,7 @@ constexpr int SKH_LD = 65;  // words per register row of a partial tile (conflic
 __global__ __launch_bounds__(SKH_W * 64) void k_layer_fp16_skinny(const Fp16Layer L, const _Float16* __restrict__ in,
                                                                    _Float16* __restrict__ out, const int64_t rows) {
     __shared__ float part[SKH_W * 16 * SKH_LD];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nt = blockIdx.x;
     const int64_t row0 = (int64_t)blockIdx.y * 32;
     const int KSr = (L.K + 15) / 16;                  // k-steps that hold real columns

@@ -65,6 +65,8 @@ bool plan_fs(const Fp16Layer* L, int n_layers, const void* obs, int in_mode0, in
 __global__ __launch_bounds__(FS_T) void k_fp16_conv_stack(const Fp16Stack S, const uint8_t* __restrict__ frames,
                                                          _Float16* __restrict__ out) {
     extern __shared__ __align__(16) int8_t smem[];
+    // (the wave index stays a vector value here: it only selects tiles, in a loop; the tests that guard MFMAs are on
+    // the scalar K.  An MFMA behind a lane-mask test could run under an empty mask, which the matrix cores ignore)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, n = lane & 31;
     const int64_t img = blockIdx.x;
     const int nc = S.nc;

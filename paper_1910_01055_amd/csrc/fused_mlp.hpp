@@ -206,7 +206,7 @@ __global__ __launch_bounds__(FT) void k_mlp_fused(const NetDev* __restrict__ net
     // it; the wide variant (NB = 2) has no registers to spare and fetches at the start of each pass
     constexpr bool XPF = NB == 1;
     const NetDev& a = *netp;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5;
     const int hh = HALF ? (lane >> 4) & 1 : 0;        // which half of the feature quads (after the fold)
     const int mrow = HALF ? lane & 15 : lane & 31;    // this lane's row within a row tile in the epilogues
     const int64_t row0 = (int64_t)blockIdx.x * ROWS;

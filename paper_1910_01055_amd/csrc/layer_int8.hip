@@ -44,7 +44,7 @@ __global__ __launch_bounds__(W * 64, (W <= 2 && !DEEP) ? 4 : 1) void k_layer_int
     const LayerDev& L = a.L[l];
     LayerTaps T{nullptr, nullptr, nullptr};
     if (TAPS) T = LayerTaps{t.acc[l], t.act[l], t.ln[l]};
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5;
     const int64_t row0 = (int64_t)blockIdx.x * ROWS;
     const bool first = l == 0, last = l == a.n_layers - 1;
     const bool ln = !last && L.act == AQ_ACT_LN_TANH;
